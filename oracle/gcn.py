@@ -1,0 +1,221 @@
+"""Checker for the per-subgraph GCN training step (fp64, CPU, numpy).
+
+TEST INFRASTRUCTURE ONLY.  This module is the slow, plain statement of what the
+device library must compute.  It is imported by the tests, by the smoke check
+and by the benchmark's CPU-baseline leg, never by the product path, and it
+shares no code with the HIP sources.
+
+Everything is in ORIGINAL node order and float64.  The steps follow the paper's
+Sec. 3.2 in its order and notation:
+
+  graph convolution   h_i = sigma( (1/(|N(i)|+1)) (x_i + sum_{j in N(i)} x_j) W )   (Eq. 3)
+  read-out            p_i = 1 / (1 + exp(-h_i))                                      (Eq. 4)
+  loss                L = alpha * sum_{(i,j) in E} p_i p_j - beta * sum_i p_i        (Eq. 5)
+  training            back-propagation, repeated for a fixed number of epochs       (Sec. 3.2, last paragraph)
+  independence        every subgraph is trained on its own edges only, with its
+                      own network                                                    (Sec. 3.3, first paragraph; Alg. 1 stage 1)
+
+Readings taken where the paper is open (listed with reasons in the design notes):
+  * N(i) is the neighbourhood INSIDE i's subgraph (cut edges are not trained on).
+  * normalisation "mean" is Eq. 3 as printed, (D+I)^-1 (A+I); "sym" is
+    (D+I)^-1/2 (A+I) (D+I)^-1/2, the form the workloads prescribe.
+  * sigma = ReLU on hidden layers; the last layer is linear and scalar and feeds
+    the sigmoid of Eq. 4 (ReLU before the sigmoid would pin every p_i >= 0.5).
+  * L layers, L in {1,2,3}: L-1 hidden layers of Eq. 3 followed by the scalar one.
+  * each undirected edge is counted once in Eq. 5.
+  * the generic QUBO of Alg. 1 is L = sum_i p_i (c_i + (q/2) s_i), s = A_loc p:
+    MIS has c_i = -beta, q = alpha; Max-Cut has c_i = -deg_i, q = 2, which is
+    sum_{(i,j) in E_loc} (2 p_i p_j - p_i - p_j).
+  * embeddings and all weight matrices are trained with Adam (beta1 0.9,
+    beta2 0.999, eps 1e-8, no weight decay), one network per subgraph unless
+    weights are declared shared.
+
+A library routine is used for two steps only: dense matmul (numpy @) and sparse
+matrix times dense matrix (scipy.sparse CSR @).
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass, field
+
+import numpy as np
+import scipy.sparse as sp
+
+
+@dataclass
+class Spec:
+    problem: str = "mis"          # "mis" | "maxcut"
+    num_layers: int = 2           # L
+    norm: str = "sym"             # "sym" | "mean"
+    alpha: float = 2.0
+    beta: float = 1.0
+    weight_sharing: bool = False  # False: one W_l per subgraph (the paper's reading)
+    train_embed: bool = True
+    lr: float = 1e-2
+    adam_b1: float = 0.9
+    adam_b2: float = 0.999
+    adam_eps: float = 1e-8
+
+
+@dataclass
+class LocalGraph:
+    """What the training step sees of (graph, partition ids)."""
+    n: int
+    num_parts: int
+    part: np.ndarray                 # int [n]
+    A_loc: sp.csr_matrix             # 0/1 symmetric adjacency of local edges, no diagonal
+    deg: np.ndarray                  # local degree, float64 [n]
+    A_hat: sp.csr_matrix             # normalised (A_loc + I)
+    members: list = field(default_factory=list)  # members[k] = node ids of subgraph k, ascending
+
+
+def local_graph(n, rowptr, col, part, num_parts, norm) -> LocalGraph:
+    """Drop cut edges, take local degrees, and normalise (Eq. 3's 1/(|N(i)|+1))."""
+    rowptr = np.asarray(rowptr, dtype=np.int64)
+    col = np.asarray(col, dtype=np.int64)
+    part = np.zeros(n, dtype=np.int64) if part is None else np.asarray(part, dtype=np.int64)
+    row = np.repeat(np.arange(n, dtype=np.int64), np.diff(rowptr))
+    same = part[row] == part[col]
+    A_loc = sp.csr_matrix((np.ones(int(same.sum())), (row[same], col[same])), shape=(n, n))
+    deg = np.asarray(A_loc.sum(axis=1)).ravel()
+    d_tilde = deg + 1.0                      # |N(i)| + 1
+    A_plus_I = (A_loc + sp.identity(n, format="csr")).tocsr()
+    if norm == "mean":
+        A_hat = sp.diags(1.0 / d_tilde) @ A_plus_I
+    elif norm == "sym":
+        s = 1.0 / np.sqrt(d_tilde)
+        A_hat = sp.diags(s) @ A_plus_I @ sp.diags(s)
+    else:
+        raise ValueError(norm)
+    members = [np.flatnonzero(part == k) for k in range(num_parts)]
+    return LocalGraph(n, num_parts, part, A_loc.tocsr(), deg, A_hat.tocsr(), members)
+
+
+def _w(W, k, spec):
+    return W[0] if spec.weight_sharing else W[k]
+
+
+def _apply_weights(lg: LocalGraph, X, W, spec):
+    """rows of subgraph k times W[k]."""
+    out = np.zeros((lg.n, W.shape[2]))
+    for k, idx in enumerate(lg.members):
+        out[idx] = X[idx] @ _w(W, k, spec)
+    return out
+
+
+def forward(lg: LocalGraph, E, Ws, spec: Spec) -> dict:
+    """Eq. 3 for the hidden layers, then the scalar layer and Eq. 4."""
+    L = spec.num_layers
+    H = [np.asarray(E, dtype=np.float64)]
+    Agg, Z = [None], [None]
+    for l in range(1, L):
+        agg = lg.A_hat @ H[l - 1]                               # aggregate
+        z = _apply_weights(lg, agg, np.asarray(Ws[l - 1], dtype=np.float64), spec)  # transform
+        Agg.append(agg)
+        Z.append(z)
+        H.append(np.maximum(z, 0.0))                            # sigma = ReLU
+    agg = lg.A_hat @ H[L - 1]
+    z_out = _apply_weights(lg, agg, np.asarray(Ws[L - 1], dtype=np.float64), spec)[:, 0]
+    Agg.append(agg)
+    p = 1.0 / (1.0 + np.exp(-z_out))                            # Eq. 4
+    return {"H": H, "Agg": Agg, "Z": Z, "z": z_out, "p": p}
+
+
+def qubo_coefficients(lg: LocalGraph, spec: Spec):
+    if spec.problem == "mis":
+        return np.full(lg.n, -spec.beta), spec.alpha
+    if spec.problem == "maxcut":
+        return -lg.deg.copy(), 2.0
+    raise ValueError(spec.problem)
+
+
+def loss(lg: LocalGraph, p, spec: Spec, extra_linear=None):
+    """Eq. 5 (or its generic-QUBO form): total and per-subgraph values.
+
+    extra_linear, if given, is added to the linear coefficients c (the
+    fine-tuning penalty of Sec. 3.3 has exactly this form)."""
+    c, q = qubo_coefficients(lg, spec)
+    if extra_linear is not None:
+        c = c + extra_linear
+    s = lg.A_loc @ p
+    per_node = p * (c + 0.5 * q * s)
+    per_part = np.array([per_node[idx].sum() for idx in lg.members])
+    return float(per_part.sum()), per_part
+
+
+def backward(lg: LocalGraph, cache: dict, Ws, spec: Spec, extra_linear=None):
+    """Exact chain rule through Eq. 5, Eq. 4 and the layers of Eq. 3.
+
+    Returns (gE [n, d], [gW_1 .. gW_L]) with gW_l shaped like W_l."""
+    L = spec.num_layers
+    c, q = qubo_coefficients(lg, spec)
+    if extra_linear is not None:
+        c = c + extra_linear
+    p = cache["p"]
+    s = lg.A_loc @ p
+    g_p = c + q * s                                   # dL/dp_i
+    g_z = g_p * p * (1.0 - p)                         # through the sigmoid
+    gWs = [np.zeros_like(np.asarray(W, dtype=np.float64)) for W in Ws]
+    # scalar layer: z = (A_hat H_{L-1}) w_L
+    WL = np.asarray(Ws[L - 1], dtype=np.float64)
+    g_agg = np.zeros_like(cache["Agg"][L])
+    for k, idx in enumerate(lg.members):
+        kk = 0 if spec.weight_sharing else k
+        gWs[L - 1][kk, :, 0] += cache["Agg"][L][idx].T @ g_z[idx]
+        g_agg[idx] = np.outer(g_z[idx], WL[kk, :, 0])
+    g_H = lg.A_hat.T @ g_agg
+    for l in range(L - 1, 0, -1):
+        g_Z = g_H * (cache["Z"][l] > 0.0)             # ReLU, derivative 0 at 0
+        Wl = np.asarray(Ws[l - 1], dtype=np.float64)
+        g_agg = np.zeros_like(cache["Agg"][l])
+        for k, idx in enumerate(lg.members):
+            kk = 0 if spec.weight_sharing else k
+            gWs[l - 1][kk] += cache["Agg"][l][idx].T @ g_Z[idx]
+            g_agg[idx] = g_Z[idx] @ Wl[kk].T
+        g_H = lg.A_hat.T @ g_agg
+    return g_H, gWs
+
+
+def adam_update(theta, g, m, v, t, spec: Spec):
+    """One Adam step (Kingma and Ba 2015, Alg. 1), t counted from 1."""
+    m = spec.adam_b1 * m + (1.0 - spec.adam_b1) * g
+    v = spec.adam_b2 * v + (1.0 - spec.adam_b2) * g * g
+    m_hat = m / (1.0 - spec.adam_b1 ** t)
+    v_hat = v / (1.0 - spec.adam_b2 ** t)
+    theta = theta - spec.lr * m_hat / (np.sqrt(v_hat) + spec.adam_eps)
+    return theta, m, v
+
+
+@dataclass
+class TrainState:
+    E: np.ndarray
+    Ws: list
+    mE: np.ndarray
+    vE: np.ndarray
+    mW: list
+    vW: list
+    t: int = 0
+
+
+def init_state(E, Ws) -> TrainState:
+    E = np.array(E, dtype=np.float64)
+    Ws = [np.array(W, dtype=np.float64) for W in Ws]
+    return TrainState(E, Ws, np.zeros_like(E), np.zeros_like(E),
+                      [np.zeros_like(W) for W in Ws], [np.zeros_like(W) for W in Ws], 0)
+
+
+def train(lg: LocalGraph, st: TrainState, spec: Spec, epochs: int, extra_linear=None):
+    """`epochs` full-batch steps.  Returns the loss at the parameters each epoch
+    started from, and per-subgraph losses [epochs, P]."""
+    losses, per_part = [], []
+    for _ in range(epochs):
+        cache = forward(lg, st.E, st.Ws, spec)
+        tot, pp = loss(lg, cache["p"], spec, extra_linear)
+        losses.append(tot)
+        per_part.append(pp)
+        gE, gWs = backward(lg, cache, st.Ws, spec, extra_linear)
+        st.t += 1
+        if spec.train_embed:
+            st.E, st.mE, st.vE = adam_update(st.E, gE, st.mE, st.vE, st.t, spec)
+        for l in range(spec.num_layers):
+            st.Ws[l], st.mW[l], st.vW[l] = adam_update(st.Ws[l], gWs[l], st.mW[l], st.vW[l], st.t, spec)
+    return np.array(losses), np.array(per_part)

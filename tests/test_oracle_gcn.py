@@ -1,0 +1,415 @@
+"""Pins for the fp64 checker of the training step (CPU only).
+
+Each test fixes the checker to something other than itself: closed forms worked
+out by hand, finite differences, dense linear algebra, brute force, invariants
+that the paper's statements imply.  A dropped term, a wrong sign or index, or a
+transposed operand in oracle/gcn.py fails at least one of them.
+"""
+import math
+
+import numpy as np
+import pytest
+
+from oracle import gcn
+from tests import helpers as hp
+
+
+
+def make(n, edges, part=None, P=1, norm="sym"):
+    rowptr, col = hp.csr_from_edges(n, edges)
+    return gcn.local_graph(n, rowptr, col, part, P, norm)
+
+
+def rand_params(rs, n, d, L, Pw):
+    E = rs.normal(0, 0.5, (n, d))
+    Ws = [rs.uniform(-0.8, 0.8, (Pw, d, d if l < L else 1)) for l in range(1, L + 1)]
+    return E, Ws
+
+
+# ---------------------------------------------------------------- normalisation
+
+def test_path3_hand_values_mean_and_sym():
+    """Path 0-1-2, one layer, d = 1, E = (1, 2, 4), w = 1: Eq. 3 by hand.
+
+    mean: z = ((1+2)/2, (1+2+4)/3, (2+4)/2).
+    sym : z_i = sum_j (A+I)_ij x_j / sqrt(d~_i d~_j), d~ = (2, 3, 2)."""
+    E = np.array([[1.0], [2.0], [4.0]])
+    Ws = [np.array([[[1.0]]])]
+    s6 = math.sqrt(6.0)
+    want = {
+        "mean": [1.5, 7.0 / 3.0, 3.0],
+        "sym": [1 / 2 + 2 / s6, 1 / s6 + 2 / 3 + 4 / s6, 2 / s6 + 4 / 2],
+    }
+    for norm, z in want.items():
+        lg = make(3, hp.path(3), norm=norm)
+        out = gcn.forward(lg, E, Ws, gcn.Spec(num_layers=1, norm=norm))
+        np.testing.assert_allclose(out["z"], z, rtol=1e-14)
+        np.testing.assert_allclose(out["p"], [1 / (1 + math.exp(-v)) for v in z], rtol=1e-14)
+
+
+def test_triangle_with_tail_hand_values():
+    """Triangle 0-1-2 with a tail 2-3, mean normalisation, one layer, d = 1,
+    x = (1, -1, 2, 1/2), w = 4/5.  Worked by hand from Eq. 3-5:
+      aggregates (1-1+2)/3, (-1+1+2)/3, (2+1-1+1/2)/4, (1/2+2)/2
+      z = 4/5 * aggregate = 8/15, 8/15, 1/2, 1
+      L = 2 (p0 p1 + p1 p2 + p0 p2 + p2 p3) - (p0 + p1 + p2 + p3)."""
+    edges = [(0, 1), (1, 2), (0, 2), (2, 3)]
+    lg = make(4, edges, norm="mean")
+    E = np.array([[1.0], [-1.0], [2.0], [0.5]])
+    Ws = [np.array([[[0.8]]])]
+    spec = gcn.Spec(problem="mis", num_layers=1, norm="mean", alpha=2.0, beta=1.0)
+    out = gcn.forward(lg, E, Ws, spec)
+    z = [8 / 15, 8 / 15, 1 / 2, 1.0]
+    p = [1 / (1 + math.exp(-v)) for v in z]
+    np.testing.assert_allclose(out["z"], z, rtol=1e-14)
+    np.testing.assert_allclose(out["p"], p, rtol=1e-14)
+    want = 2 * (p[0] * p[1] + p[1] * p[2] + p[0] * p[2] + p[2] * p[3]) - sum(p)
+    assert abs(gcn.loss(lg, out["p"], spec)[0] - want) < 1e-14
+    # dL/dw by hand: sum_i (dL/dp_i) p_i (1 - p_i) * aggregate_i
+    agg = [2 / 3, 2 / 3, 5 / 8, 5 / 4]
+    nb = {0: [1, 2], 1: [0, 2], 2: [0, 1, 3], 3: [2]}
+    gw = sum((-1 + 2 * sum(p[j] for j in nb[i])) * p[i] * (1 - p[i]) * agg[i] for i in range(4))
+    _, gWs = gcn.backward(lg, out, Ws, spec)
+    assert abs(gWs[0][0, 0, 0] - gw) < 1e-14
+
+
+@pytest.mark.parametrize("seed", [0, 1])
+def test_a_hat_properties(seed):
+    rs = np.random.RandomState(seed)
+    n = 40
+    edges = hp.random_graph(n, 0.15, rs)
+    part = rs.randint(0, 3, n)
+    sym = make(n, edges, part, 3, "sym")
+    mean = make(n, edges, part, 3, "mean")
+    A = sym.A_hat.toarray()
+    np.testing.assert_allclose(A, A.T, atol=1e-15)                    # symmetric
+    root = np.sqrt(sym.deg + 1.0)
+    np.testing.assert_allclose(A @ root, root, rtol=1e-13)            # eigenvalue 1
+    ev = np.linalg.eigvalsh(A)
+    assert ev.max() <= 1 + 1e-12 and ev.min() > -1.0
+    M = mean.A_hat.toarray()
+    np.testing.assert_allclose(M.sum(1), 1.0, rtol=1e-13)             # row-stochastic
+    assert (M >= 0).all()
+    # no entry links two subgraphs; local degrees count same-part neighbours only
+    for i in range(n):
+        for j in range(n):
+            if part[i] != part[j]:
+                assert A[i, j] == 0 and M[i, j] == 0
+    deg = np.zeros(n)
+    for u, v in edges:
+        if part[u] == part[v]:
+            deg[u] += 1
+            deg[v] += 1
+    np.testing.assert_array_equal(sym.deg, deg)
+    # entries: 1/(d~_i) on the diagonal of both; mean rows constant
+    for i in range(n):
+        assert abs(A[i, i] - 1.0 / (deg[i] + 1)) < 1e-15
+        nz = M[i][M[i] > 0]
+        np.testing.assert_allclose(nz, 1.0 / (deg[i] + 1), rtol=1e-14)
+        assert len(nz) == deg[i] + 1
+
+
+@pytest.mark.parametrize("norm", ["sym", "mean"])
+@pytest.mark.parametrize("L", [1, 2, 3])
+def test_forward_against_dense_matrices(norm, L):
+    """Forward pass redone with dense per-subgraph matrices built entry by entry."""
+    rs = np.random.RandomState(3 + L)
+    n, d, P = 25, 4, 3
+    edges = hp.random_graph(n, 0.2, rs)
+    part = rs.randint(0, P, n)
+    lg = make(n, edges, part, P, norm)
+    E, Ws = rand_params(rs, n, d, L, P)
+    out = gcn.forward(lg, E, Ws, gcn.Spec(num_layers=L, norm=norm))
+    p = np.zeros(n)
+    for k in range(P):
+        idx = [i for i in range(n) if part[i] == k]
+        pos = {v: a for a, v in enumerate(idx)}
+        B = np.eye(len(idx))
+        for u, v in edges:
+            if u in pos and v in pos:
+                B[pos[u], pos[v]] = B[pos[v], pos[u]] = 1.0
+        dt = B.sum(1)
+        Ah = B / dt[:, None] if norm == "mean" else B / np.sqrt(np.outer(dt, dt))
+        h = E[idx]
+        for l in range(1, L):
+            h = np.maximum(Ah @ h @ Ws[l - 1][k], 0)
+        z = (Ah @ h @ Ws[L - 1][k])[:, 0]
+        p[idx] = 1 / (1 + np.exp(-z))
+    np.testing.assert_allclose(out["p"], p, rtol=1e-12)
+
+
+# ---------------------------------------------------------------- loss
+
+def test_integral_energies():
+    """For 0/1 vectors Eq. 5 is alpha * (#edges inside S) - beta * |S|; the
+    Max-Cut form is minus the cut value."""
+    rs = np.random.RandomState(5)
+    n = 30
+    edges = hp.random_graph(n, 0.2, rs)
+    lg = make(n, edges)
+    for _ in range(20):
+        x = (rs.random(n) < 0.4).astype(float)
+        inside = sum(1 for u, v in edges if x[u] and x[v])
+        cut = sum(1 for u, v in edges if x[u] != x[v])
+        a, b = 2.0, 1.0
+        tot, _ = gcn.loss(lg, x, gcn.Spec(problem="mis", alpha=a, beta=b))
+        assert tot == a * inside - b * x.sum()
+        tot, _ = gcn.loss(lg, x, gcn.Spec(problem="mis", alpha=3.5, beta=0.25))
+        assert abs(tot - (3.5 * inside - 0.25 * x.sum())) < 1e-12
+        tot, _ = gcn.loss(lg, x, gcn.Spec(problem="maxcut"))
+        assert tot == -cut
+
+
+@pytest.mark.parametrize("name,n,edges,alpha_g,mc", [
+    ("K5", 5, hp.complete(5), 1, 6),
+    ("star7", 7, hp.star(7), 6, 6),
+    ("C9", 9, hp.cycle(9), 4, 8),
+    ("C8", 8, hp.cycle(8), 4, 8),
+    ("P6", 6, hp.path(6), 3, 5),
+])
+def test_textbook_optima(name, n, edges, alpha_g, mc):
+    """min over {0,1}^n of the relaxed objectives equals -alpha(G) / -maxcut(G)."""
+    assert hp.independence_number(n, edges) == alpha_g
+    assert hp.max_cut(n, edges) == mc
+    lg = make(n, edges)
+    best_mis = best_cut = 1e9
+    for s in range(1 << n):
+        x = np.array([(s >> i) & 1 for i in range(n)], dtype=float)
+        best_mis = min(best_mis, gcn.loss(lg, x, gcn.Spec(problem="mis"))[0])
+        best_cut = min(best_cut, gcn.loss(lg, x, gcn.Spec(problem="maxcut"))[0])
+    assert best_mis == -alpha_g and best_cut == -mc
+
+
+@pytest.mark.parametrize("seed", [0, 1, 2])
+def test_brute_force_random_graphs(seed):
+    rs = np.random.RandomState(seed)
+    n = 11
+    edges = hp.random_graph(n, 0.3, rs)
+    lg = make(n, edges)
+    vals_mis, vals_cut = [], []
+    for s in range(1 << n):
+        x = np.array([(s >> i) & 1 for i in range(n)], dtype=float)
+        vals_mis.append(gcn.loss(lg, x, gcn.Spec(problem="mis"))[0])
+        vals_cut.append(gcn.loss(lg, x, gcn.Spec(problem="maxcut"))[0])
+    assert min(vals_mis) == -hp.independence_number(n, edges)
+    assert min(vals_cut) == -hp.max_cut(n, edges)
+
+
+def test_loss_counts_local_edges_only_and_splits_per_part():
+    rs = np.random.RandomState(8)
+    n, P = 30, 3
+    edges = hp.random_graph(n, 0.25, rs)
+    part = rs.randint(0, P, n)
+    lg = make(n, edges, part, P)
+    p = rs.random(n)
+    tot, per = gcn.loss(lg, p, gcn.Spec(problem="mis"))
+    want = np.zeros(P)
+    for u, v in edges:
+        if part[u] == part[v]:
+            want[part[u]] += 2.0 * p[u] * p[v]
+    for i in range(n):
+        want[part[i]] -= p[i]
+    np.testing.assert_allclose(per, want, rtol=1e-13)
+    assert abs(tot - want.sum()) < 1e-12
+    tot, per = gcn.loss(lg, p, gcn.Spec(problem="maxcut"))
+    want = np.zeros(P)
+    for u, v in edges:
+        if part[u] == part[v]:
+            want[part[u]] += 2 * p[u] * p[v] - p[u] - p[v]
+    np.testing.assert_allclose(per, want, rtol=1e-12, atol=1e-13)
+
+
+# ---------------------------------------------------------------- gradients
+
+def _total_loss(lg, E, Ws, spec, extra=None):
+    return gcn.loss(lg, gcn.forward(lg, E, Ws, spec)["p"], spec, extra)[0]
+
+
+@pytest.mark.parametrize("problem", ["mis", "maxcut"])
+@pytest.mark.parametrize("norm", ["sym", "mean"])
+@pytest.mark.parametrize("L", [1, 2, 3])
+@pytest.mark.parametrize("P,share", [(1, False), (3, False), (3, True)])
+def test_gradients_by_central_differences(problem, norm, L, P, share):
+    rs = np.random.RandomState(100 + 7 * L + P)
+    n, d = 18, 3
+    edges = hp.random_graph(n, 0.25, rs)
+    part = rs.randint(0, P, n)
+    lg = make(n, edges, part, P, norm)
+    spec = gcn.Spec(problem=problem, num_layers=L, norm=norm, weight_sharing=share)
+    E, Ws = rand_params(rs, n, d, L, 1 if share else P)
+    extra = rs.random(n) if problem == "mis" else None
+    cache = gcn.forward(lg, E, Ws, spec)
+    gE, gWs = gcn.backward(lg, cache, Ws, spec, extra)
+    h = 1e-6
+
+    def fd(arr, set_arr):
+        g = np.zeros_like(arr)
+        it = np.nditer(arr, flags=["multi_index"])
+        for _ in it:
+            ix = it.multi_index
+            a = arr.copy(); a[ix] += h
+            b = arr.copy(); b[ix] -= h
+            g[ix] = (set_arr(a) - set_arr(b)) / (2 * h)
+        return g
+
+    fE = fd(E, lambda a: _total_loss(lg, a, Ws, spec, extra))
+    assert np.abs(fE - gE).max() <= 1e-6 * max(1.0, np.abs(gE).max())
+    for l in range(L):
+        def with_w(a, l=l):
+            W2 = list(Ws); W2[l] = a
+            return _total_loss(lg, E, W2, spec, extra)
+        fW = fd(Ws[l], with_w)
+        assert np.abs(fW - gWs[l]).max() <= 1e-6 * max(1.0, np.abs(gWs[l]).max())
+
+
+def test_edgeless_graph_is_a_per_node_mlp():
+    """No edges: A_hat = I, so node i computes p = sigmoid(relu(e W1) w2) alone
+    and dL/dp = -beta.  Gradients written out per node by hand."""
+    rs = np.random.RandomState(4)
+    n, d = 6, 3
+    lg = make(n, [])
+    E, Ws = rand_params(rs, n, d, 2, 1)
+    spec = gcn.Spec(problem="mis", num_layers=2, beta=1.0)
+    cache = gcn.forward(lg, E, Ws, spec)
+    gE, gWs = gcn.backward(lg, cache, Ws, spec)
+    W1, w2 = Ws[0][0], Ws[1][0][:, 0]
+    gW1, gw2, gE_want = np.zeros_like(W1), np.zeros_like(w2), np.zeros_like(E)
+    for i in range(n):
+        a = E[i] @ W1
+        hdn = np.maximum(a, 0)
+        p = 1 / (1 + math.exp(-(hdn @ w2)))
+        assert abs(p - cache["p"][i]) < 1e-14
+        gz = -1.0 * p * (1 - p)
+        gw2 += gz * hdn
+        ga = gz * w2 * (a > 0)
+        gW1 += np.outer(E[i], ga)
+        gE_want[i] = W1 @ ga
+    np.testing.assert_allclose(gWs[1][0][:, 0], gw2, rtol=1e-12)
+    np.testing.assert_allclose(gWs[0][0], gW1, rtol=1e-12, atol=1e-15)
+    np.testing.assert_allclose(gE, gE_want, rtol=1e-12, atol=1e-15)
+
+
+# ---------------------------------------------------------------- Adam
+
+def test_adam_closed_forms():
+    spec = gcn.Spec(lr=0.01)
+    rs = np.random.RandomState(0)
+    th = rs.normal(size=50)
+    g = rs.normal(size=50)
+    g[:5] = 0.0
+    # first step: every entry moves by -lr * g / (|g| + eps)
+    t1, m, v = gcn.adam_update(th, g, np.zeros(50), np.zeros(50), 1, spec)
+    np.testing.assert_allclose(t1 - th, -0.01 * g / (np.abs(g) + 1e-8), rtol=1e-9, atol=1e-18)
+    assert (t1[:5] == th[:5]).all()                       # zero gradient: no move
+    # constant gradient: the bias-corrected ratio stays g/|g|, same step every t
+    cur, steps = t1, []
+    for t in range(2, 30):
+        nxt, m, v = gcn.adam_update(cur, g, m, v, t, spec)
+        steps.append(nxt - cur)
+        cur = nxt
+    for s in steps:
+        np.testing.assert_allclose(s[5:], -0.01 * np.sign(g[5:]), rtol=1e-6)
+    # moments after two different gradients, written out
+    g2 = rs.normal(size=50)
+    _, m1, v1 = gcn.adam_update(th, g, np.zeros(50), np.zeros(50), 1, spec)
+    t2, m2, v2 = gcn.adam_update(th, g2, m1, v1, 2, spec)
+    np.testing.assert_allclose(m2, 0.9 * 0.1 * g + 0.1 * g2, rtol=1e-13)
+    np.testing.assert_allclose(v2, 0.999 * 0.001 * g * g + 0.001 * g2 * g2, rtol=1e-13)
+    mh = m2 / (1 - 0.81)
+    vh = v2 / (1 - 0.999 ** 2)
+    np.testing.assert_allclose(t2, th - 0.01 * mh / (np.sqrt(vh) + 1e-8), rtol=1e-13)
+
+
+# ---------------------------------------------------------------- invariants
+
+@pytest.mark.parametrize("problem", ["mis", "maxcut"])
+def test_batched_training_equals_training_each_subgraph_alone(problem):
+    """Subgraphs are trained without interference: a block-diagonal batch of P
+    subgraphs gives the same parameters as P separate runs, and cut edges have
+    no influence."""
+    rs = np.random.RandomState(11)
+    n, d, P, L = 36, 4, 3, 2
+    edges = hp.random_graph(n, 0.2, rs)
+    part = rs.randint(0, P, n)
+    rowptr, col = hp.csr_from_edges(n, edges)
+    spec = gcn.Spec(problem=problem, num_layers=L)
+    E, Ws = rand_params(rs, n, d, L, P)
+    lg = gcn.local_graph(n, rowptr, col, part, P, "sym")
+    st = gcn.init_state(E, Ws)
+    losses, per = gcn.train(lg, st, spec, 6)
+    for k in range(P):
+        idx = np.flatnonzero(part == k)
+        pos = -np.ones(n, dtype=int)
+        pos[idx] = np.arange(len(idx))
+        sub_edges = [(pos[u], pos[v]) for u, v in edges if part[u] == k and part[v] == k]
+        rp, cl = hp.csr_from_edges(len(idx), sub_edges)
+        lgk = gcn.local_graph(len(idx), rp, cl, None, 1, "sym")
+        stk = gcn.init_state(E[idx], [W[k:k + 1] for W in Ws])
+        lk, _ = gcn.train(lgk, stk, spec, 6)
+        np.testing.assert_allclose(lk, per[:, k], rtol=1e-11, atol=1e-13)
+        np.testing.assert_allclose(stk.E, st.E[idx], rtol=1e-9, atol=1e-12)
+        for l in range(L):
+            np.testing.assert_allclose(stk.Ws[l][0], st.Ws[l][k], rtol=1e-9, atol=1e-12)
+    # removing every cut edge from the input changes nothing
+    loc_edges = [(u, v) for u, v in edges if part[u] == part[v]]
+    rp2, cl2 = hp.csr_from_edges(n, loc_edges)
+    lg2 = gcn.local_graph(n, rp2, cl2, part, P, "sym")
+    st2 = gcn.init_state(E, Ws)
+    l2, _ = gcn.train(lg2, st2, spec, 6)
+    np.testing.assert_array_equal(l2, losses)
+
+
+def test_relabelling_nodes_permutes_probabilities():
+    rs = np.random.RandomState(12)
+    n, d, P, L = 30, 4, 2, 3
+    edges = hp.random_graph(n, 0.2, rs)
+    part = rs.randint(0, P, n)
+    E, Ws = rand_params(rs, n, d, L, P)
+    spec = gcn.Spec(num_layers=L)
+    lg = make(n, edges, part, P)
+    p = gcn.forward(lg, E, Ws, spec)["p"]
+    tot = gcn.loss(lg, p, spec)[0]
+    pi = rs.permutation(n)               # old id -> new id
+    edges2 = [(pi[u], pi[v]) for u, v in edges]
+    part2 = np.empty(n, dtype=int); part2[pi] = part
+    E2 = np.empty_like(E); E2[pi] = E
+    lg2 = make(n, edges2, part2, P)
+    p2 = gcn.forward(lg2, E2, Ws, spec)["p"]
+    np.testing.assert_allclose(p2[pi], p, rtol=1e-12)
+    assert abs(gcn.loss(lg2, p2, spec)[0] - tot) < 1e-10
+
+
+def test_frozen_embeddings_and_shared_weights():
+    rs = np.random.RandomState(13)
+    n, d, P, L = 20, 3, 2, 2
+    edges = hp.random_graph(n, 0.25, rs)
+    part = rs.randint(0, P, n)
+    lg = make(n, edges, part, P)
+    E, Ws = rand_params(rs, n, d, L, 1)
+    spec = gcn.Spec(num_layers=L, weight_sharing=True, train_embed=False)
+    st = gcn.init_state(E, Ws)
+    gcn.train(lg, st, spec, 3)
+    np.testing.assert_array_equal(st.E, E)
+    assert not np.array_equal(st.Ws[0], Ws[0])
+    # shared weights == per-part weights that start equal and receive summed gradients
+    cache = gcn.forward(lg, E, Ws, spec)
+    _, g_sh = gcn.backward(lg, cache, Ws, spec)
+    Wp = [np.repeat(W, P, axis=0) for W in Ws]
+    spec_p = gcn.Spec(num_layers=L)
+    _, g_pp = gcn.backward(lg, gcn.forward(lg, E, Wp, spec_p), Wp, spec_p)
+    for l in range(L):
+        np.testing.assert_allclose(g_sh[l][0], g_pp[l].sum(0), rtol=1e-12, atol=1e-15)
+
+
+def test_training_on_the_small_workload_behaves():
+    """Sanity only (not a pin): the loss falls and ends below zero on the
+    200-node Erdos-Renyi workload."""
+    from paper_2511_09261_amd import inputs
+    wl = inputs.make_workload("c1")
+    g = wl.graph
+    lg = gcn.local_graph(g.n, g.rowptr, g.col, wl.part, 1, "sym")
+    E, Ws = inputs.init_params(g.n, wl.part, 1, wl.num_layers, wl.dim, wl.seed)
+    spec = gcn.Spec(problem="mis", num_layers=2, lr=1e-2)
+    st = gcn.init_state(E, Ws)
+    losses, _ = gcn.train(lg, st, spec, 200)
+    assert losses[-1] < losses[0] and losses[-1] < 0
