@@ -1,0 +1,151 @@
+"""Benchmark of the subgraph-GNN training epoch on one MI355X.
+
+A step is one full-batch training epoch over all subgraphs of the workload
+(forward, loss, backward, Adam).  Inputs are resident in HBM before the timed
+region; upload and preprocessing are timed separately and reported in `extra`.
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c4]
+
+Prints one JSON line with the epochs/s of the whole job, the roofline figure of
+the dominant kernel (algorithmic bytes per launch / its mean duration, measured
+with HIP events on the library's stream inside the timed region) and the fp64
+checker timed on the host cores as a CPU baseline.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0  # MI355X HBM3E, published
+
+
+def cpu_baseline(wl, E, Ws, epochs):
+    """The fp64 checker, unmodified, on the host cores: epochs/s over `epochs`
+    epochs of the same workload."""
+    import numpy as np
+    from oracle import gcn
+    g = wl.graph
+    spec = gcn.Spec(problem=wl.problem, num_layers=wl.num_layers, lr=wl.lr)
+    lg = gcn.local_graph(g.n, g.rowptr, g.col, wl.part, wl.num_parts, "sym")
+    st = gcn.init_state(E, Ws)
+    t0 = time.perf_counter()
+    losses, _ = gcn.train(lg, st, spec, epochs)
+    dt = time.perf_counter() - t0
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        cores = os.cpu_count()
+    return {"value": epochs / dt, "unit": "epochs/s", "cores": int(cores), "kind": "oracle",
+            "sample": f"{epochs} full epochs of the same workload (all {wl.num_parts} subgraphs), fp64 numpy/scipy",
+            "first_loss": float(losses[0])}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="c4")
+    ap.add_argument("--cpu-epochs", type=int, default=2, help="0 disables the CPU baseline")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: every subgraph of the graph is batched on a single "
+              "MI355X and no multi-GPU path exists in this build; run with --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2511_09261_amd import binding, inputs
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    t0 = time.perf_counter()
+    wl = inputs.make_workload(args.workload)
+    desc = inputs.describe(wl)
+    g = wl.graph
+    E, Ws = inputs.init_params(g.n, wl.part, wl.num_parts, wl.num_layers, wl.dim, wl.seed)
+    t_gen = time.perf_counter() - t0
+
+    ctx = binding.Context(problem=wl.problem, num_layers=wl.num_layers, dim=wl.dim,
+                          storage=wl.storage, lr=wl.lr)
+    t0 = time.perf_counter()
+    ctx.upload_graph(g.n, g.rowptr, g.col, wl.part, wl.num_parts)
+    t_upload = time.perf_counter() - t0
+    ctx.set_params(E, Ws)
+
+    # short profiled pass over every kernel: finds the dominant one, gives the breakdown
+    ctx.train(max(1, args.warmup), return_loss=False)
+    ctx.sync()
+    ctx.set_profiling(1)
+    ctx.reset_timing()
+    ctx.train(5, return_loss=False)
+    breakdown = ctx.get_timing()
+    ctx.set_profiling(0)
+    per_epoch = {k: v["total_ms"] / 5 for k, v in breakdown.items() if v["launches"]}
+    dominant = max(per_epoch, key=per_epoch.get)
+
+    # timed region: only the dominant kernel carries events
+    ctx.set_params(E, Ws)
+    ctx.train(args.warmup, return_loss=False)
+    ctx.set_profiling(2, [dominant])
+    ctx.reset_timing()
+    ctx.sync()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    ctx.train(args.steps, return_loss=False)
+    ctx.sync()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    tim = ctx.get_timing()[dominant]
+    ctx.set_profiling(0)
+
+    # read-out steps, timed once each (not part of `value`)
+    t0 = time.perf_counter(); ctx.forward(); p = ctx.get_probs(); t_fwd = time.perf_counter() - t0
+    t0 = time.perf_counter(); x, obj, c_before, c_after = ctx.round_repair(0.5, "local"); t_rr = time.perf_counter() - t0
+    t0 = time.perf_counter(); u, v = ctx.cut_edges(); t_cut = time.perf_counter() - t0
+    info = ctx.graph_info()
+
+    L = wl.num_layers
+    nnz = 2 * info["m_local"]
+    ea_per_epoch = 2 * L * (nnz + g.n) + nnz
+    eps = args.steps / dt
+    avg_ms = tim["total_ms"] / max(1, tim["launches"])
+    achieved = tim["bytes_per_launch"] / (avg_ms * 1e-3) / 1e9 if avg_ms > 0 else 0.0
+    out = {
+        "metric": "GNN train epochs/s (edge-aggregations/s in extra), Youtube-shaped 1.1M-node graph, 1 GPU",
+        "value": eps, "unit": "epochs/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": dt / args.steps * 1e3, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16" if wl.storage == "bf16" else "f32", "data": "synthetic",
+        "config": {"workload": f"{wl.name}: {wl.problem} on a seeded synthetic graph, n={g.n}, m={g.m}, "
+                               f"{wl.num_parts} BFS-grown subgraphs, {L}-layer GCN width {wl.dim}, "
+                               f"{wl.storage} storage, Adam lr {wl.lr}",
+                   "m_local": info["m_local"], "m_cut": info["m_cut"],
+                   "max_local_degree": desc["max_local_degree"],
+                   "locally_isolated": desc["locally_isolated"]},
+        "roofline": {"bound": "hbm", "kernel": dominant, "achieved": achieved, "peak": HBM_PEAK_GBS,
+                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "avg_launch_ms": avg_ms, "algorithmic_bytes_per_launch": tim["bytes_per_launch"],
+                     "launches_timed": tim["launches"]},
+        "extra": {"edge_aggregations_per_s": ea_per_epoch * eps, "edge_aggregations_per_epoch": ea_per_epoch,
+                  "kernel_ms_per_epoch": per_epoch,
+                  "kernel_gbs": {k: (breakdown[k]["bytes_per_launch"] * breakdown[k]["launches"] / 5)
+                                 / (per_epoch[k] * 1e-3) / 1e9 for k in per_epoch if per_epoch[k] > 0},
+                  "generate_s": t_gen, "upload_preprocess_s": t_upload,
+                  "forward_and_read_probs_s": t_fwd, "round_repair_s": t_rr, "cut_edges_s": t_cut,
+                  "set_size_or_cut": obj, "conflicts_before": c_before, "conflicts_after": c_after,
+                  "cut_edges": int(len(u))},
+    }
+    ctx.destroy()
+    if args.cpu_epochs > 0:
+        out["cpu_baseline"] = cpu_baseline(wl, E, Ws, args.cpu_epochs)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,192 @@
+/* gco.h -- C ABI of the subgraph-GNN training library for AMD MI355X (gfx950).
+ *
+ * The library trains, on one GPU, one small graph convolutional network per
+ * subgraph of a partitioned graph, for a relaxed quadratic 0/1 objective
+ * (Maximum Independent Set, Max-Cut), and reads the result out as a 0/1 vector
+ * plus the list of cross-subgraph edges.  It covers stage 1 and stage 2 of the
+ * paper's Algorithm 1 ("Parallel Subgraph Training", "Probability
+ * Reconstruction") and the inputs of stage 3 (conflict edges); all subgraphs of
+ * a graph are trained together as one block-diagonal batch.
+ *
+ * Conventions
+ *  - Every call returns a gco_status; nothing throws or aborts across the ABI.
+ *    gco_last_error() gives the text of the last failure on that context.
+ *  - Pointers are HOST pointers unless the name says "dev".  The caller owns
+ *    every buffer it passes, before and after the call; the library copies.
+ *  - Node-indexed arrays are in the caller's ORIGINAL node order.  (Inside, nodes
+ *    are stored subgraph by subgraph; that order never shows at this boundary.)
+ *  - All device work is enqueued on the stream given at creation; calls that
+ *    return host data wait for that stream only.
+ *  - A context is not thread-safe.  Same inputs give bit-identical outputs from
+ *    run to run (no floating-point atomics are used).
+ */
+#ifndef GCO_H
+#define GCO_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct gco_ctx gco_ctx;
+
+typedef enum {
+  GCO_OK = 0,
+  GCO_EINVAL = -1,  /* bad argument or malformed graph                      */
+  GCO_ENOMEM = -2,  /* device or host allocation failed                     */
+  GCO_ESTATE = -3,  /* call out of order (e.g. train before upload_graph)   */
+  GCO_EDEVICE = -4, /* a HIP call failed                                    */
+  GCO_ERANGE = -5   /* a size is beyond what the library supports           */
+} gco_status;
+
+enum { GCO_PROBLEM_MIS = 0, GCO_PROBLEM_MAXCUT = 1 };
+enum { GCO_NORM_SYM = 0, GCO_NORM_MEAN = 1 };
+enum { GCO_STORAGE_FP32 = 0, GCO_STORAGE_BF16 = 1 };
+enum { GCO_REPAIR_NONE = 0, GCO_REPAIR_LOCAL = 1, GCO_REPAIR_ALL = 2 };
+
+/* Device memory hooks.  alloc returns a device pointer aligned to 256 bytes or
+ * NULL; free receives what alloc returned.  Both NULL => hipMalloc / hipFree. */
+typedef void* (*gco_alloc_fn)(size_t bytes, void* user);
+typedef void (*gco_free_fn)(void* dev_ptr, void* user);
+
+typedef struct {
+  int32_t problem;        /* GCO_PROBLEM_*: which quadratic objective (Alg. 1 input "QUBO Q") */
+  int32_t num_layers;     /* L in {1,2,3}: L-1 hidden ReLU layers of Eq. 3, then a scalar
+                             linear layer feeding the sigmoid of Eq. 4                        */
+  int32_t dim;            /* width of the node embedding and of every hidden layer:
+                             one of 8, 16, 32, 64, 128                                        */
+  int32_t norm;           /* GCO_NORM_MEAN: 1/(|N(i)|+1) as printed in Eq. 3;
+                             GCO_NORM_SYM: 1/sqrt((|N(i)|+1)(|N(j)|+1))                        */
+  int32_t storage;        /* GCO_STORAGE_FP32: all arithmetic and storage in fp32.
+                             GCO_STORAGE_BF16: node features and their gradients are
+                             stored in bf16 and multiplied on the matrix cores with fp32
+                             accumulation; parameters, Adam state, probabilities and the
+                             loss stay fp32 (bf16 needs dim >= 32)                            */
+  int32_t weight_sharing; /* 0: one weight set per subgraph (Alg. 1 stage 1: one net per
+                             subgraph); 1: one set shared by all subgraphs                    */
+  int32_t train_embed;    /* 1: node embeddings are trained; 0: only W (Sec. 3.2 names W only) */
+  float alpha, beta;      /* MIS: L = alpha * sum_{(i,j) in E} p_i p_j - beta * sum_i p_i (Eq. 5);
+                             ignored for Max-Cut                                              */
+  float lr, adam_b1, adam_b2, adam_eps; /* Adam hyper-parameters                              */
+  void* stream;           /* hipStream_t to enqueue on; NULL = the null stream               */
+  gco_alloc_fn dev_alloc; /* may be NULL together with dev_free                              */
+  gco_free_fn dev_free;
+  void* alloc_user;
+} gco_config;
+
+/* Fill *cfg with defaults: MIS, L=2, dim=16, SYM, fp32, per-subgraph weights,
+ * trained embeddings, alpha=2, beta=1, lr=1e-2, Adam (0.9, 0.999, 1e-8). */
+int gco_default_config(gco_config* cfg);
+
+/* Create / destroy a context bound to the current HIP device.  destroy frees
+ * every device buffer the context holds.  EINVAL for an unsupported config. */
+int gco_create(const gco_config* cfg, gco_ctx** out);
+int gco_destroy(gco_ctx* ctx);
+
+/* Text of the last failure on ctx (valid until the next call on ctx). */
+const char* gco_last_error(gco_ctx* ctx);
+
+/* Upload a graph and its subgraph ids (Alg. 1 inputs "Graph G, subgraph set {G_i}").
+ *   n        node count, 1 <= n < 2^31
+ *   rowptr   int64[n+1], rowptr[0] = 0
+ *   col      int32[rowptr[n]]: symmetric CSR of a simple undirected graph: both
+ *            directions present, columns ascending within a row, no self loops,
+ *            no duplicates
+ *   part_id  int32[n] with values in [0, num_parts), or NULL for one subgraph
+ * Builds on the device: the subgraph-contiguous node order, the CSR of local
+ * edges (both ends in one subgraph; only these are trained on, Sec. 3.3), local
+ * degrees and the normalisation of Eq. 3, and keeps the full CSR for the
+ * cross-edge export.  Resets parameters and optimizer state.
+ * EINVAL with a message for a malformed graph; may be called again with a new
+ * graph. */
+int gco_upload_graph(gco_ctx* ctx, int64_t n, const int64_t* rowptr, const int32_t* col,
+                     const int32_t* part_id, int32_t num_parts);
+
+/* Counts: nodes, undirected edges, edges inside subgraphs, edges between them. */
+int gco_graph_info(gco_ctx* ctx, int64_t* n, int64_t* m, int64_t* m_local, int64_t* m_cut);
+
+/* Parameters.  E is float[n * dim], row-major, original node order (the random
+ * initial embeddings of Sec. 3.2).  W points to num_layers host arrays:
+ * W[l-1] is float[Pw * dim * dim] for l < L and float[Pw * dim] for l = L, laid
+ * out [subgraph][d_in][d_out] row-major, Pw = num_parts or 1 if weights are
+ * shared.  set_params also zeroes the optimizer state and the step counter. */
+int gco_set_params(gco_ctx* ctx, const float* E, const float* const* W);
+int gco_get_params(gco_ctx* ctx, float* E, float* const* W);
+
+/* Adam state ("store net/optimizer states", Alg. 1 stage 1): first and second
+ * moments shaped like the parameters, and the step counter t. */
+int gco_get_opt_state(gco_ctx* ctx, float* mE, float* vE, float* const* mW, float* const* vW,
+                      int64_t* step);
+int gco_set_opt_state(gco_ctx* ctx, const float* mE, const float* vE, const float* const* mW,
+                      const float* const* vW, int64_t step);
+
+/* Optional per-node term added to the linear coefficient of the objective:
+ * L += sum_i extra[i] * p_i (the fine-tuning penalty of Sec. 3.3 is lambda on
+ * the listed nodes, 0 elsewhere).  extra = NULL clears it.  float[n]. */
+int gco_set_linear_penalty(gco_ctx* ctx, const float* extra);
+
+/* Run `epochs` full-batch training epochs (Sec. 3.2: forward Eq. 3-4, loss
+ * Eq. 5, back-propagation, parameter update), all subgraphs at once.  If
+ * loss_per_epoch is not NULL it receives double[epochs]: the total loss at the
+ * parameters each epoch started from.  Asynchronous when loss_per_epoch is
+ * NULL (use gco_sync); otherwise returns after the stream has drained. */
+int gco_train(gco_ctx* ctx, int32_t epochs, double* loss_per_epoch);
+
+/* Forward pass at the current parameters (Alg. 1 stage 2: "run forward to get p"). */
+int gco_forward(gco_ctx* ctx);
+/* Probabilities of the last forward / the forward of the last epoch: float[n]. */
+int gco_get_probs(gco_ctx* ctx, float* p);
+/* Forward + loss at the current parameters: total and, if per_part is not NULL,
+ * double[num_parts] per-subgraph values. */
+int gco_loss(gco_ctx* ctx, double* total, double* per_part);
+/* Forward + backward at the current parameters without an update (test hook):
+ * gradients shaped like the parameters. */
+int gco_get_grads(gco_ctx* ctx, float* gE, float* const* gW);
+
+/* Binarise and repair.  x[i] = (p[i] >= thr) on the fp32 probabilities of the
+ * last forward (Sec. 3.3, binarisation at 0.5).  For MIS with repair_scope !=
+ * NONE, selected nodes are then visited in the order (p descending, id
+ * ascending) and a node is kept iff no neighbour over the scope's edges (LOCAL:
+ * inside subgraphs; ALL: every edge) was kept before it.
+ *   x                 uint8[n] out
+ *   objective         out: |S| for MIS after repair; for Max-Cut the number of
+ *                     edges (all edges) whose ends differ
+ *   conflicts_before  out: edges (all edges) with both ends selected, before repair
+ *   conflicts_after   out: the same after repair           (any of the three may be NULL) */
+int gco_round_repair(gco_ctx* ctx, float thr, int32_t repair_scope, uint8_t* x,
+                     int64_t* objective, int64_t* conflicts_before, int64_t* conflicts_after);
+
+/* Cross edges (Sec. 3.3: edges whose ends lie in different subgraphs), as pairs
+ * (u[i], v[i]) with u < v sorted by (u, v).  Two-call pattern: with u = v = NULL
+ * only *count is written; otherwise *count is the capacity of u and v on entry
+ * (ERANGE if too small) and the number written on return. */
+int gco_cut_edges(gco_ctx* ctx, int64_t* count, int32_t* u, int32_t* v);
+/* Cross-node mask (Alg. 1 stage 2, "c"): c[i] = 1 iff node i touches a cross edge. uint8[n]. */
+int gco_cross_mask(gco_ctx* ctx, uint8_t* c);
+/* Conflict edges (Alg. 1 stage 3, first line): the cross edges with x[u] = x[v] = 1,
+ * same order and two-call pattern as gco_cut_edges.  x is uint8[n]. */
+int gco_conflict_edges(gco_ctx* ctx, const uint8_t* x, int64_t* count, int32_t* u, int32_t* v);
+
+/* Wait for the context's stream. */
+int gco_sync(gco_ctx* ctx);
+
+/* Per-kernel timing.  With profiling on, every kernel launch of gco_train /
+ * gco_forward is bracketed by events on the context's stream (this slows the
+ * epoch slightly).  gco_set_profiling(ctx, 2) brackets only the kernel kinds
+ * whose bit is set in kind_mask (bit i = kind i).
+ * gco_get_timing: for kernel kind i in [0, gco_num_kernel_kinds()) returns the
+ * launches counted and their summed duration in ms since the last reset, and
+ * the algorithmic bytes of one launch.  gco_kernel_kind_name gives its name. */
+int gco_set_profiling(gco_ctx* ctx, int32_t mode, uint64_t kind_mask);
+int gco_num_kernel_kinds(void);
+const char* gco_kernel_kind_name(int32_t kind);
+int gco_get_timing(gco_ctx* ctx, int32_t kind, int64_t* launches, double* total_ms,
+                   double* algorithmic_bytes_per_launch);
+int gco_reset_timing(gco_ctx* ctx);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* GCO_H */

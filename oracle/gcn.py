@@ -30,6 +30,19 @@ Readings taken where the paper is open (listed with reasons in the design notes)
     beta2 0.999, eps 1e-8, no weight decay), one network per subgraph unless
     weights are declared shared.
 
+Reduced-precision storage.  Three of the workloads prescribe "bf16 features with
+fp32 accumulate".  With Spec.storage = "bf16" the checker keeps its fp64
+arithmetic but rounds to bfloat16 (8 significant bits, round to nearest even)
+exactly the tensors that such a run stores in bf16: the working copy of the
+embeddings, every hidden activation H_l, and the stored activation gradients.
+With Spec.matrix_core_operands it also rounds the two operands of each hidden
+layer's dense transform (the aggregated rows and W_l), as a bf16 matrix-core
+multiply with fp32 accumulation does.  This matters because ReLU turns a
+floating-point value into a yes/no decision: the device and the checker must
+take that decision on values of the same precision, otherwise a handful of
+units near zero flip and the gradients of whole rows differ by O(1).
+Spec.storage = "exact" (default) rounds nothing.
+
 A library routine is used for two steps only: dense matmul (numpy @) and sparse
 matrix times dense matrix (scipy.sparse CSR @).
 """
@@ -54,6 +67,30 @@ class Spec:
     adam_b1: float = 0.9
     adam_b2: float = 0.999
     adam_eps: float = 1e-8
+    storage: str = "exact"        # "exact" | "bf16" (see the module docstring)
+    matrix_core_operands: bool = False
+
+
+def round_bf16(x):
+    """Round fp64 values to the nearest bfloat16 (ties to even), returned as fp64.
+
+    bfloat16 is the upper half of an IEEE binary32: 1 sign, 8 exponent and 7
+    fraction bits.  The value is first rounded to binary32 (as the device holds
+    it before storing), then its low 16 bits are rounded away."""
+    f = np.asarray(x, dtype=np.float64).astype(np.float32)
+    bits = f.view(np.uint32)
+    lsb = (bits >> np.uint32(16)) & np.uint32(1)
+    with np.errstate(over="ignore"):
+        bits = (bits + np.uint32(0x7FFF) + lsb) & np.uint32(0xFFFF0000)
+    return bits.view(np.float32).astype(np.float64).reshape(np.shape(x))
+
+
+def _stored(x, spec):
+    return round_bf16(x) if spec.storage == "bf16" else x
+
+
+def _operand(x, spec):
+    return round_bf16(x) if (spec.storage == "bf16" and spec.matrix_core_operands) else x
 
 
 @dataclass
@@ -105,14 +142,15 @@ def _apply_weights(lg: LocalGraph, X, W, spec):
 def forward(lg: LocalGraph, E, Ws, spec: Spec) -> dict:
     """Eq. 3 for the hidden layers, then the scalar layer and Eq. 4."""
     L = spec.num_layers
-    H = [np.asarray(E, dtype=np.float64)]
+    H = [_stored(np.asarray(E, dtype=np.float64), spec)]
     Agg, Z = [None], [None]
     for l in range(1, L):
-        agg = lg.A_hat @ H[l - 1]                               # aggregate
-        z = _apply_weights(lg, agg, np.asarray(Ws[l - 1], dtype=np.float64), spec)  # transform
+        agg = _operand(lg.A_hat @ H[l - 1], spec)               # aggregate
+        Wl = _operand(np.asarray(Ws[l - 1], dtype=np.float64), spec)
+        z = _apply_weights(lg, agg, Wl, spec)                   # transform
         Agg.append(agg)
         Z.append(z)
-        H.append(np.maximum(z, 0.0))                            # sigma = ReLU
+        H.append(_stored(np.maximum(z, 0.0), spec))             # sigma = ReLU
     agg = lg.A_hat @ H[L - 1]
     z_out = _apply_weights(lg, agg, np.asarray(Ws[L - 1], dtype=np.float64), spec)[:, 0]
     Agg.append(agg)
@@ -165,6 +203,8 @@ def backward(lg: LocalGraph, cache: dict, Ws, spec: Spec, extra_linear=None):
     g_H = lg.A_hat.T @ g_agg
     for l in range(L - 1, 0, -1):
         g_Z = g_H * (cache["Z"][l] > 0.0)             # ReLU, derivative 0 at 0
+        if l < L - 1:
+            g_Z = _stored(g_Z, spec)                  # kept in memory between two layers
         Wl = np.asarray(Ws[l - 1], dtype=np.float64)
         g_agg = np.zeros_like(cache["Agg"][l])
         for k, idx in enumerate(lg.members):

@@ -1,0 +1,1067 @@
+// Host side of the C ABI declared in include/gco.h: argument checks, device
+// memory, the static work decomposition, and the order of kernel launches that
+// makes one training epoch (Sec. 3.2 of the paper) and the read-out steps
+// (Sec. 3.3; Alg. 1 stages 2 and 3, first line).
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <limits>
+#include <string>
+#include <vector>
+
+#include "gco.h"
+#include "gco_internal.h"
+#include "graph_kernels.h"
+
+using namespace gco;
+
+namespace {
+
+const char* const kKindNames[KK_COUNT] = {
+    "fwd_hidden", "fwd_gemv", "fwd_readout", "loss", "bwd_readout",
+    "bwd_hidden", "bwd_embed_adam", "adam_w", "loss_reduce", "heavy_rows"};
+
+struct EventPair {
+  hipEvent_t a, b;
+};
+
+struct ProfilerImpl : Profiler {
+  int mode = 0;
+  uint64_t mask = ~0ull;
+  std::vector<EventPair> pending[KK_COUNT];
+  std::vector<EventPair> spare;
+  int64_t launches[KK_COUNT] = {};
+  double total_ms[KK_COUNT] = {};
+  bool on(int kind) const { return mode == 1 || (mode == 2 && ((mask >> kind) & 1ull)); }
+  void begin(int kind, hipStream_t st) override {
+    if (!on(kind)) return;
+    EventPair ev;
+    if (!spare.empty()) {
+      ev = spare.back();
+      spare.pop_back();
+    } else {
+      if (hipEventCreate(&ev.a) != hipSuccess || hipEventCreate(&ev.b) != hipSuccess) return;
+    }
+    (void)hipEventRecord(ev.a, st);
+    pending[kind].push_back(ev);
+  }
+  void end(int kind, hipStream_t st) override {
+    if (!on(kind) || pending[kind].empty()) return;
+    (void)hipEventRecord(pending[kind].back().b, st);
+  }
+  void harvest() {  // the stream must be idle
+    for (int k = 0; k < KK_COUNT; ++k) {
+      for (EventPair& ev : pending[k]) {
+        float ms = 0.f;
+        if (hipEventElapsedTime(&ms, ev.a, ev.b) == hipSuccess) {
+          total_ms[k] += ms;
+          launches[k] += 1;
+        }
+        spare.push_back(ev);
+      }
+      pending[k].clear();
+    }
+  }
+  void reset() {
+    harvest();
+    for (int k = 0; k < KK_COUNT; ++k) {
+      launches[k] = 0;
+      total_ms[k] = 0.0;
+    }
+  }
+  ~ProfilerImpl() override {
+    for (int k = 0; k < KK_COUNT; ++k)
+      for (EventPair& ev : pending[k]) spare.push_back(ev);
+    for (EventPair& ev : spare) {
+      (void)hipEventDestroy(ev.a);
+      (void)hipEventDestroy(ev.b);
+    }
+  }
+};
+
+}  // namespace
+
+struct gco_ctx {
+  gco_config cfg{};
+  hipStream_t st = nullptr;
+  std::string err;
+  ProfilerImpl prof;
+
+  // ---- graph ----
+  bool has_graph = false;
+  int n = 0, P = 1, Pw = 1;
+  int64_t nnz_full = 0, nnz_loc = 0;
+  int64_t* d_rowptr = nullptr;  // original order, full graph
+  int32_t* d_col = nullptr;
+  int32_t* d_part = nullptr;
+  int32_t* d_perm = nullptr;    // new row -> original node
+  int32_t* d_inv = nullptr;     // original node -> new row
+  int32_t* d_lrowptr = nullptr; // local CSR, new order
+  int32_t* d_lcol = nullptr;
+  float *d_sa = nullptr, *d_sb = nullptr, *d_cbase = nullptr, *d_c = nullptr;
+  int32_t* d_part_rows = nullptr;
+  int32_t *d_blk_k = nullptr, *d_blk_s = nullptr, *d_nblk_k = nullptr, *d_nblk_s = nullptr;
+  int32_t *d_pbl_ptr = nullptr, *d_pbl_list = nullptr;
+  int32_t *d_heavy_of_row = nullptr, *d_heavy_chunk_ptr = nullptr, *d_chunk_begin = nullptr,
+          *d_chunk_end = nullptr, *d_chunk_part = nullptr;
+  float* d_heavy_partial = nullptr;
+  GraphView gv;
+  std::vector<void*> graph_allocs;
+
+  // ---- parameters and activations (new order) ----
+  bool has_params = false;
+  bool probs_valid = false;
+  int64_t step = 0;
+  float *E = nullptr, *mE = nullptr, *vE = nullptr;
+  void* Eb = nullptr;
+  float *W[3] = {}, *mW[3] = {}, *vW[3] = {};
+  float* gW_partial[3] = {};  // [l-1] for hidden layers; the scalar layer uses gwout_partial
+  float* gwout_partial = nullptr;
+  void* H[3] = {};            // H[0] aliases the embedding in storage type
+  void* GZ[3] = {};
+  float *t = nullptr, *z = nullptr, *p = nullptr, *g_z = nullptr, *g_t = nullptr;
+  double *loss_partial = nullptr, *loss_part = nullptr, *loss_hist = nullptr, *loss_one = nullptr;
+  int64_t loss_hist_cap = 0;
+
+  double kind_bytes[KK_COUNT] = {};
+
+  int fail(int code, const char* fmt, ...) {
+    char buf[512];
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(buf, sizeof buf, fmt, ap);
+    va_end(ap);
+    err = buf;
+    return code;
+  }
+
+  void* raw_alloc(size_t bytes) {
+    if (bytes == 0) bytes = 256;
+    if (cfg.dev_alloc) return cfg.dev_alloc(bytes, cfg.alloc_user);
+    void* ptr = nullptr;
+    if (hipMalloc(&ptr, bytes) != hipSuccess) {
+      (void)hipGetLastError();
+      return nullptr;
+    }
+    return ptr;
+  }
+  void raw_free(void* ptr) {
+    if (!ptr) return;
+    if (cfg.dev_free) cfg.dev_free(ptr, cfg.alloc_user);
+    else (void)hipFree(ptr);
+  }
+  template <typename T>
+  bool galloc(T** out, size_t count) {
+    void* ptr = raw_alloc(count * sizeof(T));
+    if (!ptr) return false;
+    graph_allocs.push_back(ptr);
+    *out = static_cast<T*>(ptr);
+    return true;
+  }
+  void free_graph() {
+    (void)hipStreamSynchronize(st);
+    prof.harvest();
+    for (void* q : graph_allocs) raw_free(q);
+    graph_allocs.clear();
+    has_graph = has_params = probs_valid = false;
+    loss_hist_cap = 0;
+    loss_hist = nullptr;
+  }
+  int elem_bytes() const { return cfg.storage == GCO_STORAGE_BF16 ? 2 : 4; }
+  Launch launch() { return Launch{st, prof.mode ? &prof : nullptr}; }
+};
+
+#define HIPCHK(expr)                                                                   \
+  do {                                                                                 \
+    hipError_t e_ = (expr);                                                            \
+    if (e_ != hipSuccess)                                                              \
+      return ctx->fail(GCO_EDEVICE, "%s failed: %s", #expr, hipGetErrorString(e_));    \
+  } while (0)
+
+#define NEED(cond, code, ...) \
+  do {                        \
+    if (!(cond)) return ctx->fail(code, __VA_ARGS__); \
+  } while (0)
+
+#define GALLOC(ptr, count)                                                              \
+  do {                                                                                  \
+    if (!ctx->galloc(&(ptr), (count)))                                                  \
+      return ctx->fail(GCO_ENOMEM, "device allocation of %zu bytes failed (%s)",        \
+                       static_cast<size_t>(count) * sizeof(*(ptr)), #ptr);              \
+  } while (0)
+
+namespace {
+
+// RAII for short-lived device scratch of one call.
+struct Scratch {
+  gco_ctx* ctx;
+  std::vector<void*> ptrs;
+  explicit Scratch(gco_ctx* c) : ctx(c) {}
+  template <typename T>
+  T* get(size_t count) {
+    void* q = ctx->raw_alloc(count * sizeof(T));
+    if (q) ptrs.push_back(q);
+    return static_cast<T*>(q);
+  }
+  ~Scratch() {
+    (void)hipStreamSynchronize(ctx->st);
+    for (void* q : ptrs) ctx->raw_free(q);
+  }
+};
+
+template <typename T>
+hipError_t h2d(gco_ctx* ctx, T* dst, const T* src, size_t count) {
+  if (count == 0) return hipSuccess;
+  hipError_t e = hipMemcpyAsync(dst, src, count * sizeof(T), hipMemcpyHostToDevice, ctx->st);
+  if (e != hipSuccess) return e;
+  return hipStreamSynchronize(ctx->st);  // the host buffer belongs to the caller again on return
+}
+template <typename T>
+hipError_t d2h(gco_ctx* ctx, T* dst, const T* src, size_t count) {
+  if (count == 0) return hipStreamSynchronize(ctx->st);
+  hipError_t e = hipMemcpyAsync(dst, src, count * sizeof(T), hipMemcpyDeviceToHost, ctx->st);
+  if (e != hipSuccess) return e;
+  return hipStreamSynchronize(ctx->st);
+}
+
+int w_elems(const gco_ctx* ctx, int l /*1..L*/) {
+  const int D = ctx->cfg.dim;
+  return l < ctx->cfg.num_layers ? D * D : D;
+}
+
+// Workgroup -> (subgraph, first tile) tables.  With at least 8 subgraphs the
+// workgroups of one subgraph are given ids that are equal modulo 8, so that
+// they land on one XCD and share its L2 (workgroups are dealt to the 8 XCDs
+// round-robin by id).
+void build_block_map(int P, const std::vector<int>& part_rows, int tile_rows, int target_blocks,
+                     std::vector<int>& blk_k, std::vector<int>& blk_s, int& S) {
+  int max_tiles = 1;
+  for (int k = 0; k < P; ++k)
+    max_tiles = std::max(max_tiles, (part_rows[k + 1] - part_rows[k] + tile_rows - 1) / tile_rows);
+  S = std::max(1, std::min(max_tiles, (target_blocks + P - 1) / P));
+  blk_k.clear();
+  blk_s.clear();
+  if (P >= 8) {
+    const int groups = (P + 7) / 8;
+    const int nb = groups * S * 8;
+    blk_k.assign(nb, -1);
+    blk_s.assign(nb, 0);
+    for (int b = 0; b < nb; ++b) {
+      const int xcd = b % 8, q = b / 8;
+      const int k = (q / S) * 8 + xcd;
+      if (k < P) {
+        blk_k[b] = k;
+        blk_s[b] = q % S;
+      }
+    }
+  } else {
+    for (int k = 0; k < P; ++k)
+      for (int s = 0; s < S; ++s) {
+        blk_k.push_back(k);
+        blk_s.push_back(s);
+      }
+  }
+}
+
+void traffic_model(gco_ctx* ctx) {
+  const double n = ctx->n, nnz = static_cast<double>(ctx->nnz_loc), D = ctx->cfg.dim;
+  const double s = ctx->elem_bytes(), Pw = ctx->Pw, NB = ctx->gv.num_blocks;
+  const int L = ctx->cfg.num_layers;
+  const double idx = nnz * 4 + (n + 1) * 4, scales = 2 * n * 4;
+  double* kb = ctx->kind_bytes;
+  for (int k = 0; k < KK_COUNT; ++k) kb[k] = 0;
+  // hidden forward: X read + Y write + W (+ t and w_out on the last hidden layer; averaged)
+  if (L >= 2) {
+    const double base = idx + scales + 2 * n * D * s + Pw * D * D * 4;
+    kb[KK_FWD_HIDDEN] = base + (n * 4 + Pw * D * 4) / (L - 1);
+  }
+  kb[KK_FWD_GEMV] = n * D * s + Pw * D * 4 + n * 4;
+  kb[KK_FWD_READOUT] = idx + scales + 3 * n * 4;
+  kb[KK_LOSS] = idx + 3 * n * 4;
+  kb[KK_BWD_READOUT] = idx + scales + 2 * n * 4;
+  const double wpart = Pw * D * D * 4 + NB * D * D * 4;
+  // gathered gradient source + Hprev read + GZ write
+  kb[KK_BWD_HIDDEN] = idx + scales + 3 * n * D * s + wpart + (L == 3 ? n * 4 + NB * D * 4 : 0);
+  // first layer: gathered source + embedding (working copy) read + Adam state in/out
+  const double adam_e = ctx->cfg.train_embed ? (6 * n * D * 4 + (s == 2 ? n * D * 2 : 0)) : 0;
+  const double hprev_read = (s == 2 || !ctx->cfg.train_embed) ? n * D * s : 0;  // fp32: E is read by Adam already
+  if (L >= 2)
+    kb[KK_BWD_EMBED] = idx + scales + n * D * s + hprev_read + wpart + adam_e + (L == 2 ? n * 4 + NB * D * 4 : 0);
+  else
+    kb[KK_BWD_EMBED] = n * 4 + hprev_read + adam_e + NB * D * 4;
+  double wtot = 0;
+  for (int l = 1; l <= L; ++l) {
+    const double e = l < L ? D * D : D;
+    wtot += Pw * e * 24 + NB * e * 4;
+  }
+  kb[KK_ADAM_W] = wtot / L;
+  kb[KK_LOSS_REDUCE] = ctx->gv.num_nblocks * 8.0 + ctx->P * 8.0;
+  kb[KK_HEAVY] = 0;  // reported by time only
+}
+
+}  // namespace
+
+// =============================================================================
+// C ABI
+// =============================================================================
+extern "C" {
+
+int gco_default_config(gco_config* cfg) {
+  if (!cfg) return GCO_EINVAL;
+  std::memset(cfg, 0, sizeof *cfg);
+  cfg->problem = GCO_PROBLEM_MIS;
+  cfg->num_layers = 2;
+  cfg->dim = 16;
+  cfg->norm = GCO_NORM_SYM;
+  cfg->storage = GCO_STORAGE_FP32;
+  cfg->weight_sharing = 0;
+  cfg->train_embed = 1;
+  cfg->alpha = 2.f;
+  cfg->beta = 1.f;
+  cfg->lr = 1e-2f;
+  cfg->adam_b1 = 0.9f;
+  cfg->adam_b2 = 0.999f;
+  cfg->adam_eps = 1e-8f;
+  return GCO_OK;
+}
+
+int gco_create(const gco_config* cfg, gco_ctx** out) {
+  if (!cfg || !out) return GCO_EINVAL;
+  *out = nullptr;
+  const int D = cfg->dim;
+  const bool dim_ok = D == 8 || D == 16 || D == 32 || D == 64 || D == 128;
+  if (!dim_ok || cfg->num_layers < 1 || cfg->num_layers > 3) return GCO_EINVAL;
+  if (cfg->problem != GCO_PROBLEM_MIS && cfg->problem != GCO_PROBLEM_MAXCUT) return GCO_EINVAL;
+  if (cfg->norm != GCO_NORM_SYM && cfg->norm != GCO_NORM_MEAN) return GCO_EINVAL;
+  if (cfg->storage != GCO_STORAGE_FP32 && cfg->storage != GCO_STORAGE_BF16) return GCO_EINVAL;
+  if (cfg->storage == GCO_STORAGE_BF16 && D < 32) return GCO_EINVAL;
+  if ((cfg->dev_alloc == nullptr) != (cfg->dev_free == nullptr)) return GCO_EINVAL;
+  if (!(cfg->lr > 0.f) || !(cfg->adam_b1 >= 0.f && cfg->adam_b1 < 1.f) ||
+      !(cfg->adam_b2 >= 0.f && cfg->adam_b2 < 1.f) || !(cfg->adam_eps > 0.f))
+    return GCO_EINVAL;
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess) {
+    (void)hipGetLastError();
+    return GCO_EDEVICE;
+  }
+  gco_ctx* ctx = new (std::nothrow) gco_ctx();
+  if (!ctx) return GCO_ENOMEM;
+  ctx->cfg = *cfg;
+  ctx->st = static_cast<hipStream_t>(cfg->stream);
+  *out = ctx;
+  return GCO_OK;
+}
+
+int gco_destroy(gco_ctx* ctx) {
+  if (!ctx) return GCO_EINVAL;
+  ctx->free_graph();
+  delete ctx;
+  return GCO_OK;
+}
+
+const char* gco_last_error(gco_ctx* ctx) { return ctx ? ctx->err.c_str() : "null context"; }
+
+int gco_sync(gco_ctx* ctx) {
+  if (!ctx) return GCO_EINVAL;
+  HIPCHK(hipStreamSynchronize(ctx->st));
+  return GCO_OK;
+}
+
+int gco_upload_graph(gco_ctx* ctx, int64_t n64, const int64_t* rowptr, const int32_t* col,
+                     const int32_t* part_id, int32_t num_parts) {
+  if (!ctx) return GCO_EINVAL;
+  NEED(rowptr != nullptr, GCO_EINVAL, "rowptr is NULL");
+  NEED(n64 >= 1 && n64 < std::numeric_limits<int32_t>::max(), GCO_ERANGE, "n = %lld out of range",
+       static_cast<long long>(n64));
+  const int n = static_cast<int>(n64);
+  if (!part_id) num_parts = 1;
+  NEED(num_parts >= 1 && num_parts <= n, GCO_EINVAL, "num_parts = %d not in [1, n]", num_parts);
+  NEED(rowptr[0] == 0, GCO_EINVAL, "rowptr[0] != 0");
+  for (int i = 0; i < n; ++i)
+    NEED(rowptr[i + 1] >= rowptr[i], GCO_EINVAL, "rowptr decreases at row %d", i);
+  const int64_t nnz = rowptr[n];
+  NEED(nnz == 0 || col != nullptr, GCO_EINVAL, "col is NULL");
+  NEED(nnz % 2 == 0, GCO_EINVAL, "odd number of CSR entries: not a symmetric graph");
+  const int P = num_parts;
+  std::vector<int> part_rows(P + 1, 0);
+  if (part_id) {
+    for (int i = 0; i < n; ++i) {
+      NEED(part_id[i] >= 0 && part_id[i] < P, GCO_EINVAL, "part_id[%d] = %d not in [0, %d)", i,
+           part_id[i], P);
+      part_rows[part_id[i] + 1]++;
+    }
+  } else {
+    part_rows[1] = n;
+  }
+  for (int k = 0; k < P; ++k) part_rows[k + 1] += part_rows[k];
+
+  ctx->free_graph();
+  ctx->n = n;
+  ctx->P = P;
+  ctx->Pw = ctx->cfg.weight_sharing ? 1 : P;
+  ctx->nnz_full = nnz;
+  const int D = ctx->cfg.dim;
+  const int L = ctx->cfg.num_layers;
+  hipStream_t st = ctx->st;
+
+  // stable counting sort by subgraph id: perm (new -> original), inv (original -> new)
+  std::vector<int32_t> perm(n), inv(n);
+  {
+    std::vector<int> cursor(part_rows.begin(), part_rows.end() - 1);
+    for (int i = 0; i < n; ++i) {
+      const int k = part_id ? part_id[i] : 0;
+      const int r = cursor[k]++;
+      perm[r] = i;
+      inv[i] = r;
+    }
+  }
+
+  GALLOC(ctx->d_rowptr, static_cast<size_t>(n) + 1);
+  GALLOC(ctx->d_col, static_cast<size_t>(nnz));
+  GALLOC(ctx->d_part, static_cast<size_t>(n));
+  GALLOC(ctx->d_perm, static_cast<size_t>(n));
+  GALLOC(ctx->d_inv, static_cast<size_t>(n));
+  GALLOC(ctx->d_part_rows, static_cast<size_t>(P) + 1);
+  HIPCHK(h2d(ctx, ctx->d_rowptr, rowptr, static_cast<size_t>(n) + 1));
+  HIPCHK(h2d(ctx, ctx->d_col, col, static_cast<size_t>(nnz)));
+  if (part_id) {
+    HIPCHK(h2d(ctx, ctx->d_part, part_id, static_cast<size_t>(n)));
+  } else {
+    launch_fill_u32(st, ctx->d_part, n, 0u);
+  }
+  HIPCHK(h2d(ctx, ctx->d_perm, perm.data(), perm.size()));
+  HIPCHK(h2d(ctx, ctx->d_inv, inv.data(), inv.size()));
+  HIPCHK(h2d(ctx, ctx->d_part_rows, part_rows.data(), part_rows.size()));
+
+  std::vector<int32_t> lrowptr(static_cast<size_t>(n) + 1);
+  {
+    Scratch tmp(ctx);
+    int* d_err = tmp.get<int>(1);
+    int64_t* d_count = tmp.get<int64_t>(static_cast<size_t>(n) + 1);
+    int64_t* d_lptr64 = tmp.get<int64_t>(static_cast<size_t>(n) + 1);
+    int64_t* d_scan = tmp.get<int64_t>(scan_temp_elems(static_cast<int64_t>(n) + 1));
+    NEED(d_err && d_count && d_lptr64 && d_scan, GCO_ENOMEM, "device scratch allocation failed");
+    launch_fill_u32(st, d_err, 1, 0u);
+    launch_check_graph(st, n, ctx->d_rowptr, ctx->d_col, nnz, d_err);
+    int err = 0;
+    HIPCHK(d2h(ctx, &err, d_err, 1));
+    static const char* const kWhy[] = {"", "a column index is out of range", "self loop",
+                                       "columns of a row are not strictly ascending",
+                                       "an edge is stored in one direction only"};
+    NEED(err == 0, GCO_EINVAL, "malformed graph: %s", kWhy[err < 5 ? err : 0]);
+
+    launch_fill_u32(st, d_count + n, 2, 0u);  // count[n] = 0
+    launch_local_count(st, n, ctx->d_rowptr, ctx->d_col, ctx->d_part, ctx->d_perm, d_count);
+    exclusive_scan_i64(st, d_count, d_lptr64, static_cast<int64_t>(n) + 1, d_scan);
+    int64_t nnz_loc = 0;
+    HIPCHK(d2h(ctx, &nnz_loc, d_lptr64 + n, 1));
+    NEED(nnz_loc < std::numeric_limits<int32_t>::max(), GCO_ERANGE,
+         "more than 2^31 local CSR entries");
+    ctx->nnz_loc = nnz_loc;
+    GALLOC(ctx->d_lrowptr, static_cast<size_t>(n) + 1);
+    GALLOC(ctx->d_lcol, static_cast<size_t>(nnz_loc));
+    launch_local_fill(st, n, ctx->d_rowptr, ctx->d_col, ctx->d_part, ctx->d_perm, ctx->d_inv,
+                      d_lptr64, ctx->d_lrowptr, ctx->d_lcol);
+    HIPCHK(d2h(ctx, lrowptr.data(), ctx->d_lrowptr, lrowptr.size()));
+  }
+
+  GALLOC(ctx->d_sa, static_cast<size_t>(n));
+  GALLOC(ctx->d_sb, static_cast<size_t>(n));
+  GALLOC(ctx->d_cbase, static_cast<size_t>(n));
+  GALLOC(ctx->d_c, static_cast<size_t>(n));
+  launch_scales(st, n, ctx->d_lrowptr, ctx->cfg.norm, ctx->cfg.problem, ctx->cfg.beta, ctx->d_sa,
+                ctx->d_sb, ctx->d_cbase);
+  launch_linear_coeff(st, n, ctx->d_cbase, nullptr, ctx->d_perm, ctx->d_c);
+
+  // work decomposition
+  std::vector<int> blk_k, blk_s, nblk_k, nblk_s;
+  int S = 1, nS = 1;
+  build_block_map(P, part_rows, kTileRows, 1024, blk_k, blk_s, S);
+  build_block_map(P, part_rows, kNarrowRows, 1024, nblk_k, nblk_s, nS);
+  GALLOC(ctx->d_blk_k, blk_k.size());
+  GALLOC(ctx->d_blk_s, blk_s.size());
+  GALLOC(ctx->d_nblk_k, nblk_k.size());
+  GALLOC(ctx->d_nblk_s, nblk_s.size());
+  HIPCHK(h2d(ctx, ctx->d_blk_k, blk_k.data(), blk_k.size()));
+  HIPCHK(h2d(ctx, ctx->d_blk_s, blk_s.data(), blk_s.size()));
+  HIPCHK(h2d(ctx, ctx->d_nblk_k, nblk_k.data(), nblk_k.size()));
+  HIPCHK(h2d(ctx, ctx->d_nblk_s, nblk_s.data(), nblk_s.size()));
+  // workgroups whose weight-gradient partials belong to weight set kw
+  {
+    const int Pw = ctx->Pw;
+    std::vector<int> ptr(Pw + 1, 0), list;
+    for (int kw = 0; kw < Pw; ++kw) {
+      for (size_t b = 0; b < blk_k.size(); ++b)
+        if (blk_k[b] >= 0 && (Pw == 1 || blk_k[b] == kw)) list.push_back(static_cast<int>(b));
+      ptr[kw + 1] = static_cast<int>(list.size());
+    }
+    GALLOC(ctx->d_pbl_ptr, ptr.size());
+    GALLOC(ctx->d_pbl_list, std::max<size_t>(1, list.size()));
+    HIPCHK(h2d(ctx, ctx->d_pbl_ptr, ptr.data(), ptr.size()));
+    HIPCHK(h2d(ctx, ctx->d_pbl_list, list.data(), list.size()));
+  }
+  // very long rows
+  std::vector<int> heavy_of_row, heavy_chunk_ptr(1, 0), chunk_begin, chunk_end, chunk_part;
+  int num_heavy = 0;
+  {
+    int k = 0;
+    for (int r = 0; r < n; ++r) {
+      while (r >= part_rows[k + 1]) ++k;
+      const int deg = lrowptr[r + 1] - lrowptr[r];
+      if (deg >= kHeavyMin) {
+        if (heavy_of_row.empty()) heavy_of_row.assign(n, -1);
+        heavy_of_row[r] = num_heavy++;
+        for (int e = lrowptr[r]; e < lrowptr[r + 1]; e += kChunk) {
+          chunk_begin.push_back(e);
+          chunk_end.push_back(std::min(e + kChunk, lrowptr[r + 1]));
+          chunk_part.push_back(k);
+        }
+        heavy_chunk_ptr.push_back(static_cast<int>(chunk_begin.size()));
+      }
+    }
+  }
+  const int num_chunks = static_cast<int>(chunk_begin.size());
+  if (num_heavy > 0) {
+    GALLOC(ctx->d_heavy_of_row, static_cast<size_t>(n));
+    GALLOC(ctx->d_heavy_chunk_ptr, heavy_chunk_ptr.size());
+    GALLOC(ctx->d_chunk_begin, chunk_begin.size());
+    GALLOC(ctx->d_chunk_end, chunk_end.size());
+    GALLOC(ctx->d_chunk_part, chunk_part.size());
+    GALLOC(ctx->d_heavy_partial, static_cast<size_t>(num_chunks) * D);
+    HIPCHK(h2d(ctx, ctx->d_heavy_of_row, heavy_of_row.data(), heavy_of_row.size()));
+    HIPCHK(h2d(ctx, ctx->d_heavy_chunk_ptr, heavy_chunk_ptr.data(), heavy_chunk_ptr.size()));
+    HIPCHK(h2d(ctx, ctx->d_chunk_begin, chunk_begin.data(), chunk_begin.size()));
+    HIPCHK(h2d(ctx, ctx->d_chunk_end, chunk_end.data(), chunk_end.size()));
+    HIPCHK(h2d(ctx, ctx->d_chunk_part, chunk_part.data(), chunk_part.size()));
+  }
+
+  GraphView& g = ctx->gv;
+  g = GraphView{};
+  g.n = n;
+  g.P = P;
+  g.rowptr = ctx->d_lrowptr;
+  g.col = ctx->d_lcol;
+  g.sa = ctx->d_sa;
+  g.sb = ctx->d_sb;
+  g.part_rows = ctx->d_part_rows;
+  g.blk_k = ctx->d_blk_k;
+  g.blk_s = ctx->d_blk_s;
+  g.S = S;
+  g.num_blocks = static_cast<int>(blk_k.size());
+  g.nblk_k = ctx->d_nblk_k;
+  g.nblk_s = ctx->d_nblk_s;
+  g.nS = nS;
+  g.num_nblocks = static_cast<int>(nblk_k.size());
+  g.num_heavy = num_heavy;
+  g.num_chunks = num_chunks;
+  g.heavy_of_row = ctx->d_heavy_of_row;
+  g.heavy_chunk_ptr = ctx->d_heavy_chunk_ptr;
+  g.chunk_begin = ctx->d_chunk_begin;
+  g.chunk_end = ctx->d_chunk_end;
+  g.chunk_part = ctx->d_chunk_part;
+
+  // parameters, optimizer state, activations
+  const size_t nd = static_cast<size_t>(n) * D;
+  const int eb = ctx->elem_bytes();
+  GALLOC(ctx->E, nd);
+  GALLOC(ctx->mE, nd);
+  GALLOC(ctx->vE, nd);
+  if (eb == 2) {
+    uint16_t* q = nullptr;
+    GALLOC(q, nd);
+    ctx->Eb = q;
+    ctx->H[0] = q;
+  } else {
+    ctx->Eb = nullptr;
+    ctx->H[0] = ctx->E;
+  }
+  for (int l = 1; l <= L; ++l) {
+    const size_t cnt = static_cast<size_t>(ctx->Pw) * w_elems(ctx, l);
+    GALLOC(ctx->W[l - 1], cnt);
+    GALLOC(ctx->mW[l - 1], cnt);
+    GALLOC(ctx->vW[l - 1], cnt);
+  }
+  for (int l = 1; l <= L - 1; ++l) {
+    uint8_t* q = nullptr;
+    GALLOC(q, nd * eb);
+    ctx->H[l] = q;
+    GALLOC(ctx->gW_partial[l - 1], static_cast<size_t>(g.num_blocks) * D * D);
+  }
+  for (int l = 1; l <= L - 2; ++l) {
+    uint8_t* q = nullptr;
+    GALLOC(q, nd * eb);
+    ctx->GZ[l] = q;
+  }
+  GALLOC(ctx->gwout_partial, static_cast<size_t>(g.num_blocks) * D);
+  GALLOC(ctx->t, static_cast<size_t>(n));
+  GALLOC(ctx->z, static_cast<size_t>(n));
+  GALLOC(ctx->p, static_cast<size_t>(n));
+  GALLOC(ctx->g_z, static_cast<size_t>(n));
+  GALLOC(ctx->g_t, static_cast<size_t>(n));
+  GALLOC(ctx->loss_partial, static_cast<size_t>(g.num_nblocks));
+  GALLOC(ctx->loss_part, static_cast<size_t>(P));
+  GALLOC(ctx->loss_one, 1);
+  HIPCHK(hipStreamSynchronize(st));
+  traffic_model(ctx);
+  ctx->has_graph = true;
+  ctx->step = 0;
+  return GCO_OK;
+}
+
+int gco_graph_info(gco_ctx* ctx, int64_t* n, int64_t* m, int64_t* m_local, int64_t* m_cut) {
+  if (!ctx) return GCO_EINVAL;
+  NEED(ctx->has_graph, GCO_ESTATE, "no graph uploaded");
+  if (n) *n = ctx->n;
+  if (m) *m = ctx->nnz_full / 2;
+  if (m_local) *m_local = ctx->nnz_loc / 2;
+  if (m_cut) *m_cut = (ctx->nnz_full - ctx->nnz_loc) / 2;
+  return GCO_OK;
+}
+
+// ---- parameter transfer -------------------------------------------------------
+
+static int upload_node_matrix(gco_ctx* ctx, const float* host_orig, float* dev_new) {
+  const size_t nd = static_cast<size_t>(ctx->n) * ctx->cfg.dim;
+  Scratch tmp(ctx);
+  float* stage = tmp.get<float>(nd);
+  NEED(stage, GCO_ENOMEM, "device scratch allocation failed");
+  HIPCHK(h2d(ctx, stage, host_orig, nd));
+  launch_gather_rows(ctx->st, ctx->n, ctx->cfg.dim, stage, ctx->d_perm, dev_new);
+  return GCO_OK;
+}
+
+static int download_node_matrix(gco_ctx* ctx, float* host_orig, const float* dev_new) {
+  const size_t nd = static_cast<size_t>(ctx->n) * ctx->cfg.dim;
+  Scratch tmp(ctx);
+  float* stage = tmp.get<float>(nd);
+  NEED(stage, GCO_ENOMEM, "device scratch allocation failed");
+  launch_gather_rows(ctx->st, ctx->n, ctx->cfg.dim, dev_new, ctx->d_inv, stage);
+  HIPCHK(d2h(ctx, host_orig, stage, nd));
+  return GCO_OK;
+}
+
+int gco_set_params(gco_ctx* ctx, const float* E, const float* const* W) {
+  if (!ctx) return GCO_EINVAL;
+  NEED(ctx->has_graph, GCO_ESTATE, "no graph uploaded");
+  NEED(E && W, GCO_EINVAL, "NULL parameter pointer");
+  const int L = ctx->cfg.num_layers;
+  for (int l = 1; l <= L; ++l) NEED(W[l - 1], GCO_EINVAL, "W[%d] is NULL", l - 1);
+  const size_t nd = static_cast<size_t>(ctx->n) * ctx->cfg.dim;
+  int rc = upload_node_matrix(ctx, E, ctx->E);
+  if (rc != GCO_OK) return rc;
+  HIPCHK(hipMemsetAsync(ctx->mE, 0, nd * sizeof(float), ctx->st));
+  HIPCHK(hipMemsetAsync(ctx->vE, 0, nd * sizeof(float), ctx->st));
+  for (int l = 1; l <= L; ++l) {
+    const size_t cnt = static_cast<size_t>(ctx->Pw) * w_elems(ctx, l);
+    HIPCHK(h2d(ctx, ctx->W[l - 1], W[l - 1], cnt));
+    HIPCHK(hipMemsetAsync(ctx->mW[l - 1], 0, cnt * sizeof(float), ctx->st));
+    HIPCHK(hipMemsetAsync(ctx->vW[l - 1], 0, cnt * sizeof(float), ctx->st));
+  }
+  if (ctx->Eb) launch_to_bf16(ctx->launch(), ctx->E, ctx->Eb, static_cast<int64_t>(nd));
+  HIPCHK(hipStreamSynchronize(ctx->st));
+  ctx->step = 0;
+  ctx->has_params = true;
+  ctx->probs_valid = false;
+  return GCO_OK;
+}
+
+int gco_get_params(gco_ctx* ctx, float* E, float* const* W) {
+  if (!ctx) return GCO_EINVAL;
+  NEED(ctx->has_params, GCO_ESTATE, "no parameters set");
+  if (E) {
+    int rc = download_node_matrix(ctx, E, ctx->E);
+    if (rc != GCO_OK) return rc;
+  }
+  if (W)
+    for (int l = 1; l <= ctx->cfg.num_layers; ++l)
+      if (W[l - 1])
+        HIPCHK(d2h(ctx, W[l - 1], ctx->W[l - 1], static_cast<size_t>(ctx->Pw) * w_elems(ctx, l)));
+  return GCO_OK;
+}
+
+int gco_get_opt_state(gco_ctx* ctx, float* mE, float* vE, float* const* mW, float* const* vW,
+                      int64_t* step) {
+  if (!ctx) return GCO_EINVAL;
+  NEED(ctx->has_params, GCO_ESTATE, "no parameters set");
+  int rc;
+  if (mE && (rc = download_node_matrix(ctx, mE, ctx->mE)) != GCO_OK) return rc;
+  if (vE && (rc = download_node_matrix(ctx, vE, ctx->vE)) != GCO_OK) return rc;
+  for (int l = 1; l <= ctx->cfg.num_layers; ++l) {
+    const size_t cnt = static_cast<size_t>(ctx->Pw) * w_elems(ctx, l);
+    if (mW && mW[l - 1]) HIPCHK(d2h(ctx, mW[l - 1], ctx->mW[l - 1], cnt));
+    if (vW && vW[l - 1]) HIPCHK(d2h(ctx, vW[l - 1], ctx->vW[l - 1], cnt));
+  }
+  if (step) *step = ctx->step;
+  return GCO_OK;
+}
+
+int gco_set_opt_state(gco_ctx* ctx, const float* mE, const float* vE, const float* const* mW,
+                      const float* const* vW, int64_t step) {
+  if (!ctx) return GCO_EINVAL;
+  NEED(ctx->has_params, GCO_ESTATE, "no parameters set");
+  NEED(mE && vE && mW && vW && step >= 0, GCO_EINVAL, "bad optimizer state argument");
+  int rc;
+  if ((rc = upload_node_matrix(ctx, mE, ctx->mE)) != GCO_OK) return rc;
+  if ((rc = upload_node_matrix(ctx, vE, ctx->vE)) != GCO_OK) return rc;
+  for (int l = 1; l <= ctx->cfg.num_layers; ++l) {
+    NEED(mW[l - 1] && vW[l - 1], GCO_EINVAL, "NULL moment pointer for layer %d", l);
+    const size_t cnt = static_cast<size_t>(ctx->Pw) * w_elems(ctx, l);
+    HIPCHK(h2d(ctx, ctx->mW[l - 1], mW[l - 1], cnt));
+    HIPCHK(h2d(ctx, ctx->vW[l - 1], vW[l - 1], cnt));
+  }
+  HIPCHK(hipStreamSynchronize(ctx->st));
+  ctx->step = step;
+  return GCO_OK;
+}
+
+int gco_set_linear_penalty(gco_ctx* ctx, const float* extra) {
+  if (!ctx) return GCO_EINVAL;
+  NEED(ctx->has_graph, GCO_ESTATE, "no graph uploaded");
+  if (!extra) {
+    launch_linear_coeff(ctx->st, ctx->n, ctx->d_cbase, nullptr, ctx->d_perm, ctx->d_c);
+    return GCO_OK;
+  }
+  Scratch tmp(ctx);
+  float* stage = tmp.get<float>(static_cast<size_t>(ctx->n));
+  NEED(stage, GCO_ENOMEM, "device scratch allocation failed");
+  HIPCHK(h2d(ctx, stage, extra, static_cast<size_t>(ctx->n)));
+  launch_linear_coeff(ctx->st, ctx->n, ctx->d_cbase, stage, ctx->d_perm, ctx->d_c);
+  return GCO_OK;
+}
+
+// ---- one epoch ------------------------------------------------------------------
+
+static void run_forward(gco_ctx* ctx) {
+  const Launch ln = ctx->launch();
+  const gco_config& c = ctx->cfg;
+  const int D = c.dim, L = c.num_layers;
+  const int ws = ctx->Pw == 1 ? 0 : D * D, wos = ctx->Pw == 1 ? 0 : D;
+  if (L == 1) {
+    launch_fwd_gemv(ln, c.storage, D, ctx->gv, ctx->H[0], ctx->W[0], wos, ctx->t);
+  } else {
+    for (int l = 1; l <= L - 1; ++l) {
+      const bool last = l == L - 1;
+      launch_fwd_hidden(ln, c.storage, D, ctx->gv, ctx->H[l - 1], ctx->W[l - 1], ws, ctx->H[l],
+                        last ? ctx->W[L - 1] : nullptr, wos, ctx->t, ctx->d_heavy_partial);
+    }
+  }
+  launch_fwd_readout(ln, ctx->gv, ctx->t, ctx->z, ctx->p, ctx->d_heavy_partial);
+  ctx->probs_valid = true;
+}
+
+static void run_loss(gco_ctx* ctx, double* loss_out) {
+  const Launch ln = ctx->launch();
+  const float q = ctx->cfg.problem == GCO_PROBLEM_MAXCUT ? 2.f : ctx->cfg.alpha;
+  launch_loss(ln, ctx->gv, ctx->p, ctx->d_c, q, ctx->g_z, ctx->loss_partial, ctx->d_heavy_partial);
+  launch_loss_reduce(ln, ctx->gv, ctx->loss_partial, ctx->loss_part, loss_out);
+}
+
+// update = true: Adam step t = ++step.  update = false: gradients are written to gE / gW.
+static void run_backward(gco_ctx* ctx, bool update, float* gE, float* const* gW) {
+  const Launch ln = ctx->launch();
+  const gco_config& c = ctx->cfg;
+  const int D = c.dim, L = c.num_layers;
+  const int ws = ctx->Pw == 1 ? 0 : D * D, wos = ctx->Pw == 1 ? 0 : D;
+  AdamStep ad{};
+  if (update) {
+    ctx->step += 1;
+    const double tt = static_cast<double>(ctx->step);
+    ad.lr = c.lr;
+    ad.b1 = c.adam_b1;
+    ad.b2 = c.adam_b2;
+    ad.eps = c.adam_eps;
+    ad.inv_bc1 = static_cast<float>(1.0 / (1.0 - std::pow(static_cast<double>(c.adam_b1), tt)));
+    ad.inv_sqrt_bc2 = static_cast<float>(1.0 / std::sqrt(1.0 - std::pow(static_cast<double>(c.adam_b2), tt)));
+  }
+  launch_bwd_readout(ln, ctx->gv, ctx->g_z, ctx->g_t, ctx->d_heavy_partial);
+  BwdArgs a;
+  a.g_t = ctx->g_t;
+  a.w_out = ctx->W[L - 1];
+  a.wout_stride = wos;
+  a.gwout_partial = ctx->gwout_partial;
+  a.E = ctx->E;
+  a.mE = ctx->mE;
+  a.vE = ctx->vE;
+  a.Eb = ctx->Eb;
+  a.gE = gE;
+  a.adam = ad;
+  a.heavy_partial = ctx->d_heavy_partial;
+  a.mode = update ? (c.train_embed ? EMBED_ADAM : EMBED_SKIP) : (gE ? EMBED_WRITE_GRAD : EMBED_SKIP);
+  if (L == 1) {
+    a.Hprev = ctx->H[0];
+    launch_bwd_single(ln, c.storage, D, ctx->gv, a);
+  } else {
+    for (int l = L - 1; l >= 1; --l) {
+      const bool last = l == L - 1, to_embed = l == 1;
+      a.GZ_in = last ? nullptr : ctx->GZ[l];
+      a.Hcur = last ? ctx->H[l] : nullptr;
+      a.Hprev = ctx->H[l - 1];
+      a.W = ctx->W[l - 1];
+      a.w_stride = ws;
+      a.gW_partial = ctx->gW_partial[l - 1];
+      a.GZ_out = to_embed ? nullptr : ctx->GZ[l - 1];
+      launch_bwd_hidden(ln, c.storage, D, last, to_embed, ctx->gv, a);
+    }
+  }
+  for (int l = 1; l <= L; ++l) {
+    WeightTensor wt;
+    wt.W = ctx->W[l - 1];
+    wt.m = ctx->mW[l - 1];
+    wt.v = ctx->vW[l - 1];
+    wt.partial = l < L ? ctx->gW_partial[l - 1] : ctx->gwout_partial;
+    wt.grad_out = (!update && gW) ? gW[l - 1] : nullptr;
+    wt.elems = w_elems(ctx, l);
+    launch_adam_w(ln, ctx->gv, ctx->d_pbl_ptr, ctx->d_pbl_list, ctx->Pw, wt, ad, update);
+  }
+  if (update) ctx->probs_valid = true;  // p is that of the parameters before the step
+}
+
+int gco_train(gco_ctx* ctx, int32_t epochs, double* loss_per_epoch) {
+  if (!ctx) return GCO_EINVAL;
+  NEED(ctx->has_params, GCO_ESTATE, "set_params must precede train");
+  NEED(epochs >= 0, GCO_EINVAL, "negative epoch count");
+  if (epochs == 0) return GCO_OK;
+  if (ctx->loss_hist_cap < epochs) {
+    // the old array (if any) stays owned by the graph allocation list
+    ctx->loss_hist = nullptr;
+    GALLOC(ctx->loss_hist, static_cast<size_t>(epochs));
+    ctx->loss_hist_cap = epochs;
+  }
+  for (int e = 0; e < epochs; ++e) {
+    run_forward(ctx);
+    run_loss(ctx, ctx->loss_hist + e);
+    run_backward(ctx, true, nullptr, nullptr);
+  }
+  HIPCHK(hipGetLastError());
+  if (loss_per_epoch) HIPCHK(d2h(ctx, loss_per_epoch, ctx->loss_hist, static_cast<size_t>(epochs)));
+  return GCO_OK;
+}
+
+int gco_forward(gco_ctx* ctx) {
+  if (!ctx) return GCO_EINVAL;
+  NEED(ctx->has_params, GCO_ESTATE, "set_params must precede forward");
+  run_forward(ctx);
+  HIPCHK(hipGetLastError());
+  return GCO_OK;
+}
+
+int gco_get_probs(gco_ctx* ctx, float* p) {
+  if (!ctx) return GCO_EINVAL;
+  NEED(ctx->probs_valid, GCO_ESTATE, "no forward pass has run");
+  NEED(p, GCO_EINVAL, "p is NULL");
+  Scratch tmp(ctx);
+  float* stage = tmp.get<float>(static_cast<size_t>(ctx->n));
+  NEED(stage, GCO_ENOMEM, "device scratch allocation failed");
+  launch_gather_rows(ctx->st, ctx->n, 1, ctx->p, ctx->d_inv, stage);
+  HIPCHK(d2h(ctx, p, stage, static_cast<size_t>(ctx->n)));
+  return GCO_OK;
+}
+
+int gco_loss(gco_ctx* ctx, double* total, double* per_part) {
+  if (!ctx) return GCO_EINVAL;
+  NEED(ctx->has_params, GCO_ESTATE, "set_params must precede loss");
+  run_forward(ctx);
+  run_loss(ctx, ctx->loss_one);
+  HIPCHK(hipGetLastError());
+  if (total) HIPCHK(d2h(ctx, total, ctx->loss_one, 1));
+  if (per_part) HIPCHK(d2h(ctx, per_part, ctx->loss_part, static_cast<size_t>(ctx->P)));
+  return GCO_OK;
+}
+
+int gco_get_grads(gco_ctx* ctx, float* gE, float* const* gW) {
+  if (!ctx) return GCO_EINVAL;
+  NEED(ctx->has_params, GCO_ESTATE, "set_params must precede get_grads");
+  const int L = ctx->cfg.num_layers;
+  const size_t nd = static_cast<size_t>(ctx->n) * ctx->cfg.dim;
+  Scratch tmp(ctx);
+  float* d_gE = gE ? tmp.get<float>(nd) : nullptr;
+  NEED(!gE || d_gE, GCO_ENOMEM, "device scratch allocation failed");
+  float* d_gW[3] = {};
+  for (int l = 1; l <= L; ++l) {
+    d_gW[l - 1] = tmp.get<float>(static_cast<size_t>(ctx->Pw) * w_elems(ctx, l));
+    NEED(d_gW[l - 1], GCO_ENOMEM, "device scratch allocation failed");
+  }
+  run_forward(ctx);
+  run_loss(ctx, ctx->loss_one);
+  run_backward(ctx, false, d_gE, d_gW);
+  HIPCHK(hipGetLastError());
+  if (gE) {
+    int rc = download_node_matrix(ctx, gE, d_gE);
+    if (rc != GCO_OK) return rc;
+  }
+  if (gW)
+    for (int l = 1; l <= L; ++l)
+      if (gW[l - 1])
+        HIPCHK(d2h(ctx, gW[l - 1], d_gW[l - 1], static_cast<size_t>(ctx->Pw) * w_elems(ctx, l)));
+  return GCO_OK;
+}
+
+// ---- read-out -------------------------------------------------------------------
+
+int gco_round_repair(gco_ctx* ctx, float thr, int32_t repair_scope, uint8_t* x, int64_t* objective,
+                     int64_t* conflicts_before, int64_t* conflicts_after) {
+  if (!ctx) return GCO_EINVAL;
+  NEED(ctx->probs_valid, GCO_ESTATE, "no forward pass has run");
+  NEED(x, GCO_EINVAL, "x is NULL");
+  NEED(repair_scope >= GCO_REPAIR_NONE && repair_scope <= GCO_REPAIR_ALL, GCO_EINVAL,
+       "bad repair_scope %d", repair_scope);
+  const int n = ctx->n;
+  hipStream_t st = ctx->st;
+  Scratch tmp(ctx);
+  const size_t npad = (static_cast<size_t>(n) + 3) / 4 * 4;
+  float* p_orig = tmp.get<float>(static_cast<size_t>(n));
+  uint8_t* state = tmp.get<uint8_t>(npad);
+  uint8_t* x_orig = tmp.get<uint8_t>(npad);
+  uint8_t* x_new = tmp.get<uint8_t>(npad);
+  unsigned long long* counts = tmp.get<unsigned long long>(8);
+  int* undecided = tmp.get<int>(4);
+  NEED(p_orig && state && x_orig && x_new && counts && undecided, GCO_ENOMEM,
+       "device scratch allocation failed");
+  launch_gather_rows(st, n, 1, ctx->p, ctx->d_inv, p_orig);
+  launch_round(st, n, p_orig, thr, x_orig);  // 0/1 in original order
+  launch_fill_u32(st, counts, 16, 0u);
+  launch_edge_counts(st, n, ctx->d_rowptr, ctx->d_col, x_orig, counts);
+  const bool repair = ctx->cfg.problem == GCO_PROBLEM_MIS && repair_scope != GCO_REPAIR_NONE;
+  if (repair) {
+    const bool local = repair_scope == GCO_REPAIR_LOCAL;
+    if (local) launch_round(st, n, ctx->p, thr, state);
+    else launch_round(st, n, p_orig, thr, state);
+    // each batch of four rounds ends with a count of the nodes still undecided
+    for (int64_t guard = 0; guard <= static_cast<int64_t>(n) + 4; guard += 4) {
+      launch_fill_u32(st, undecided, 4, 0u);
+      for (int q = 0; q < 4; ++q) {
+        if (local)
+          launch_repair_round_local(st, n, ctx->d_lrowptr, ctx->d_lcol, ctx->p, state, undecided + q);
+        else
+          launch_repair_round_all(st, n, ctx->d_rowptr, ctx->d_col, p_orig, state, undecided + q);
+      }
+      int left = 0;
+      HIPCHK(d2h(ctx, &left, undecided + 3, 1));
+      if (left == 0) break;
+    }
+    if (local) {
+      launch_state_to_x(st, n, state, x_new);
+      launch_gather_bytes(st, n, x_new, ctx->d_inv, x_orig);
+    } else {
+      launch_state_to_x(st, n, state, x_orig);
+    }
+  }
+  launch_edge_counts(st, n, ctx->d_rowptr, ctx->d_col, x_orig, counts + 4);
+  unsigned long long h[8];
+  HIPCHK(d2h(ctx, h, counts, 8));
+  HIPCHK(d2h(ctx, x, x_orig, static_cast<size_t>(n)));
+  if (conflicts_before) *conflicts_before = static_cast<int64_t>(h[1]);
+  if (conflicts_after) *conflicts_after = static_cast<int64_t>(h[5]);
+  if (objective)
+    *objective = static_cast<int64_t>(ctx->cfg.problem == GCO_PROBLEM_MIS ? h[4] : h[6]);
+  return GCO_OK;
+}
+
+static int cross_edges_impl(gco_ctx* ctx, const uint8_t* d_x, int64_t* count, int32_t* u, int32_t* v,
+                            uint8_t* cross_host) {
+  const int n = ctx->n;
+  hipStream_t st = ctx->st;
+  Scratch tmp(ctx);
+  int64_t* cnt = tmp.get<int64_t>(static_cast<size_t>(n) + 1);
+  int64_t* offs = tmp.get<int64_t>(static_cast<size_t>(n) + 1);
+  int64_t* scan = tmp.get<int64_t>(scan_temp_elems(static_cast<int64_t>(n) + 1));
+  NEED(cnt && offs && scan, GCO_ENOMEM, "device scratch allocation failed");
+  launch_fill_u32(st, cnt + n, 2, 0u);
+  launch_cut_count(st, n, ctx->d_rowptr, ctx->d_col, ctx->d_part, d_x, cnt);
+  exclusive_scan_i64(st, cnt, offs, static_cast<int64_t>(n) + 1, scan);
+  int64_t total = 0;
+  HIPCHK(d2h(ctx, &total, offs + n, 1));
+  if (cross_host) {
+    const size_t npad = (static_cast<size_t>(n) + 3) / 4 * 4;
+    uint8_t* cross = tmp.get<uint8_t>(npad);
+    NEED(cross, GCO_ENOMEM, "device scratch allocation failed");
+    launch_fill_u32(st, cross, static_cast<int64_t>(npad / 4), 0u);
+    launch_cut_fill(st, n, ctx->d_rowptr, ctx->d_col, ctx->d_part, d_x, offs, nullptr, nullptr, cross);
+    HIPCHK(d2h(ctx, cross_host, cross, static_cast<size_t>(n)));
+    return GCO_OK;
+  }
+  if (!u && !v) {
+    *count = total;
+    return GCO_OK;
+  }
+  NEED(u && v, GCO_EINVAL, "u and v must both be given");
+  NEED(*count >= total, GCO_ERANGE, "capacity %lld < %lld cross edges",
+       static_cast<long long>(*count), static_cast<long long>(total));
+  int32_t* du = tmp.get<int32_t>(static_cast<size_t>(total));
+  int32_t* dv = tmp.get<int32_t>(static_cast<size_t>(total));
+  NEED(du && dv, GCO_ENOMEM, "device scratch allocation failed");
+  launch_cut_fill(st, n, ctx->d_rowptr, ctx->d_col, ctx->d_part, d_x, offs, du, dv, nullptr);
+  HIPCHK(d2h(ctx, u, du, static_cast<size_t>(total)));
+  HIPCHK(d2h(ctx, v, dv, static_cast<size_t>(total)));
+  *count = total;
+  return GCO_OK;
+}
+
+int gco_cut_edges(gco_ctx* ctx, int64_t* count, int32_t* u, int32_t* v) {
+  if (!ctx) return GCO_EINVAL;
+  NEED(ctx->has_graph, GCO_ESTATE, "no graph uploaded");
+  NEED(count, GCO_EINVAL, "count is NULL");
+  return cross_edges_impl(ctx, nullptr, count, u, v, nullptr);
+}
+
+int gco_cross_mask(gco_ctx* ctx, uint8_t* c) {
+  if (!ctx) return GCO_EINVAL;
+  NEED(ctx->has_graph, GCO_ESTATE, "no graph uploaded");
+  NEED(c, GCO_EINVAL, "c is NULL");
+  int64_t dummy = 0;
+  return cross_edges_impl(ctx, nullptr, &dummy, nullptr, nullptr, c);
+}
+
+int gco_conflict_edges(gco_ctx* ctx, const uint8_t* x, int64_t* count, int32_t* u, int32_t* v) {
+  if (!ctx) return GCO_EINVAL;
+  NEED(ctx->has_graph, GCO_ESTATE, "no graph uploaded");
+  NEED(x && count, GCO_EINVAL, "x or count is NULL");
+  Scratch tmp(ctx);
+  uint8_t* dx = tmp.get<uint8_t>(static_cast<size_t>(ctx->n));
+  NEED(dx, GCO_ENOMEM, "device scratch allocation failed");
+  HIPCHK(h2d(ctx, dx, x, static_cast<size_t>(ctx->n)));
+  return cross_edges_impl(ctx, dx, count, u, v, nullptr);
+}
+
+// ---- timing ---------------------------------------------------------------------
+
+int gco_set_profiling(gco_ctx* ctx, int32_t mode, uint64_t kind_mask) {
+  if (!ctx) return GCO_EINVAL;
+  NEED(mode >= 0 && mode <= 2, GCO_EINVAL, "bad profiling mode %d", mode);
+  HIPCHK(hipStreamSynchronize(ctx->st));
+  ctx->prof.harvest();
+  ctx->prof.mode = mode;
+  ctx->prof.mask = kind_mask;
+  return GCO_OK;
+}
+
+int gco_num_kernel_kinds(void) { return KK_COUNT; }
+
+const char* gco_kernel_kind_name(int32_t kind) {
+  return kind >= 0 && kind < KK_COUNT ? kKindNames[kind] : "";
+}
+
+int gco_get_timing(gco_ctx* ctx, int32_t kind, int64_t* launches, double* total_ms,
+                   double* algorithmic_bytes_per_launch) {
+  if (!ctx) return GCO_EINVAL;
+  NEED(kind >= 0 && kind < KK_COUNT, GCO_EINVAL, "bad kernel kind %d", kind);
+  HIPCHK(hipStreamSynchronize(ctx->st));
+  ctx->prof.harvest();
+  if (launches) *launches = ctx->prof.launches[kind];
+  if (total_ms) *total_ms = ctx->prof.total_ms[kind];
+  if (algorithmic_bytes_per_launch) *algorithmic_bytes_per_launch = ctx->kind_bytes[kind];
+  return GCO_OK;
+}
+
+int gco_reset_timing(gco_ctx* ctx) {
+  if (!ctx) return GCO_EINVAL;
+  HIPCHK(hipStreamSynchronize(ctx->st));
+  ctx->prof.reset();
+  return GCO_OK;
+}
+
+}  // extern "C"

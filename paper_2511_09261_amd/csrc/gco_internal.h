@@ -1,0 +1,180 @@
+// Internal declarations shared by the host API and the HIP kernel files.
+// Nothing here is part of the public ABI (see include/gco.h).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include <string>
+#include <vector>
+
+#include "gco.h"
+
+namespace gco {
+
+constexpr int kBlock = 256;      // threads per workgroup in every kernel here (4 wavefronts)
+constexpr int kTileRows = 64;    // rows of one feature tile in the wide kernels
+constexpr int kNarrowRows = 256; // rows of one tile in the width-1 kernels
+constexpr int kLightMax = 64;    // rows with more local neighbours are reduced by the whole block
+constexpr int kHeavyMin = 2048;  // rows with at least this many neighbours are pre-reduced in chunks
+constexpr int kChunk = 512;      // neighbours per chunk of a pre-reduced row
+
+enum KernelKind : int {
+  KK_FWD_HIDDEN = 0,   // aggregate + transform + ReLU of one hidden layer (Eq. 3)
+  KK_FWD_GEMV,         // t = E w (only when there is no hidden layer)
+  KK_FWD_READOUT,      // z = A_hat t, p = sigmoid(z) (Eq. 4)
+  KK_LOSS,             // loss and dL/dz (Eq. 5)
+  KK_BWD_READOUT,      // g_t = A_hat^T g_z
+  KK_BWD_HIDDEN,       // backward of a hidden layer that is not the first
+  KK_BWD_EMBED,        // backward of the first layer + Adam on the embeddings
+  KK_ADAM_W,           // gradient reduction + Adam on the weight matrices
+  KK_LOSS_REDUCE,      // per-subgraph and total loss
+  KK_HEAVY,            // chunked pre-reduction of very long rows
+  KK_COUNT
+};
+
+// Device view of the local (trained-on) graph in subgraph-contiguous node order,
+// plus the static work decomposition.  All pointers are device pointers.
+struct GraphView {
+  int n = 0;
+  int P = 0;
+  const int* rowptr = nullptr;    // [n+1] local CSR
+  const int* col = nullptr;       // [nnz]
+  const float* sa = nullptr;      // [n] row scale of A_hat   (A_hat_ij = sa_i * sb_j)
+  const float* sb = nullptr;      // [n] column scale of A_hat
+  const int* part_rows = nullptr; // [P+1] first row of each subgraph
+  // wide kernels: workgroup b works on tiles s, s+S, ... of subgraph blk_k[b]
+  const int* blk_k = nullptr;
+  const int* blk_s = nullptr;
+  int S = 1;
+  int num_blocks = 0;
+  // narrow kernels: same scheme with kNarrowRows-row tiles
+  const int* nblk_k = nullptr;
+  const int* nblk_s = nullptr;
+  int nS = 1;
+  int num_nblocks = 0;
+  // very long rows, pre-reduced in chunks: row heavy_row[h] owns chunks
+  // heavy_chunk_ptr[h] .. heavy_chunk_ptr[h+1]; chunk c covers CSR entries
+  // chunk_begin[c] .. chunk_end[c].  heavy_of_row[i] = h or -1.
+  int num_heavy = 0;
+  int num_chunks = 0;
+  const int* heavy_of_row = nullptr;  // [n]
+  const int* heavy_chunk_ptr = nullptr;
+  const int* chunk_begin = nullptr;
+  const int* chunk_end = nullptr;
+  const int* chunk_part = nullptr;    // subgraph of the row that owns the chunk
+};
+
+// Per-call Adam constants (bias corrections evaluated on the host in double).
+struct AdamStep {
+  float lr, b1, b2, eps;
+  float inv_bc1;       // 1 / (1 - b1^t)
+  float inv_sqrt_bc2;  // 1 / sqrt(1 - b2^t)
+};
+
+// Where to enqueue, and an optional per-kernel timer: begin/end bracket exactly
+// one kernel launch of the given kind with events on the stream.
+struct Profiler {
+  virtual void begin(int kind, hipStream_t st) = 0;
+  virtual void end(int kind, hipStream_t st) = 0;
+  virtual ~Profiler() {}
+};
+struct Launch {
+  hipStream_t st = nullptr;
+  Profiler* prof = nullptr;
+  void begin(int kind) const { if (prof) prof->begin(kind, st); }
+  void end(int kind) const { if (prof) prof->end(kind, st); }
+};
+
+enum EmbedMode : int { EMBED_ADAM = 0, EMBED_WRITE_GRAD = 1, EMBED_SKIP = 2 };
+
+// ---- launchers implemented in train_kernels.hip (storage: 0 fp32, 1 bf16) ----
+
+// Hidden layer forward: Y = relu((A_hat X) W^k); with w_out != nullptr also
+// t = Y w_out^k (the scalar layer's transform fused into the last hidden layer).
+void launch_fwd_hidden(const Launch& ln, int storage, int D, const GraphView& g, const void* X,
+                       const float* W, int w_stride, void* Y, const float* w_out,
+                       int wout_stride, float* t, float* heavy_partial);
+
+// t = X w^k (used only when L = 1).
+void launch_fwd_gemv(const Launch& ln, int storage, int D, const GraphView& g, const void* X,
+                     const float* w, int w_stride, float* t);
+
+// z = A_hat t, p = sigmoid(z).
+void launch_fwd_readout(const Launch& ln, const GraphView& g, const float* t, float* z, float* p,
+                        float* heavy_partial);
+
+// s = A_loc p; g_z = (c + q s) p (1 - p); loss partial per workgroup.
+void launch_loss(const Launch& ln, const GraphView& g, const float* p, const float* c, float q,
+                 float* g_z, double* loss_partial, float* heavy_partial);
+
+// loss_part[k] = sum of the partials of subgraph k; loss_out[0] = sum_k loss_part[k].
+void launch_loss_reduce(const Launch& ln, const GraphView& g, const double* loss_partial,
+                        double* loss_part, double* loss_out);
+
+// g_t = A_hat^T g_z.
+void launch_bwd_readout(const Launch& ln, const GraphView& g, const float* g_z, float* g_t,
+                        float* heavy_partial);
+
+// Backward of hidden layer l (and of the scalar layer when `last`):
+//   last:  G_Z[j,:] = g_t[j] * w_out^k * [Hcur[j,:] > 0] is formed while gathering,
+//          and gw_out partials = sum_i Hcur[i,:] g_t[i] are produced;
+//   else:  G_Z is read from GZ_in.
+//   G_T = A_hat^T G_Z;  gW partial += Hprev^T G_T;  G_Hprev = G_T W^T.
+//   to_embed: Hprev is the embedding: apply `mode` (Adam / write gE / nothing);
+//   else write GZ_out = G_Hprev * [Hprev > 0].
+struct BwdArgs {
+  const void* GZ_in = nullptr;   // [n, D] storage type (not last)
+  const void* Hcur = nullptr;    // [n, D] storage type (last)
+  const float* g_t = nullptr;    // [n] (last)
+  const float* w_out = nullptr;  // [Pw, D] (last)
+  int wout_stride = 0;
+  float* gwout_partial = nullptr;  // [num_blocks, D] (last)
+  const void* Hprev = nullptr;   // [n, D] storage type
+  const float* W = nullptr;      // [Pw, D, D]
+  int w_stride = 0;
+  float* gW_partial = nullptr;   // [num_blocks, D*D]
+  void* GZ_out = nullptr;        // [n, D] storage type (not to_embed)
+  // to_embed
+  int mode = EMBED_ADAM;
+  float* E = nullptr;            // fp32 master embeddings [n, D]
+  float* mE = nullptr;
+  float* vE = nullptr;
+  void* Eb = nullptr;            // bf16 working copy (bf16 storage only)
+  float* gE = nullptr;           // EMBED_WRITE_GRAD
+  AdamStep adam{};
+  float* heavy_partial = nullptr;
+};
+void launch_bwd_hidden(const Launch& ln, int storage, int D, bool last, bool to_embed,
+                       const GraphView& g, const BwdArgs& a);
+
+// L = 1 backward: gw partial = sum_i X[i,:] g_t[i]; gE[i,:] = g_t[i] w^k.
+void launch_bwd_single(const Launch& ln, int storage, int D, const GraphView& g, const BwdArgs& a);
+
+// Sum the per-workgroup partials of each weight tensor in a fixed order, then
+// apply Adam (or only write the gradient when grad_out != nullptr).
+struct WeightTensor {
+  float* W = nullptr;
+  float* m = nullptr;
+  float* v = nullptr;
+  const float* partial = nullptr;  // [num_blocks, elems]
+  float* grad_out = nullptr;       // [Pw, elems] or nullptr
+  int elems = 0;                   // per subgraph
+};
+void launch_adam_w(const Launch& ln, const GraphView& g, const int* part_blk_ptr,
+                   const int* part_blk_list, int Pw, const WeightTensor& wt, const AdamStep& adam,
+                   bool update);
+
+// fp32 -> bf16 copy (round to nearest even).
+void launch_to_bf16(const Launch& ln, const float* src, void* dst, int64_t count);
+
+// ---- launchers implemented in graph_kernels.hip ----
+
+struct GraphBuildOut {
+  int64_t nnz_local = 0;
+  int64_t m_cut = 0;
+  int error = 0;  // 0 ok; else a GCO_E* code with `message` set
+  std::string message;
+};
+
+}  // namespace gco

@@ -1,0 +1,845 @@
+// Training-step kernels for gfx950: fused aggregate+transform layers (Eq. 3),
+// read-out (Eq. 4), loss and its gradient (Eq. 5), backward passes and Adam.
+//
+// Work decomposition.  Nodes are stored subgraph by subgraph.  A workgroup is
+// bound to one subgraph k (so its weight matrix W^k sits in LDS once) and walks
+// that subgraph's row tiles s, s+S, s+2S, ...  Within a tile:
+//   phase 1  gather: A_hat rows times the feature matrix, fp32 accumulation,
+//            result left in an LDS tile.  Short rows are taken by small lane
+//            groups (one 16-byte slice of the feature row per lane), long rows by
+//            the whole workgroup, very long rows come pre-reduced in chunks;
+//   phase 2  dense transform of the LDS tile with W^k and the fused epilogue.
+// Every sum is taken in an order fixed by the launch shape, so results are
+// bit-identical from run to run.
+#include "device_utils.h"
+#include "gco_internal.h"
+
+namespace gco {
+namespace {
+
+constexpr int R = kTileRows;
+
+template <int D>
+struct Geo {
+  static constexpr int LD = D + 4;  // LDS row pitch in floats (keeps 16-byte alignment)
+};
+
+// ---------------------------------------------------------------------------
+// Sources of gathered rows
+// ---------------------------------------------------------------------------
+
+// v = sb[j] * X[j, c0 .. c0+VEC)
+template <typename T, int D>
+struct PlainSrc {
+  static constexpr int VEC = Store<T>::VEC;
+  const T* X;
+  const float* sb;
+  __device__ __forceinline__ void set_part(int, int) {}
+  __device__ __forceinline__ void load(int j, int c0, float (&v)[VEC]) const {
+    Store<T>::load(X + static_cast<size_t>(j) * D + c0, v);
+    const float s = sb[j];
+#pragma unroll
+    for (int x = 0; x < VEC; ++x) v[x] *= s;
+  }
+};
+
+// Gradient of the last hidden layer's pre-activation, formed on the fly:
+// v = sb[j] * g_t[j] * w_out[c] * [H[j, c] > 0]
+template <typename T, int D>
+struct LastSrc {
+  static constexpr int VEC = Store<T>::VEC;
+  const T* H;
+  const float* sb;
+  const float* g_t;
+  const float* w_out;  // [Pw, D]
+  int wout_stride;
+  float w[VEC];
+  __device__ __forceinline__ void set_part(int k, int c0) {
+#pragma unroll
+    for (int x = 0; x < VEC; ++x) w[x] = w_out[static_cast<size_t>(k) * wout_stride + c0 + x];
+  }
+  __device__ __forceinline__ void load(int j, int c0, float (&v)[VEC]) const {
+    Store<T>::load(H + static_cast<size_t>(j) * D + c0, v);
+    const float s = sb[j] * g_t[j];
+#pragma unroll
+    for (int x = 0; x < VEC; ++x) v[x] = v[x] > 0.f ? s * w[x] : 0.f;
+  }
+};
+
+// acc += sum over entries e0, e0+stride, ... < e1 of src(col[e]); four rows in flight.
+template <class Src>
+__device__ __forceinline__ void gather_range(const Src& src, const int* __restrict__ col, int e0,
+                                             int e1, int stride, int c0,
+                                             float (&acc)[Src::VEC]) {
+  constexpr int VEC = Src::VEC;
+  int e = e0;
+  for (; e + 3 * stride < e1; e += 4 * stride) {
+    const int j0 = col[e], j1 = col[e + stride], j2 = col[e + 2 * stride], j3 = col[e + 3 * stride];
+    float v0[VEC], v1[VEC], v2[VEC], v3[VEC];
+    src.load(j0, c0, v0);
+    src.load(j1, c0, v1);
+    src.load(j2, c0, v2);
+    src.load(j3, c0, v3);
+#pragma unroll
+    for (int x = 0; x < VEC; ++x) acc[x] = (((acc[x] + v0[x]) + v1[x]) + v2[x]) + v3[x];
+  }
+  for (; e < e1; e += stride) {
+    float v0[VEC];
+    src.load(col[e], c0, v0);
+#pragma unroll
+    for (int x = 0; x < VEC; ++x) acc[x] += v0[x];
+  }
+}
+
+// Phase 1: tile[r, :] = sa_i * ( src(i) + sum_{j in N(i)} src(j) ) for the rows
+// row0 .. row0+nrows of the tile; rows nrows..R are zero-filled.
+// LDS: tile [R][LD], red [kBlock * VEC], hlist [R + 1].
+template <typename T, int D, class Src>
+__device__ void aggregate_tile(const GraphView& g, const Src& src, int row0, int nrows,
+                               float* tile, float* red, int* hlist,
+                               const float* __restrict__ heavy_partial) {
+  constexpr int VEC = Store<T>::VEC;
+  constexpr int LPR = D / VEC;        // lanes per feature row
+  constexpr int G = kBlock / LPR;     // lane groups per workgroup
+  constexpr int LD = Geo<D>::LD;
+  const int tid = threadIdx.x;
+  const int grp = tid / LPR;
+  const int c0 = (tid % LPR) * VEC;
+  if (tid == 0) hlist[0] = 0;
+  __syncthreads();
+  for (int r = grp; r < R; r += G) {
+    float acc[VEC];
+    if (r >= nrows) {
+#pragma unroll
+      for (int x = 0; x < VEC; ++x) tile[r * LD + c0 + x] = 0.f;
+      continue;
+    }
+    const int i = row0 + r;
+    const int e0 = g.rowptr[i], e1 = g.rowptr[i + 1];
+    const int h = g.num_heavy > 0 ? g.heavy_of_row[i] : -1;
+    if (h < 0 && e1 - e0 > kLightMax) {
+      if (tid % LPR == 0) {
+        const int q = atomicAdd(&hlist[0], 1);
+        hlist[1 + q] = r;
+      }
+      continue;
+    }
+    src.load(i, c0, acc);  // the self loop of A + I
+    if (h >= 0) {
+      for (int ch = g.heavy_chunk_ptr[h]; ch < g.heavy_chunk_ptr[h + 1]; ++ch) {
+        const float4* pp = reinterpret_cast<const float4*>(heavy_partial + static_cast<size_t>(ch) * D + c0);
+#pragma unroll
+        for (int x = 0; x < VEC; x += 4) {
+          const float4 q4 = pp[x / 4];
+          acc[x] += q4.x; acc[x + 1] += q4.y; acc[x + 2] += q4.z; acc[x + 3] += q4.w;
+        }
+      }
+    } else {
+      gather_range(src, g.col, e0, e1, 1, c0, acc);
+    }
+    const float sa = g.sa[i];
+#pragma unroll
+    for (int x = 0; x < VEC; ++x) tile[r * LD + c0 + x] = sa * acc[x];
+  }
+  __syncthreads();
+  const int nh = hlist[0];
+  for (int q = 0; q < nh; ++q) {
+    const int r = hlist[1 + q];
+    const int i = row0 + r;
+    const int e0 = g.rowptr[i], e1 = g.rowptr[i + 1];
+    float acc[VEC];
+    if (grp == 0) {
+      src.load(i, c0, acc);
+    } else {
+#pragma unroll
+      for (int x = 0; x < VEC; ++x) acc[x] = 0.f;
+    }
+    gather_range(src, g.col, e0 + grp, e1, G, c0, acc);
+#pragma unroll
+    for (int x = 0; x < VEC; ++x) red[grp * D + c0 + x] = acc[x];
+    __syncthreads();
+    if (tid < D) {
+      float s = 0.f;
+      for (int gq = 0; gq < G; ++gq) s += red[gq * D + tid];
+      tile[r * LD + tid] = g.sa[i] * s;
+    }
+    __syncthreads();
+  }
+}
+
+// Chunked pre-reduction of very long rows: partial[c, :] = sum_{e in chunk c} src(col[e]).
+template <typename T, int D, class Src>
+__global__ __launch_bounds__(kBlock) void heavy_wide_kernel(GraphView g, Src src, float* partial) {
+  constexpr int VEC = Store<T>::VEC;
+  constexpr int LPR = D / VEC;
+  constexpr int G = kBlock / LPR;
+  __shared__ float red[kBlock * VEC];
+  const int ch = blockIdx.x;
+  const int tid = threadIdx.x;
+  const int grp = tid / LPR;
+  const int c0 = (tid % LPR) * VEC;
+  src.set_part(g.chunk_part[ch], c0);
+  float acc[VEC];
+#pragma unroll
+  for (int x = 0; x < VEC; ++x) acc[x] = 0.f;
+  gather_range(src, g.col, g.chunk_begin[ch] + grp, g.chunk_end[ch], G, c0, acc);
+#pragma unroll
+  for (int x = 0; x < VEC; ++x) red[grp * D + c0 + x] = acc[x];
+  __syncthreads();
+  if (tid < D) {
+    float s = 0.f;
+    for (int gq = 0; gq < G; ++gq) s += red[gq * D + tid];
+    partial[static_cast<size_t>(ch) * D + tid] = s;
+  }
+}
+
+// ---------------------------------------------------------------------------
+// Dense transform of an LDS tile (fp32 FMA form)
+// ---------------------------------------------------------------------------
+
+// out[i] = sum_k tile[r_i, k] * Wl[k, c] for this thread's column c = tid % D and
+// rows r_i = tid / D + i * (kBlock / D).
+template <int D>
+__device__ __forceinline__ void tile_times_matrix(const float* tile, const float* Wl,
+                                                  float (&out)[R * D / kBlock]) {
+  constexpr int RG = kBlock / D;
+  constexpr int NR = R / RG;
+  constexpr int LD = Geo<D>::LD;
+  const int c = threadIdx.x % D;
+  const int rg = threadIdx.x / D;
+#pragma unroll
+  for (int i = 0; i < NR; ++i) out[i] = 0.f;
+  for (int k = 0; k < D; k += 4) {
+    const float w0 = Wl[(k + 0) * D + c], w1 = Wl[(k + 1) * D + c];
+    const float w2 = Wl[(k + 2) * D + c], w3 = Wl[(k + 3) * D + c];
+#pragma unroll
+    for (int i = 0; i < NR; ++i) {
+      const float4 a = *reinterpret_cast<const float4*>(tile + (rg + i * RG) * LD + k);
+      out[i] = fmaf(a.x, w0, out[i]);
+      out[i] = fmaf(a.y, w1, out[i]);
+      out[i] = fmaf(a.z, w2, out[i]);
+      out[i] = fmaf(a.w, w3, out[i]);
+    }
+  }
+}
+
+template <int D>
+constexpr size_t fwd_lds_bytes(int vec) {
+  return (static_cast<size_t>(R) * Geo<D>::LD + D * D + kBlock * vec + D) * sizeof(float) +
+         (R + 4) * sizeof(int);
+}
+template <int D>
+constexpr size_t bwd_lds_bytes(int vec) {
+  return (2 * static_cast<size_t>(R) * Geo<D>::LD + D * D + kBlock * vec + D) * sizeof(float) +
+         (R + 4) * sizeof(int);
+}
+
+// ---------------------------------------------------------------------------
+// Forward, hidden layer: Y = relu((A_hat X) W^k)  [+ t = Y w_out^k]
+// ---------------------------------------------------------------------------
+template <typename T, int D>
+__global__ __launch_bounds__(kBlock) void fwd_hidden_kernel(GraphView g, const T* __restrict__ X,
+                                                            const float* __restrict__ W,
+                                                            int w_stride, T* __restrict__ Y,
+                                                            const float* __restrict__ w_out,
+                                                            int wout_stride, float* __restrict__ t,
+                                                            const float* __restrict__ heavy_partial) {
+  constexpr int VEC = Store<T>::VEC;
+  constexpr int LD = Geo<D>::LD;
+  constexpr int RG = kBlock / D;
+  constexpr int NR = R / RG;
+  extern __shared__ __align__(16) unsigned char smem[];
+  float* tile = reinterpret_cast<float*>(smem);
+  float* Wl = tile + R * LD;
+  float* red = Wl + D * D;
+  float* wo = red + kBlock * VEC;
+  int* hlist = reinterpret_cast<int*>(wo + D);
+
+  const int k = g.blk_k[blockIdx.x];
+  if (k < 0) return;
+  const int s = g.blk_s[blockIdx.x];
+  const int tid = threadIdx.x;
+  const float* Wk = W + static_cast<size_t>(k) * w_stride;
+  for (int idx = tid; idx < D * D; idx += kBlock) Wl[idx] = Wk[idx];
+  if (w_out != nullptr && tid < D) wo[tid] = w_out[static_cast<size_t>(k) * wout_stride + tid];
+  PlainSrc<T, D> src{X, g.sb};
+  const int rbeg = g.part_rows[k], rend = g.part_rows[k + 1];
+  const int c = tid % D, rg = tid / D;
+  for (int row0 = rbeg + s * R; row0 < rend; row0 += g.S * R) {
+    const int nrows = min(R, rend - row0);
+    aggregate_tile<T, D>(g, src, row0, nrows, tile, red, hlist, heavy_partial);
+    __syncthreads();
+    float out[NR];
+    tile_times_matrix<D>(tile, Wl, out);
+#pragma unroll
+    for (int i = 0; i < NR; ++i) {
+      const int r = rg + i * RG;
+      out[i] = Store<T>::as_stored(fmaxf(out[i], 0.f));
+      if (r < nrows) Store<T>::put(Y + static_cast<size_t>(row0 + r) * D + c, out[i]);
+    }
+    if (w_out != nullptr) {
+      __syncthreads();
+#pragma unroll
+      for (int i = 0; i < NR; ++i) tile[(rg + i * RG) * LD + c] = out[i];
+      __syncthreads();
+      if (tid < nrows) {
+        float acc = 0.f;
+        for (int cc = 0; cc < D; ++cc) acc = fmaf(tile[tid * LD + cc], wo[cc], acc);
+        t[row0 + tid] = acc;
+      }
+    }
+    __syncthreads();
+  }
+}
+
+// t = X w^k for L = 1 (no hidden layer).
+template <typename T, int D>
+__global__ __launch_bounds__(kBlock) void fwd_gemv_kernel(GraphView g, const T* __restrict__ X,
+                                                          const float* __restrict__ w, int w_stride,
+                                                          float* __restrict__ t) {
+  const int k = g.nblk_k[blockIdx.x];
+  if (k < 0) return;
+  const int s = g.nblk_s[blockIdx.x];
+  const int rbeg = g.part_rows[k], rend = g.part_rows[k + 1];
+  const float* wk = w + static_cast<size_t>(k) * w_stride;
+  for (int row0 = rbeg + s * kNarrowRows; row0 < rend; row0 += g.nS * kNarrowRows) {
+    const int i = row0 + threadIdx.x;
+    if (i < rend) {
+      float acc = 0.f;
+      for (int cc = 0; cc < D; ++cc)
+        acc = fmaf(Store<T>::get(X + static_cast<size_t>(i) * D + cc), wk[cc], acc);
+      t[i] = acc;
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------
+// Backward of a hidden layer (see BwdArgs)
+// ---------------------------------------------------------------------------
+template <typename T, int D, bool LAST, bool TO_EMBED>
+__global__ __launch_bounds__(kBlock) void bwd_hidden_kernel(GraphView g, BwdArgs a) {
+  constexpr int VEC = Store<T>::VEC;
+  constexpr int LPR = D / VEC;
+  constexpr int LD = Geo<D>::LD;
+  constexpr int RG = kBlock / D;
+  constexpr int NR = R / RG;
+  constexpr int AG = kBlock / D;                       // row groups of the D x D gradient
+  constexpr int NA = (D * D >= kBlock) ? (D * D / kBlock) : 1;
+  extern __shared__ __align__(16) unsigned char smem[];
+  float* tile = reinterpret_cast<float*>(smem);        // G_T tile
+  float* hp = tile + R * LD;                           // Hprev tile
+  float* Wt = hp + R * LD;                             // Wt[b, a] = W[a, b]
+  float* red = Wt + D * D;
+  float* gtl = red + kBlock * VEC;                     // g_t of the tile rows (LAST)
+  int* hlist = reinterpret_cast<int*>(gtl + D);
+
+  const int k = g.blk_k[blockIdx.x];
+  if (k < 0) return;
+  const int s = g.blk_s[blockIdx.x];
+  const int tid = threadIdx.x;
+  const T* Hprev = static_cast<const T*>(a.Hprev);
+  const float* Wk = a.W + static_cast<size_t>(k) * a.w_stride;
+  for (int idx = tid; idx < D * D; idx += kBlock) Wt[(idx % D) * D + idx / D] = Wk[idx];
+
+  PlainSrc<T, D> psrc{static_cast<const T*>(a.GZ_in), g.sb};
+  LastSrc<T, D> lsrc{static_cast<const T*>(a.Hcur), g.sb, a.g_t, a.w_out, a.wout_stride, {}};
+  if (LAST) lsrc.set_part(k, (tid % LPR) * VEC);
+
+  const int rbeg = g.part_rows[k], rend = g.part_rows[k + 1];
+  const int c = tid % D, rg = tid / D;
+  const bool gw_active = (D * D >= kBlock) || (rg < D);
+  float gw[NA];
+#pragma unroll
+  for (int i = 0; i < NA; ++i) gw[i] = 0.f;
+  float gwo = 0.f;  // gradient of w_out[c] (LAST, threads tid < D)
+
+  for (int row0 = rbeg + s * R; row0 < rend; row0 += g.S * R) {
+    const int nrows = min(R, rend - row0);
+    if (LAST)
+      aggregate_tile<T, D>(g, lsrc, row0, nrows, tile, red, hlist, a.heavy_partial);
+    else
+      aggregate_tile<T, D>(g, psrc, row0, nrows, tile, red, hlist, a.heavy_partial);
+    // Hprev tile -> LDS (fp32), zero beyond the tile's rows
+    for (int idx = tid; idx < R * LPR; idx += kBlock) {
+      const int r = idx / LPR, cc = (idx % LPR) * VEC;
+      float v[VEC];
+      if (r < nrows) {
+        Store<T>::load(Hprev + static_cast<size_t>(row0 + r) * D + cc, v);
+      } else {
+#pragma unroll
+        for (int x = 0; x < VEC; ++x) v[x] = 0.f;
+      }
+#pragma unroll
+      for (int x = 0; x < VEC; ++x) hp[r * LD + cc + x] = v[x];
+    }
+    if (LAST && tid < D) {
+      const T* Hcur = static_cast<const T*>(a.Hcur);
+      for (int r = 0; r < nrows; ++r)
+        gwo = fmaf(Store<T>::get(Hcur + static_cast<size_t>(row0 + r) * D + tid), a.g_t[row0 + r], gwo);
+    }
+    __syncthreads();
+    // gW[a_, c] += sum_r Hprev[r, a_] * G_T[r, c]
+    if (gw_active) {
+      for (int r = 0; r < R; ++r) {
+        const float gt = tile[r * LD + c];
+#pragma unroll
+        for (int i = 0; i < NA; ++i) gw[i] = fmaf(hp[r * LD + rg + i * AG], gt, gw[i]);
+      }
+    }
+    // G_Hprev[r, c] = sum_b G_T[r, b] * W[c, b]
+    if (!(TO_EMBED && a.mode == EMBED_SKIP)) {
+      float gh[NR];
+      tile_times_matrix<D>(tile, Wt, gh);
+#pragma unroll
+      for (int i = 0; i < NR; ++i) {
+        const int r = rg + i * RG;
+        if (r >= nrows) continue;
+        const size_t idx = static_cast<size_t>(row0 + r) * D + c;
+        if (TO_EMBED) {
+          if (a.mode == EMBED_WRITE_GRAD) {
+            a.gE[idx] = gh[i];
+          } else {
+            const float gq = gh[i];
+            const float m = a.adam.b1 * a.mE[idx] + (1.f - a.adam.b1) * gq;
+            const float v = a.adam.b2 * a.vE[idx] + (1.f - a.adam.b2) * gq * gq;
+            const float upd = (m * a.adam.inv_bc1) / (sqrtf(v) * a.adam.inv_sqrt_bc2 + a.adam.eps);
+            const float e = a.E[idx] - a.adam.lr * upd;
+            a.mE[idx] = m;
+            a.vE[idx] = v;
+            a.E[idx] = e;
+            if (sizeof(T) == 2) Store<T>::put(static_cast<T*>(a.Eb) + idx, e);
+          }
+        } else {
+          Store<T>::put(static_cast<T*>(a.GZ_out) + idx, hp[r * LD + c] > 0.f ? gh[i] : 0.f);
+        }
+      }
+    }
+    __syncthreads();
+  }
+  if (gw_active) {
+#pragma unroll
+    for (int i = 0; i < NA; ++i)
+      a.gW_partial[static_cast<size_t>(blockIdx.x) * D * D + (rg + i * AG) * D + c] = gw[i];
+  }
+  if (LAST && tid < D) a.gwout_partial[static_cast<size_t>(blockIdx.x) * D + tid] = gwo;
+}
+
+// L = 1: p = sigmoid(A_hat (E w)).  gw partial = sum_i X[i,:] g_t[i]; gE[i,:] = g_t[i] w.
+template <typename T, int D>
+__global__ __launch_bounds__(kBlock) void bwd_single_kernel(GraphView g, BwdArgs a) {
+  constexpr int RG = kBlock / D;
+  const int k = g.blk_k[blockIdx.x];
+  if (k < 0) return;
+  const int s = g.blk_s[blockIdx.x];
+  const int tid = threadIdx.x;
+  const int c = tid % D, rg = tid / D;
+  __shared__ float red[kBlock];
+  const T* X = static_cast<const T*>(a.Hprev);
+  const float wc = a.w_out[static_cast<size_t>(k) * a.wout_stride + c];
+  const int rbeg = g.part_rows[k], rend = g.part_rows[k + 1];
+  float gw = 0.f;
+  for (int row0 = rbeg + s * R; row0 < rend; row0 += g.S * R) {
+    const int nrows = min(R, rend - row0);
+    for (int r = rg; r < nrows; r += RG) {
+      const size_t idx = static_cast<size_t>(row0 + r) * D + c;
+      const float gt = a.g_t[row0 + r];
+      gw = fmaf(Store<T>::get(X + idx), gt, gw);
+      const float gq = gt * wc;
+      if (a.mode == EMBED_WRITE_GRAD) {
+        a.gE[idx] = gq;
+      } else if (a.mode == EMBED_ADAM) {
+        const float m = a.adam.b1 * a.mE[idx] + (1.f - a.adam.b1) * gq;
+        const float v = a.adam.b2 * a.vE[idx] + (1.f - a.adam.b2) * gq * gq;
+        const float upd = (m * a.adam.inv_bc1) / (sqrtf(v) * a.adam.inv_sqrt_bc2 + a.adam.eps);
+        const float e = a.E[idx] - a.adam.lr * upd;
+        a.mE[idx] = m;
+        a.vE[idx] = v;
+        a.E[idx] = e;
+        if (sizeof(T) == 2) Store<T>::put(static_cast<T*>(a.Eb) + idx, e);
+      }
+    }
+  }
+  red[tid] = gw;
+  __syncthreads();
+  if (tid < D) {
+    float sacc = 0.f;
+    for (int q = 0; q < RG; ++q) sacc += red[q * D + tid];
+    a.gwout_partial[static_cast<size_t>(blockIdx.x) * D + tid] = sacc;
+  }
+}
+
+// ---------------------------------------------------------------------------
+// Width-1 passes: y_i = f_self(i) + sum_{j in N(i)} f(j), then an epilogue per row
+// ---------------------------------------------------------------------------
+
+// Row sums for one 256-row tile into rs[0..256): thread per short row, one
+// wavefront per longer row, chunk partials for the very long ones.
+template <class F>
+__device__ void narrow_row_sums(const GraphView& g, const F& f, int row0, int nrows, float* rs,
+                                int* mlist, const float* __restrict__ heavy_partial) {
+  const int tid = threadIdx.x;
+  if (tid == 0) mlist[0] = 0;
+  __syncthreads();
+  if (tid < nrows) {
+    const int i = row0 + tid;
+    const int e0 = g.rowptr[i], e1 = g.rowptr[i + 1];
+    const int h = g.num_heavy > 0 ? g.heavy_of_row[i] : -1;
+    if (h >= 0) {
+      float acc = 0.f;
+      for (int ch = g.heavy_chunk_ptr[h]; ch < g.heavy_chunk_ptr[h + 1]; ++ch) acc += heavy_partial[ch];
+      rs[tid] = acc;
+    } else if (e1 - e0 > 32) {
+      const int q = atomicAdd(&mlist[0], 1);
+      mlist[1 + q] = tid;
+    } else {
+      float acc = 0.f;
+      for (int e = e0; e < e1; ++e) acc += f(g.col[e]);
+      rs[tid] = acc;
+    }
+  }
+  __syncthreads();
+  const int nm = mlist[0];
+  const int wave = tid / 64, lane = tid % 64;
+  for (int q = wave; q < nm; q += kBlock / 64) {
+    const int r = mlist[1 + q];
+    const int i = row0 + r;
+    float acc = 0.f;
+    for (int e = g.rowptr[i] + lane; e < g.rowptr[i + 1]; e += 64) acc += f(g.col[e]);
+    acc = wave_sum(acc);
+    if (lane == 0) rs[r] = acc;
+  }
+  __syncthreads();
+}
+
+template <class F>
+__global__ __launch_bounds__(kBlock) void heavy_narrow_kernel(GraphView g, F f, float* partial) {
+  __shared__ float red[kBlock / 64];
+  const int ch = blockIdx.x;
+  float acc = 0.f;
+  for (int e = g.chunk_begin[ch] + threadIdx.x; e < g.chunk_end[ch]; e += kBlock) acc += f(g.col[e]);
+  acc = wave_sum(acc);
+  if (threadIdx.x % 64 == 0) red[threadIdx.x / 64] = acc;
+  __syncthreads();
+  if (threadIdx.x == 0) partial[ch] = ((red[0] + red[1]) + red[2]) + red[3];
+}
+
+struct ScaledValue {  // f(j) = sb[j] * x[j]
+  const float* sb;
+  const float* x;
+  __device__ __forceinline__ float operator()(int j) const { return sb[j] * x[j]; }
+};
+struct PlainValue {  // f(j) = x[j]
+  const float* x;
+  __device__ __forceinline__ float operator()(int j) const { return x[j]; }
+};
+
+// z = A_hat t; p = sigmoid(z)
+__global__ __launch_bounds__(kBlock) void fwd_readout_kernel(GraphView g, const float* __restrict__ t,
+                                                             float* __restrict__ z,
+                                                             float* __restrict__ p,
+                                                             const float* __restrict__ heavy_partial) {
+  __shared__ float rs[kNarrowRows];
+  __shared__ int mlist[kNarrowRows + 1];
+  const int k = g.nblk_k[blockIdx.x];
+  if (k < 0) return;
+  const int s = g.nblk_s[blockIdx.x];
+  const int rbeg = g.part_rows[k], rend = g.part_rows[k + 1];
+  ScaledValue f{g.sb, t};
+  for (int row0 = rbeg + s * kNarrowRows; row0 < rend; row0 += g.nS * kNarrowRows) {
+    const int nrows = min(kNarrowRows, rend - row0);
+    narrow_row_sums(g, f, row0, nrows, rs, mlist, heavy_partial);
+    if (threadIdx.x < nrows) {
+      const int i = row0 + threadIdx.x;
+      const float zi = g.sa[i] * (f(i) + rs[threadIdx.x]);
+      z[i] = zi;
+      p[i] = 1.f / (1.f + expf(-zi));
+    }
+    __syncthreads();
+  }
+}
+
+// g_t = A_hat^T g_z  (the view passed in has sa and sb exchanged)
+__global__ __launch_bounds__(kBlock) void bwd_readout_kernel(GraphView g, const float* __restrict__ g_z,
+                                                             float* __restrict__ g_t,
+                                                             const float* __restrict__ heavy_partial) {
+  __shared__ float rs[kNarrowRows];
+  __shared__ int mlist[kNarrowRows + 1];
+  const int k = g.nblk_k[blockIdx.x];
+  if (k < 0) return;
+  const int s = g.nblk_s[blockIdx.x];
+  const int rbeg = g.part_rows[k], rend = g.part_rows[k + 1];
+  ScaledValue f{g.sb, g_z};
+  for (int row0 = rbeg + s * kNarrowRows; row0 < rend; row0 += g.nS * kNarrowRows) {
+    const int nrows = min(kNarrowRows, rend - row0);
+    narrow_row_sums(g, f, row0, nrows, rs, mlist, heavy_partial);
+    if (threadIdx.x < nrows) {
+      const int i = row0 + threadIdx.x;
+      g_t[i] = g.sa[i] * (f(i) + rs[threadIdx.x]);
+    }
+    __syncthreads();
+  }
+}
+
+// s = A_loc p; g_z = (c + q s) p (1 - p); loss partial = sum_i p_i (c_i + q/2 s_i)
+__global__ __launch_bounds__(kBlock) void loss_kernel(GraphView g, const float* __restrict__ p,
+                                                      const float* __restrict__ cl, float q,
+                                                      float* __restrict__ g_z,
+                                                      double* __restrict__ loss_partial,
+                                                      const float* __restrict__ heavy_partial) {
+  __shared__ float rs[kNarrowRows];
+  __shared__ int mlist[kNarrowRows + 1];
+  __shared__ double wred[kBlock / 64];
+  const int k = g.nblk_k[blockIdx.x];
+  if (k < 0) return;
+  const int s = g.nblk_s[blockIdx.x];
+  const int rbeg = g.part_rows[k], rend = g.part_rows[k + 1];
+  PlainValue f{p};
+  double lsum = 0.0;
+  for (int row0 = rbeg + s * kNarrowRows; row0 < rend; row0 += g.nS * kNarrowRows) {
+    const int nrows = min(kNarrowRows, rend - row0);
+    narrow_row_sums(g, f, row0, nrows, rs, mlist, heavy_partial);
+    if (threadIdx.x < nrows) {
+      const int i = row0 + threadIdx.x;
+      const float pi = p[i], ci = cl[i], si = rs[threadIdx.x];
+      g_z[i] = (ci + q * si) * pi * (1.f - pi);
+      lsum += static_cast<double>(pi) * (static_cast<double>(ci) + 0.5 * static_cast<double>(q) * static_cast<double>(si));
+    }
+    __syncthreads();
+  }
+  lsum = wave_sum(lsum);
+  if (threadIdx.x % 64 == 0) wred[threadIdx.x / 64] = lsum;
+  __syncthreads();
+  if (threadIdx.x == 0) loss_partial[blockIdx.x] = ((wred[0] + wred[1]) + wred[2]) + wred[3];
+}
+
+// One workgroup: thread k sums the partials of subgraph k in launch order.
+__global__ __launch_bounds__(kBlock) void loss_reduce_kernel(GraphView g, const double* __restrict__ partial,
+                                                             double* __restrict__ loss_part,
+                                                             double* __restrict__ loss_out) {
+  __shared__ double tot[kBlock];
+  double mine = 0.0;
+  for (int k = threadIdx.x; k < g.P; k += kBlock) {
+    double acc = 0.0;
+    for (int b = 0; b < g.num_nblocks; ++b)
+      if (g.nblk_k[b] == k) acc += partial[b];
+    loss_part[k] = acc;
+    mine += acc;
+  }
+  tot[threadIdx.x] = mine;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    double acc = 0.0;
+    for (int q = 0; q < kBlock; ++q) acc += tot[q];
+    loss_out[0] = acc;
+  }
+}
+
+// ---------------------------------------------------------------------------
+// Adam on the weight matrices (with the fixed-order reduction of the partials)
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(kBlock) void adam_w_kernel(const int* __restrict__ part_blk_ptr,
+                                                        const int* __restrict__ part_blk_list, int Pw,
+                                                        WeightTensor wt, AdamStep ad, int update) {
+  const int64_t gid = static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x;
+  if (gid >= static_cast<int64_t>(Pw) * wt.elems) return;
+  const int k = static_cast<int>(gid / wt.elems);
+  const int idx = static_cast<int>(gid % wt.elems);
+  float gsum = 0.f;
+  for (int q = part_blk_ptr[k]; q < part_blk_ptr[k + 1]; ++q)
+    gsum += wt.partial[static_cast<size_t>(part_blk_list[q]) * wt.elems + idx];
+  if (wt.grad_out != nullptr) wt.grad_out[gid] = gsum;
+  if (update) {
+    const float m = ad.b1 * wt.m[gid] + (1.f - ad.b1) * gsum;
+    const float v = ad.b2 * wt.v[gid] + (1.f - ad.b2) * gsum * gsum;
+    wt.m[gid] = m;
+    wt.v[gid] = v;
+    wt.W[gid] -= ad.lr * (m * ad.inv_bc1) / (sqrtf(v) * ad.inv_sqrt_bc2 + ad.eps);
+  }
+}
+
+__global__ __launch_bounds__(kBlock) void to_bf16_kernel(const float* __restrict__ src,
+                                                         bf16_t* __restrict__ dst, int64_t count) {
+  const int64_t i = static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x;
+  if (i < count) dst[i] = f32_to_bf16(src[i]);
+}
+
+template <typename K>
+void allow_lds(K kernel, size_t bytes) {
+  if (bytes > 48 * 1024)
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(bytes));
+}
+
+GraphView transposed(const GraphView& g) {
+  GraphView gt = g;
+  gt.sa = g.sb;
+  gt.sb = g.sa;
+  return gt;
+}
+
+}  // namespace
+
+// ---------------------------------------------------------------------------
+// Launchers
+// ---------------------------------------------------------------------------
+#define GCO_DISPATCH_D(T, D, ...)                                   \
+  switch (D) {                                                      \
+    case 8: if (sizeof(T) == 4) { constexpr int DD = 8; __VA_ARGS__; } break;   \
+    case 16: if (sizeof(T) == 4) { constexpr int DD = 16; __VA_ARGS__; } break; \
+    case 32: { constexpr int DD = 32; __VA_ARGS__; } break;         \
+    case 64: { constexpr int DD = 64; __VA_ARGS__; } break;         \
+    case 128: { constexpr int DD = 128; __VA_ARGS__; } break;       \
+    default: break;                                                 \
+  }
+
+template <typename T, int D>
+static void fwd_hidden_t(const Launch& ln, const GraphView& g, const void* X, const float* W,
+                         int w_stride, void* Y, const float* w_out, int wout_stride, float* t,
+                         float* heavy_partial) {
+  if (g.num_chunks > 0) {
+    ln.begin(KK_HEAVY);
+    PlainSrc<T, D> src{static_cast<const T*>(X), g.sb};
+    heavy_wide_kernel<T, D, PlainSrc<T, D>><<<g.num_chunks, kBlock, 0, ln.st>>>(g, src, heavy_partial);
+    ln.end(KK_HEAVY);
+  }
+  const size_t lds = fwd_lds_bytes<D>(Store<T>::VEC);
+  allow_lds(fwd_hidden_kernel<T, D>, lds);
+  ln.begin(KK_FWD_HIDDEN);
+  fwd_hidden_kernel<T, D><<<g.num_blocks, kBlock, lds, ln.st>>>(
+      g, static_cast<const T*>(X), W, w_stride, static_cast<T*>(Y), w_out, wout_stride, t, heavy_partial);
+  ln.end(KK_FWD_HIDDEN);
+}
+
+void launch_fwd_hidden(const Launch& ln, int storage, int D, const GraphView& g, const void* X,
+                       const float* W, int w_stride, void* Y, const float* w_out, int wout_stride,
+                       float* t, float* heavy_partial) {
+  if (storage == GCO_STORAGE_BF16) {
+    GCO_DISPATCH_D(bf16_t, D, (fwd_hidden_t<bf16_t, (DD < 32 ? 32 : DD)>(ln, g, X, W, w_stride, Y, w_out, wout_stride, t, heavy_partial)))
+  } else {
+    GCO_DISPATCH_D(float, D, (fwd_hidden_t<float, DD>(ln, g, X, W, w_stride, Y, w_out, wout_stride, t, heavy_partial)))
+  }
+}
+
+void launch_fwd_gemv(const Launch& ln, int storage, int D, const GraphView& g, const void* X,
+                     const float* w, int w_stride, float* t) {
+  ln.begin(KK_FWD_GEMV);
+  if (storage == GCO_STORAGE_BF16) {
+    GCO_DISPATCH_D(bf16_t, D, (fwd_gemv_kernel<bf16_t, DD><<<g.num_nblocks, kBlock, 0, ln.st>>>(g, static_cast<const bf16_t*>(X), w, w_stride, t)))
+  } else {
+    GCO_DISPATCH_D(float, D, (fwd_gemv_kernel<float, DD><<<g.num_nblocks, kBlock, 0, ln.st>>>(g, static_cast<const float*>(X), w, w_stride, t)))
+  }
+  ln.end(KK_FWD_GEMV);
+}
+
+void launch_fwd_readout(const Launch& ln, const GraphView& g, const float* t, float* z, float* p,
+                        float* heavy_partial) {
+  if (g.num_chunks > 0) {
+    ln.begin(KK_HEAVY);
+    heavy_narrow_kernel<ScaledValue><<<g.num_chunks, kBlock, 0, ln.st>>>(g, ScaledValue{g.sb, t}, heavy_partial);
+    ln.end(KK_HEAVY);
+  }
+  ln.begin(KK_FWD_READOUT);
+  fwd_readout_kernel<<<g.num_nblocks, kBlock, 0, ln.st>>>(g, t, z, p, heavy_partial);
+  ln.end(KK_FWD_READOUT);
+}
+
+void launch_loss(const Launch& ln, const GraphView& g, const float* p, const float* c, float q,
+                 float* g_z, double* loss_partial, float* heavy_partial) {
+  if (g.num_chunks > 0) {
+    ln.begin(KK_HEAVY);
+    heavy_narrow_kernel<PlainValue><<<g.num_chunks, kBlock, 0, ln.st>>>(g, PlainValue{p}, heavy_partial);
+    ln.end(KK_HEAVY);
+  }
+  ln.begin(KK_LOSS);
+  loss_kernel<<<g.num_nblocks, kBlock, 0, ln.st>>>(g, p, c, q, g_z, loss_partial, heavy_partial);
+  ln.end(KK_LOSS);
+}
+
+void launch_loss_reduce(const Launch& ln, const GraphView& g, const double* loss_partial,
+                        double* loss_part, double* loss_out) {
+  ln.begin(KK_LOSS_REDUCE);
+  loss_reduce_kernel<<<1, kBlock, 0, ln.st>>>(g, loss_partial, loss_part, loss_out);
+  ln.end(KK_LOSS_REDUCE);
+}
+
+void launch_bwd_readout(const Launch& ln, const GraphView& g, const float* g_z, float* g_t,
+                        float* heavy_partial) {
+  const GraphView gt = transposed(g);
+  if (g.num_chunks > 0) {
+    ln.begin(KK_HEAVY);
+    heavy_narrow_kernel<ScaledValue><<<g.num_chunks, kBlock, 0, ln.st>>>(gt, ScaledValue{gt.sb, g_z}, heavy_partial);
+    ln.end(KK_HEAVY);
+  }
+  ln.begin(KK_BWD_READOUT);
+  bwd_readout_kernel<<<g.num_nblocks, kBlock, 0, ln.st>>>(gt, g_z, g_t, heavy_partial);
+  ln.end(KK_BWD_READOUT);
+}
+
+template <typename T, int D>
+static void bwd_hidden_t(const Launch& ln, bool last, bool to_embed, const GraphView& g,
+                         const BwdArgs& a) {
+  const GraphView gt = transposed(g);
+  if (g.num_chunks > 0) {
+    ln.begin(KK_HEAVY);
+    if (last) {
+      LastSrc<T, D> src{static_cast<const T*>(a.Hcur), gt.sb, a.g_t, a.w_out, a.wout_stride, {}};
+      heavy_wide_kernel<T, D, LastSrc<T, D>><<<g.num_chunks, kBlock, 0, ln.st>>>(gt, src, a.heavy_partial);
+    } else {
+      PlainSrc<T, D> src{static_cast<const T*>(a.GZ_in), gt.sb};
+      heavy_wide_kernel<T, D, PlainSrc<T, D>><<<g.num_chunks, kBlock, 0, ln.st>>>(gt, src, a.heavy_partial);
+    }
+    ln.end(KK_HEAVY);
+  }
+  const size_t lds = bwd_lds_bytes<D>(Store<T>::VEC);
+  const int kind = to_embed ? KK_BWD_EMBED : KK_BWD_HIDDEN;
+  ln.begin(kind);
+#define GCO_BWD(L_, E_)                                                        \
+  {                                                                            \
+    allow_lds(bwd_hidden_kernel<T, D, L_, E_>, lds);                           \
+    bwd_hidden_kernel<T, D, L_, E_><<<g.num_blocks, kBlock, lds, ln.st>>>(gt, a); \
+  }
+  if (last && to_embed) GCO_BWD(true, true)
+  else if (last) GCO_BWD(true, false)
+  else if (to_embed) GCO_BWD(false, true)
+  else GCO_BWD(false, false)
+#undef GCO_BWD
+  ln.end(kind);
+}
+
+void launch_bwd_hidden(const Launch& ln, int storage, int D, bool last, bool to_embed,
+                       const GraphView& g, const BwdArgs& a) {
+  if (storage == GCO_STORAGE_BF16) {
+    GCO_DISPATCH_D(bf16_t, D, (bwd_hidden_t<bf16_t, (DD < 32 ? 32 : DD)>(ln, last, to_embed, g, a)))
+  } else {
+    GCO_DISPATCH_D(float, D, (bwd_hidden_t<float, DD>(ln, last, to_embed, g, a)))
+  }
+}
+
+void launch_bwd_single(const Launch& ln, int storage, int D, const GraphView& g, const BwdArgs& a) {
+  ln.begin(KK_BWD_EMBED);
+  if (storage == GCO_STORAGE_BF16) {
+    GCO_DISPATCH_D(bf16_t, D, (bwd_single_kernel<bf16_t, DD><<<g.num_blocks, kBlock, 0, ln.st>>>(g, a)))
+  } else {
+    GCO_DISPATCH_D(float, D, (bwd_single_kernel<float, DD><<<g.num_blocks, kBlock, 0, ln.st>>>(g, a)))
+  }
+  ln.end(KK_BWD_EMBED);
+}
+
+void launch_adam_w(const Launch& ln, const GraphView& g, const int* part_blk_ptr,
+                   const int* part_blk_list, int Pw, const WeightTensor& wt, const AdamStep& adam,
+                   bool update) {
+  (void)g;
+  const int64_t total = static_cast<int64_t>(Pw) * wt.elems;
+  const int blocks = static_cast<int>((total + kBlock - 1) / kBlock);
+  ln.begin(KK_ADAM_W);
+  adam_w_kernel<<<blocks, kBlock, 0, ln.st>>>(part_blk_ptr, part_blk_list, Pw, wt, adam, update ? 1 : 0);
+  ln.end(KK_ADAM_W);
+}
+
+void launch_to_bf16(const Launch& ln, const float* src, void* dst, int64_t count) {
+  const int blocks = static_cast<int>((count + kBlock - 1) / kBlock);
+  if (blocks > 0)
+    to_bf16_kernel<<<blocks, kBlock, 0, ln.st>>>(src, static_cast<bf16_t*>(dst), count);
+}
+
+}  // namespace gco

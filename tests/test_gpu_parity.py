@@ -1,0 +1,310 @@
+"""GPU parity: the device library against the fp64 checker, through the C ABI.
+
+Tolerances (norm-wise: max |a - b| / max |b| per tensor):
+  fp32 storage  forward probabilities and every gradient tensor  1e-5
+                ten-epoch loss trajectory                        1e-4
+  bf16 storage  forward probabilities and gradients              2e-2
+The bf16 comparison is against the checker in its bf16-storage mode, so that both
+sides take the ReLU decisions on values of the same precision; probabilities and
+loss are compared with the unrounded fp64 checker as well.
+Integer results (rounding, repair, cross edges, masks) are compared bit for bit.
+"""
+import numpy as np
+import pytest
+
+from oracle import combinatorial as cb
+from oracle import gcn
+from paper_2511_09261_amd import inputs
+from tests import helpers as hp
+
+pytestmark = pytest.mark.gpu
+
+
+# whether the library's bf16 path rounds the operands of the dense transforms
+MATRIX_CORE_OPERANDS = False
+
+
+def rel(a, b):
+    a = np.asarray(a, dtype=np.float64)
+    b = np.asarray(b, dtype=np.float64)
+    return np.abs(a - b).max() / max(np.abs(b).max(), 1e-300)
+
+
+def graph_with_long_rows(n, seed, hubs=(2500, 700, 90), base_deg=4):
+    """Sparse random graph plus a few hub nodes whose degrees span the three
+    row classes of the gather (short, workgroup-wide, pre-reduced)."""
+    rs = np.random.RandomState(seed)
+    m = n * base_deg // 2
+    u = rs.randint(0, n, m)
+    v = rs.randint(0, n, m)
+    us, vs = [u], [v]
+    for h, deg in enumerate(hubs):
+        nb = rs.choice(n, size=min(deg, n - 1), replace=False)
+        us.append(np.full(nb.shape[0], h * 7 + 3))
+        vs.append(nb)
+    return inputs.from_edges(n, np.concatenate(us), np.concatenate(vs))
+
+
+def make_case(kind, seed):
+    if kind == "random":        # several tiles, ragged tails, isolated nodes
+        rs = np.random.RandomState(seed)
+        n = 1500 + 37
+        g = inputs.from_edges(n, rs.randint(0, n, 4000), rs.randint(0, n, 4000))
+        part = rs.randint(0, 5, n).astype(np.int32)
+        part[part == 4] = 3      # subgraph 4 is empty
+        return g, part, 5
+    if kind == "hubs":          # long rows; one subgraph so the hubs stay long
+        g = graph_with_long_rows(6000, seed)
+        return g, None, 1
+    if kind == "hubs_parts":
+        g = graph_with_long_rows(9000, seed, hubs=(5000, 2300, 300))
+        part = (np.arange(9000) % 2).astype(np.int32)
+        return g, part, 2
+    if kind == "bfs12":         # more than 8 subgraphs: the XCD-grouped block map
+        g = inputs.random_regular(3000, 6, seed)
+        return g, inputs.bfs_partition(g, 12, seed), 12
+    raise ValueError(kind)
+
+
+def run_pair(gco, g, part, P, *, problem="mis", L=2, D=16, norm="sym", storage="fp32",
+             share=False, train_embed=True, seed=0, lr=1e-2, extra=None):
+    Pw = 1 if share else P
+    E, Ws = inputs.init_params(g.n, part, Pw, L, D, seed)
+    # larger weights than the training initialisation, so that every term matters
+    Ws = [W * 1.5 for W in Ws]
+    E = (E * 5).astype(np.float32)
+    ctx = gco.Context(problem=problem, num_layers=L, dim=D, norm=norm, storage=storage,
+                      weight_sharing=share, train_embed=train_embed, lr=lr)
+    ctx.upload_graph(g.n, g.rowptr, g.col, part, P)
+    ctx.set_params(E, Ws)
+    if extra is not None:
+        ctx.set_linear_penalty(extra)
+    spec = gcn.Spec(problem=problem, num_layers=L, norm=norm, weight_sharing=share,
+                    train_embed=train_embed, lr=lr,
+                    storage="bf16" if storage == "bf16" else "exact",
+                    matrix_core_operands=MATRIX_CORE_OPERANDS)
+    lg = gcn.local_graph(g.n, g.rowptr, g.col, part, P, norm)
+    return ctx, spec, lg, E, Ws
+
+
+FWD_BWD_CASES = [
+    # kind, problem, L, D, norm, storage, share
+    ("random", "mis", 2, 16, "sym", "fp32", False),
+    ("random", "maxcut", 3, 32, "mean", "fp32", False),
+    ("random", "mis", 1, 8, "sym", "fp32", False),
+    ("random", "mis", 3, 64, "sym", "fp32", True),
+    ("random", "maxcut", 2, 128, "sym", "fp32", False),
+    ("hubs", "mis", 3, 16, "sym", "fp32", False),
+    ("hubs", "mis", 2, 64, "mean", "fp32", False),
+    ("hubs_parts", "maxcut", 3, 32, "sym", "fp32", False),
+    ("bfs12", "mis", 3, 32, "sym", "fp32", False),
+    ("bfs12", "maxcut", 1, 16, "mean", "fp32", True),
+    ("random", "mis", 3, 64, "sym", "bf16", False),
+    ("random", "maxcut", 2, 32, "mean", "bf16", False),
+    ("hubs", "mis", 3, 64, "sym", "bf16", False),
+    ("hubs_parts", "mis", 2, 128, "sym", "bf16", False),
+    ("bfs12", "maxcut", 3, 128, "sym", "bf16", True),
+    ("bfs12", "mis", 1, 64, "sym", "bf16", False),
+]
+
+
+@pytest.mark.parametrize("kind,problem,L,D,norm,storage,share", FWD_BWD_CASES)
+def test_forward_and_gradients_at_fixed_weights(gco, kind, problem, L, D, norm, storage, share):
+    g, part, P = make_case(kind, seed=L * 100 + D)
+    rs = np.random.RandomState(1)
+    extra = (rs.random(g.n) < 0.1).astype(np.float32) * 0.7 if problem == "mis" else None
+    ctx, spec, lg, E, Ws = run_pair(gco, g, part, P, problem=problem, L=L, D=D, norm=norm,
+                                    storage=storage, share=share, extra=extra)
+    tol = 1e-5 if storage == "fp32" else 2e-2
+    cache = gcn.forward(lg, E, Ws, spec)
+    want_loss, want_per = gcn.loss(lg, cache["p"], spec, extra)
+    gE, gWs = gcn.backward(lg, cache, Ws, spec, extra)
+
+    ctx.forward()
+    p = ctx.get_probs()
+    assert rel(p, cache["p"]) <= tol
+    if storage == "bf16":
+        import dataclasses
+        exact = gcn.forward(lg, E, Ws, dataclasses.replace(spec, storage="exact"))
+        assert rel(p, exact["p"]) <= tol
+        assert abs(ctx.loss()[0] - gcn.loss(lg, exact["p"], spec, extra)[0]) <= tol * np.abs(want_per).sum()
+    tot, per = ctx.loss()
+    assert abs(tot - want_loss) <= tol * max(1.0, np.abs(want_per).sum())
+    assert rel(per, want_per) <= tol * 10
+    dE, dWs = ctx.get_grads()
+    assert rel(dE, gE) <= tol
+    for l in range(L):
+        assert rel(dWs[l], gWs[l]) <= tol, f"layer {l + 1}"
+    ctx.destroy()
+
+
+@pytest.mark.parametrize("kind,problem,L,D", [
+    ("random", "mis", 2, 16), ("bfs12", "maxcut", 3, 32), ("hubs", "mis", 3, 64), ("random", "mis", 1, 16)])
+def test_ten_epoch_loss_trajectory_fp32(gco, kind, problem, L, D):
+    g, part, P = make_case(kind, seed=5)
+    ctx, spec, lg, E, Ws = run_pair(gco, g, part, P, problem=problem, L=L, D=D)
+    got = ctx.train(10)
+    st = gcn.init_state(E, Ws)
+    want, _ = gcn.train(lg, st, spec, 10)
+    assert np.abs(got - want).max() <= 1e-4 * np.abs(want).max()
+    # parameters after ten steps stay close as well (Adam amplifies tiny gradient
+    # differences, so this bound is loose and the loss bound above is the contract)
+    E2, W2 = ctx.get_params()
+    assert rel(E2, st.E) <= 5e-3
+    ctx.destroy()
+
+
+def test_frozen_embeddings_and_shared_weights_train(gco):
+    g, part, P = make_case("random", seed=9)
+    ctx, spec, lg, E, Ws = run_pair(gco, g, part, P, L=2, D=16, share=True, train_embed=False)
+    got = ctx.train(5)
+    st = gcn.init_state(E, Ws)
+    want, _ = gcn.train(lg, st, spec, 5)
+    assert np.abs(got - want).max() <= 1e-4 * np.abs(want).max()
+    E2, W2 = ctx.get_params()
+    np.testing.assert_array_equal(E2, E)
+    assert rel(W2[0], st.Ws[0]) <= 1e-3
+    ctx.destroy()
+
+
+def test_parameter_round_trip_and_checkpoint_resume(gco):
+    g, part, P = make_case("bfs12", seed=3)
+    ctx, spec, lg, E, Ws = run_pair(gco, g, part, P, L=3, D=32)
+    E2, W2 = ctx.get_params()
+    np.testing.assert_array_equal(E2, E)          # the node permutation is invisible
+    for a, b in zip(W2, Ws):
+        np.testing.assert_array_equal(a, b.astype(np.float32))
+    l10 = ctx.train(10)
+    Ea, Wa = ctx.get_params()
+    # same run again: bit-identical (no floating-point atomics anywhere)
+    ctx.set_params(E, Ws)
+    np.testing.assert_array_equal(ctx.train(10), l10)
+    np.testing.assert_array_equal(ctx.get_params()[0], Ea)
+    # 5 epochs, save, restore into a fresh context, 5 more
+    ctx.set_params(E, Ws)
+    l5 = ctx.train(5)
+    Em, Wm = ctx.get_params()
+    state = ctx.get_opt_state()
+    ctx.destroy()
+    ctx2 = gco.Context(problem="mis", num_layers=3, dim=32)
+    ctx2.upload_graph(g.n, g.rowptr, g.col, part, P)
+    ctx2.set_params(Em, Wm)
+    ctx2.set_opt_state(*state)
+    l5b = ctx2.train(5)
+    np.testing.assert_array_equal(np.concatenate([l5, l5b]), l10)
+    np.testing.assert_array_equal(ctx2.get_params()[0], Ea)
+    ctx2.destroy()
+
+
+# ------------------------------------------------------------------ integer paths
+
+@pytest.mark.parametrize("kind", ["random", "hubs_parts", "bfs12"])
+def test_cut_edges_cross_mask_conflicts_bit_exact(gco, kind):
+    g, part, P = make_case(kind, seed=2)
+    ctx = gco.Context()
+    ctx.upload_graph(g.n, g.rowptr, g.col, part, P)
+    u, v = ctx.cut_edges()
+    wu, wv = cb.cut_edges_vectorised(g.n, g.rowptr, g.col, part)
+    np.testing.assert_array_equal(u, wu)
+    np.testing.assert_array_equal(v, wv)
+    info = ctx.graph_info()
+    assert info["m_cut"] == len(wu) and info["m"] == g.m and info["m_local"] == g.m - len(wu)
+    np.testing.assert_array_equal(ctx.cross_mask(), cb.cross_mask(g.n, wu, wv))
+    x = (np.random.RandomState(0).random(g.n) < 0.5).astype(np.uint8)
+    cu, cv = ctx.conflict_edges(x)
+    ku, kv = cb.conflict_edges(wu, wv, x)
+    np.testing.assert_array_equal(cu, ku)
+    np.testing.assert_array_equal(cv, kv)
+    ctx.destroy()
+
+
+def test_single_subgraph_has_no_cut_edges(gco):
+    g, _, _ = make_case("random", seed=4)
+    ctx = gco.Context()
+    ctx.upload_graph(g.n, g.rowptr, g.col, None, 1)
+    u, v = ctx.cut_edges()
+    assert len(u) == 0 and ctx.cross_mask().sum() == 0
+    ctx.destroy()
+
+
+@pytest.mark.parametrize("kind,scope", [("random", "local"), ("random", "all"), ("hubs_parts", "all"),
+                                        ("bfs12", "local"), ("hubs", "local")])
+def test_round_and_repair_bit_exact(gco, kind, scope):
+    g, part, P = make_case(kind, seed=6)
+    ctx, spec, lg, E, Ws = run_pair(gco, g, part, P, L=2, D=16)
+    ctx.forward()
+    p = ctx.get_probs()                      # the device's own fp32 probabilities
+    x0, obj0, cb0, ca0 = ctx.round_repair(0.5, "none")
+    np.testing.assert_array_equal(x0, cb.round_probs(p))
+    assert cb0 == ca0 == cb.count_conflicts(g.n, g.rowptr, g.col, part, x0, "all")
+    assert obj0 == x0.sum()
+    x, obj, cbefore, cafter = ctx.round_repair(0.5, scope)
+    want = cb.repair(g.n, g.rowptr, g.col, part, p, x0, scope)
+    np.testing.assert_array_equal(x, want)
+    assert obj == want.sum() and cbefore == cb0
+    assert cafter == cb.count_conflicts(g.n, g.rowptr, g.col, part, want, "all")
+    assert cb.count_conflicts(g.n, g.rowptr, g.col, part, x, scope) == 0
+    assert x0.sum() > 0 and cb0 > 0          # the case exercises the repair
+    ctx.destroy()
+
+
+def test_repair_with_tied_probabilities_on_a_path(gco):
+    """All probabilities equal: the id tie-break alone decides, and the chain
+    of dependencies is as long as the path."""
+    n = 3000
+    rowptr, col = hp.csr_from_edges(n, hp.path(n))
+    ctx = gco.Context(num_layers=1, dim=8)
+    ctx.upload_graph(n, rowptr, col, None, 1)
+    E = np.ones((n, 8), dtype=np.float32)
+    ctx.set_params(E, [np.zeros((1, 8, 1), dtype=np.float32)])   # z = 0, p = 0.5 everywhere
+    ctx.forward()
+    p = ctx.get_probs()
+    assert (p == 0.5).all()
+    x, obj, cbefore, cafter = ctx.round_repair(0.5, "all")
+    np.testing.assert_array_equal(x, (np.arange(n) % 2 == 0).astype(np.uint8))
+    assert obj == n // 2 and cbefore == n - 1 and cafter == 0
+    ctx.destroy()
+
+
+def test_maxcut_objective_is_the_cut_value(gco):
+    g, part, P = make_case("bfs12", seed=8)
+    ctx, spec, lg, E, Ws = run_pair(gco, g, part, P, problem="maxcut", L=2, D=16)
+    ctx.forward()
+    x, obj, _, _ = ctx.round_repair(0.5, "local")     # repair is a no-op for Max-Cut
+    np.testing.assert_array_equal(x, cb.round_probs(ctx.get_probs()))
+    assert obj == cb.cut_value(g.n, g.rowptr, g.col, part, x, "all")
+    ctx.destroy()
+
+
+# ------------------------------------------------------------------ errors
+
+def test_malformed_inputs_are_rejected_with_codes(gco):
+    ctx = gco.Context()
+    with pytest.raises(gco.GcoError) as e:
+        ctx.train(1)
+    assert e.value.code == gco.ESTATE
+    n = 4
+    good_rp, good_col = hp.csr_from_edges(n, [(0, 1), (1, 2)])
+    cases = {
+        "one direction": (np.array([0, 1, 1, 1, 1]), np.array([1])),
+        "self loop": (np.array([0, 2, 2, 2, 2]), np.array([0, 0])),
+        "unsorted": (np.array([0, 2, 3, 4, 4]), np.array([2, 1, 0, 0])),
+        "out of range": (np.array([0, 1, 2, 2, 2]), np.array([9, 0])),
+    }
+    for name, (rp, cl) in cases.items():
+        with pytest.raises(gco.GcoError) as e:
+            ctx.upload_graph(n, rp, cl, None, 1)
+        assert e.value.code == gco.EINVAL, name
+    with pytest.raises(gco.GcoError) as e:
+        ctx.upload_graph(n, good_rp, good_col, np.array([0, 1, 2, 7]), 3)
+    assert e.value.code == gco.EINVAL
+    ctx.upload_graph(n, good_rp, good_col, np.array([0, 0, 1, 1]), 2)    # still usable
+    assert ctx.graph_info() == {"n": 4, "m": 2, "m_local": 1, "m_cut": 1}
+    with pytest.raises(gco.GcoError) as e:
+        ctx.get_probs()
+    assert e.value.code == gco.ESTATE
+    ctx.destroy()
+    with pytest.raises(gco.GcoError):
+        gco.Context(dim=24)
+    with pytest.raises(gco.GcoError):
+        gco.Context(dim=16, storage="bf16")

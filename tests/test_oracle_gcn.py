@@ -289,6 +289,61 @@ def test_edgeless_graph_is_a_per_node_mlp():
     np.testing.assert_allclose(gE, gE_want, rtol=1e-12, atol=1e-15)
 
 
+# ---------------------------------------------------------------- bf16 storage
+
+def test_bfloat16_rounding_rule():
+    """bfloat16 keeps 8 significant bits; halfway cases go to the even neighbour."""
+    u = 2.0 ** -7                                   # spacing of bfloat16 in [1, 2)
+    cases = {
+        1.0: 1.0, 1.0 + u: 1.0 + u, -3.5: -3.5, 0.0: 0.0,
+        1.0 + u / 2: 1.0,                           # tie -> even fraction (0)
+        1.0 + 3 * u / 2: 1.0 + 2 * u,               # tie -> even fraction (2)
+        1.0 + u / 2 + 2.0 ** -20: 1.0 + u,          # just above the tie
+        1.0 + u / 2 - 2.0 ** -20: 1.0,              # just below the tie
+        -(1.0 + 3 * u / 2): -(1.0 + 2 * u),
+        2.0 ** -100 * (1 + u / 4): 2.0 ** -100,
+    }
+    for x, want in cases.items():
+        assert gcn.round_bf16(np.array([x]))[0] == want, x
+    rs = np.random.RandomState(0)
+    x = rs.normal(size=10000) * 10.0 ** rs.randint(-6, 6, 10000)
+    q = gcn.round_bf16(x)
+    assert (np.abs(q - x) <= np.abs(x) * 2.0 ** -8).all()           # half a unit in the last place
+    np.testing.assert_array_equal(gcn.round_bf16(q), q)             # idempotent
+    np.testing.assert_array_equal(gcn.round_bf16(-x), -q)           # odd
+    frac, _ = np.frexp(q)
+    np.testing.assert_array_equal(frac * 256, np.round(frac * 256))  # 8 significant bits
+
+
+def test_bf16_storage_mode_stays_close_and_rounds_the_right_tensors():
+    rs = np.random.RandomState(21)
+    n, d, P, L = 40, 8, 2, 3
+    edges = hp.random_graph(n, 0.15, rs)
+    part = rs.randint(0, P, n)
+    lg = make(n, edges, part, P)
+    E, Ws = rand_params(rs, n, d, L, P)
+    exact = gcn.forward(lg, E, Ws, gcn.Spec(num_layers=L))
+    for mc in (False, True):
+        spec = gcn.Spec(num_layers=L, storage="bf16", matrix_core_operands=mc)
+        out = gcn.forward(lg, E, Ws, spec)
+        assert 0 < np.abs(out["p"] - exact["p"]).max() < 3e-2
+        for H in out["H"]:
+            np.testing.assert_array_equal(gcn.round_bf16(H), H)      # stored tensors are bf16 values
+        np.testing.assert_array_equal(out["H"][0], gcn.round_bf16(E))
+        if mc:
+            np.testing.assert_array_equal(gcn.round_bf16(out["Agg"][1]), out["Agg"][1])
+        # the gradient is the exact derivative of the rounded forward wherever no
+        # rounding intervenes: check dL/dW_L (last layer sees only exact operations)
+        gE, gWs = gcn.backward(lg, out, Ws, spec)
+        h = 1e-6
+        for k in range(P):
+            Wp = [W.copy() for W in Ws]; Wp[L - 1][k, 0, 0] += h
+            Wm = [W.copy() for W in Ws]; Wm[L - 1][k, 0, 0] -= h
+            fd = (gcn.loss(lg, gcn.forward(lg, E, Wp, spec)["p"], spec)[0] -
+                  gcn.loss(lg, gcn.forward(lg, E, Wm, spec)["p"], spec)[0]) / (2 * h)
+            assert abs(fd - gWs[L - 1][k, 0, 0]) < 1e-6 * max(1, abs(fd))
+
+
 # ---------------------------------------------------------------- Adam
 
 def test_adam_closed_forms():
