@@ -145,6 +145,12 @@ int gco_loss(gco_ctx* ctx, double* total, double* per_part);
  * gradients shaped like the parameters. */
 int gco_get_grads(gco_ctx* ctx, float* gE, float* const* gW);
 
+/* Hidden activations H_l of the last forward pass, l in [1, num_layers - 1], as
+ * float[n * dim] in original node order (test hook; bf16 storage is widened to
+ * fp32 exactly).  The ReLU decisions of the backward pass are the signs of
+ * these values. */
+int gco_get_hidden(gco_ctx* ctx, int32_t layer, float* H);
+
 /* Binarise and repair.  x[i] = (p[i] >= thr) on the fp32 probabilities of the
  * last forward (Sec. 3.3, binarisation at 0.5).  For MIS with repair_scope !=
  * NONE, selected nodes are then visited in the order (p descending, id

@@ -180,10 +180,16 @@ def loss(lg: LocalGraph, p, spec: Spec, extra_linear=None):
     return float(per_part.sum()), per_part
 
 
-def backward(lg: LocalGraph, cache: dict, Ws, spec: Spec, extra_linear=None):
+def backward(lg: LocalGraph, cache: dict, Ws, spec: Spec, extra_linear=None, relu_on=None):
     """Exact chain rule through Eq. 5, Eq. 4 and the layers of Eq. 3.
 
-    Returns (gE [n, d], [gW_1 .. gW_L]) with gW_l shaped like W_l."""
+    Returns (gE [n, d], [gW_1 .. gW_L]) with gW_l shaped like W_l.
+
+    relu_on, if given, is a list indexed by layer l of boolean arrays that say
+    where the ReLU of layer l passes the gradient; it replaces the checker's own
+    decision Z_l > 0.  Tests of reduced-precision runs pass the decisions the
+    device took, because a unit whose pre-activation is zero to within rounding
+    may legitimately fall on either side."""
     L = spec.num_layers
     c, q = qubo_coefficients(lg, spec)
     if extra_linear is not None:
@@ -202,7 +208,8 @@ def backward(lg: LocalGraph, cache: dict, Ws, spec: Spec, extra_linear=None):
         g_agg[idx] = np.outer(g_z[idx], WL[kk, :, 0])
     g_H = lg.A_hat.T @ g_agg
     for l in range(L - 1, 0, -1):
-        g_Z = g_H * (cache["Z"][l] > 0.0)             # ReLU, derivative 0 at 0
+        on = (cache["Z"][l] > 0.0) if relu_on is None else relu_on[l]
+        g_Z = g_H * on                                # ReLU, derivative 0 at 0
         if l < L - 1:
             g_Z = _stored(g_Z, spec)                  # kept in memory between two layers
         Wl = np.asarray(Ws[l - 1], dtype=np.float64)

@@ -65,6 +65,7 @@ _PROTOTYPES = {
     "gco_get_probs": (C.c_int, [C.c_void_p, C.c_void_p]),
     "gco_loss": (C.c_int, [C.c_void_p, C.POINTER(C.c_double), C.c_void_p]),
     "gco_get_grads": (C.c_int, [C.c_void_p, C.c_void_p, C.POINTER(C.c_void_p)]),
+    "gco_get_hidden": (C.c_int, [C.c_void_p, C.c_int32, C.c_void_p]),
     "gco_round_repair": (C.c_int, [C.c_void_p, C.c_float, C.c_int32, C.c_void_p] + [C.POINTER(C.c_int64)] * 3),
     "gco_cut_edges": (C.c_int, [C.c_void_p, C.POINTER(C.c_int64), C.c_void_p, C.c_void_p]),
     "gco_cross_mask": (C.c_int, [C.c_void_p, C.c_void_p]),
@@ -275,6 +276,11 @@ class Context:
         gWs = [np.empty(s, dtype=np.float32) for s in self._w_shapes()]
         self._check(self.lib.gco_get_grads(self.h, _ptr(gE), self._ptr_array(gWs)))
         return gE, gWs
+
+    def get_hidden(self, layer):
+        H = np.empty((self.n, self.dim), dtype=np.float32)
+        self._check(self.lib.gco_get_hidden(self.h, layer, _ptr(H)))
+        return H
 
     def round_repair(self, thr=0.5, repair_scope="local"):
         x = np.empty(self.n, dtype=np.uint8)

@@ -106,6 +106,7 @@ struct gco_ctx {
   int32_t* d_part_rows = nullptr;
   int32_t *d_blk_k = nullptr, *d_blk_s = nullptr, *d_nblk_k = nullptr, *d_nblk_s = nullptr;
   int32_t *d_pbl_ptr = nullptr, *d_pbl_list = nullptr;
+  int32_t *d_nbl_ptr = nullptr, *d_nbl_list = nullptr;
   int32_t *d_heavy_of_row = nullptr, *d_heavy_chunk_ptr = nullptr, *d_chunk_begin = nullptr,
           *d_chunk_end = nullptr, *d_chunk_part = nullptr;
   float* d_heavy_partial = nullptr;
@@ -265,6 +266,20 @@ void build_block_map(int P, const std::vector<int>& part_rows, int tile_rows, in
         blk_s.push_back(s);
       }
   }
+}
+
+// Workgroup ids grouped by the subgraph they work on (ascending within a group);
+// with num_sets == 1 every valid workgroup goes to the single group.
+void bucket_blocks(const std::vector<int>& blk_k, int num_sets, std::vector<int>& ptr,
+                   std::vector<int>& list) {
+  ptr.assign(num_sets + 1, 0);
+  for (int k : blk_k)
+    if (k >= 0) ptr[(num_sets == 1 ? 0 : k) + 1]++;
+  for (int q = 0; q < num_sets; ++q) ptr[q + 1] += ptr[q];
+  list.assign(static_cast<size_t>(ptr[num_sets]), 0);
+  std::vector<int> cursor(ptr.begin(), ptr.end() - 1);
+  for (size_t b = 0; b < blk_k.size(); ++b)
+    if (blk_k[b] >= 0) list[cursor[num_sets == 1 ? 0 : blk_k[b]]++] = static_cast<int>(b);
 }
 
 void traffic_model(gco_ctx* ctx) {
@@ -493,16 +508,21 @@ int gco_upload_graph(gco_ctx* ctx, int64_t n64, const int64_t* rowptr, const int
   // workgroups whose weight-gradient partials belong to weight set kw
   {
     const int Pw = ctx->Pw;
-    std::vector<int> ptr(Pw + 1, 0), list;
-    for (int kw = 0; kw < Pw; ++kw) {
-      for (size_t b = 0; b < blk_k.size(); ++b)
-        if (blk_k[b] >= 0 && (Pw == 1 || blk_k[b] == kw)) list.push_back(static_cast<int>(b));
-      ptr[kw + 1] = static_cast<int>(list.size());
-    }
+    std::vector<int> ptr, list;
+    bucket_blocks(blk_k, Pw, ptr, list);
     GALLOC(ctx->d_pbl_ptr, ptr.size());
     GALLOC(ctx->d_pbl_list, std::max<size_t>(1, list.size()));
     HIPCHK(h2d(ctx, ctx->d_pbl_ptr, ptr.data(), ptr.size()));
     HIPCHK(h2d(ctx, ctx->d_pbl_list, list.data(), list.size()));
+  }
+  // narrow workgroups of each subgraph (loss reduction)
+  {
+    std::vector<int> ptr, list;
+    bucket_blocks(nblk_k, P, ptr, list);
+    GALLOC(ctx->d_nbl_ptr, ptr.size());
+    GALLOC(ctx->d_nbl_list, std::max<size_t>(1, list.size()));
+    HIPCHK(h2d(ctx, ctx->d_nbl_ptr, ptr.data(), ptr.size()));
+    HIPCHK(h2d(ctx, ctx->d_nbl_list, list.data(), list.size()));
   }
   // very long rows
   std::vector<int> heavy_of_row, heavy_chunk_ptr(1, 0), chunk_begin, chunk_end, chunk_part;
@@ -556,6 +576,8 @@ int gco_upload_graph(gco_ctx* ctx, int64_t n64, const int64_t* rowptr, const int
   g.nblk_s = ctx->d_nblk_s;
   g.nS = nS;
   g.num_nblocks = static_cast<int>(nblk_k.size());
+  g.nblk_ptr = ctx->d_nbl_ptr;
+  g.nblk_list = ctx->d_nbl_list;
   g.num_heavy = num_heavy;
   g.num_chunks = num_chunks;
   g.heavy_of_row = ctx->d_heavy_of_row;
@@ -898,6 +920,23 @@ int gco_get_grads(gco_ctx* ctx, float* gE, float* const* gW) {
       if (gW[l - 1])
         HIPCHK(d2h(ctx, gW[l - 1], d_gW[l - 1], static_cast<size_t>(ctx->Pw) * w_elems(ctx, l)));
   return GCO_OK;
+}
+
+int gco_get_hidden(gco_ctx* ctx, int32_t layer, float* H) {
+  if (!ctx) return GCO_EINVAL;
+  NEED(ctx->probs_valid, GCO_ESTATE, "no forward pass has run");
+  NEED(H, GCO_EINVAL, "H is NULL");
+  NEED(layer >= 1 && layer <= ctx->cfg.num_layers - 1, GCO_EINVAL, "layer %d has no hidden activation", layer);
+  const size_t nd = static_cast<size_t>(ctx->n) * ctx->cfg.dim;
+  const float* src = static_cast<const float*>(ctx->H[layer]);
+  Scratch tmp(ctx);
+  if (ctx->cfg.storage == GCO_STORAGE_BF16) {
+    float* wide = tmp.get<float>(nd);
+    NEED(wide, GCO_ENOMEM, "device scratch allocation failed");
+    launch_from_bf16(ctx->launch(), ctx->H[layer], wide, static_cast<int64_t>(nd));
+    src = wide;
+  }
+  return download_node_matrix(ctx, H, src);
 }
 
 // ---- read-out -------------------------------------------------------------------

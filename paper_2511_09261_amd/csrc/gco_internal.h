@@ -53,6 +53,9 @@ struct GraphView {
   const int* nblk_s = nullptr;
   int nS = 1;
   int num_nblocks = 0;
+  // narrow workgroups of subgraph k: nblk_list[nblk_ptr[k] .. nblk_ptr[k+1])
+  const int* nblk_ptr = nullptr;
+  const int* nblk_list = nullptr;
   // very long rows, pre-reduced in chunks: row heavy_row[h] owns chunks
   // heavy_chunk_ptr[h] .. heavy_chunk_ptr[h+1]; chunk c covers CSR entries
   // chunk_begin[c] .. chunk_end[c].  heavy_of_row[i] = h or -1.
@@ -148,6 +151,14 @@ struct BwdArgs {
 void launch_bwd_hidden(const Launch& ln, int storage, int D, bool last, bool to_embed,
                        const GraphView& g, const BwdArgs& a);
 
+// bf16-storage, matrix-core versions (layer_kernels_bf16.hip); `gt` already has
+// the scale vectors of A_hat^T.
+void launch_fwd_hidden_bf16(const Launch& ln, int D, const GraphView& g, const void* X, const float* W,
+                            int w_stride, void* Y, const float* w_out, int wout_stride, float* t,
+                            float* heavy_partial);
+void launch_bwd_hidden_bf16(const Launch& ln, int D, bool last, bool to_embed, const GraphView& gt,
+                            const BwdArgs& a);
+
 // L = 1 backward: gw partial = sum_i X[i,:] g_t[i]; gE[i,:] = g_t[i] w^k.
 void launch_bwd_single(const Launch& ln, int storage, int D, const GraphView& g, const BwdArgs& a);
 
@@ -167,6 +178,8 @@ void launch_adam_w(const Launch& ln, const GraphView& g, const int* part_blk_ptr
 
 // fp32 -> bf16 copy (round to nearest even).
 void launch_to_bf16(const Launch& ln, const float* src, void* dst, int64_t count);
+// bf16 -> fp32 copy (exact).
+void launch_from_bf16(const Launch& ln, const void* src, float* dst, int64_t count);
 
 // ---- launchers implemented in graph_kernels.hip ----
 

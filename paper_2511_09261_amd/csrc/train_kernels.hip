@@ -12,6 +12,7 @@
 // Every sum is taken in an order fixed by the launch shape, so results are
 // bit-identical from run to run.
 #include "device_utils.h"
+#include "gather.h"
 #include "gco_internal.h"
 
 namespace gco {
@@ -24,174 +25,17 @@ struct Geo {
   static constexpr int LD = D + 4;  // LDS row pitch in floats (keeps 16-byte alignment)
 };
 
-// ---------------------------------------------------------------------------
-// Sources of gathered rows
-// ---------------------------------------------------------------------------
-
-// v = sb[j] * X[j, c0 .. c0+VEC)
-template <typename T, int D>
-struct PlainSrc {
-  static constexpr int VEC = Store<T>::VEC;
-  const T* X;
-  const float* sb;
-  __device__ __forceinline__ void set_part(int, int) {}
-  __device__ __forceinline__ void load(int j, int c0, float (&v)[VEC]) const {
-    Store<T>::load(X + static_cast<size_t>(j) * D + c0, v);
-    const float s = sb[j];
+// Where the fp32 kernels leave the gathered rows: an fp32 LDS tile [R][LD].
+template <int D>
+struct TileSink {
+  float* tile;
+  template <int VEC>
+  __device__ __forceinline__ void put_vec(int r, int c0, const float (&v)[VEC]) const {
 #pragma unroll
-    for (int x = 0; x < VEC; ++x) v[x] *= s;
+    for (int x = 0; x < VEC; ++x) tile[r * Geo<D>::LD + c0 + x] = v[x];
   }
+  __device__ __forceinline__ void put_one(int r, int c, float v) const { tile[r * Geo<D>::LD + c] = v; }
 };
-
-// Gradient of the last hidden layer's pre-activation, formed on the fly:
-// v = sb[j] * g_t[j] * w_out[c] * [H[j, c] > 0]
-template <typename T, int D>
-struct LastSrc {
-  static constexpr int VEC = Store<T>::VEC;
-  const T* H;
-  const float* sb;
-  const float* g_t;
-  const float* w_out;  // [Pw, D]
-  int wout_stride;
-  float w[VEC];
-  __device__ __forceinline__ void set_part(int k, int c0) {
-#pragma unroll
-    for (int x = 0; x < VEC; ++x) w[x] = w_out[static_cast<size_t>(k) * wout_stride + c0 + x];
-  }
-  __device__ __forceinline__ void load(int j, int c0, float (&v)[VEC]) const {
-    Store<T>::load(H + static_cast<size_t>(j) * D + c0, v);
-    const float s = sb[j] * g_t[j];
-#pragma unroll
-    for (int x = 0; x < VEC; ++x) v[x] = v[x] > 0.f ? s * w[x] : 0.f;
-  }
-};
-
-// acc += sum over entries e0, e0+stride, ... < e1 of src(col[e]); four rows in flight.
-template <class Src>
-__device__ __forceinline__ void gather_range(const Src& src, const int* __restrict__ col, int e0,
-                                             int e1, int stride, int c0,
-                                             float (&acc)[Src::VEC]) {
-  constexpr int VEC = Src::VEC;
-  int e = e0;
-  for (; e + 3 * stride < e1; e += 4 * stride) {
-    const int j0 = col[e], j1 = col[e + stride], j2 = col[e + 2 * stride], j3 = col[e + 3 * stride];
-    float v0[VEC], v1[VEC], v2[VEC], v3[VEC];
-    src.load(j0, c0, v0);
-    src.load(j1, c0, v1);
-    src.load(j2, c0, v2);
-    src.load(j3, c0, v3);
-#pragma unroll
-    for (int x = 0; x < VEC; ++x) acc[x] = (((acc[x] + v0[x]) + v1[x]) + v2[x]) + v3[x];
-  }
-  for (; e < e1; e += stride) {
-    float v0[VEC];
-    src.load(col[e], c0, v0);
-#pragma unroll
-    for (int x = 0; x < VEC; ++x) acc[x] += v0[x];
-  }
-}
-
-// Phase 1: tile[r, :] = sa_i * ( src(i) + sum_{j in N(i)} src(j) ) for the rows
-// row0 .. row0+nrows of the tile; rows nrows..R are zero-filled.
-// LDS: tile [R][LD], red [kBlock * VEC], hlist [R + 1].
-template <typename T, int D, class Src>
-__device__ void aggregate_tile(const GraphView& g, const Src& src, int row0, int nrows,
-                               float* tile, float* red, int* hlist,
-                               const float* __restrict__ heavy_partial) {
-  constexpr int VEC = Store<T>::VEC;
-  constexpr int LPR = D / VEC;        // lanes per feature row
-  constexpr int G = kBlock / LPR;     // lane groups per workgroup
-  constexpr int LD = Geo<D>::LD;
-  const int tid = threadIdx.x;
-  const int grp = tid / LPR;
-  const int c0 = (tid % LPR) * VEC;
-  if (tid == 0) hlist[0] = 0;
-  __syncthreads();
-  for (int r = grp; r < R; r += G) {
-    float acc[VEC];
-    if (r >= nrows) {
-#pragma unroll
-      for (int x = 0; x < VEC; ++x) tile[r * LD + c0 + x] = 0.f;
-      continue;
-    }
-    const int i = row0 + r;
-    const int e0 = g.rowptr[i], e1 = g.rowptr[i + 1];
-    const int h = g.num_heavy > 0 ? g.heavy_of_row[i] : -1;
-    if (h < 0 && e1 - e0 > kLightMax) {
-      if (tid % LPR == 0) {
-        const int q = atomicAdd(&hlist[0], 1);
-        hlist[1 + q] = r;
-      }
-      continue;
-    }
-    src.load(i, c0, acc);  // the self loop of A + I
-    if (h >= 0) {
-      for (int ch = g.heavy_chunk_ptr[h]; ch < g.heavy_chunk_ptr[h + 1]; ++ch) {
-        const float4* pp = reinterpret_cast<const float4*>(heavy_partial + static_cast<size_t>(ch) * D + c0);
-#pragma unroll
-        for (int x = 0; x < VEC; x += 4) {
-          const float4 q4 = pp[x / 4];
-          acc[x] += q4.x; acc[x + 1] += q4.y; acc[x + 2] += q4.z; acc[x + 3] += q4.w;
-        }
-      }
-    } else {
-      gather_range(src, g.col, e0, e1, 1, c0, acc);
-    }
-    const float sa = g.sa[i];
-#pragma unroll
-    for (int x = 0; x < VEC; ++x) tile[r * LD + c0 + x] = sa * acc[x];
-  }
-  __syncthreads();
-  const int nh = hlist[0];
-  for (int q = 0; q < nh; ++q) {
-    const int r = hlist[1 + q];
-    const int i = row0 + r;
-    const int e0 = g.rowptr[i], e1 = g.rowptr[i + 1];
-    float acc[VEC];
-    if (grp == 0) {
-      src.load(i, c0, acc);
-    } else {
-#pragma unroll
-      for (int x = 0; x < VEC; ++x) acc[x] = 0.f;
-    }
-    gather_range(src, g.col, e0 + grp, e1, G, c0, acc);
-#pragma unroll
-    for (int x = 0; x < VEC; ++x) red[grp * D + c0 + x] = acc[x];
-    __syncthreads();
-    if (tid < D) {
-      float s = 0.f;
-      for (int gq = 0; gq < G; ++gq) s += red[gq * D + tid];
-      tile[r * LD + tid] = g.sa[i] * s;
-    }
-    __syncthreads();
-  }
-}
-
-// Chunked pre-reduction of very long rows: partial[c, :] = sum_{e in chunk c} src(col[e]).
-template <typename T, int D, class Src>
-__global__ __launch_bounds__(kBlock) void heavy_wide_kernel(GraphView g, Src src, float* partial) {
-  constexpr int VEC = Store<T>::VEC;
-  constexpr int LPR = D / VEC;
-  constexpr int G = kBlock / LPR;
-  __shared__ float red[kBlock * VEC];
-  const int ch = blockIdx.x;
-  const int tid = threadIdx.x;
-  const int grp = tid / LPR;
-  const int c0 = (tid % LPR) * VEC;
-  src.set_part(g.chunk_part[ch], c0);
-  float acc[VEC];
-#pragma unroll
-  for (int x = 0; x < VEC; ++x) acc[x] = 0.f;
-  gather_range(src, g.col, g.chunk_begin[ch] + grp, g.chunk_end[ch], G, c0, acc);
-#pragma unroll
-  for (int x = 0; x < VEC; ++x) red[grp * D + c0 + x] = acc[x];
-  __syncthreads();
-  if (tid < D) {
-    float s = 0.f;
-    for (int gq = 0; gq < G; ++gq) s += red[gq * D + tid];
-    partial[static_cast<size_t>(ch) * D + tid] = s;
-  }
-}
 
 // ---------------------------------------------------------------------------
 // Dense transform of an LDS tile (fp32 FMA form)
@@ -267,7 +111,7 @@ __global__ __launch_bounds__(kBlock) void fwd_hidden_kernel(GraphView g, const T
   const int c = tid % D, rg = tid / D;
   for (int row0 = rbeg + s * R; row0 < rend; row0 += g.S * R) {
     const int nrows = min(R, rend - row0);
-    aggregate_tile<T, D>(g, src, row0, nrows, tile, red, hlist, heavy_partial);
+    aggregate_tile<T, D>(g, src, TileSink<D>{tile}, row0, nrows, red, hlist, heavy_partial);
     __syncthreads();
     float out[NR];
     tile_times_matrix<D>(tile, Wl, out);
@@ -356,9 +200,9 @@ __global__ __launch_bounds__(kBlock) void bwd_hidden_kernel(GraphView g, BwdArgs
   for (int row0 = rbeg + s * R; row0 < rend; row0 += g.S * R) {
     const int nrows = min(R, rend - row0);
     if (LAST)
-      aggregate_tile<T, D>(g, lsrc, row0, nrows, tile, red, hlist, a.heavy_partial);
+      aggregate_tile<T, D>(g, lsrc, TileSink<D>{tile}, row0, nrows, red, hlist, a.heavy_partial);
     else
-      aggregate_tile<T, D>(g, psrc, row0, nrows, tile, red, hlist, a.heavy_partial);
+      aggregate_tile<T, D>(g, psrc, TileSink<D>{tile}, row0, nrows, red, hlist, a.heavy_partial);
     // Hprev tile -> LDS (fp32), zero beyond the tile's rows
     for (int idx = tid; idx < R * LPR; idx += kBlock) {
       const int r = idx / LPR, cc = (idx % LPR) * VEC;
@@ -612,19 +456,23 @@ __global__ __launch_bounds__(kBlock) void loss_kernel(GraphView g, const float* 
   if (threadIdx.x == 0) loss_partial[blockIdx.x] = ((wred[0] + wred[1]) + wred[2]) + wred[3];
 }
 
-// One workgroup: thread k sums the partials of subgraph k in launch order.
+// One workgroup.  Each wavefront takes subgraphs k = wave, wave + 4, ...: its
+// lanes sum the workgroup partials of k in a strided, fixed order, then the
+// wavefront total is formed by a butterfly.  Thread 0 adds the subgraph values.
 __global__ __launch_bounds__(kBlock) void loss_reduce_kernel(GraphView g, const double* __restrict__ partial,
                                                              double* __restrict__ loss_part,
                                                              double* __restrict__ loss_out) {
+  const int wave = threadIdx.x / 64, lane = threadIdx.x % 64;
+  for (int k = wave; k < g.P; k += kBlock / 64) {
+    double acc = 0.0;
+    for (int q = g.nblk_ptr[k] + lane; q < g.nblk_ptr[k + 1]; q += 64) acc += partial[g.nblk_list[q]];
+    acc = wave_sum(acc);
+    if (lane == 0) loss_part[k] = acc;
+  }
+  __syncthreads();
   __shared__ double tot[kBlock];
   double mine = 0.0;
-  for (int k = threadIdx.x; k < g.P; k += kBlock) {
-    double acc = 0.0;
-    for (int b = 0; b < g.num_nblocks; ++b)
-      if (g.nblk_k[b] == k) acc += partial[b];
-    loss_part[k] = acc;
-    mine += acc;
-  }
+  for (int k = threadIdx.x; k < g.P; k += kBlock) mine += loss_part[k];
   tot[threadIdx.x] = mine;
   __syncthreads();
   if (threadIdx.x == 0) {
@@ -661,6 +509,12 @@ __global__ __launch_bounds__(kBlock) void to_bf16_kernel(const float* __restrict
                                                          bf16_t* __restrict__ dst, int64_t count) {
   const int64_t i = static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x;
   if (i < count) dst[i] = f32_to_bf16(src[i]);
+}
+
+__global__ __launch_bounds__(kBlock) void from_bf16_kernel(const bf16_t* __restrict__ src,
+                                                           float* __restrict__ dst, int64_t count) {
+  const int64_t i = static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x;
+  if (i < count) dst[i] = bf16_to_f32(src[i]);
 }
 
 template <typename K>
@@ -714,7 +568,7 @@ void launch_fwd_hidden(const Launch& ln, int storage, int D, const GraphView& g,
                        const float* W, int w_stride, void* Y, const float* w_out, int wout_stride,
                        float* t, float* heavy_partial) {
   if (storage == GCO_STORAGE_BF16) {
-    GCO_DISPATCH_D(bf16_t, D, (fwd_hidden_t<bf16_t, (DD < 32 ? 32 : DD)>(ln, g, X, W, w_stride, Y, w_out, wout_stride, t, heavy_partial)))
+    launch_fwd_hidden_bf16(ln, D, g, X, W, w_stride, Y, w_out, wout_stride, t, heavy_partial);
   } else {
     GCO_DISPATCH_D(float, D, (fwd_hidden_t<float, DD>(ln, g, X, W, w_stride, Y, w_out, wout_stride, t, heavy_partial)))
   }
@@ -809,7 +663,7 @@ static void bwd_hidden_t(const Launch& ln, bool last, bool to_embed, const Graph
 void launch_bwd_hidden(const Launch& ln, int storage, int D, bool last, bool to_embed,
                        const GraphView& g, const BwdArgs& a) {
   if (storage == GCO_STORAGE_BF16) {
-    GCO_DISPATCH_D(bf16_t, D, (bwd_hidden_t<bf16_t, (DD < 32 ? 32 : DD)>(ln, last, to_embed, g, a)))
+    launch_bwd_hidden_bf16(ln, D, last, to_embed, transposed(g), a);
   } else {
     GCO_DISPATCH_D(float, D, (bwd_hidden_t<float, DD>(ln, last, to_embed, g, a)))
   }
@@ -840,6 +694,12 @@ void launch_to_bf16(const Launch& ln, const float* src, void* dst, int64_t count
   const int blocks = static_cast<int>((count + kBlock - 1) / kBlock);
   if (blocks > 0)
     to_bf16_kernel<<<blocks, kBlock, 0, ln.st>>>(src, static_cast<bf16_t*>(dst), count);
+}
+
+void launch_from_bf16(const Launch& ln, const void* src, float* dst, int64_t count) {
+  const int blocks = static_cast<int>((count + kBlock - 1) / kBlock);
+  if (blocks > 0)
+    from_bf16_kernel<<<blocks, kBlock, 0, ln.st>>>(static_cast<const bf16_t*>(src), dst, count);
 }
 
 }  // namespace gco
