@@ -105,10 +105,13 @@ struct gco_ctx {
   float *d_sa = nullptr, *d_sb = nullptr, *d_cbase = nullptr, *d_c = nullptr;
   int32_t* d_part_rows = nullptr;
   int32_t *d_blk_k = nullptr, *d_blk_s = nullptr, *d_nblk_k = nullptr, *d_nblk_s = nullptr;
+  int32_t *d_blk_S = nullptr, *d_nblk_S = nullptr;
   int32_t *d_pbl_ptr = nullptr, *d_pbl_list = nullptr;
   int32_t *d_nbl_ptr = nullptr, *d_nbl_list = nullptr;
   int32_t *d_heavy_of_row = nullptr, *d_heavy_chunk_ptr = nullptr, *d_chunk_begin = nullptr,
           *d_chunk_end = nullptr, *d_chunk_part = nullptr;
+  int32_t* d_heavy_rows = nullptr;
+  int2 *d_ent = nullptr, *d_ent_t = nullptr;
   float* d_heavy_partial = nullptr;
   GraphView gv;
   std::vector<void*> graph_allocs;
@@ -234,37 +237,74 @@ int w_elems(const gco_ctx* ctx, int l /*1..L*/) {
   return l < ctx->cfg.num_layers ? D * D : D;
 }
 
-// Workgroup -> (subgraph, first tile) tables.  With at least 8 subgraphs the
-// workgroups of one subgraph are given ids that are equal modulo 8, so that
+// Workgroup -> (subgraph k, first tile s, stride S_k) tables: workgroup b walks
+// tiles s, s + S_k, s + 2 S_k, ... of subgraph k.  S_k is proportional to the
+// subgraph's share of the work (rows and CSR entries), at least
+// ceil(tiles_k / max_tiles_per_block), at most tiles_k.  With 8 subgraphs or
+// more, all workgroups of a subgraph get ids that are equal modulo 8, so that
 // they land on one XCD and share its L2 (workgroups are dealt to the 8 XCDs
-// round-robin by id).
-void build_block_map(int P, const std::vector<int>& part_rows, int tile_rows, int target_blocks,
-                     std::vector<int>& blk_k, std::vector<int>& blk_s, int& S) {
-  int max_tiles = 1;
-  for (int k = 0; k < P; ++k)
-    max_tiles = std::max(max_tiles, (part_rows[k + 1] - part_rows[k] + tile_rows - 1) / tile_rows);
-  S = std::max(1, std::min(max_tiles, (target_blocks + P - 1) / P));
+// round-robin by id); subgraphs are spread over the XCDs longest-first.
+void build_block_map(int P, const std::vector<int>& part_rows, const std::vector<int32_t>& lrowptr,
+                     int tile_rows, int target_blocks, int max_tiles_per_block,
+                     std::vector<int>& blk_k, std::vector<int>& blk_s, std::vector<int>& blk_S) {
+  std::vector<int> tiles(P), Sk(P);
+  std::vector<double> work(P);
+  double total = 0;
+  for (int k = 0; k < P; ++k) {
+    const int rows = part_rows[k + 1] - part_rows[k];
+    tiles[k] = (rows + tile_rows - 1) / tile_rows;
+    work[k] = 2.0 * rows + (lrowptr[part_rows[k + 1]] - lrowptr[part_rows[k]]);
+    total += work[k];
+  }
+  for (int k = 0; k < P; ++k) {
+    int want = total > 0 ? static_cast<int>(std::lround(target_blocks * work[k] / total)) : 1;
+    if (max_tiles_per_block > 0)
+      want = std::max(want, (tiles[k] + max_tiles_per_block - 1) / max_tiles_per_block);
+    Sk[k] = std::max(1, std::min(tiles[k], want));
+    if (tiles[k] == 0) Sk[k] = 0;
+  }
   blk_k.clear();
   blk_s.clear();
+  blk_S.clear();
   if (P >= 8) {
-    const int groups = (P + 7) / 8;
-    const int nb = groups * S * 8;
-    blk_k.assign(nb, -1);
-    blk_s.assign(nb, 0);
-    for (int b = 0; b < nb; ++b) {
-      const int xcd = b % 8, q = b / 8;
-      const int k = (q / S) * 8 + xcd;
-      if (k < P) {
-        blk_k[b] = k;
-        blk_s[b] = q % S;
+    std::vector<int> order(P);
+    for (int k = 0; k < P; ++k) order[k] = k;
+    std::stable_sort(order.begin(), order.end(), [&](int x, int y) { return Sk[x] > Sk[y]; });
+    std::vector<std::vector<int>> per_xcd(8);   // unit = k * 2^? not needed: store (k, s) pairs flat
+    std::vector<std::vector<int>> per_xcd_s(8);
+    for (int k : order) {
+      int best = 0;
+      for (int x = 1; x < 8; ++x)
+        if (per_xcd[x].size() < per_xcd[best].size()) best = x;
+      for (int sidx = 0; sidx < Sk[k]; ++sidx) {
+        per_xcd[best].push_back(k);
+        per_xcd_s[best].push_back(sidx);
       }
     }
+    size_t depth = 0;
+    for (int x = 0; x < 8; ++x) depth = std::max(depth, per_xcd[x].size());
+    blk_k.assign(depth * 8, -1);
+    blk_s.assign(depth * 8, 0);
+    blk_S.assign(depth * 8, 1);
+    for (int x = 0; x < 8; ++x)
+      for (size_t q = 0; q < per_xcd[x].size(); ++q) {
+        const size_t b = q * 8 + x;
+        blk_k[b] = per_xcd[x][q];
+        blk_s[b] = per_xcd_s[x][q];
+        blk_S[b] = Sk[per_xcd[x][q]];
+      }
   } else {
     for (int k = 0; k < P; ++k)
-      for (int s = 0; s < S; ++s) {
+      for (int sidx = 0; sidx < Sk[k]; ++sidx) {
         blk_k.push_back(k);
-        blk_s.push_back(s);
+        blk_s.push_back(sidx);
+        blk_S.push_back(Sk[k]);
       }
+  }
+  if (blk_k.empty()) {  // keep the grid non-empty
+    blk_k.push_back(-1);
+    blk_s.push_back(0);
+    blk_S.push_back(1);
   }
 }
 
@@ -491,16 +531,30 @@ int gco_upload_graph(gco_ctx* ctx, int64_t n64, const int64_t* rowptr, const int
   launch_scales(st, n, ctx->d_lrowptr, ctx->cfg.norm, ctx->cfg.problem, ctx->cfg.beta, ctx->d_sa,
                 ctx->d_sb, ctx->d_cbase);
   launch_linear_coeff(st, n, ctx->d_cbase, nullptr, ctx->d_perm, ctx->d_c);
+  // packed {column, column scale} entries of A_hat and of its transpose
+  GALLOC(ctx->d_ent, static_cast<size_t>(ctx->nnz_loc));
+  launch_pack_entries(st, ctx->nnz_loc, ctx->d_lcol, ctx->d_sb, ctx->d_ent);
+  if (ctx->cfg.norm == GCO_NORM_SYM) {
+    ctx->d_ent_t = ctx->d_ent;  // symmetric normalisation: A_hat^T = A_hat
+  } else {
+    GALLOC(ctx->d_ent_t, static_cast<size_t>(ctx->nnz_loc));
+    launch_pack_entries(st, ctx->nnz_loc, ctx->d_lcol, ctx->d_sa, ctx->d_ent_t);
+  }
 
   // work decomposition
-  std::vector<int> blk_k, blk_s, nblk_k, nblk_s;
-  int S = 1, nS = 1;
-  build_block_map(P, part_rows, kTileRows, 1024, blk_k, blk_s, S);
-  build_block_map(P, part_rows, kNarrowRows, 1024, nblk_k, nblk_s, nS);
+  std::vector<int> blk_k, blk_s, blk_S, nblk_k, nblk_s, nblk_S;
+  build_block_map(P, part_rows, lrowptr, kTileRows, kWideBlocks, kMaxTilesPerBlock, blk_k, blk_s, blk_S);
+  // width-1 kernels: one 256-row tile per workgroup
+  build_block_map(P, part_rows, lrowptr, kNarrowRows, std::numeric_limits<int>::max() / 2, 1, nblk_k,
+                  nblk_s, nblk_S);
   GALLOC(ctx->d_blk_k, blk_k.size());
   GALLOC(ctx->d_blk_s, blk_s.size());
   GALLOC(ctx->d_nblk_k, nblk_k.size());
   GALLOC(ctx->d_nblk_s, nblk_s.size());
+  GALLOC(ctx->d_blk_S, blk_S.size());
+  GALLOC(ctx->d_nblk_S, nblk_S.size());
+  HIPCHK(h2d(ctx, ctx->d_blk_S, blk_S.data(), blk_S.size()));
+  HIPCHK(h2d(ctx, ctx->d_nblk_S, nblk_S.data(), nblk_S.size()));
   HIPCHK(h2d(ctx, ctx->d_blk_k, blk_k.data(), blk_k.size()));
   HIPCHK(h2d(ctx, ctx->d_blk_s, blk_s.data(), blk_s.size()));
   HIPCHK(h2d(ctx, ctx->d_nblk_k, nblk_k.data(), nblk_k.size()));
@@ -525,7 +579,7 @@ int gco_upload_graph(gco_ctx* ctx, int64_t n64, const int64_t* rowptr, const int
     HIPCHK(h2d(ctx, ctx->d_nbl_list, list.data(), list.size()));
   }
   // very long rows
-  std::vector<int> heavy_of_row, heavy_chunk_ptr(1, 0), chunk_begin, chunk_end, chunk_part;
+  std::vector<int> heavy_of_row, heavy_rows, heavy_chunk_ptr(1, 0), chunk_begin, chunk_end, chunk_part;
   int num_heavy = 0;
   {
     int k = 0;
@@ -535,6 +589,7 @@ int gco_upload_graph(gco_ctx* ctx, int64_t n64, const int64_t* rowptr, const int
       if (deg >= kHeavyMin) {
         if (heavy_of_row.empty()) heavy_of_row.assign(n, -1);
         heavy_of_row[r] = num_heavy++;
+        heavy_rows.push_back(r);
         for (int e = lrowptr[r]; e < lrowptr[r + 1]; e += kChunk) {
           chunk_begin.push_back(e);
           chunk_end.push_back(std::min(e + kChunk, lrowptr[r + 1]));
@@ -547,6 +602,8 @@ int gco_upload_graph(gco_ctx* ctx, int64_t n64, const int64_t* rowptr, const int
   const int num_chunks = static_cast<int>(chunk_begin.size());
   if (num_heavy > 0) {
     GALLOC(ctx->d_heavy_of_row, static_cast<size_t>(n));
+    GALLOC(ctx->d_heavy_rows, heavy_rows.size());
+    HIPCHK(h2d(ctx, ctx->d_heavy_rows, heavy_rows.data(), heavy_rows.size()));
     GALLOC(ctx->d_heavy_chunk_ptr, heavy_chunk_ptr.size());
     GALLOC(ctx->d_chunk_begin, chunk_begin.size());
     GALLOC(ctx->d_chunk_end, chunk_end.size());
@@ -570,17 +627,20 @@ int gco_upload_graph(gco_ctx* ctx, int64_t n64, const int64_t* rowptr, const int
   g.part_rows = ctx->d_part_rows;
   g.blk_k = ctx->d_blk_k;
   g.blk_s = ctx->d_blk_s;
-  g.S = S;
+  g.blk_S = ctx->d_blk_S;
   g.num_blocks = static_cast<int>(blk_k.size());
   g.nblk_k = ctx->d_nblk_k;
   g.nblk_s = ctx->d_nblk_s;
-  g.nS = nS;
+  g.nblk_S = ctx->d_nblk_S;
   g.num_nblocks = static_cast<int>(nblk_k.size());
   g.nblk_ptr = ctx->d_nbl_ptr;
   g.nblk_list = ctx->d_nbl_list;
   g.num_heavy = num_heavy;
   g.num_chunks = num_chunks;
   g.heavy_of_row = ctx->d_heavy_of_row;
+  g.heavy_rows = ctx->d_heavy_rows;
+  g.ent = ctx->d_ent;
+  g.ent_t = ctx->d_ent_t;
   g.heavy_chunk_ptr = ctx->d_heavy_chunk_ptr;
   g.chunk_begin = ctx->d_chunk_begin;
   g.chunk_end = ctx->d_chunk_end;

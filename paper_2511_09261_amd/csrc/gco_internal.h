@@ -18,6 +18,8 @@ constexpr int kNarrowRows = 256; // rows of one tile in the width-1 kernels
 constexpr int kLightMax = 64;    // rows with more local neighbours are reduced by the whole block
 constexpr int kHeavyMin = 2048;  // rows with at least this many neighbours are pre-reduced in chunks
 constexpr int kChunk = 512;      // neighbours per chunk of a pre-reduced row
+constexpr int kWideBlocks = 2048;        // workgroups aimed at by the wide kernels
+constexpr int kMaxTilesPerBlock = 16;    // tiles one wide workgroup may own
 
 enum KernelKind : int {
   KK_FWD_HIDDEN = 0,   // aggregate + transform + ReLU of one hidden layer (Eq. 3)
@@ -42,16 +44,21 @@ struct GraphView {
   const int* col = nullptr;       // [nnz]
   const float* sa = nullptr;      // [n] row scale of A_hat   (A_hat_ij = sa_i * sb_j)
   const float* sb = nullptr;      // [n] column scale of A_hat
+  // the CSR entries again, packed as {column, bits of the column scale sb[column]};
+  // ent_t carries sa[column] instead (the entries of A_hat^T)
+  const int2* ent = nullptr;      // [nnz]
+  const int2* ent_t = nullptr;    // [nnz]
   const int* part_rows = nullptr; // [P+1] first row of each subgraph
-  // wide kernels: workgroup b works on tiles s, s+S, ... of subgraph blk_k[b]
+  // wide kernels: workgroup b works on tiles blk_s[b], + blk_S[b], + 2 blk_S[b], ...
+  // of subgraph blk_k[b] (blk_k[b] < 0: nothing to do)
   const int* blk_k = nullptr;
   const int* blk_s = nullptr;
-  int S = 1;
+  const int* blk_S = nullptr;
   int num_blocks = 0;
   // narrow kernels: same scheme with kNarrowRows-row tiles
   const int* nblk_k = nullptr;
   const int* nblk_s = nullptr;
-  int nS = 1;
+  const int* nblk_S = nullptr;
   int num_nblocks = 0;
   // narrow workgroups of subgraph k: nblk_list[nblk_ptr[k] .. nblk_ptr[k+1])
   const int* nblk_ptr = nullptr;
@@ -62,6 +69,7 @@ struct GraphView {
   int num_heavy = 0;
   int num_chunks = 0;
   const int* heavy_of_row = nullptr;  // [n]
+  const int* heavy_rows = nullptr;    // [num_heavy] ascending row ids
   const int* heavy_chunk_ptr = nullptr;
   const int* chunk_begin = nullptr;
   const int* chunk_end = nullptr;

@@ -203,6 +203,15 @@ __global__ __launch_bounds__(kBlock) void scales_kernel(int n, const int32_t* __
   c_base[r] = problem == GCO_PROBLEM_MAXCUT ? -static_cast<float>(deg) : -beta;
 }
 
+__global__ __launch_bounds__(kBlock) void pack_entries_kernel(int64_t nnz, const int32_t* __restrict__ col,
+                                                              const float* __restrict__ scale,
+                                                              int2* __restrict__ ent) {
+  const int64_t e = static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x;
+  if (e >= nnz) return;
+  const int j = col[e];
+  ent[e] = make_int2(j, __float_as_int(scale[j]));
+}
+
 // c[r] = c_base[r] + extra_orig[perm[r]]
 __global__ __launch_bounds__(kBlock) void linear_coeff_kernel(int n, const float* __restrict__ c_base,
                                                               const float* __restrict__ extra_orig,
@@ -359,28 +368,41 @@ __global__ __launch_bounds__(kBlock) void edge_counts_kernel(int n, const int64_
                                                              const int32_t* __restrict__ col,
                                                              const uint8_t* __restrict__ x,
                                                              unsigned long long* __restrict__ counts) {
-  const int i = blockIdx.x * (kBlock / 64) + threadIdx.x / 64;
-  if (i >= n) return;
-  const int lane = threadIdx.x % 64;
-  const int xi = x[i];
-  int both = 0, differ = 0;
-  for (int64_t e = rowptr[i] + lane; e < rowptr[i + 1]; e += 64) {
-    const int j = col[e];
-    if (j > i) {
-      const int xj = x[j];
-      both += (xi & xj);
-      differ += (xi ^ xj);
+  // one wavefront per row, 16 rows per wavefront; integer sums are combined per
+  // workgroup before the three atomics, so the totals are exact and contention is low
+  __shared__ unsigned int part[3][kBlock / 64];
+  const int lane = threadIdx.x % 64, wave = threadIdx.x / 64;
+  unsigned int sel = 0, both = 0, differ = 0;
+  for (int q = 0; q < 16; ++q) {
+    const int i = (blockIdx.x * 16 + q) * (kBlock / 64) + wave;
+    if (i >= n) break;
+    const int xi = x[i];
+    if (lane == 0) sel += xi;
+    for (int64_t e = rowptr[i] + lane; e < rowptr[i + 1]; e += 64) {
+      const int j = col[e];
+      if (j > i) {
+        const int xj = x[j];
+        both += (xi & xj);
+        differ += (xi ^ xj);
+      }
     }
   }
 #pragma unroll
   for (int off = 32; off > 0; off >>= 1) {
+    sel += __shfl_xor(sel, off, 64);
     both += __shfl_xor(both, off, 64);
     differ += __shfl_xor(differ, off, 64);
   }
   if (lane == 0) {
-    if (xi) atomicAdd(&counts[0], 1ull);
-    if (both) atomicAdd(&counts[1], static_cast<unsigned long long>(both));
-    if (differ) atomicAdd(&counts[2], static_cast<unsigned long long>(differ));
+    part[0][wave] = sel;
+    part[1][wave] = both;
+    part[2][wave] = differ;
+  }
+  __syncthreads();
+  if (threadIdx.x < 3) {
+    unsigned long long tot = 0;
+    for (int w = 0; w < kBlock / 64; ++w) tot += part[threadIdx.x][w];
+    if (tot) atomicAdd(&counts[threadIdx.x], tot);
   }
 }
 
@@ -416,6 +438,10 @@ void launch_local_fill(hipStream_t st, int n, const int64_t* rowptr, const int32
 void launch_scales(hipStream_t st, int n, const int32_t* lrowptr, int norm, int problem, float beta,
                    float* sa, float* sb, float* c_base) {
   scales_kernel<<<blocks_for(n, kBlock), kBlock, 0, st>>>(n, lrowptr, norm, problem, beta, sa, sb, c_base);
+}
+
+void launch_pack_entries(hipStream_t st, int64_t nnz, const int32_t* col, const float* scale, int2* ent) {
+  if (nnz > 0) pack_entries_kernel<<<blocks_for(nnz, kBlock), kBlock, 0, st>>>(nnz, col, scale, ent);
 }
 
 void launch_linear_coeff(hipStream_t st, int n, const float* c_base, const float* extra_orig,
@@ -468,7 +494,7 @@ void launch_state_to_x(hipStream_t st, int n, const uint8_t* state, uint8_t* x) 
 
 void launch_edge_counts(hipStream_t st, int n, const int64_t* rowptr, const int32_t* col,
                         const uint8_t* x, unsigned long long* counts) {
-  edge_counts_kernel<<<blocks_for(n, kBlock / 64), kBlock, 0, st>>>(n, rowptr, col, x, counts);
+  edge_counts_kernel<<<blocks_for(n, 16 * (kBlock / 64)), kBlock, 0, st>>>(n, rowptr, col, x, counts);
 }
 
 void launch_fill_u32(hipStream_t st, void* dst, int64_t count, uint32_t value) {

@@ -13,8 +13,18 @@
 // and as [feature][row] for the weight gradient, which is contracted over rows.
 // Row pitches are padded by 16 bytes, which spreads 16 consecutive rows over all
 // 64 LDS banks for 16-byte reads.
+//
+// The gather is organised to keep many loads in flight, because its address
+// chain (row pointer -> entry -> feature row) is otherwise paid serially:
+//   * the row pointers of every tile a workgroup owns are read into LDS once;
+//   * CSR entries are packed as {column, scale} pairs; the entries and the own
+//     rows of tile q+1 are requested before tile q is gathered and parked in
+//     registers, then committed to LDS when tile q is done;
+//   * a lane group gathers its rows of the tile together, eight 16-byte row
+//     slices per lane in flight, and sums them in a fixed order.
+#include <type_traits>
+
 #include "device_utils.h"
-#include "gather.h"
 #include "gco_internal.h"
 
 namespace gco {
@@ -37,6 +47,10 @@ struct MG {
   static constexpr int NTM = (MT + WPC - 1) / WPC;      // row tiles per wave
   static constexpr int NGW = (NT * NT + 3) / 4;         // weight-gradient tiles per wave
   static constexpr int LPR = D / 8;                     // lanes per feature row (16 bytes each)
+  static constexpr int G = kBlock / LPR;                // lane groups per workgroup
+  static constexpr int NCH = R / G;                     // rows of a tile per lane group
+  static constexpr int UNR = 8 / NCH;                   // entries per row requested together
+  static_assert(NCH >= 1 && NCH * G == R && UNR >= 1, "tile rows must divide over the lane groups");
   static constexpr int PO = D + 4;                      // pitch of the fp32 staging tile
   static constexpr size_t at_bytes = static_cast<size_t>(R) * PA * 2;
   static constexpr size_t tt_bytes = static_cast<size_t>(D) * PT * 2;
@@ -85,6 +99,301 @@ struct BfSink {
   }
 };
 
+constexpr int kEntCap = 512;                 // CSR entries of a tile kept in LDS
+constexpr int kEntPerThread = kEntCap / kBlock;
+
+__device__ __forceinline__ void unpack8(const uint4& x, float (&v)[8]) {
+  v[0] = __uint_as_float(x.x << 16); v[1] = __uint_as_float(x.x & 0xffff0000u);
+  v[2] = __uint_as_float(x.y << 16); v[3] = __uint_as_float(x.y & 0xffff0000u);
+  v[4] = __uint_as_float(x.z << 16); v[5] = __uint_as_float(x.z & 0xffff0000u);
+  v[6] = __uint_as_float(x.w << 16); v[7] = __uint_as_float(x.w & 0xffff0000u);
+}
+
+// Gather sources.  A source names the feature matrix whose rows are gathered,
+// the scale of the own row (self loop) and of an entry, and how a raw 16-byte
+// slice is added to the accumulator.
+template <int D>
+struct PlainB {  // acc += scale * X[j, c0..c0+8)
+  const bf16_t* X;
+  const float* sb;
+  __device__ __forceinline__ void set_part(int, int) {}
+  __device__ __forceinline__ float own_scale(int i) const { return sb[i]; }
+  __device__ __forceinline__ float entry_scale(int, float w) const { return w; }
+  __device__ __forceinline__ void apply(const uint4& raw, float sc, float (&acc)[8]) const {
+    float v[8];
+    unpack8(raw, v);
+#pragma unroll
+    for (int x = 0; x < 8; ++x) acc[x] = fmaf(sc, v[x], acc[x]);
+  }
+};
+
+template <int D>
+struct LastB {  // gradient of the last hidden pre-activation, formed on the fly:
+                // acc += scale * g_t[j] * w_out[c] * [H[j, c] > 0]
+  const bf16_t* X;
+  const float* sb;
+  const float* g_t;
+  const float* w_out;
+  int wout_stride;
+  float w[8];
+  __device__ __forceinline__ void set_part(int k, int c0) {
+#pragma unroll
+    for (int x = 0; x < 8; ++x) w[x] = w_out[static_cast<size_t>(k) * wout_stride + c0 + x];
+  }
+  __device__ __forceinline__ float own_scale(int i) const { return sb[i] * g_t[i]; }
+  __device__ __forceinline__ float entry_scale(int j, float we) const { return we * g_t[j]; }
+  __device__ __forceinline__ void apply(const uint4& raw, float sc, float (&acc)[8]) const {
+    float v[8];
+    unpack8(raw, v);
+#pragma unroll
+    for (int x = 0; x < 8; ++x) acc[x] += v[x] > 0.f ? sc * w[x] : 0.f;
+  }
+};
+
+// What a thread holds of the next tile while the current one is worked on.
+template <int D>
+struct TileRegs {
+  uint4 own[MG<D>::NCH];        // its slices of the tile's own rows (zero beyond the last row)
+  int2 ent[kEntPerThread];      // its share of the tile's CSR entries
+  bool in_lds;                  // the tile's entries fit the LDS buffer
+};
+
+template <int D, class Src>
+__device__ __forceinline__ void prefetch_tile(const GraphView& g, const Src& src, int row0, int nrows,
+                                              const int* rpq, TileRegs<D>& tr) {
+  using M = MG<D>;
+  const int tid = threadIdx.x;
+  const int grp = tid / M::LPR, c0 = (tid % M::LPR) * 8;
+#pragma unroll
+  for (int u = 0; u < M::NCH; ++u) {
+    const int r = grp + M::G * u;
+    tr.own[u] = make_uint4(0u, 0u, 0u, 0u);
+    if (r < nrows)
+      tr.own[u] = *reinterpret_cast<const uint4*>(src.X + static_cast<size_t>(row0 + r) * D + c0);
+  }
+  const int e_base = rpq[0], E = rpq[R] - e_base;
+  tr.in_lds = E <= kEntCap;
+#pragma unroll
+  for (int x = 0; x < kEntPerThread; ++x) {
+    const int idx = tid + kBlock * x;
+    tr.ent[x] = make_int2(0, 0);
+    if (tr.in_lds && idx < E) tr.ent[x] = g.ent[e_base + idx];
+  }
+}
+
+// out[u] = this thread's 16-byte slice of row row0 + grp + G * u of `base` (zero past nrows).
+template <int D>
+__device__ __forceinline__ void prefetch_rows(const bf16_t* base, int row0, int nrows,
+                                              uint4 (&out)[MG<D>::NCH]) {
+  using M = MG<D>;
+  const int grp = threadIdx.x / M::LPR, c0 = (threadIdx.x % M::LPR) * 8;
+#pragma unroll
+  for (int u = 0; u < M::NCH; ++u) {
+    const int r = grp + M::G * u;
+    out[u] = make_uint4(0u, 0u, 0u, 0u);
+    if (r < nrows) out[u] = *reinterpret_cast<const uint4*>(base + static_cast<size_t>(row0 + r) * D + c0);
+  }
+}
+
+template <int D>
+__device__ __forceinline__ void commit_entries(const TileRegs<D>& tr, int2* ents) {
+  if (tr.in_lds) {
+#pragma unroll
+    for (int x = 0; x < kEntPerThread; ++x) ents[threadIdx.x + kBlock * x] = tr.ent[x];
+  }
+}
+
+__device__ __forceinline__ int find_heavy(const GraphView& g, int i) {
+  int lo = 0, hi = g.num_heavy - 1;
+  while (lo < hi) {
+    const int mid = (lo + hi) >> 1;
+    if (g.heavy_rows[mid] < i) lo = mid + 1; else hi = mid;
+  }
+  return lo;
+}
+
+// Rows row0 .. row0+nrows of A_hat times the source matrix, into `sink`
+// (rows nrows..R get zeros).  `rpq` holds the tile's R + 1 row pointers (LDS),
+// `ents` the tile's entries if in_lds, `own` the thread's slices of the own rows.
+// hlist[0] must be 0 on entry.  Ends with a barrier.
+template <int D, class Src, class Sink>
+__device__ void gather_tile(const GraphView& g, const Src& src, const Sink& sink, int row0, int nrows,
+                            const int* rpq, const int2* ents, bool in_lds,
+                            const uint4 (&own)[MG<D>::NCH], float* red, int* hlist,
+                            const float* __restrict__ heavy_partial) {
+  using M = MG<D>;
+  const int tid = threadIdx.x;
+  const int grp = tid / M::LPR, c0 = (tid % M::LPR) * 8;
+  const int e_base = rpq[0];
+  const auto entry = [&](int e) -> int2 { return in_lds ? ents[e - e_base] : g.ent[e]; };
+  float acc[M::NCH][8];
+  int pos[M::NCH], end[M::NCH];
+  float sa[M::NCH];
+  bool direct[M::NCH];  // this lane group finishes the row itself
+#pragma unroll
+  for (int u = 0; u < M::NCH; ++u) {
+    const int r = grp + M::G * u;
+#pragma unroll
+    for (int x = 0; x < 8; ++x) acc[u][x] = 0.f;
+    pos[u] = end[u] = 0;
+    sa[u] = 0.f;
+    direct[u] = true;
+    if (r < nrows) {
+      const int i = row0 + r;
+      const int ea = rpq[r], eb = rpq[r + 1];
+      const int deg = eb - ea;
+      sa[u] = g.sa[i];
+      if (deg >= kHeavyMin) {          // pre-reduced in chunks
+        src.apply(own[u], src.own_scale(i), acc[u]);
+        const int h = find_heavy(g, i);
+        for (int ch = g.heavy_chunk_ptr[h]; ch < g.heavy_chunk_ptr[h + 1]; ++ch) {
+          const float4* pp = reinterpret_cast<const float4*>(heavy_partial + static_cast<size_t>(ch) * D + c0);
+          const float4 p0 = pp[0], p1 = pp[1];
+          acc[u][0] += p0.x; acc[u][1] += p0.y; acc[u][2] += p0.z; acc[u][3] += p0.w;
+          acc[u][4] += p1.x; acc[u][5] += p1.y; acc[u][6] += p1.z; acc[u][7] += p1.w;
+        }
+      } else if (deg > kLightMax) {    // left to the whole workgroup
+        direct[u] = false;
+        if (tid % M::LPR == 0) {
+          const int q = atomicAdd(&hlist[0], 1);
+          hlist[1 + q] = r;
+        }
+      } else {
+        src.apply(own[u], src.own_scale(i), acc[u]);
+        pos[u] = ea;
+        end[u] = eb;
+      }
+    }
+  }
+  // rounds: UNR entries of each of the group's rows are requested together
+  for (;;) {
+    bool more = false;
+#pragma unroll
+    for (int u = 0; u < M::NCH; ++u) more = more || pos[u] < end[u];
+    if (!more) break;
+    uint4 raw[M::NCH][M::UNR];
+    float sc[M::NCH][M::UNR];
+#pragma unroll
+    for (int u = 0; u < M::NCH; ++u) {
+#pragma unroll
+      for (int x = 0; x < M::UNR; ++x) {
+        const int e = pos[u] + x;
+        raw[u][x] = make_uint4(0u, 0u, 0u, 0u);
+        sc[u][x] = 0.f;
+        if (e < end[u]) {
+          const int2 en = entry(e);
+          raw[u][x] = *reinterpret_cast<const uint4*>(src.X + static_cast<size_t>(en.x) * D + c0);
+          sc[u][x] = src.entry_scale(en.x, __int_as_float(en.y));
+        }
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < M::NCH; ++u) {
+#pragma unroll
+      for (int x = 0; x < M::UNR; ++x) src.apply(raw[u][x], sc[u][x], acc[u]);
+      pos[u] += M::UNR;
+    }
+  }
+#pragma unroll
+  for (int u = 0; u < M::NCH; ++u) {
+    const int r = grp + M::G * u;
+    if (direct[u]) {
+#pragma unroll
+      for (int x = 0; x < 8; ++x) acc[u][x] *= sa[u];
+      sink.template put_vec<8>(r, c0, acc[u]);
+    }
+  }
+  __syncthreads();
+  const int nh = hlist[0];
+  for (int q = 0; q < nh; ++q) {  // rows summed by all lane groups together
+    const int r = hlist[1 + q];
+    const int i = row0 + r;
+    const int ea = rpq[r], eb = rpq[r + 1];
+    float a8[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    if (grp == 0) {
+      const uint4 self = *reinterpret_cast<const uint4*>(src.X + static_cast<size_t>(i) * D + c0);
+      src.apply(self, src.own_scale(i), a8);
+    }
+    for (int e = ea + grp; e < eb; e += 4 * M::G) {
+      uint4 rw[4];
+      float s4[4];
+#pragma unroll
+      for (int x = 0; x < 4; ++x) {
+        const int ee = e + x * M::G;
+        rw[x] = make_uint4(0u, 0u, 0u, 0u);
+        s4[x] = 0.f;
+        if (ee < eb) {
+          const int2 en = entry(ee);
+          rw[x] = *reinterpret_cast<const uint4*>(src.X + static_cast<size_t>(en.x) * D + c0);
+          s4[x] = src.entry_scale(en.x, __int_as_float(en.y));
+        }
+      }
+#pragma unroll
+      for (int x = 0; x < 4; ++x) src.apply(rw[x], s4[x], a8);
+    }
+#pragma unroll
+    for (int x = 0; x < 8; ++x) red[grp * D + c0 + x] = a8[x];
+    __syncthreads();
+    if (tid < D) {
+      float sum = 0.f;
+      for (int gq = 0; gq < M::G; ++gq) sum += red[gq * D + tid];
+      sink.put_one(r, tid, g.sa[i] * sum);
+    }
+    __syncthreads();
+  }
+}
+
+// Chunked pre-reduction of very long rows: partial[c, :] = sum over the entries of chunk c.
+template <int D, class Src>
+__global__ __launch_bounds__(kBlock) void heavy_wide_b_kernel(GraphView g, Src src, float* partial) {
+  using M = MG<D>;
+  __shared__ float red[kBlock * 8];
+  const int ch = blockIdx.x;
+  const int tid = threadIdx.x;
+  const int grp = tid / M::LPR, c0 = (tid % M::LPR) * 8;
+  src.set_part(g.chunk_part[ch], c0);
+  float a8[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  const int eb = g.chunk_end[ch];
+  for (int e = g.chunk_begin[ch] + grp; e < eb; e += 4 * M::G) {
+    uint4 rw[4];
+    float s4[4];
+#pragma unroll
+    for (int x = 0; x < 4; ++x) {
+      const int ee = e + x * M::G;
+      rw[x] = make_uint4(0u, 0u, 0u, 0u);
+      s4[x] = 0.f;
+      if (ee < eb) {
+        const int2 en = g.ent[ee];
+        rw[x] = *reinterpret_cast<const uint4*>(src.X + static_cast<size_t>(en.x) * D + c0);
+        s4[x] = src.entry_scale(en.x, __int_as_float(en.y));
+      }
+    }
+#pragma unroll
+    for (int x = 0; x < 4; ++x) src.apply(rw[x], s4[x], a8);
+  }
+#pragma unroll
+  for (int x = 0; x < 8; ++x) red[grp * D + c0 + x] = a8[x];
+  __syncthreads();
+  if (tid < D) {
+    float sum = 0.f;
+    for (int gq = 0; gq < M::G; ++gq) sum += red[gq * D + tid];
+    partial[static_cast<size_t>(ch) * D + tid] = sum;
+  }
+}
+
+// Row pointers of every tile this workgroup owns -> LDS: rp[q * (R + 1) + t] is
+// the pointer of row min(row0_q + t, rend), so rows past the subgraph are empty.
+__device__ __forceinline__ int preload_row_pointers(const GraphView& g, int rbeg, int rend, int s,
+                                                    int S, int* rp) {
+  const int tiles = (rend - rbeg + R - 1) / R;
+  const int Q = tiles > s ? (tiles - s + S - 1) / S : 0;
+  for (int idx = threadIdx.x; idx < Q * (R + 1); idx += kBlock) {
+    const int q = idx / (R + 1), t = idx % (R + 1);
+    rp[idx] = g.rowptr[min(rbeg + (s + q * S) * R + t, rend)];
+  }
+  return Q;
+}
+
 // acc[q] = (rows of row tile tm) x (this wave's column tile), contracted over the D features.
 template <int D>
 __device__ __forceinline__ void tile_product(const bf16_t* at, const bf16x8 (&bfrag)[MG<D>::KS],
@@ -107,13 +416,17 @@ __device__ __forceinline__ void tile_product(const bf16_t* at, const bf16x8 (&bf
   }
 }
 
+constexpr size_t kGatherLds = kBlock * 8 * sizeof(float)                      // red
+                              + kEntCap * sizeof(int2)                        // ents
+                              + kMaxTilesPerBlock * (R + 1) * sizeof(int)     // rp
+                              + (R + 4) * sizeof(int);                        // hlist
 template <int D>
 constexpr size_t fwd_lds() {
-  return MG<D>::at_bytes + kBlock * 8 * sizeof(float) + D * sizeof(float) + (R + 4) * sizeof(int);
+  return MG<D>::at_bytes + kGatherLds + D * sizeof(float);
 }
 template <int D>
 constexpr size_t bwd_lds() {
-  return MG<D>::at_bytes + 2 * MG<D>::tt_bytes + kBlock * 8 * sizeof(float) + (R + 4) * sizeof(int);
+  return MG<D>::at_bytes + 2 * MG<D>::tt_bytes + kGatherLds;
 }
 
 // ---------------------------------------------------------------------------
@@ -128,14 +441,18 @@ __global__ __launch_bounds__(kBlock) void fwd_hidden_bf16_kernel(
   extern __shared__ __align__(16) unsigned char smem[];
   bf16_t* at = reinterpret_cast<bf16_t*>(smem);
   float* red = reinterpret_cast<float*>(smem + M::at_bytes);
-  float* wo = red + kBlock * 8;
-  int* hlist = reinterpret_cast<int*>(wo + D);
+  int2* ents = reinterpret_cast<int2*>(red + kBlock * 8);
+  int* rp = reinterpret_cast<int*>(ents + kEntCap);
+  int* hlist = rp + kMaxTilesPerBlock * (R + 1);
+  float* wo = reinterpret_cast<float*>(hlist + R + 4);
 
   const int k = g.blk_k[blockIdx.x];
   if (k < 0) return;
-  const int s = g.blk_s[blockIdx.x];
+  const int s = g.blk_s[blockIdx.x], S = g.blk_S[blockIdx.x];
   const int tid = threadIdx.x, lane = tid % 64, wave = tid / 64;
   const int tn = wave % M::NT, tm0 = wave / M::NT;
+  const int rbeg = g.part_rows[k], rend = g.part_rows[k + 1];
+  const int Q = preload_row_pointers(g, rbeg, rend, s, S, rp);
   const float* Wk = W + static_cast<size_t>(k) * w_stride;
   // B operand: B[kk][j] = W[kk][j], j = tn * 32 + lane % 32, kept in registers
   bf16x8 bfrag[M::KS];
@@ -147,23 +464,38 @@ __global__ __launch_bounds__(kBlock) void fwd_hidden_bf16_kernel(
     bfrag[ks] = as_frag(pack8(v));
   }
   if (w_out != nullptr && tid < D) wo[tid] = w_out[static_cast<size_t>(k) * wout_stride + tid];
-  PlainSrc<bf16_t, D> src{X, g.sb};
+  const PlainB<D> src{X, g.sb};
   const BfSink<D, false> sink{at, nullptr};
-  const int rbeg = g.part_rows[k], rend = g.part_rows[k + 1];
-  for (int row0 = rbeg + s * R; row0 < rend; row0 += g.S * R) {
+  __syncthreads();  // row pointers are in LDS
+  TileRegs<D> next;
+  if (Q > 0) prefetch_tile<D>(g, src, rbeg + s * R, min(R, rend - (rbeg + s * R)), rp, next);
+  for (int q = 0; q < Q; ++q) {
+    const int row0 = rbeg + (s + q * S) * R;
     const int nrows = min(R, rend - row0);
-    aggregate_tile<bf16_t, D>(g, src, sink, row0, nrows, red, hlist, heavy_partial);
+    const int* rpq = rp + q * (R + 1);
+    uint4 own[M::NCH];
+#pragma unroll
+    for (int u = 0; u < M::NCH; ++u) own[u] = next.own[u];
+    const bool in_lds = next.in_lds;
+    commit_entries<D>(next, ents);
+    if (tid == 0) hlist[0] = 0;
+    __syncthreads();
+    if (q + 1 < Q) {
+      const int row1 = row0 + S * R;
+      prefetch_tile<D>(g, src, row1, min(R, rend - row1), rpq + (R + 1), next);
+    }
+    gather_tile<D>(g, src, sink, row0, nrows, rpq, ents, in_lds, own, red, hlist, heavy_partial);
     floatx16 acc[M::NTM];
     tile_product<D>(at, bfrag, tm0, acc);
     __syncthreads();  // every wave has read its A fragments: the tile can be reused for Y
 #pragma unroll
-    for (int q = 0; q < M::NTM; ++q) {
-      const int tm = tm0 + q * M::WPC;
+    for (int qq = 0; qq < M::NTM; ++qq) {
+      const int tm = tm0 + qq * M::WPC;
       if (tm < M::MT) {
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
           const int i = tm * 32 + (r / 4) * 8 + (lane / 32) * 4 + r % 4;
-          at[i * M::PA + tn * 32 + lane % 32] = f32_to_bf16(fmaxf(acc[q][r], 0.f));
+          at[i * M::PA + tn * 32 + lane % 32] = f32_to_bf16(fmaxf(acc[qq][r], 0.f));
         }
       }
     }
@@ -190,6 +522,16 @@ __global__ __launch_bounds__(kBlock) void fwd_hidden_bf16_kernel(
 // ---------------------------------------------------------------------------
 // Backward of a hidden layer (see BwdArgs in gco_internal.h)
 // ---------------------------------------------------------------------------
+template <int D, bool LAST>
+__device__ __host__ __forceinline__ typename std::conditional<LAST, LastB<D>, PlainB<D>>::type make_src(
+    const BwdArgs& a, const GraphView& g) {
+  if constexpr (LAST) {
+    return LastB<D>{static_cast<const bf16_t*>(a.Hcur), g.sb, a.g_t, a.w_out, a.wout_stride, {}};
+  } else {
+    return PlainB<D>{static_cast<const bf16_t*>(a.GZ_in), g.sb};
+  }
+}
+
 template <int D, bool LAST, bool TO_EMBED>
 __global__ __launch_bounds__(kBlock) void bwd_hidden_bf16_kernel(GraphView g, BwdArgs a) {
   using M = MG<D>;
@@ -198,16 +540,19 @@ __global__ __launch_bounds__(kBlock) void bwd_hidden_bf16_kernel(GraphView g, Bw
   bf16_t* gtt = reinterpret_cast<bf16_t*>(smem + M::at_bytes);               // G_T [feature][row]
   bf16_t* hpt = reinterpret_cast<bf16_t*>(smem + M::at_bytes + M::tt_bytes); // Hprev [feature][row]
   float* red = reinterpret_cast<float*>(smem + M::at_bytes + 2 * M::tt_bytes);
-  int* hlist = reinterpret_cast<int*>(red + kBlock * 8);
+  int2* ents = reinterpret_cast<int2*>(red + kBlock * 8);
+  int* rp = reinterpret_cast<int*>(ents + kEntCap);
+  int* hlist = rp + kMaxTilesPerBlock * (R + 1);
   float* stage = reinterpret_cast<float*>(smem);  // fp32 [R][PO], over at + gtt, after the products
 
   const int k = g.blk_k[blockIdx.x];
   if (k < 0) return;
-  const int s = g.blk_s[blockIdx.x];
+  const int s = g.blk_s[blockIdx.x], S = g.blk_S[blockIdx.x];
   const int tid = threadIdx.x, lane = tid % 64, wave = tid / 64;
   const int tn = wave % M::NT, tm0 = wave / M::NT;
+  const int rbeg = g.part_rows[k], rend = g.part_rows[k + 1];
+  const int Q = preload_row_pointers(g, rbeg, rend, s, S, rp);
   const bf16_t* Hprev = static_cast<const bf16_t*>(a.Hprev);
-  const bf16_t* Hcur = static_cast<const bf16_t*>(a.Hcur);
   const float* Wk = a.W + static_cast<size_t>(k) * a.w_stride;
   const bool need_gh = !(TO_EMBED && a.mode == EMBED_SKIP);
   // B operand of G_H = G_T W^T: B[b][j] = W[j][b], j = tn * 32 + lane % 32
@@ -222,10 +567,10 @@ __global__ __launch_bounds__(kBlock) void bwd_hidden_bf16_kernel(GraphView g, Bw
     v[4] = w1.x; v[5] = w1.y; v[6] = w1.z; v[7] = w1.w;
     wfrag[ks] = as_frag(pack8(v));
   }
-  PlainSrc<bf16_t, D> psrc{static_cast<const bf16_t*>(a.GZ_in), g.sb};
-  LastSrc<bf16_t, D> lsrc{Hcur, g.sb, a.g_t, a.w_out, a.wout_stride, {}};
   const int c0 = (tid % M::LPR) * 8;  // this thread's feature slice in row-chunk loops
-  if (LAST) lsrc.set_part(k, c0);
+  using Src = typename std::conditional<LAST, LastB<D>, PlainB<D>>::type;
+  Src src = make_src<D, LAST>(a, g);
+  src.set_part(k, c0);
   const BfSink<D, true> sink{at, gtt};
 
   floatx16 gw[M::NGW];
@@ -235,19 +580,39 @@ __global__ __launch_bounds__(kBlock) void bwd_hidden_bf16_kernel(GraphView g, Bw
     for (int r = 0; r < 16; ++r) gw[q][r] = 0.f;
   float gwo[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 
-  const int rbeg = g.part_rows[k], rend = g.part_rows[k + 1];
-  for (int row0 = rbeg + s * R; row0 < rend; row0 += g.S * R) {
+  __syncthreads();  // row pointers are in LDS
+  TileRegs<D> next;
+  uint4 hp_next[M::NCH];
+  if (Q > 0) {
+    const int nr0 = min(R, rend - (rbeg + s * R));
+    prefetch_tile<D>(g, src, rbeg + s * R, nr0, rp, next);
+    prefetch_rows<D>(Hprev, rbeg + s * R, nr0, hp_next);
+  }
+  for (int qt = 0; qt < Q; ++qt) {
+    const int row0 = rbeg + (s + qt * S) * R;
     const int nrows = min(R, rend - row0);
-    if (LAST)
-      aggregate_tile<bf16_t, D>(g, lsrc, sink, row0, nrows, red, hlist, a.heavy_partial);
-    else
-      aggregate_tile<bf16_t, D>(g, psrc, sink, row0, nrows, red, hlist, a.heavy_partial);
-    // Hprev tile, transposed into LDS (zero beyond the tile's rows)
-    for (int idx = tid; idx < R * M::LPR; idx += kBlock) {
-      const int r = idx / M::LPR;
-      uint4 v = make_uint4(0u, 0u, 0u, 0u);
-      if (r < nrows) v = *reinterpret_cast<const uint4*>(Hprev + static_cast<size_t>(row0 + r) * D + c0);
-      const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+    const int* rpq = rp + qt * (R + 1);
+    uint4 own[M::NCH], hp[M::NCH];
+#pragma unroll
+    for (int u = 0; u < M::NCH; ++u) {
+      own[u] = next.own[u];
+      hp[u] = hp_next[u];
+    }
+    const bool in_lds = next.in_lds;
+    commit_entries<D>(next, ents);
+    if (tid == 0) hlist[0] = 0;
+    __syncthreads();
+    if (qt + 1 < Q) {
+      const int row1 = row0 + S * R;
+      prefetch_tile<D>(g, src, row1, min(R, rend - row1), rpq + (R + 1), next);
+      prefetch_rows<D>(Hprev, row1, min(R, rend - row1), hp_next);
+    }
+    gather_tile<D>(g, src, sink, row0, nrows, rpq, ents, in_lds, own, red, hlist, a.heavy_partial);
+    // Hprev tile (prefetched), transposed into LDS; zero beyond the tile's rows
+#pragma unroll
+    for (int u = 0; u < M::NCH; ++u) {
+      const int r = tid / M::LPR + M::G * u;
+      const uint32_t w[4] = {hp[u].x, hp[u].y, hp[u].z, hp[u].w};
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
         hpt[(c0 + 2 * q) * M::PT + r] = static_cast<bf16_t>(w[q] & 0xffffu);
@@ -255,7 +620,7 @@ __global__ __launch_bounds__(kBlock) void bwd_hidden_bf16_kernel(GraphView g, Bw
       }
       if (LAST && r < nrows) {  // gradient of w_out: sum_r Hcur[r, c] * g_t[r]
         float h[8];
-        Store<bf16_t>::load(Hcur + static_cast<size_t>(row0 + r) * D + c0, h);
+        unpack8(own[u], h);
         const float gt = a.g_t[row0 + r];
 #pragma unroll
         for (int x = 0; x < 8; ++x) gwo[x] = fmaf(h[x], gt, gwo[x]);
@@ -394,8 +759,8 @@ void fwd_t(const Launch& ln, const GraphView& g, const void* X, const float* W, 
            const float* w_out, int wout_stride, float* t, float* heavy_partial) {
   if (g.num_chunks > 0) {
     ln.begin(KK_HEAVY);
-    PlainSrc<bf16_t, D> src{static_cast<const bf16_t*>(X), g.sb};
-    heavy_wide_kernel<bf16_t, D, PlainSrc<bf16_t, D>><<<g.num_chunks, kBlock, 0, ln.st>>>(g, src, heavy_partial);
+    const PlainB<D> src{static_cast<const bf16_t*>(X), g.sb};
+    heavy_wide_b_kernel<D, PlainB<D>><<<g.num_chunks, kBlock, 0, ln.st>>>(g, src, heavy_partial);
     ln.end(KK_HEAVY);
   }
   allow_lds(fwd_hidden_bf16_kernel<D>, fwd_lds<D>());
@@ -411,11 +776,11 @@ void bwd_t(const Launch& ln, bool last, bool to_embed, const GraphView& gt, cons
   if (gt.num_chunks > 0) {
     ln.begin(KK_HEAVY);
     if (last) {
-      LastSrc<bf16_t, D> src{static_cast<const bf16_t*>(a.Hcur), gt.sb, a.g_t, a.w_out, a.wout_stride, {}};
-      heavy_wide_kernel<bf16_t, D, LastSrc<bf16_t, D>><<<gt.num_chunks, kBlock, 0, ln.st>>>(gt, src, a.heavy_partial);
+      const LastB<D> src{static_cast<const bf16_t*>(a.Hcur), gt.sb, a.g_t, a.w_out, a.wout_stride, {}};
+      heavy_wide_b_kernel<D, LastB<D>><<<gt.num_chunks, kBlock, 0, ln.st>>>(gt, src, a.heavy_partial);
     } else {
-      PlainSrc<bf16_t, D> src{static_cast<const bf16_t*>(a.GZ_in), gt.sb};
-      heavy_wide_kernel<bf16_t, D, PlainSrc<bf16_t, D>><<<gt.num_chunks, kBlock, 0, ln.st>>>(gt, src, a.heavy_partial);
+      const PlainB<D> src{static_cast<const bf16_t*>(a.GZ_in), gt.sb};
+      heavy_wide_b_kernel<D, PlainB<D>><<<gt.num_chunks, kBlock, 0, ln.st>>>(gt, src, a.heavy_partial);
     }
     ln.end(KK_HEAVY);
   }

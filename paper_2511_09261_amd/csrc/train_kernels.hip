@@ -109,7 +109,7 @@ __global__ __launch_bounds__(kBlock) void fwd_hidden_kernel(GraphView g, const T
   PlainSrc<T, D> src{X, g.sb};
   const int rbeg = g.part_rows[k], rend = g.part_rows[k + 1];
   const int c = tid % D, rg = tid / D;
-  for (int row0 = rbeg + s * R; row0 < rend; row0 += g.S * R) {
+  for (int row0 = rbeg + s * R; row0 < rend; row0 += g.blk_S[blockIdx.x] * R) {
     const int nrows = min(R, rend - row0);
     aggregate_tile<T, D>(g, src, TileSink<D>{tile}, row0, nrows, red, hlist, heavy_partial);
     __syncthreads();
@@ -146,7 +146,7 @@ __global__ __launch_bounds__(kBlock) void fwd_gemv_kernel(GraphView g, const T* 
   const int s = g.nblk_s[blockIdx.x];
   const int rbeg = g.part_rows[k], rend = g.part_rows[k + 1];
   const float* wk = w + static_cast<size_t>(k) * w_stride;
-  for (int row0 = rbeg + s * kNarrowRows; row0 < rend; row0 += g.nS * kNarrowRows) {
+  for (int row0 = rbeg + s * kNarrowRows; row0 < rend; row0 += g.nblk_S[blockIdx.x] * kNarrowRows) {
     const int i = row0 + threadIdx.x;
     if (i < rend) {
       float acc = 0.f;
@@ -197,7 +197,7 @@ __global__ __launch_bounds__(kBlock) void bwd_hidden_kernel(GraphView g, BwdArgs
   for (int i = 0; i < NA; ++i) gw[i] = 0.f;
   float gwo = 0.f;  // gradient of w_out[c] (LAST, threads tid < D)
 
-  for (int row0 = rbeg + s * R; row0 < rend; row0 += g.S * R) {
+  for (int row0 = rbeg + s * R; row0 < rend; row0 += g.blk_S[blockIdx.x] * R) {
     const int nrows = min(R, rend - row0);
     if (LAST)
       aggregate_tile<T, D>(g, lsrc, TileSink<D>{tile}, row0, nrows, red, hlist, a.heavy_partial);
@@ -282,7 +282,7 @@ __global__ __launch_bounds__(kBlock) void bwd_single_kernel(GraphView g, BwdArgs
   const float wc = a.w_out[static_cast<size_t>(k) * a.wout_stride + c];
   const int rbeg = g.part_rows[k], rend = g.part_rows[k + 1];
   float gw = 0.f;
-  for (int row0 = rbeg + s * R; row0 < rend; row0 += g.S * R) {
+  for (int row0 = rbeg + s * R; row0 < rend; row0 += g.blk_S[blockIdx.x] * R) {
     const int nrows = min(R, rend - row0);
     for (int r = rg; r < nrows; r += RG) {
       const size_t idx = static_cast<size_t>(row0 + r) * D + c;
@@ -389,7 +389,7 @@ __global__ __launch_bounds__(kBlock) void fwd_readout_kernel(GraphView g, const 
   const int s = g.nblk_s[blockIdx.x];
   const int rbeg = g.part_rows[k], rend = g.part_rows[k + 1];
   ScaledValue f{g.sb, t};
-  for (int row0 = rbeg + s * kNarrowRows; row0 < rend; row0 += g.nS * kNarrowRows) {
+  for (int row0 = rbeg + s * kNarrowRows; row0 < rend; row0 += g.nblk_S[blockIdx.x] * kNarrowRows) {
     const int nrows = min(kNarrowRows, rend - row0);
     narrow_row_sums(g, f, row0, nrows, rs, mlist, heavy_partial);
     if (threadIdx.x < nrows) {
@@ -413,7 +413,7 @@ __global__ __launch_bounds__(kBlock) void bwd_readout_kernel(GraphView g, const 
   const int s = g.nblk_s[blockIdx.x];
   const int rbeg = g.part_rows[k], rend = g.part_rows[k + 1];
   ScaledValue f{g.sb, g_z};
-  for (int row0 = rbeg + s * kNarrowRows; row0 < rend; row0 += g.nS * kNarrowRows) {
+  for (int row0 = rbeg + s * kNarrowRows; row0 < rend; row0 += g.nblk_S[blockIdx.x] * kNarrowRows) {
     const int nrows = min(kNarrowRows, rend - row0);
     narrow_row_sums(g, f, row0, nrows, rs, mlist, heavy_partial);
     if (threadIdx.x < nrows) {
@@ -439,7 +439,7 @@ __global__ __launch_bounds__(kBlock) void loss_kernel(GraphView g, const float* 
   const int rbeg = g.part_rows[k], rend = g.part_rows[k + 1];
   PlainValue f{p};
   double lsum = 0.0;
-  for (int row0 = rbeg + s * kNarrowRows; row0 < rend; row0 += g.nS * kNarrowRows) {
+  for (int row0 = rbeg + s * kNarrowRows; row0 < rend; row0 += g.nblk_S[blockIdx.x] * kNarrowRows) {
     const int nrows = min(kNarrowRows, rend - row0);
     narrow_row_sums(g, f, row0, nrows, rs, mlist, heavy_partial);
     if (threadIdx.x < nrows) {
@@ -528,6 +528,8 @@ GraphView transposed(const GraphView& g) {
   GraphView gt = g;
   gt.sa = g.sb;
   gt.sb = g.sa;
+  gt.ent = g.ent_t;
+  gt.ent_t = g.ent;
   return gt;
 }
 
