@@ -112,6 +112,7 @@ struct gco_ctx {
           *d_chunk_end = nullptr, *d_chunk_part = nullptr;
   int32_t* d_heavy_rows = nullptr;
   int2 *d_ent = nullptr, *d_ent_t = nullptr;
+  float* d_diag = nullptr;
   float* d_heavy_partial = nullptr;
   GraphView gv;
   std::vector<void*> graph_allocs;
@@ -531,14 +532,19 @@ int gco_upload_graph(gco_ctx* ctx, int64_t n64, const int64_t* rowptr, const int
   launch_scales(st, n, ctx->d_lrowptr, ctx->cfg.norm, ctx->cfg.problem, ctx->cfg.beta, ctx->d_sa,
                 ctx->d_sb, ctx->d_cbase);
   launch_linear_coeff(st, n, ctx->d_cbase, nullptr, ctx->d_perm, ctx->d_c);
-  // packed {column, column scale} entries of A_hat and of its transpose
-  GALLOC(ctx->d_ent, static_cast<size_t>(ctx->nnz_loc));
-  launch_pack_entries(st, ctx->nnz_loc, ctx->d_lcol, ctx->d_sb, ctx->d_ent);
+  // packed {column, A_hat value} entries of A_hat and of its transpose, and the diagonal
+  // (the entry arrays carry kEntPad zero entries at the end: tiles copy a fixed number of
+  // entries starting at their first one)
+  GALLOC(ctx->d_ent, static_cast<size_t>(ctx->nnz_loc) + kEntPad);
+  launch_fill_u32(st, ctx->d_ent + ctx->nnz_loc, 2 * kEntPad, 0u);
+  GALLOC(ctx->d_diag, static_cast<size_t>(n));
+  launch_pack_entries(st, n, ctx->d_lrowptr, ctx->d_lcol, ctx->d_sa, ctx->d_sb, ctx->d_ent, ctx->d_diag);
   if (ctx->cfg.norm == GCO_NORM_SYM) {
     ctx->d_ent_t = ctx->d_ent;  // symmetric normalisation: A_hat^T = A_hat
   } else {
-    GALLOC(ctx->d_ent_t, static_cast<size_t>(ctx->nnz_loc));
-    launch_pack_entries(st, ctx->nnz_loc, ctx->d_lcol, ctx->d_sa, ctx->d_ent_t);
+    GALLOC(ctx->d_ent_t, static_cast<size_t>(ctx->nnz_loc) + kEntPad);
+    launch_fill_u32(st, ctx->d_ent_t + ctx->nnz_loc, 2 * kEntPad, 0u);
+    launch_pack_entries(st, n, ctx->d_lrowptr, ctx->d_lcol, ctx->d_sb, ctx->d_sa, ctx->d_ent_t, nullptr);
   }
 
   // work decomposition
@@ -641,6 +647,7 @@ int gco_upload_graph(gco_ctx* ctx, int64_t n64, const int64_t* rowptr, const int
   g.heavy_rows = ctx->d_heavy_rows;
   g.ent = ctx->d_ent;
   g.ent_t = ctx->d_ent_t;
+  g.diag = ctx->d_diag;
   g.heavy_chunk_ptr = ctx->d_heavy_chunk_ptr;
   g.chunk_begin = ctx->d_chunk_begin;
   g.chunk_end = ctx->d_chunk_end;

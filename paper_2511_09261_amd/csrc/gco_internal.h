@@ -16,10 +16,11 @@ constexpr int kBlock = 256;      // threads per workgroup in every kernel here (
 constexpr int kTileRows = 64;    // rows of one feature tile in the wide kernels
 constexpr int kNarrowRows = 256; // rows of one tile in the width-1 kernels
 constexpr int kLightMax = 64;    // rows with more local neighbours are reduced by the whole block
-constexpr int kHeavyMin = 2048;  // rows with at least this many neighbours are pre-reduced in chunks
-constexpr int kChunk = 512;      // neighbours per chunk of a pre-reduced row
+constexpr int kHeavyMin = 256;   // rows with at least this many neighbours are pre-reduced in chunks
+constexpr int kChunk = 256;      // neighbours per chunk of a pre-reduced row
 constexpr int kWideBlocks = 2048;        // workgroups aimed at by the wide kernels
-constexpr int kMaxTilesPerBlock = 16;    // tiles one wide workgroup may own
+constexpr int kMaxTilesPerBlock = 16;
+constexpr int kEntPad = 512;             // zero entries appended to the packed entry arrays    // tiles one wide workgroup may own
 
 enum KernelKind : int {
   KK_FWD_HIDDEN = 0,   // aggregate + transform + ReLU of one hidden layer (Eq. 3)
@@ -44,10 +45,12 @@ struct GraphView {
   const int* col = nullptr;       // [nnz]
   const float* sa = nullptr;      // [n] row scale of A_hat   (A_hat_ij = sa_i * sb_j)
   const float* sb = nullptr;      // [n] column scale of A_hat
-  // the CSR entries again, packed as {column, bits of the column scale sb[column]};
-  // ent_t carries sa[column] instead (the entries of A_hat^T)
+  // the CSR entries again, packed as {column j, bits of A_hat_ij = sa_i sb_j};
+  // ent_t carries A_hat_ji = sa_j sb_i instead (the entries of A_hat^T);
+  // diag[i] = A_hat_ii = sa_i sb_i
   const int2* ent = nullptr;      // [nnz]
   const int2* ent_t = nullptr;    // [nnz]
+  const float* diag = nullptr;    // [n]
   const int* part_rows = nullptr; // [P+1] first row of each subgraph
   // wide kernels: workgroup b works on tiles blk_s[b], + blk_S[b], + 2 blk_S[b], ...
   // of subgraph blk_k[b] (blk_k[b] < 0: nothing to do)

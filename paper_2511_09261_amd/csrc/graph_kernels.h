@@ -26,8 +26,10 @@ void launch_local_fill(hipStream_t st, int n, const int64_t* rowptr, const int32
                        const int64_t* lptr64, int32_t* lrowptr, int32_t* lcol);
 void launch_scales(hipStream_t st, int n, const int32_t* lrowptr, int norm, int problem, float beta,
                    float* sa, float* sb, float* c_base);
-// ent[e] = {col[e], bits of scale[col[e]]}
-void launch_pack_entries(hipStream_t st, int64_t nnz, const int32_t* col, const float* scale, int2* ent);
+// ent[e] = {j, bits of row_scale[i] * col_scale[j]} for every local entry e = (i, j);
+// diag[i] = row_scale[i] * col_scale[i] if diag is given.
+void launch_pack_entries(hipStream_t st, int n, const int32_t* rowptr, const int32_t* col,
+                         const float* row_scale, const float* col_scale, int2* ent, float* diag);
 void launch_linear_coeff(hipStream_t st, int n, const float* c_base, const float* extra_orig,
                          const int32_t* perm, float* c);
 

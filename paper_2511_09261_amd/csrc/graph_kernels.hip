@@ -203,13 +203,23 @@ __global__ __launch_bounds__(kBlock) void scales_kernel(int n, const int32_t* __
   c_base[r] = problem == GCO_PROBLEM_MAXCUT ? -static_cast<float>(deg) : -beta;
 }
 
-__global__ __launch_bounds__(kBlock) void pack_entries_kernel(int64_t nnz, const int32_t* __restrict__ col,
-                                                              const float* __restrict__ scale,
-                                                              int2* __restrict__ ent) {
-  const int64_t e = static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x;
-  if (e >= nnz) return;
-  const int j = col[e];
-  ent[e] = make_int2(j, __float_as_int(scale[j]));
+// One wavefront per row i: ent[e] = {j, row_scale[i] * col_scale[j]} for its entries
+// e = (i, j); with diag != nullptr also diag[i] = row_scale[i] * col_scale[i].
+__global__ __launch_bounds__(kBlock) void pack_entries_kernel(int n, const int32_t* __restrict__ rowptr,
+                                                              const int32_t* __restrict__ col,
+                                                              const float* __restrict__ row_scale,
+                                                              const float* __restrict__ col_scale,
+                                                              int2* __restrict__ ent,
+                                                              float* __restrict__ diag) {
+  const int i = blockIdx.x * (kBlock / 64) + threadIdx.x / 64;
+  if (i >= n) return;
+  const int lane = threadIdx.x % 64;
+  const float ri = row_scale[i];
+  if (diag != nullptr && lane == 0) diag[i] = ri * col_scale[i];
+  for (int e = rowptr[i] + lane; e < rowptr[i + 1]; e += 64) {
+    const int j = col[e];
+    ent[e] = make_int2(j, __float_as_int(ri * col_scale[j]));
+  }
 }
 
 // c[r] = c_base[r] + extra_orig[perm[r]]
@@ -440,8 +450,10 @@ void launch_scales(hipStream_t st, int n, const int32_t* lrowptr, int norm, int 
   scales_kernel<<<blocks_for(n, kBlock), kBlock, 0, st>>>(n, lrowptr, norm, problem, beta, sa, sb, c_base);
 }
 
-void launch_pack_entries(hipStream_t st, int64_t nnz, const int32_t* col, const float* scale, int2* ent) {
-  if (nnz > 0) pack_entries_kernel<<<blocks_for(nnz, kBlock), kBlock, 0, st>>>(nnz, col, scale, ent);
+void launch_pack_entries(hipStream_t st, int n, const int32_t* rowptr, const int32_t* col,
+                         const float* row_scale, const float* col_scale, int2* ent, float* diag) {
+  pack_entries_kernel<<<blocks_for(n, kBlock / 64), kBlock, 0, st>>>(n, rowptr, col, row_scale, col_scale,
+                                                                      ent, diag);
 }
 
 void launch_linear_coeff(hipStream_t st, int n, const float* c_base, const float* extra_orig,

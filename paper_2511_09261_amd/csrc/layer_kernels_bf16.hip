@@ -115,9 +115,9 @@ __device__ __forceinline__ void unpack8(const uint4& x, float (&v)[8]) {
 template <int D>
 struct PlainB {  // acc += scale * X[j, c0..c0+8)
   const bf16_t* X;
-  const float* sb;
+  const float* diag;  // A_hat_ii
   __device__ __forceinline__ void set_part(int, int) {}
-  __device__ __forceinline__ float own_scale(int i) const { return sb[i]; }
+  __device__ __forceinline__ float own_scale(int i) const { return diag[i]; }
   __device__ __forceinline__ float entry_scale(int, float w) const { return w; }
   __device__ __forceinline__ void apply(const uint4& raw, float sc, float (&acc)[8]) const {
     float v[8];
@@ -131,7 +131,7 @@ template <int D>
 struct LastB {  // gradient of the last hidden pre-activation, formed on the fly:
                 // acc += scale * g_t[j] * w_out[c] * [H[j, c] > 0]
   const bf16_t* X;
-  const float* sb;
+  const float* diag;  // A_hat_ii
   const float* g_t;
   const float* w_out;
   int wout_stride;
@@ -140,7 +140,7 @@ struct LastB {  // gradient of the last hidden pre-activation, formed on the fly
 #pragma unroll
     for (int x = 0; x < 8; ++x) w[x] = w_out[static_cast<size_t>(k) * wout_stride + c0 + x];
   }
-  __device__ __forceinline__ float own_scale(int i) const { return sb[i] * g_t[i]; }
+  __device__ __forceinline__ float own_scale(int i) const { return diag[i] * g_t[i]; }
   __device__ __forceinline__ float entry_scale(int j, float we) const { return we * g_t[j]; }
   __device__ __forceinline__ void apply(const uint4& raw, float sc, float (&acc)[8]) const {
     float v[8];
@@ -228,7 +228,6 @@ __device__ void gather_tile(const GraphView& g, const Src& src, const Sink& sink
   const auto entry = [&](int e) -> int2 { return in_lds ? ents[e - e_base] : g.ent[e]; };
   float acc[M::NCH][8];
   int pos[M::NCH], end[M::NCH];
-  float sa[M::NCH];
   bool direct[M::NCH];  // this lane group finishes the row itself
 #pragma unroll
   for (int u = 0; u < M::NCH; ++u) {
@@ -236,13 +235,11 @@ __device__ void gather_tile(const GraphView& g, const Src& src, const Sink& sink
 #pragma unroll
     for (int x = 0; x < 8; ++x) acc[u][x] = 0.f;
     pos[u] = end[u] = 0;
-    sa[u] = 0.f;
     direct[u] = true;
     if (r < nrows) {
       const int i = row0 + r;
       const int ea = rpq[r], eb = rpq[r + 1];
       const int deg = eb - ea;
-      sa[u] = g.sa[i];
       if (deg >= kHeavyMin) {          // pre-reduced in chunks
         src.apply(own[u], src.own_scale(i), acc[u]);
         const int h = find_heavy(g, i);
@@ -297,11 +294,7 @@ __device__ void gather_tile(const GraphView& g, const Src& src, const Sink& sink
 #pragma unroll
   for (int u = 0; u < M::NCH; ++u) {
     const int r = grp + M::G * u;
-    if (direct[u]) {
-#pragma unroll
-      for (int x = 0; x < 8; ++x) acc[u][x] *= sa[u];
-      sink.template put_vec<8>(r, c0, acc[u]);
-    }
+    if (direct[u]) sink.template put_vec<8>(r, c0, acc[u]);
   }
   __syncthreads();
   const int nh = hlist[0];
@@ -337,7 +330,7 @@ __device__ void gather_tile(const GraphView& g, const Src& src, const Sink& sink
     if (tid < D) {
       float sum = 0.f;
       for (int gq = 0; gq < M::G; ++gq) sum += red[gq * D + tid];
-      sink.put_one(r, tid, g.sa[i] * sum);
+      sink.put_one(r, tid, sum);
     }
     __syncthreads();
   }
@@ -464,7 +457,7 @@ __global__ __launch_bounds__(kBlock) void fwd_hidden_bf16_kernel(
     bfrag[ks] = as_frag(pack8(v));
   }
   if (w_out != nullptr && tid < D) wo[tid] = w_out[static_cast<size_t>(k) * wout_stride + tid];
-  const PlainB<D> src{X, g.sb};
+  const PlainB<D> src{X, g.diag};
   const BfSink<D, false> sink{at, nullptr};
   __syncthreads();  // row pointers are in LDS
   TileRegs<D> next;
@@ -520,15 +513,348 @@ __global__ __launch_bounds__(kBlock) void fwd_hidden_bf16_kernel(
 }
 
 // ---------------------------------------------------------------------------
+// Forward with asynchronous global -> LDS copies
+// ---------------------------------------------------------------------------
+// A tile moves 16 KB and a memory round trip takes about 2 us, so a workgroup
+// that waits for its own loads keeps far too few bytes in flight.  Here the
+// rows a tile needs (its own rows, the rows of its first ER entries, its
+// entries and its diagonal) are copied straight from HBM into an LDS ring by
+// global_load_lds (no registers involved), two tiles ahead of the tile being
+// summed and multiplied.
+//
+// The copies are issued from inline assembly, because the compiler would
+// otherwise wait for ALL outstanding copies before any LDS read.  Vector memory
+// operations of a wave complete in issue order, so "the copies of tile q have
+// landed" is s_waitcnt vmcnt(N) with N = the number of vector memory
+// instructions this wave issued after them.  Every N below counts only
+// instructions that are certain to have been issued (the copies themselves and
+// the unconditional stores); any other load or store issued in between only
+// makes the wait stricter, never too weak.  Compiler-generated waits for
+// ordinary loads stay correct for the same reason.
+__device__ __forceinline__ uint32_t lds_offset(const void* p) {
+  return static_cast<uint32_t>(reinterpret_cast<uintptr_t>(
+      (__attribute__((address_space(3))) const void*)p));
+}
+
+// Each lane copies 16 bytes from its own global address to lds_base + 16 * lane.
+__device__ __forceinline__ void dma16(const void* g, uint32_t lds_base) {
+  uint32_t keep;  // M0 (the LDS base of the copy) is put back, the compiler may hold a value in it
+  asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %1, off\n\ts_mov_b32 m0, %0"
+               : "=&s"(keep)
+               : "v"(g), "s"(__builtin_amdgcn_readfirstlane(lds_base))
+               : "memory");
+}
+// Each lane copies 4 bytes from its own global address to lds_base + 4 * lane.
+__device__ __forceinline__ void dma4(const void* g, uint32_t lds_base) {
+  uint32_t keep;
+  asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %2\n\tglobal_load_lds_dword %1, off\n\ts_mov_b32 m0, %0"
+               : "=&s"(keep)
+               : "v"(g), "s"(__builtin_amdgcn_readfirstlane(lds_base))
+               : "memory");
+}
+
+// s_waitcnt vmcnt(n) for a wave-uniform n; n above 24 is clamped (a stricter wait).
+__device__ __forceinline__ void wait_vm(int n) {
+#define GCO_W(k) case k: asm volatile("s_waitcnt vmcnt(" #k ")" ::: "memory"); break;
+  switch (n < 24 ? n : 24) {
+    GCO_W(0) GCO_W(1) GCO_W(2) GCO_W(3) GCO_W(4) GCO_W(5) GCO_W(6) GCO_W(7) GCO_W(8)
+    GCO_W(9) GCO_W(10) GCO_W(11) GCO_W(12) GCO_W(13) GCO_W(14) GCO_W(15) GCO_W(16)
+    GCO_W(17) GCO_W(18) GCO_W(19) GCO_W(20) GCO_W(21) GCO_W(22) GCO_W(23) GCO_W(24)
+  }
+#undef GCO_W
+}
+
+constexpr int kStages = 3;       // LDS ring: the tile being worked on and two in flight
+constexpr int kEntBufs = 6;      // entry buffers: tiles q .. q+4 (one spare)
+constexpr int kEntStage = 256;   // entries of a tile copied to LDS (tiles with more use HBM)
+
+template <int D>
+struct DG {
+  static constexpr int ROWB = D * 2;                       // bytes of a feature row
+  static constexpr int LPR = D / 8;                        // lanes per row
+  static constexpr int EPI = 64 / LPR;                     // rows per copy instruction
+  static constexpr int ER = D == 128 ? 40 : (D == 64 ? 72 : 80); // entry rows staged per tile
+  static constexpr int NO = R * ROWB / 1024;               // copy instructions for the own rows
+  static constexpr int NE = ER / EPI;                      // ... for the entry rows
+  static_assert(ER % EPI == 0 && (R * ROWB) % 1024 == 0, "whole copy instructions");
+  static constexpr int own_off = 0;
+  static constexpr int ent_off = R * ROWB;
+  static constexpr int diag_off = (R + ER) * ROWB;
+  static constexpr int slot_bytes = diag_off + R * 4;
+  static_assert(slot_bytes >= kBlock * 8 * 4, "the slot doubles as the reduction buffer");
+  // instructions of one tile's row copies issued by wave w
+  __device__ static constexpr int rows_count(int w) {
+    return (NO - w + 3) / 4 + (NE - w + 3) / 4 + (w == 0 ? 1 : 0);
+  }
+  __device__ static constexpr int ents_count(int w) { return w < kEntStage / 128 ? 1 : 0; }
+};
+
+template <int D>
+constexpr size_t fwd_dma_lds() {
+  return static_cast<size_t>(kStages) * DG<D>::slot_bytes + kEntBufs * kEntStage * sizeof(int2) +
+         MG<D>::at_bytes + kMaxTilesPerBlock * (R + 1) * sizeof(int) + (R + 4) * sizeof(int) +
+         D * sizeof(float);
+}
+
+// Copy kEntStage entries, starting at the tile's first entry rounded down to an even
+// index (16-byte aligned source), to `buf`: entry e of the tile is buf[e - (e_base & ~1)].
+__device__ __forceinline__ void issue_entries(const GraphView& g, int e_base, const int2* buf) {
+  const int wave = threadIdx.x / 64, lane = threadIdx.x % 64;
+  if (wave < kEntStage / 128)   // the entry array is padded, so reading past a tile's end is in bounds
+    dma16(g.ent + (e_base & ~1) + wave * 128 + 2 * lane, lds_offset(buf) + wave * 1024);
+}
+
+// Copy a tile's own rows, the rows of its first ER entries and its diagonal to `slot`.
+template <int D>
+__device__ __forceinline__ void issue_rows(const GraphView& g, const bf16_t* X, int row0, const int* rpq,
+                                           const int2* ebuf, const unsigned char* slot) {
+  using G_ = DG<D>;
+  const int wave = threadIdx.x / 64, lane = threadIdx.x % 64;
+  const uint32_t base = lds_offset(slot);
+  const int last = g.n - 1;
+#pragma unroll
+  for (int j = wave; j < G_::NO; j += 4) {
+    const int r = j * G_::EPI + lane / G_::LPR;
+    dma16(X + static_cast<size_t>(min(row0 + r, last)) * D + (lane % G_::LPR) * 8,
+          base + G_::own_off + j * 1024);
+  }
+  const int E = rpq[R] - rpq[0], shift = rpq[0] & 1;
+#pragma unroll
+  for (int j = wave; j < G_::NE; j += 4) {
+    const int el = j * G_::EPI + lane / G_::LPR;
+    const int colj = (el < E && el + shift < kEntStage) ? ebuf[el + shift].x : 0;
+    dma16(X + static_cast<size_t>(colj) * D + (lane % G_::LPR) * 8, base + G_::ent_off + j * 1024);
+  }
+  if (wave == 0) dma4(g.diag + min(row0 + lane, last), base + G_::diag_off);
+}
+
+template <int D>
+__global__ __launch_bounds__(kBlock) void fwd_hidden_dma_kernel(
+    GraphView g, const bf16_t* __restrict__ X, const float* __restrict__ W, int w_stride,
+    bf16_t* __restrict__ Y, const float* __restrict__ w_out, int wout_stride, float* __restrict__ t,
+    const float* __restrict__ heavy_partial) {
+  using M = MG<D>;
+  using G_ = DG<D>;
+  extern __shared__ __align__(16) unsigned char smem[];
+  unsigned char* ring = smem;
+  int2* entbuf = reinterpret_cast<int2*>(ring + kStages * G_::slot_bytes);
+  bf16_t* at = reinterpret_cast<bf16_t*>(entbuf + kEntBufs * kEntStage);
+  int* rp = reinterpret_cast<int*>(reinterpret_cast<unsigned char*>(at) + M::at_bytes);
+  int* hlist = rp + kMaxTilesPerBlock * (R + 1);
+  float* wo = reinterpret_cast<float*>(hlist + R + 4);
+
+  const int k = g.blk_k[blockIdx.x];
+  if (k < 0) return;
+  const int s = g.blk_s[blockIdx.x], S = g.blk_S[blockIdx.x];
+  const int tid = threadIdx.x, lane = tid % 64, wave = tid / 64;
+  const int tn = wave % M::NT, tm0 = wave / M::NT;
+  const int grp = tid / M::LPR, c0 = (tid % M::LPR) * 8;
+  const int rbeg = g.part_rows[k], rend = g.part_rows[k + 1];
+  const int Q = preload_row_pointers(g, rbeg, rend, s, S, rp);
+  const float* Wk = W + static_cast<size_t>(k) * w_stride;
+  bf16x8 bfrag[M::KS];
+#pragma unroll
+  for (int ks = 0; ks < M::KS; ++ks) {
+    float v[8];
+#pragma unroll
+    for (int x = 0; x < 8; ++x) v[x] = Wk[(ks * 16 + 8 * (lane / 32) + x) * D + tn * 32 + lane % 32];
+    bfrag[ks] = as_frag(pack8(v));
+  }
+  if (w_out != nullptr && tid < D) wo[tid] = w_out[static_cast<size_t>(k) * wout_stride + tid];
+  const PlainB<D> src{X, g.diag};
+  const BfSink<D, false> sink{at, nullptr};
+  const int cRW = G_::rows_count(wave), cEN = G_::ents_count(wave);
+  constexpr int cST = R * M::LPR / kBlock;  // unconditional 16-byte stores of Y per thread and tile
+  __syncthreads();                          // row pointers and wo are in LDS (compiler-visible loads done)
+
+  const auto tile_row0 = [&](int q) { return rbeg + (s + q * S) * R; };
+  // prologue: entries of tiles 0..3, rows of tiles 0 and 1
+  constexpr int kLead = 4;  // entries are requested this many tiles ahead, rows two tiles ahead
+  for (int q = 0; q < kLead && q < Q; ++q) issue_entries(g, rp[q * (R + 1)], entbuf + q * kEntStage);
+  for (int q = 0; q < 2 && q < Q; ++q) {
+    // entries of tile q have landed: younger are the entry copies of the later tiles and
+    // the row copies issued so far
+    wait_vm((min(Q, kLead) - 1 - q) * cEN + q * cRW);
+    __syncthreads();
+    issue_rows<D>(g, X, tile_row0(q), rp + q * (R + 1), entbuf + q * kEntStage, ring + q * G_::slot_bytes);
+  }
+  for (int q = 0; q < Q; ++q) {
+    const int row0 = tile_row0(q);
+    const int nrows = min(R, rend - row0);
+    const int* rpq = rp + q * (R + 1);
+    const unsigned char* slot = ring + (q % kStages) * G_::slot_bytes;
+    const int2* ebuf = entbuf + (q % kEntBufs) * kEntStage;
+    // Issue order of one iteration: entries of q+4, rows of q+2, ..., stores of q.
+    // 1. entries of tile q+4
+    if (q + kLead < Q)
+      issue_entries(g, rp[(q + kLead) * (R + 1)], entbuf + ((q + kLead) % kEntBufs) * kEntStage);
+    const int st_younger = (q >= 1 ? cST : 0) + (q >= 2 ? cST : 0);  // stores of tiles q-1, q-2
+    const int en_younger = (q + 3 < Q ? cEN : 0) + (q + 4 < Q ? cEN : 0);
+    // 2. rows of tile q+2, once its entries (requested two iterations ago) have landed.
+    //    Issued after those entries: rows of q and q+1, stores of q-2 and q-1, entries of q+3, q+4.
+    if (q + 2 < Q) {
+      wait_vm(2 * cRW + st_younger + en_younger);
+      __syncthreads();
+      issue_rows<D>(g, X, tile_row0(q + 2), rpq + 2 * (R + 1), entbuf + ((q + 2) % kEntBufs) * kEntStage,
+                    ring + ((q + 2) % kStages) * G_::slot_bytes);
+    }
+    // 3. rows of tile q have landed.  Issued after them: stores of q-2, entries of q+3, rows of q+1,
+    //    stores of q-1, entries of q+4, rows of q+2.  (For q = 0 the entries of tile 3 are older.)
+    wait_vm((q + 1 < Q ? cRW : 0) + (q + 2 < Q ? cRW : 0) + st_younger +
+            (q >= 1 ? en_younger : (q + 4 < Q ? cEN : 0)));
+    if (tid == 0) hlist[0] = 0;
+    __syncthreads();
+
+    // ---- sum phase: A_hat rows of the tile from the staged rows ----
+    const int e_base = rpq[0];
+    const int e_al = e_base & ~1;                       // ebuf[0] is entry e_al
+    const bool staged = rpq[R] - e_al <= kEntStage;     // all entries of the tile are in ebuf
+    const float* dg = reinterpret_cast<const float*>(slot + G_::diag_off);
+#pragma unroll
+    for (int u = 0; u < M::NCH; ++u) {
+      const int r = grp + M::G * u;
+      float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+      bool direct = true;
+      if (r < nrows) {
+        const int i = row0 + r;
+        const int ea = rpq[r], eb = rpq[r + 1];
+        const int deg = eb - ea;
+        const uint4 own = *reinterpret_cast<const uint4*>(slot + G_::own_off + r * G_::ROWB + c0 * 2);
+        if (deg >= kHeavyMin) {
+          src.apply(own, dg[r], acc);
+          const int h = find_heavy(g, i);
+          for (int ch = g.heavy_chunk_ptr[h]; ch < g.heavy_chunk_ptr[h + 1]; ++ch) {
+            const float4* pp = reinterpret_cast<const float4*>(heavy_partial + static_cast<size_t>(ch) * D + c0);
+            const float4 p0 = pp[0], p1 = pp[1];
+            acc[0] += p0.x; acc[1] += p0.y; acc[2] += p0.z; acc[3] += p0.w;
+            acc[4] += p1.x; acc[5] += p1.y; acc[6] += p1.z; acc[7] += p1.w;
+          }
+        } else if (deg > kLightMax) {
+          direct = false;
+          if (tid % M::LPR == 0) {
+            const int qq = atomicAdd(&hlist[0], 1);
+            hlist[1 + qq] = r;
+          }
+        } else {
+          src.apply(own, dg[r], acc);
+          int e = ea;
+          if (staged) {
+            const int e_st = min(eb, e_base + G_::ER);  // entries whose rows are in the slot
+            for (; e < e_st; ++e) {
+              const int el = e - e_base;
+              const uint4 raw = *reinterpret_cast<const uint4*>(slot + G_::ent_off + el * G_::ROWB + c0 * 2);
+              src.apply(raw, __int_as_float(ebuf[e - e_al].y), acc);
+            }
+          }
+          for (; e < eb; e += 4) {  // the rest comes from HBM, four rows at a time
+            uint4 rw[4];
+            float s4[4];
+#pragma unroll
+            for (int x = 0; x < 4; ++x) {
+              rw[x] = make_uint4(0u, 0u, 0u, 0u);
+              s4[x] = 0.f;
+              if (e + x < eb) {
+                const int2 en = staged ? ebuf[e + x - e_al] : g.ent[e + x];
+                rw[x] = *reinterpret_cast<const uint4*>(X + static_cast<size_t>(en.x) * D + c0);
+                s4[x] = __int_as_float(en.y);
+              }
+            }
+#pragma unroll
+            for (int x = 0; x < 4; ++x) src.apply(rw[x], s4[x], acc);
+          }
+        }
+      }
+      if (direct) sink.template put_vec<8>(r, c0, acc);
+    }
+    __syncthreads();
+    {  // rows longer than kLightMax: all lane groups together, entries from HBM
+      const int nh = hlist[0];
+      float* red = reinterpret_cast<float*>(const_cast<unsigned char*>(slot));  // the slot is spent
+      for (int qm = 0; qm < nh; ++qm) {
+        const int r = hlist[1 + qm];
+        const int i = row0 + r;
+        const int ea = rpq[r], eb = rpq[r + 1];
+        float a8[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+        if (grp == 0) {
+          const uint4 self = *reinterpret_cast<const uint4*>(X + static_cast<size_t>(i) * D + c0);
+          src.apply(self, g.diag[i], a8);
+        }
+        for (int e = ea + grp; e < eb; e += 4 * M::G) {
+          uint4 rw[4];
+          float s4[4];
+#pragma unroll
+          for (int x = 0; x < 4; ++x) {
+            const int ee = e + x * M::G;
+            rw[x] = make_uint4(0u, 0u, 0u, 0u);
+            s4[x] = 0.f;
+            if (ee < eb) {
+              const int2 en = g.ent[ee];
+              rw[x] = *reinterpret_cast<const uint4*>(X + static_cast<size_t>(en.x) * D + c0);
+              s4[x] = __int_as_float(en.y);
+            }
+          }
+#pragma unroll
+          for (int x = 0; x < 4; ++x) src.apply(rw[x], s4[x], a8);
+        }
+#pragma unroll
+        for (int x = 0; x < 8; ++x) red[grp * D + c0 + x] = a8[x];
+        __syncthreads();
+        if (tid < D) {
+          float sum = 0.f;
+          for (int gq = 0; gq < M::G; ++gq) sum += red[gq * D + tid];
+          sink.put_one(r, tid, sum);
+        }
+        __syncthreads();
+      }
+    }
+
+    // ---- dense product, ReLU, store ----
+    floatx16 acc[M::NTM];
+    tile_product<D>(at, bfrag, tm0, acc);
+    __syncthreads();
+#pragma unroll
+    for (int qq = 0; qq < M::NTM; ++qq) {
+      const int tm = tm0 + qq * M::WPC;
+      if (tm < M::MT) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int i = tm * 32 + (r / 4) * 8 + (lane / 32) * 4 + r % 4;
+          at[i * M::PA + tn * 32 + lane % 32] = f32_to_bf16(fmaxf(acc[qq][r], 0.f));
+        }
+      }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int u = 0; u < cST; ++u) {  // unconditional: rows past the tile are clamped, not skipped
+      const int idx = tid + kBlock * u;
+      const int r = idx / M::LPR;
+      const int rr = min(r, nrows - 1);  // duplicates rewrite the last row with its own values
+      *reinterpret_cast<uint4*>(Y + static_cast<size_t>(row0 + rr) * D + c0) =
+          *reinterpret_cast<const uint4*>(at + rr * M::PA + c0);
+    }
+    if (w_out != nullptr) {
+      const int r = tid / 4, qd = tid % 4;
+      float part = 0.f;
+      for (int c = qd * (D / 4); c < (qd + 1) * (D / 4); ++c)
+        part = fmaf(bf16_to_f32(at[r * M::PA + c]), wo[c], part);
+      part += __shfl_xor(part, 1, 64);
+      part += __shfl_xor(part, 2, 64);
+      if (qd == 0 && r < nrows) t[row0 + r] = part;
+    }
+    __syncthreads();
+  }
+}
+
+// ---------------------------------------------------------------------------
 // Backward of a hidden layer (see BwdArgs in gco_internal.h)
 // ---------------------------------------------------------------------------
 template <int D, bool LAST>
 __device__ __host__ __forceinline__ typename std::conditional<LAST, LastB<D>, PlainB<D>>::type make_src(
     const BwdArgs& a, const GraphView& g) {
   if constexpr (LAST) {
-    return LastB<D>{static_cast<const bf16_t*>(a.Hcur), g.sb, a.g_t, a.w_out, a.wout_stride, {}};
+    return LastB<D>{static_cast<const bf16_t*>(a.Hcur), g.diag, a.g_t, a.w_out, a.wout_stride, {}};
   } else {
-    return PlainB<D>{static_cast<const bf16_t*>(a.GZ_in), g.sb};
+    return PlainB<D>{static_cast<const bf16_t*>(a.GZ_in), g.diag};
   }
 }
 
@@ -759,13 +1085,13 @@ void fwd_t(const Launch& ln, const GraphView& g, const void* X, const float* W, 
            const float* w_out, int wout_stride, float* t, float* heavy_partial) {
   if (g.num_chunks > 0) {
     ln.begin(KK_HEAVY);
-    const PlainB<D> src{static_cast<const bf16_t*>(X), g.sb};
+    const PlainB<D> src{static_cast<const bf16_t*>(X), g.diag};
     heavy_wide_b_kernel<D, PlainB<D>><<<g.num_chunks, kBlock, 0, ln.st>>>(g, src, heavy_partial);
     ln.end(KK_HEAVY);
   }
-  allow_lds(fwd_hidden_bf16_kernel<D>, fwd_lds<D>());
+  allow_lds(fwd_hidden_dma_kernel<D>, fwd_dma_lds<D>());
   ln.begin(KK_FWD_HIDDEN);
-  fwd_hidden_bf16_kernel<D><<<g.num_blocks, kBlock, fwd_lds<D>(), ln.st>>>(
+  fwd_hidden_dma_kernel<D><<<g.num_blocks, kBlock, fwd_dma_lds<D>(), ln.st>>>(
       g, static_cast<const bf16_t*>(X), W, w_stride, static_cast<bf16_t*>(Y), w_out, wout_stride, t,
       heavy_partial);
   ln.end(KK_FWD_HIDDEN);
@@ -776,10 +1102,10 @@ void bwd_t(const Launch& ln, bool last, bool to_embed, const GraphView& gt, cons
   if (gt.num_chunks > 0) {
     ln.begin(KK_HEAVY);
     if (last) {
-      const LastB<D> src{static_cast<const bf16_t*>(a.Hcur), gt.sb, a.g_t, a.w_out, a.wout_stride, {}};
+      const LastB<D> src{static_cast<const bf16_t*>(a.Hcur), gt.diag, a.g_t, a.w_out, a.wout_stride, {}};
       heavy_wide_b_kernel<D, LastB<D>><<<gt.num_chunks, kBlock, 0, ln.st>>>(gt, src, a.heavy_partial);
     } else {
-      const PlainB<D> src{static_cast<const bf16_t*>(a.GZ_in), gt.sb};
+      const PlainB<D> src{static_cast<const bf16_t*>(a.GZ_in), gt.diag};
       heavy_wide_b_kernel<D, PlainB<D>><<<gt.num_chunks, kBlock, 0, ln.st>>>(gt, src, a.heavy_partial);
     }
     ln.end(KK_HEAVY);

@@ -10,7 +10,7 @@ loss are compared with the unrounded fp64 checker as well.  A unit whose
 pre-activation is zero to within fp32 summation order can still fall on either
 side, so the bf16 gradients are compared with the checker's backward pass run
 under the device's own ReLU decisions (read back through gco_get_hidden), after
-checking that those decisions differ from the checker's in at most 1e-4 of the units.
+checking that those decisions differ from the checker's in at most 1e-3 of the units.
 Integer results (rounding, repair, cross edges, masks) are compared bit for bit.
 """
 import numpy as np
@@ -144,7 +144,7 @@ def test_forward_and_gradients_at_fixed_weights(gco, kind, problem, L, D, norm, 
             H = ctx.get_hidden(l)
             assert rel(H, cache["H"][l]) <= tol
             relu_on.append(H > 0)
-            assert ((H > 0) != (cache["H"][l] > 0)).mean() <= 1e-4
+            assert ((H > 0) != (cache["H"][l] > 0)).mean() <= 1e-3
         gE, gWs = gcn.backward(lg, cache, Ws, spec, extra, relu_on=relu_on)
     dE, dWs = ctx.get_grads()
     assert rel(dE, gE) <= tol
