@@ -14,10 +14,32 @@ __device__ __forceinline__ float bf16_to_f32(bf16_t h) {
 
 // Round to nearest, ties to even (IEEE 754 roundTiesToEven on the upper 16 bits).
 __device__ __forceinline__ bf16_t f32_to_bf16(float f) {
-  uint32_t u = __float_as_uint(f);
-  if ((u & 0x7fffffffu) > 0x7f800000u) return static_cast<bf16_t>((u >> 16) | 0x40u);  // NaN
-  u += 0x7fffu + ((u >> 16) & 1u);
-  return static_cast<bf16_t>(u >> 16);
+  const __bf16 b = static_cast<__bf16>(f);  // round to nearest even (v_cvt_pk_bf16_f32)
+  bf16_t u;
+  __builtin_memcpy(&u, &b, 2);
+  return u;
+}
+
+// Two fp32 values rounded to bf16 in one word (a in the lower half).
+__device__ __forceinline__ uint32_t f32x2_to_bf16x2(float a, float b) {
+  typedef float f32x2_t __attribute__((ext_vector_type(2)));
+  typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+  const f32x2_t v = {a, b};
+  const bf16x2_t r = __builtin_convertvector(v, bf16x2_t);
+  uint32_t u;
+  __builtin_memcpy(&u, &r, 4);
+  return u;
+}
+
+// max(x, 0) on two packed bf16 values: a negative bf16 is a negative 16-bit integer.
+__device__ __forceinline__ uint32_t relu_bf16x2(uint32_t u) {
+  typedef short i16x2_t __attribute__((ext_vector_type(2)));
+  i16x2_t s;
+  __builtin_memcpy(&s, &u, 4);
+  const i16x2_t zero = {0, 0};
+  s = __builtin_elementwise_max(s, zero);
+  __builtin_memcpy(&u, &s, 4);
+  return u;
 }
 
 // Storage traits: how a feature row is kept in HBM.
@@ -51,10 +73,10 @@ struct Store<bf16_t> {
   }
   static __device__ __forceinline__ void store(bf16_t* p, const float (&v)[8]) {
     uint4 x;
-    x.x = static_cast<uint32_t>(f32_to_bf16(v[0])) | (static_cast<uint32_t>(f32_to_bf16(v[1])) << 16);
-    x.y = static_cast<uint32_t>(f32_to_bf16(v[2])) | (static_cast<uint32_t>(f32_to_bf16(v[3])) << 16);
-    x.z = static_cast<uint32_t>(f32_to_bf16(v[4])) | (static_cast<uint32_t>(f32_to_bf16(v[5])) << 16);
-    x.w = static_cast<uint32_t>(f32_to_bf16(v[6])) | (static_cast<uint32_t>(f32_to_bf16(v[7])) << 16);
+    x.x = f32x2_to_bf16x2(v[0], v[1]);
+    x.y = f32x2_to_bf16x2(v[2], v[3]);
+    x.z = f32x2_to_bf16x2(v[4], v[5]);
+    x.w = f32x2_to_bf16x2(v[6], v[7]);
     *reinterpret_cast<uint4*>(p) = x;
   }
   static __device__ __forceinline__ float get(const bf16_t* p) { return bf16_to_f32(*p); }

@@ -111,6 +111,11 @@ struct gco_ctx {
   int32_t *d_heavy_of_row = nullptr, *d_heavy_chunk_ptr = nullptr, *d_chunk_begin = nullptr,
           *d_chunk_end = nullptr, *d_chunk_part = nullptr;
   int32_t* d_heavy_rows = nullptr;
+  int32_t *d_wblk_k = nullptr, *d_wrowptr = nullptr;
+  int2* d_wwave_tiles = nullptr;
+  int32_t *d_wpbl_ptr = nullptr, *d_wpbl_list = nullptr;
+  int2 *d_went = nullptr, *d_went_t = nullptr;
+  int32_t *d_wtile_base = nullptr, *d_wtile_hptr = nullptr;
   int2 *d_ent = nullptr, *d_ent_t = nullptr;
   float* d_diag = nullptr;
   float* d_heavy_partial = nullptr;
@@ -306,6 +311,49 @@ void build_block_map(int P, const std::vector<int>& part_rows, const std::vector
     blk_k.push_back(-1);
     blk_s.push_back(0);
     blk_S.push_back(1);
+  }
+}
+
+// Wave-per-tile kernels: workgroups are dealt to the subgraphs as above; the tiles of a
+// subgraph (kWaveRows rows each) are then cut into one contiguous run per wavefront such
+// that every run holds about the same number of light-stream entries (one per row plus
+// the neighbours of rows that are not pre-reduced).
+void build_wave_map(int P, const std::vector<int>& part_rows, const std::vector<int32_t>& lrowptr,
+                    int target_blocks, std::vector<int>& wblk_k, std::vector<int2>& wwave_tiles) {
+  constexpr int kWaves = kBlock / 64;
+  std::vector<int> blk_s, blk_S;
+  build_block_map(P, part_rows, lrowptr, kWaveRows * kWaves, target_blocks, 0, wblk_k, blk_s, blk_S);
+  wwave_tiles.assign(wblk_k.size() * kWaves, make_int2(0, 0));
+  std::vector<std::vector<int>> cuts(P);  // cuts[k][v] = first tile of wavefront v of subgraph k
+  for (size_t b = 0; b < wblk_k.size(); ++b) {
+    const int k = wblk_k[b];
+    if (k < 0) continue;
+    if (cuts[k].empty()) {
+      const int rows = part_rows[k + 1] - part_rows[k];
+      const int tiles = (rows + kWaveRows - 1) / kWaveRows;
+      std::vector<int64_t> pre(static_cast<size_t>(tiles) + 1, 0);  // entries before tile t
+      for (int t = 0; t < tiles; ++t) {
+        int64_t c = 0;
+        for (int r = part_rows[k] + t * kWaveRows; r < std::min(part_rows[k + 1], part_rows[k] + (t + 1) * kWaveRows); ++r) {
+          const int deg = lrowptr[r + 1] - lrowptr[r];
+          c += 1 + (deg >= kHeavyMin ? 0 : deg);
+        }
+        pre[t + 1] = pre[t] + c;
+      }
+      const int V = blk_S[b] * kWaves;
+      cuts[k].assign(static_cast<size_t>(V) + 1, tiles);
+      cuts[k][0] = 0;
+      int t = 0;
+      for (int v = 1; v < V; ++v) {
+        const int64_t want = pre[tiles] * v / V;
+        while (t < tiles && pre[t] < want) ++t;
+        cuts[k][v] = t;
+      }
+    }
+    for (int q = 0; q < kWaves; ++q) {
+      const int v = blk_s[b] * kWaves + q;
+      wwave_tiles[b * kWaves + q] = make_int2(cuts[k][v], cuts[k][v + 1]);
+    }
   }
 }
 
@@ -547,9 +595,52 @@ int gco_upload_graph(gco_ctx* ctx, int64_t n64, const int64_t* rowptr, const int
     launch_pack_entries(st, n, ctx->d_lrowptr, ctx->d_lcol, ctx->d_sb, ctx->d_sa, ctx->d_ent_t, nullptr);
   }
 
+  // light stream for the wave-per-tile kernels
+  {
+    Scratch tmp(ctx);
+    int64_t* d_cnt = tmp.get<int64_t>(static_cast<size_t>(n) + 1);
+    int64_t* d_wptr64 = tmp.get<int64_t>(static_cast<size_t>(n) + 1);
+    int64_t* d_scan = tmp.get<int64_t>(scan_temp_elems(static_cast<int64_t>(n) + 1));
+    NEED(d_cnt && d_wptr64 && d_scan, GCO_ENOMEM, "device scratch allocation failed");
+    launch_fill_u32(st, d_cnt + n, 2, 0u);
+    launch_light_count(st, n, ctx->d_lrowptr, d_cnt);
+    exclusive_scan_i64(st, d_cnt, d_wptr64, static_cast<int64_t>(n) + 1, d_scan);
+    int64_t nnz_light = 0;
+    HIPCHK(d2h(ctx, &nnz_light, d_wptr64 + n, 1));
+    NEED(nnz_light + kEntPad < std::numeric_limits<int32_t>::max(), GCO_ERANGE,
+         "nodes plus local entries exceed 32-bit offsets");
+    GALLOC(ctx->d_wrowptr, static_cast<size_t>(n) + 1);
+    GALLOC(ctx->d_went, static_cast<size_t>(nnz_light) + kEntPad);
+    launch_fill_u32(st, ctx->d_went + nnz_light, 2 * kEntPad, 0u);
+    launch_light_fill(st, n, ctx->d_lrowptr, ctx->d_ent, ctx->d_diag, d_wptr64, ctx->d_wrowptr, ctx->d_went);
+    if (ctx->d_ent_t == ctx->d_ent) {
+      ctx->d_went_t = ctx->d_went;
+    } else {
+      GALLOC(ctx->d_went_t, static_cast<size_t>(nnz_light) + kEntPad);
+      launch_fill_u32(st, ctx->d_went_t + nnz_light, 2 * kEntPad, 0u);
+      launch_light_fill(st, n, ctx->d_lrowptr, ctx->d_ent_t, ctx->d_diag, d_wptr64, ctx->d_wrowptr,
+                        ctx->d_went_t);
+    }
+  }
+
   // work decomposition
   std::vector<int> blk_k, blk_s, blk_S, nblk_k, nblk_s, nblk_S;
   build_block_map(P, part_rows, lrowptr, kTileRows, kWideBlocks, kMaxTilesPerBlock, blk_k, blk_s, blk_S);
+  std::vector<int> wblk_k;
+  std::vector<int2> wwave_tiles;
+  build_wave_map(P, part_rows, lrowptr, kWaveBlocks, wblk_k, wwave_tiles);
+  GALLOC(ctx->d_wblk_k, wblk_k.size());
+  GALLOC(ctx->d_wwave_tiles, wwave_tiles.size());
+  HIPCHK(h2d(ctx, ctx->d_wblk_k, wblk_k.data(), wblk_k.size()));
+  HIPCHK(h2d(ctx, ctx->d_wwave_tiles, wwave_tiles.data(), wwave_tiles.size()));
+  {
+    std::vector<int> ptr, list;
+    bucket_blocks(wblk_k, ctx->Pw, ptr, list);
+    GALLOC(ctx->d_wpbl_ptr, ptr.size());
+    GALLOC(ctx->d_wpbl_list, std::max<size_t>(1, list.size()));
+    HIPCHK(h2d(ctx, ctx->d_wpbl_ptr, ptr.data(), ptr.size()));
+    HIPCHK(h2d(ctx, ctx->d_wpbl_list, list.data(), list.size()));
+  }
   // width-1 kernels: one 256-row tile per workgroup
   build_block_map(P, part_rows, lrowptr, kNarrowRows, std::numeric_limits<int>::max() / 2, 1, nblk_k,
                   nblk_s, nblk_S);
@@ -606,6 +697,22 @@ int gco_upload_graph(gco_ctx* ctx, int64_t n64, const int64_t* rowptr, const int
     }
   }
   const int num_chunks = static_cast<int>(chunk_begin.size());
+  {  // pre-reduced rows per wave tile
+    std::vector<int> tbase(P + 1, 0);
+    for (int kk = 0; kk < P; ++kk)
+      tbase[kk + 1] = tbase[kk] + (part_rows[kk + 1] - part_rows[kk] + kWaveRows - 1) / kWaveRows;
+    std::vector<int> hptr(static_cast<size_t>(tbase[P]) + 1, 0);
+    int kk = 0;
+    for (int r : heavy_rows) {
+      while (r >= part_rows[kk + 1]) ++kk;
+      hptr[tbase[kk] + (r - part_rows[kk]) / kWaveRows + 1]++;
+    }
+    for (size_t q = 1; q < hptr.size(); ++q) hptr[q] += hptr[q - 1];
+    GALLOC(ctx->d_wtile_base, tbase.size());
+    GALLOC(ctx->d_wtile_hptr, hptr.size());
+    HIPCHK(h2d(ctx, ctx->d_wtile_base, tbase.data(), tbase.size()));
+    HIPCHK(h2d(ctx, ctx->d_wtile_hptr, hptr.data(), hptr.size()));
+  }
   if (num_heavy > 0) {
     GALLOC(ctx->d_heavy_of_row, static_cast<size_t>(n));
     GALLOC(ctx->d_heavy_rows, heavy_rows.size());
@@ -635,6 +742,14 @@ int gco_upload_graph(gco_ctx* ctx, int64_t n64, const int64_t* rowptr, const int
   g.blk_s = ctx->d_blk_s;
   g.blk_S = ctx->d_blk_S;
   g.num_blocks = static_cast<int>(blk_k.size());
+  g.wblk_k = ctx->d_wblk_k;
+  g.wwave_tiles = ctx->d_wwave_tiles;
+  g.num_wblocks = static_cast<int>(wblk_k.size());
+  g.wrowptr = ctx->d_wrowptr;
+  g.wtile_base = ctx->d_wtile_base;
+  g.wtile_hptr = ctx->d_wtile_hptr;
+  g.went = ctx->d_went;
+  g.went_t = ctx->d_went_t;
   g.nblk_k = ctx->d_nblk_k;
   g.nblk_s = ctx->d_nblk_s;
   g.nblk_S = ctx->d_nblk_S;

@@ -19,8 +19,10 @@ constexpr int kLightMax = 64;    // rows with more local neighbours are reduced 
 constexpr int kHeavyMin = 256;   // rows with at least this many neighbours are pre-reduced in chunks
 constexpr int kChunk = 256;      // neighbours per chunk of a pre-reduced row
 constexpr int kWideBlocks = 2048;        // workgroups aimed at by the wide kernels
-constexpr int kMaxTilesPerBlock = 16;
-constexpr int kEntPad = 512;             // zero entries appended to the packed entry arrays    // tiles one wide workgroup may own
+constexpr int kMaxTilesPerBlock = 16;     // tiles one wide workgroup may own
+constexpr int kWaveRows = 32;            // rows of a tile in the wave-per-tile kernels
+constexpr int kWaveBlocks = 1536;        // workgroups aimed at by the wave-per-tile kernels
+constexpr int kEntPad = 512;             // zero entries appended to the packed entry arrays
 
 enum KernelKind : int {
   KK_FWD_HIDDEN = 0,   // aggregate + transform + ReLU of one hidden layer (Eq. 3)
@@ -58,6 +60,24 @@ struct GraphView {
   const int* blk_s = nullptr;
   const int* blk_S = nullptr;
   int num_blocks = 0;
+  // wave-per-tile kernels: workgroup b serves subgraph wblk_k[b] (< 0: nothing to do);
+  // its wavefront q owns tiles wwave_tiles[4b+q].x .. .y (kWaveRows rows each, counted
+  // from the subgraph's first row) -- contiguous runs, cut so that the wavefronts of a
+  // subgraph stream about equally many entries
+  const int* wblk_k = nullptr;
+  const int2* wwave_tiles = nullptr;
+  int num_wblocks = 0;
+  // light stream: per row its diagonal entry {i, A_hat_ii}, then its packed entries unless
+  // the row is pre-reduced; row i owns went[wrowptr[i] .. wrowptr[i+1]).  went_t holds the
+  // entries of A_hat^T.  kEntPad zero entries follow the last row.
+  const int* wrowptr = nullptr;   // [n+1]
+  // wave tiles are numbered subgraph by subgraph: tile tau of subgraph k has the global
+  // number wtile_base[k] + tau; the pre-reduced rows inside global tile T are
+  // heavy_rows[wtile_hptr[T] .. wtile_hptr[T+1])
+  const int* wtile_base = nullptr;  // [P+1]
+  const int* wtile_hptr = nullptr;  // [tiles+1]
+  const int2* went = nullptr;
+  const int2* went_t = nullptr;
   // narrow kernels: same scheme with kNarrowRows-row tiles
   const int* nblk_k = nullptr;
   const int* nblk_s = nullptr;
@@ -169,6 +189,11 @@ void launch_fwd_hidden_bf16(const Launch& ln, int D, const GraphView& g, const v
                             float* heavy_partial);
 void launch_bwd_hidden_bf16(const Launch& ln, int D, bool last, bool to_embed, const GraphView& gt,
                             const BwdArgs& a);
+
+// wave-per-tile bf16 kernels (wave_kernels_bf16.hip), width 64
+void launch_fwd_hidden_wave(const Launch& ln, int D, const GraphView& g, const void* X, const float* W,
+                            int w_stride, void* Y, const float* w_out, int wout_stride, float* t,
+                            float* heavy_partial);
 
 // L = 1 backward: gw partial = sum_i X[i,:] g_t[i]; gE[i,:] = g_t[i] w^k.
 void launch_bwd_single(const Launch& ln, int storage, int D, const GraphView& g, const BwdArgs& a);

@@ -222,6 +222,47 @@ __global__ __launch_bounds__(kBlock) void pack_entries_kernel(int n, const int32
   }
 }
 
+// count[i] = number of entries of row i in the light stream: its diagonal entry, and
+// its neighbours unless the row is pre-reduced
+__global__ __launch_bounds__(kBlock) void light_count_kernel(int n, const int32_t* __restrict__ rowptr,
+                                                             int64_t* __restrict__ count) {
+  const int i = blockIdx.x * kBlock + threadIdx.x;
+  if (i >= n) return;
+  const int deg = rowptr[i + 1] - rowptr[i];
+  count[i] = 1 + (deg >= kHeavyMin ? 0 : deg);
+}
+
+// An fp32 value as two bf16 numbers hi + lo (hi in the upper half of the word): hi is the
+// value rounded to bf16, lo the rounded remainder.
+__device__ __forceinline__ int split_bf16(float w) {
+  const uint32_t hi = f32_to_bf16(w);
+  const uint32_t lo = f32_to_bf16(w - __uint_as_float(hi << 16));
+  return static_cast<int>((hi << 16) | lo);
+}
+
+// One wavefront per row: {i, diag[i]}, then a light row's entries, to the light stream,
+// the values split into bf16 pairs.
+__global__ __launch_bounds__(kBlock) void light_fill_kernel(int n, const int32_t* __restrict__ rowptr,
+                                                            const int2* __restrict__ ent,
+                                                            const float* __restrict__ diag,
+                                                            const int64_t* __restrict__ wptr64,
+                                                            int32_t* __restrict__ wrowptr,
+                                                            int2* __restrict__ went) {
+  const int i = blockIdx.x * (kBlock / 64) + threadIdx.x / 64;
+  if (i > n) return;
+  const int lane = threadIdx.x % 64;
+  if (lane == 0) wrowptr[i] = static_cast<int32_t>(wptr64[i]);
+  if (i == n) return;
+  const int64_t out = wptr64[i];
+  if (lane == 0) went[out] = make_int2(i, split_bf16(diag[i]));
+  const int deg = rowptr[i + 1] - rowptr[i];
+  if (deg >= kHeavyMin) return;
+  for (int q = lane; q < deg; q += 64) {
+    const int2 en = ent[rowptr[i] + q];
+    went[out + 1 + q] = make_int2(en.x, split_bf16(__int_as_float(en.y)));
+  }
+}
+
 // c[r] = c_base[r] + extra_orig[perm[r]]
 __global__ __launch_bounds__(kBlock) void linear_coeff_kernel(int n, const float* __restrict__ c_base,
                                                               const float* __restrict__ extra_orig,
@@ -454,6 +495,16 @@ void launch_pack_entries(hipStream_t st, int n, const int32_t* rowptr, const int
                          const float* row_scale, const float* col_scale, int2* ent, float* diag) {
   pack_entries_kernel<<<blocks_for(n, kBlock / 64), kBlock, 0, st>>>(n, rowptr, col, row_scale, col_scale,
                                                                       ent, diag);
+}
+
+void launch_light_count(hipStream_t st, int n, const int32_t* rowptr, int64_t* count) {
+  light_count_kernel<<<blocks_for(n, kBlock), kBlock, 0, st>>>(n, rowptr, count);
+}
+
+void launch_light_fill(hipStream_t st, int n, const int32_t* rowptr, const int2* ent, const float* diag,
+                       const int64_t* wptr64, int32_t* wrowptr, int2* went) {
+  light_fill_kernel<<<blocks_for(static_cast<int64_t>(n) + 1, kBlock / 64), kBlock, 0, st>>>(
+      n, rowptr, ent, diag, wptr64, wrowptr, went);
 }
 
 void launch_linear_coeff(hipStream_t st, int n, const float* c_base, const float* extra_orig,

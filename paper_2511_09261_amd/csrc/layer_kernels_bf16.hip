@@ -24,14 +24,13 @@
 //     slices per lane in flight, and sums them in a fixed order.
 #include <type_traits>
 
+#include "bf16_common.h"
 #include "device_utils.h"
 #include "gco_internal.h"
 
 namespace gco {
 namespace {
 
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef float floatx16 __attribute__((ext_vector_type(16)));
 
 constexpr int R = kTileRows;
 static_assert(R == 64, "the wave-to-tile maps below assume 64-row tiles");
@@ -58,20 +57,7 @@ struct MG {
   static_assert(at_bytes + tt_bytes >= static_cast<size_t>(R) * PO * 4, "fp32 staging must fit");
 };
 
-__device__ __forceinline__ bf16x8 as_frag(const uint4& u) {
-  bf16x8 v;
-  __builtin_memcpy(&v, &u, 16);
-  return v;
-}
 
-__device__ __forceinline__ uint4 pack8(const float (&v)[8]) {
-  uint4 x;
-  x.x = static_cast<uint32_t>(f32_to_bf16(v[0])) | (static_cast<uint32_t>(f32_to_bf16(v[1])) << 16);
-  x.y = static_cast<uint32_t>(f32_to_bf16(v[2])) | (static_cast<uint32_t>(f32_to_bf16(v[3])) << 16);
-  x.z = static_cast<uint32_t>(f32_to_bf16(v[4])) | (static_cast<uint32_t>(f32_to_bf16(v[5])) << 16);
-  x.w = static_cast<uint32_t>(f32_to_bf16(v[6])) | (static_cast<uint32_t>(f32_to_bf16(v[7])) << 16);
-  return x;
-}
 
 // Gathered rows -> bf16 LDS tiles: [row][feature] and, if asked, [feature][row].
 template <int D, bool TRANSPOSED>
@@ -102,12 +88,6 @@ struct BfSink {
 constexpr int kEntCap = 512;                 // CSR entries of a tile kept in LDS
 constexpr int kEntPerThread = kEntCap / kBlock;
 
-__device__ __forceinline__ void unpack8(const uint4& x, float (&v)[8]) {
-  v[0] = __uint_as_float(x.x << 16); v[1] = __uint_as_float(x.x & 0xffff0000u);
-  v[2] = __uint_as_float(x.y << 16); v[3] = __uint_as_float(x.y & 0xffff0000u);
-  v[4] = __uint_as_float(x.z << 16); v[5] = __uint_as_float(x.z & 0xffff0000u);
-  v[6] = __uint_as_float(x.w << 16); v[7] = __uint_as_float(x.w & 0xffff0000u);
-}
 
 // Gather sources.  A source names the feature matrix whose rows are gathered,
 // the scale of the own row (self loop) and of an entry, and how a raw 16-byte
@@ -203,14 +183,6 @@ __device__ __forceinline__ void commit_entries(const TileRegs<D>& tr, int2* ents
   }
 }
 
-__device__ __forceinline__ int find_heavy(const GraphView& g, int i) {
-  int lo = 0, hi = g.num_heavy - 1;
-  while (lo < hi) {
-    const int mid = (lo + hi) >> 1;
-    if (g.heavy_rows[mid] < i) lo = mid + 1; else hi = mid;
-  }
-  return lo;
-}
 
 // Rows row0 .. row0+nrows of A_hat times the source matrix, into `sink`
 // (rows nrows..R get zeros).  `rpq` holds the tile's R + 1 row pointers (LDS),
@@ -1088,6 +1060,10 @@ void fwd_t(const Launch& ln, const GraphView& g, const void* X, const float* W, 
     const PlainB<D> src{static_cast<const bf16_t*>(X), g.diag};
     heavy_wide_b_kernel<D, PlainB<D>><<<g.num_chunks, kBlock, 0, ln.st>>>(g, src, heavy_partial);
     ln.end(KK_HEAVY);
+  }
+  if (D == 64) {  // wave-per-tile kernel
+    launch_fwd_hidden_wave(ln, D, g, X, W, w_stride, Y, w_out, wout_stride, t, heavy_partial);
+    return;
   }
   allow_lds(fwd_hidden_dma_kernel<D>, fwd_dma_lds<D>());
   ln.begin(KK_FWD_HIDDEN);

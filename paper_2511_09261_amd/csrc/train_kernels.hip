@@ -530,6 +530,8 @@ GraphView transposed(const GraphView& g) {
   gt.sb = g.sa;
   gt.ent = g.ent_t;
   gt.ent_t = g.ent;
+  gt.went = g.went_t;
+  gt.went_t = g.went;
   return gt;
 }
 

@@ -1,0 +1,386 @@
+// Wave-per-tile bf16 layer kernels.
+//
+// Every 64-lane wavefront owns a contiguous run of 32-row tiles of one subgraph
+// and works through it alone: there is no workgroup barrier after the prologue,
+// so the wavefronts of a compute unit overlap each other's memory round trips
+// freely.  The four wavefronts of a workgroup only share the LDS copy of their
+// subgraph's weight matrix.
+//
+// The aggregation A_hat X is driven by the light stream: the entries of all rows
+// that are not pre-reduced, each row's list led by its diagonal entry {i, A_hat_ii},
+// row after row; an entry's value is kept as two bf16 numbers hi + lo (relative
+// error 2^-17).  A wavefront's tiles own a contiguous range of that stream, which
+// it consumes in steps of SE entries ("slots"), whatever the row lengths:
+//   * lane group g (the lanes that share one 16-byte-per-lane feature row) fetches
+//     the source rows of slots 8g .. 8g+7 together with the entries of the next
+//     step -- one full wait per step, all loads of the step in flight together;
+//   * the rows go to a wave-private LDS buffer transposed ([feature][slot]), from
+//     which every lane reads matrix-core fragments: 8 consecutive slots of one
+//     feature;
+//   * the sum over each row's entries is a product on the matrix cores,
+//         AGG^T[feature, row] += sum_slot X[slot, feature] * S[slot, row],
+//     with S[slot, row] = the entry's value if the slot belongs to the row, else 0
+//     (once with the hi parts and once with the lo parts): its cost does not depend
+//     on how the entries are spread over the rows;
+//   * when a step reaches the end of a tile's entries the tile is complete:
+//     pre-reduced rows add their chunk partials and the caller's dense part runs
+//     on the fp32 accumulators; the step's remaining slots belong to the next tile.
+// Row pointers of the next two tiles are requested ahead.  The LDS traffic of one
+// wavefront needs no barrier: its LDS operations execute in program order.
+//
+// v_mfma_f32_32x32x16_bf16, lane l = (n = l % 32, h = l / 32):
+//   A operand: row n of the left matrix, contraction indices 8h .. 8h+7
+//   B operand: column n of the right matrix, contraction indices 8h .. 8h+7
+//   C/D register r: row 8 (r/4) + 4h + r%4, column n
+// AGG^T therefore leaves the first product with lane (n, h) holding, for row n of the
+// tile, features 32 tn + 8i + 4h + {0..3} (i = 0..3) -- exactly a B operand of the
+// second product Z^T = W^T AGG^T if contraction index 8h + e of its step (tn, p)
+// stands for feature 32 tn + 16 p + 8 (e/4) + 4h + e%4; the LDS copy of W^k is laid
+// out in that order, so the aggregate never leaves the registers.
+#include "bf16_common.h"
+#include "device_utils.h"
+#include "gco_internal.h"
+
+namespace gco {
+namespace {
+
+constexpr int RW = kWaveRows;
+static_assert(RW == 32, "one 32-row matrix-core tile per wavefront tile");
+
+template <int D>
+struct WG {
+  static constexpr int LPR = D / 8;      // lanes per feature row (16 bytes each)
+  static constexpr int NG = 64 / LPR;    // lane groups per wavefront
+  static constexpr int SE = 8 * NG;      // slots (entries) per step
+  static constexpr int KS1 = SE / 16;    // contraction steps over the slots
+  static constexpr int NT = D / 32;      // 32-wide feature tiles
+  static constexpr int KS2 = D / 16;     // contraction steps over the features
+  static constexpr int NO = RW / NG;     // output rows per lane group
+  static constexpr int XP = SE * 2 + 16; // bytes per feature in the transposed row buffer
+  static constexpr int PA = D + 8;       // pitch of the bf16 output tile
+  static constexpr size_t xf_bytes = static_cast<size_t>(D) * XP;
+  static constexpr size_t wts_bytes = static_cast<size_t>(SE) * 4;  // hi halves, then lo halves
+  static constexpr size_t ot_bytes = static_cast<size_t>(RW) * PA * 2;
+  // the output tile reuses the row buffer: the step's fragments are in registers by then
+  static constexpr size_t wave_bytes = xf_bytes + wts_bytes;
+  static_assert(ot_bytes <= xf_bytes, "the output tile overlays the row buffer");
+  static constexpr size_t w_bytes = static_cast<size_t>(D) * D * 2;
+  static_assert(SE <= 64, "slot masks are 64 bits wide");
+  static_assert(wave_bytes % 16 == 0 && w_bytes % 16 == 0 && XP % 16 == 0, "alignment");
+  static_assert(2 * SE <= kEntPad, "the stream is read up to two steps past a wavefront's range");
+};
+
+// Feature that contraction index (h, e) of step ks2 of the second product stands for.
+__host__ __device__ constexpr int feature_of(int ks2, int h, int e) {
+  return 32 * (ks2 / 2) + 16 * (ks2 % 2) + 8 * (e / 4) + 4 * h + e % 4;
+}
+
+// Feature held in register r of accumulator tile tn by a lane of half h.
+__host__ __device__ constexpr int acc_feature(int tn, int h, int r) { return 32 * tn + 8 * (r / 4) + 4 * h + r % 4; }
+
+// W^k (fp32 [D][D] in HBM) -> LDS as A operands of Z^T = W^T AGG^T:
+// wfr[((tj * KS2 + ks2) * 64 + lane) * 8 + e] = W[feature_of(ks2, h, e)][32 tj + n].
+template <int D>
+__device__ __forceinline__ void load_weight_fragments(const float* __restrict__ Wk, bf16_t* wfr) {
+  constexpr int kPer = D * D / 4 / kBlock;  // float4 loads per thread
+  static_assert(D * D % (4 * kBlock) == 0, "whole float4 loads");
+  float4 v[kPer];
+#pragma unroll
+  for (int q = 0; q < kPer; ++q) v[q] = reinterpret_cast<const float4*>(Wk)[threadIdx.x + q * kBlock];
+#pragma unroll
+  for (int q = 0; q < kPer; ++q) {
+    const int idx = (threadIdx.x + q * kBlock) * 4;
+    const int f = idx / D, j0 = idx % D;  // W[f][j0 .. j0+3]
+    // inverse of feature_of: f = 32 tn + 16 p + 8 (e/4) + 4 h + e%4
+    const int ks2 = f / 16, h = (f / 4) % 2, e = ((f / 8) % 2) * 4 + f % 4;
+    const float w[4] = {v[q].x, v[q].y, v[q].z, v[q].w};
+#pragma unroll
+    for (int x = 0; x < 4; ++x) {
+      const int j = j0 + x;
+      wfr[(((j / 32) * WG<D>::KS2 + ks2) * 64 + h * 32 + j % 32) * 8 + e] = f32_to_bf16(w[x]);
+    }
+  }
+}
+
+// pair_mask[b] for an 8-bit pattern b: four words whose 16-bit halves are all ones where
+// the corresponding bit of b is set (bit 2d -> lower half of word d).
+__device__ __forceinline__ void fill_pair_masks(uint4* pair_mask) {
+  for (int b = threadIdx.x; b < 256; b += kBlock) {
+    uint32_t d[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q)
+      d[q] = ((b >> (2 * q)) & 1 ? 0xffffu : 0u) | ((b >> (2 * q + 1)) & 1 ? 0xffff0000u : 0u);
+    pair_mask[b] = make_uint4(d[0], d[1], d[2], d[3]);
+  }
+}
+
+// Lower (upper) halves of two words, x first.
+__device__ __forceinline__ uint32_t lower_halves(uint32_t x, uint32_t y) {
+  return __builtin_amdgcn_perm(y, x, 0x05040100u);
+}
+__device__ __forceinline__ uint32_t upper_halves(uint32_t x, uint32_t y) {
+  return __builtin_amdgcn_perm(y, x, 0x07060302u);
+}
+
+// Calls on_tile(row0, nrows, agg) for every tile tau in [tile0, tile1) of subgraph k, in
+// order.  agg[tn][r] at lane (n, h) is element (row0 + n, acc_feature(tn, h, r)) of
+// A_hat X in fp32 (zero for rows past nrows).  `went` is the light stream of the matrix
+// that is applied (A_hat or its transpose); wave_lds is this wavefront's xf_bytes +
+// wts_bytes of LDS; pair_mask is the workgroup's table from fill_pair_masks.
+template <int D, typename OnTile>
+__device__ __forceinline__ void stream_tiles(const GraphView& g, const int2* __restrict__ went,
+                                             const bf16_t* __restrict__ X, int k, int tile0, int tile1,
+                                             unsigned char* wave_lds, const uint4* pair_mask,
+                                             const float* __restrict__ heavy_partial, OnTile&& on_tile) {
+  using G_ = WG<D>;
+  const int lane = threadIdx.x % 64;
+  const int n = lane % 32, h = lane / 32;
+  const int grp = lane / G_::LPR, sub = lane % G_::LPR;
+  unsigned char* xf = wave_lds;
+  uint32_t* wts = reinterpret_cast<uint32_t*>(wave_lds + G_::xf_bytes);
+
+  const int rbeg = g.part_rows[k], rend = g.part_rows[k + 1];
+  const int row_end = min(rend, rbeg + tile1 * RW);
+  const int E0 = g.wrowptr[rbeg + tile0 * RW], E1 = g.wrowptr[row_end];
+  const int tglob = g.wtile_base[k];
+  // Lane-held facts of tile tau: lanes 0..32 the stream offsets of its rows (clamped to
+  // the tile's end), lanes 33 and 34 its range in the list of pre-reduced rows.
+  auto tile_facts = [&](int tau) -> int {
+    if (tau >= tile1) return 0;
+    const int r0 = rbeg + tau * RW, nr = min(RW, rend - r0);
+    const int* p = g.wrowptr + r0 + min(lane, nr);
+    if (lane == RW + 1 || lane == RW + 2) p = g.wtile_hptr + tglob + tau + (lane - RW - 1);
+    return *p;
+  };
+  int factsA = tile_facts(tile0), factsB = tile_facts(tile0 + 1), factsC = tile_facts(tile0 + 2);
+  int tau = tile0;
+  int row0 = rbeg + tau * RW, nrows = min(RW, rend - row0);
+  int te0 = __builtin_amdgcn_readlane(factsA, 0), te1 = __builtin_amdgcn_readlane(factsA, nrows);
+  int ra = __shfl(factsA, n, 64), rb = __shfl(factsA, n + 1, 64);  // stream range of row n of the tile
+  floatx16 agg[G_::NT];
+#pragma unroll
+  for (int tn = 0; tn < G_::NT; ++tn)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) agg[tn][r] = 0.f;
+
+  int2 cur[8];
+#pragma unroll
+  for (int j = 0; j < 8; ++j) cur[j] = went[E0 + grp * 8 + j];
+
+  for (int b0 = E0; b0 < E1; b0 += G_::SE) {
+    // the next step's entries and this step's source rows: one round trip
+    int2 nxt[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) nxt[j] = went[b0 + G_::SE + grp * 8 + j];
+    uint4 raw[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      raw[j] = make_uint4(0u, 0u, 0u, 0u);
+      if (b0 + grp * 8 + j < E1)
+        raw[j] = *reinterpret_cast<const uint4*>(X + static_cast<size_t>(cur[j].x) * D + sub * 8);
+    }
+    // transpose in the lane (8 slots x 8 features) and park as [feature][slot]
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      uint32_t d[4];
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const uint32_t x = (&raw[2 * q].x)[i / 2], y = (&raw[2 * q + 1].x)[i / 2];
+        d[q] = (i % 2 == 0) ? lower_halves(x, y) : upper_halves(x, y);
+      }
+      *reinterpret_cast<uint4*>(xf + (sub * 8 + i) * G_::XP + grp * 16) = make_uint4(d[0], d[1], d[2], d[3]);
+    }
+    if (sub == 0) {  // values of slots 8 grp .. 8 grp + 7: the hi halves, the lo halves
+      const uint32_t y[8] = {static_cast<uint32_t>(cur[0].y), static_cast<uint32_t>(cur[1].y),
+                             static_cast<uint32_t>(cur[2].y), static_cast<uint32_t>(cur[3].y),
+                             static_cast<uint32_t>(cur[4].y), static_cast<uint32_t>(cur[5].y),
+                             static_cast<uint32_t>(cur[6].y), static_cast<uint32_t>(cur[7].y)};
+      *reinterpret_cast<uint4*>(wts + grp * 4) = make_uint4(upper_halves(y[0], y[1]), upper_halves(y[2], y[3]),
+                                                            upper_halves(y[4], y[5]), upper_halves(y[6], y[7]));
+      *reinterpret_cast<uint4*>(wts + G_::SE / 2 + grp * 4) =
+          make_uint4(lower_halves(y[0], y[1]), lower_halves(y[2], y[3]), lower_halves(y[4], y[5]),
+                     lower_halves(y[6], y[7]));
+    }
+    // fragments of the step: slots 16 ks + 8h .. + 7 of feature 32 tn + n, and their values
+    bf16x8 xa[G_::NT][G_::KS1];
+#pragma unroll
+    for (int tn = 0; tn < G_::NT; ++tn)
+#pragma unroll
+      for (int ks = 0; ks < G_::KS1; ++ks)
+        xa[tn][ks] = as_frag(*reinterpret_cast<const uint4*>(xf + (tn * 32 + n) * G_::XP + (2 * ks + h) * 16));
+    const int b1 = min(b0 + G_::SE, E1);
+    while (true) {
+      // slots of the step that belong to row n of the current tile, as a bit mask
+      const int mlo = min(max(ra - b0, 0), G_::SE), mhi = min(max(rb - b0, 0), G_::SE);
+      unsigned long long m64 = 0ull;
+      if (mlo < mhi) m64 = (mhi >= 64 ? ~0ull : ((1ull << mhi) - 1ull)) & ~((1ull << mlo) - 1ull);
+      m64 >>= 8 * h;
+      const int tlo = max(te0, b0) - b0, thi = min(te1, b1) - b0;  // the tile's slots in this step
+#pragma unroll
+      for (int ks = 0; ks < G_::KS1; ++ks) {
+        if (16 * ks < thi && 16 * ks + 16 > tlo) {
+          uint4 shi = *reinterpret_cast<const uint4*>(wts + (2 * ks + h) * 4);
+          uint4 slo = *reinterpret_cast<const uint4*>(wts + G_::SE / 2 + (2 * ks + h) * 4);
+          const uint32_t half = static_cast<uint32_t>(m64 >> (ks >= 2 ? 32 : 0));
+          const uint4 pm = pair_mask[(half >> ((16 * ks) % 32)) & 0xffu];
+          shi.x &= pm.x; shi.y &= pm.y; shi.z &= pm.z; shi.w &= pm.w;
+          slo.x &= pm.x; slo.y &= pm.y; slo.z &= pm.z; slo.w &= pm.w;
+#pragma unroll
+          for (int tn = 0; tn < G_::NT; ++tn) {
+            agg[tn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xa[tn][ks], as_frag(shi), agg[tn], 0, 0, 0);
+            agg[tn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xa[tn][ks], as_frag(slo), agg[tn], 0, 0, 0);
+          }
+        }
+      }
+      if (te1 > b1) break;  // the tile goes on in the next step
+      // the tile is complete: pre-reduced rows take their chunk partials
+      const int h0 = __builtin_amdgcn_readlane(factsA, RW + 1), h1 = __builtin_amdgcn_readlane(factsA, RW + 2);
+      for (int hh = h0; hh < h1; ++hh) {
+        if (g.heavy_rows[hh] - row0 == n) {
+          for (int ch = g.heavy_chunk_ptr[hh]; ch < g.heavy_chunk_ptr[hh + 1]; ++ch) {
+            const float* pp = heavy_partial + static_cast<size_t>(ch) * D;
+#pragma unroll
+            for (int tn = 0; tn < G_::NT; ++tn)
+#pragma unroll
+              for (int i = 0; i < 4; ++i) {
+                const float4 pv = *reinterpret_cast<const float4*>(pp + acc_feature(tn, h, 4 * i));
+                agg[tn][4 * i] += pv.x; agg[tn][4 * i + 1] += pv.y;
+                agg[tn][4 * i + 2] += pv.z; agg[tn][4 * i + 3] += pv.w;
+              }
+          }
+        }
+      }
+      on_tile(row0, nrows, agg);
+#pragma unroll
+      for (int tn = 0; tn < G_::NT; ++tn)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) agg[tn][r] = 0.f;
+      // next tile
+      ++tau;
+      if (tau >= tile1) break;
+      factsA = factsB;
+      factsB = factsC;
+      factsC = tile_facts(tau + 2);
+      row0 = rbeg + tau * RW;
+      nrows = min(RW, rend - row0);
+      te0 = te1;
+      te1 = __builtin_amdgcn_readlane(factsA, nrows);
+      ra = __shfl(factsA, n, 64);
+      rb = __shfl(factsA, n + 1, 64);
+    }
+#pragma unroll
+    for (int j = 0; j < 8; ++j) cur[j] = nxt[j];
+  }
+}
+
+template <int D>
+constexpr size_t fwd_wave_lds() {
+  return WG<D>::w_bytes + D * sizeof(float) + 256 * sizeof(uint4) + 4 * WG<D>::wave_bytes;
+}
+
+// ---------------------------------------------------------------------------
+// Forward: Y = relu((A_hat X) W^k)  [+ t = Y w_out^k]
+// ---------------------------------------------------------------------------
+template <int D>
+__global__ __launch_bounds__(kBlock, 3) void fwd_wave_kernel(
+    GraphView g, const bf16_t* __restrict__ X, const float* __restrict__ W, int w_stride,
+    bf16_t* __restrict__ Y, const float* __restrict__ w_out, int wout_stride, float* __restrict__ t,
+    const float* __restrict__ heavy_partial) {
+  using G_ = WG<D>;
+  extern __shared__ __align__(16) unsigned char smem[];
+  bf16_t* wfr = reinterpret_cast<bf16_t*>(smem);
+  float* wo = reinterpret_cast<float*>(smem + G_::w_bytes);
+  uint4* pair_mask = reinterpret_cast<uint4*>(smem + G_::w_bytes + D * sizeof(float));
+  unsigned char* wave_mem = reinterpret_cast<unsigned char*>(pair_mask + 256);
+
+  const int k = g.wblk_k[blockIdx.x];
+  if (k < 0) return;
+  const int tid = threadIdx.x, lane = tid % 64;
+  const int wave = __builtin_amdgcn_readfirstlane(tid / 64);
+  const int n = lane % 32, h = lane / 32;
+  const int grp = lane / G_::LPR, c0 = (lane % G_::LPR) * 8;
+  load_weight_fragments<D>(W + static_cast<size_t>(k) * w_stride, wfr);
+  fill_pair_masks(pair_mask);
+  if (tid < D) wo[tid] = w_out != nullptr ? w_out[static_cast<size_t>(k) * wout_stride + tid] : 0.f;
+  __syncthreads();  // the only workgroup barrier: W^k and w_out are in LDS
+
+  const int2 tiles = g.wwave_tiles[blockIdx.x * (kBlock / 64) + wave];
+  if (tiles.x >= tiles.y) return;
+  unsigned char* my_lds = wave_mem + wave * G_::wave_bytes;
+  bf16_t* ot = reinterpret_cast<bf16_t*>(my_lds);  // overlays the row buffer
+  stream_tiles<D>(g, g.went, X, k, tiles.x, tiles.y, my_lds, pair_mask, heavy_partial,
+                  [&](int row0, int nrows, const floatx16 (&agg)[G_::NT]) {
+    // Z^T = W^T AGG^T: the rounded aggregate is the B operand as it stands
+    floatx16 z[G_::NT];
+#pragma unroll
+    for (int tj = 0; tj < G_::NT; ++tj)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) z[tj][r] = 0.f;
+#pragma unroll
+    for (int ks2 = 0; ks2 < G_::KS2; ++ks2) {
+      float v[8];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) v[e] = agg[ks2 / 2][8 * (ks2 % 2) + e];
+      const bf16x8 b = as_frag(pack8(v));
+#pragma unroll
+      for (int tj = 0; tj < G_::NT; ++tj) {
+        const bf16x8 a = as_frag(*reinterpret_cast<const uint4*>(wfr + ((tj * G_::KS2 + ks2) * 64 + lane) * 8));
+        z[tj] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, z[tj], 0, 0, 0);
+      }
+    }
+    // ReLU, round; lane (n, h) holds features acc_feature(tj, h, r) of row n
+    float part = 0.f;
+#pragma unroll
+    for (int tj = 0; tj < G_::NT; ++tj)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int f0 = acc_feature(tj, 0, 4 * i) + 4 * h;
+        uint2 pk;
+        pk.x = relu_bf16x2(f32x2_to_bf16x2(z[tj][4 * i], z[tj][4 * i + 1]));
+        pk.y = relu_bf16x2(f32x2_to_bf16x2(z[tj][4 * i + 2], z[tj][4 * i + 3]));
+        if (w_out != nullptr) {
+          const float4 wv = *reinterpret_cast<const float4*>(wo + f0);
+          part = fmaf(__uint_as_float(pk.x << 16), wv.x, part);
+          part = fmaf(__uint_as_float(pk.x & 0xffff0000u), wv.y, part);
+          part = fmaf(__uint_as_float(pk.y << 16), wv.z, part);
+          part = fmaf(__uint_as_float(pk.y & 0xffff0000u), wv.w, part);
+        }
+        *reinterpret_cast<uint2*>(ot + n * G_::PA + f0) = pk;
+      }
+    // full rows, 16 bytes per lane
+#pragma unroll
+    for (int u = 0; u < G_::NO; ++u) {
+      const int r = u * G_::NG + grp;
+      if (r < nrows)
+        *reinterpret_cast<uint4*>(Y + static_cast<size_t>(row0 + r) * D + c0) =
+            *reinterpret_cast<const uint4*>(ot + r * G_::PA + c0);
+    }
+    if (w_out != nullptr) {  // t[r] = sum_c Y[r, c] * w_out[c]
+      part += __shfl_xor(part, 32, 64);
+      if (h == 0 && n < nrows) t[row0 + n] = part;
+    }
+  });
+}
+
+template <typename K>
+void allow_lds(K kernel, size_t bytes) {
+  if (bytes > 48 * 1024)
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(bytes));
+}
+
+}  // namespace
+
+void launch_fwd_hidden_wave(const Launch& ln, int D, const GraphView& g, const void* X, const float* W,
+                            int w_stride, void* Y, const float* w_out, int wout_stride, float* t,
+                            float* heavy_partial) {
+  if (D != 64) return;
+  allow_lds(fwd_wave_kernel<64>, fwd_wave_lds<64>());
+  ln.begin(KK_FWD_HIDDEN);
+  fwd_wave_kernel<64><<<g.num_wblocks, kBlock, fwd_wave_lds<64>(), ln.st>>>(
+      g, static_cast<const bf16_t*>(X), W, w_stride, static_cast<bf16_t*>(Y), w_out, wout_stride, t,
+      heavy_partial);
+  ln.end(KK_FWD_HIDDEN);
+}
+
+}  // namespace gco
