@@ -108,6 +108,7 @@ struct gco_ctx {
   int32_t *d_blk_S = nullptr, *d_nblk_S = nullptr;
   int32_t *d_pbl_ptr = nullptr, *d_pbl_list = nullptr;
   int32_t *d_nbl_ptr = nullptr, *d_nbl_list = nullptr;
+  int32_t *d_nwbl_ptr = nullptr, *d_nwbl_list = nullptr;  // narrow workgroups per weight set
   int32_t *d_heavy_of_row = nullptr, *d_heavy_chunk_ptr = nullptr, *d_chunk_begin = nullptr,
           *d_chunk_end = nullptr, *d_chunk_part = nullptr;
   int32_t* d_heavy_rows = nullptr;
@@ -182,6 +183,8 @@ struct gco_ctx {
     loss_hist = nullptr;
   }
   int elem_bytes() const { return cfg.storage == GCO_STORAGE_BF16 ? 2 : 4; }
+  // the hidden layers run on the wave-per-tile kernels (bf16 storage, width 64)
+  bool wave_path() const { return cfg.storage == GCO_STORAGE_BF16 && cfg.dim == 64; }
   Launch launch() { return Launch{st, prof.mode ? &prof : nullptr}; }
 };
 
@@ -675,6 +678,14 @@ int gco_upload_graph(gco_ctx* ctx, int64_t n64, const int64_t* rowptr, const int
     HIPCHK(h2d(ctx, ctx->d_nbl_ptr, ptr.data(), ptr.size()));
     HIPCHK(h2d(ctx, ctx->d_nbl_list, list.data(), list.size()));
   }
+  {
+    std::vector<int> ptr, list;
+    bucket_blocks(nblk_k, ctx->Pw, ptr, list);
+    GALLOC(ctx->d_nwbl_ptr, ptr.size());
+    GALLOC(ctx->d_nwbl_list, std::max<size_t>(1, list.size()));
+    HIPCHK(h2d(ctx, ctx->d_nwbl_ptr, ptr.data(), ptr.size()));
+    HIPCHK(h2d(ctx, ctx->d_nwbl_list, list.data(), list.size()));
+  }
   // very long rows
   std::vector<int> heavy_of_row, heavy_rows, heavy_chunk_ptr(1, 0), chunk_begin, chunk_end, chunk_part;
   int num_heavy = 0;
@@ -793,14 +804,15 @@ int gco_upload_graph(gco_ctx* ctx, int64_t n64, const int64_t* rowptr, const int
     uint8_t* q = nullptr;
     GALLOC(q, nd * eb);
     ctx->H[l] = q;
-    GALLOC(ctx->gW_partial[l - 1], static_cast<size_t>(g.num_blocks) * D * D);
+    GALLOC(ctx->gW_partial[l - 1], static_cast<size_t>(std::max(g.num_blocks, g.num_wblocks)) * D * D);
   }
-  for (int l = 1; l <= L - 2; ++l) {
+  // G_Z between two hidden layers; the wave-per-tile kernels also store that of the last one
+  for (int l = 1; l <= (ctx->wave_path() ? L - 1 : L - 2); ++l) {
     uint8_t* q = nullptr;
     GALLOC(q, nd * eb);
     ctx->GZ[l] = q;
   }
-  GALLOC(ctx->gwout_partial, static_cast<size_t>(g.num_blocks) * D);
+  GALLOC(ctx->gwout_partial, static_cast<size_t>(std::max(g.num_blocks, g.num_nblocks)) * D);
   GALLOC(ctx->t, static_cast<size_t>(n));
   GALLOC(ctx->z, static_cast<size_t>(n));
   GALLOC(ctx->p, static_cast<size_t>(n));
@@ -994,6 +1006,7 @@ static void run_backward(gco_ctx* ctx, bool update, float* gE, float* const* gW)
   a.gE = gE;
   a.adam = ad;
   a.heavy_partial = ctx->d_heavy_partial;
+  a.GZ_last = L >= 2 ? ctx->GZ[L - 1] : nullptr;
   a.mode = update ? (c.train_embed ? EMBED_ADAM : EMBED_SKIP) : (gE ? EMBED_WRITE_GRAD : EMBED_SKIP);
   if (L == 1) {
     a.Hprev = ctx->H[0];
@@ -1011,16 +1024,21 @@ static void run_backward(gco_ctx* ctx, bool update, float* gE, float* const* gW)
       launch_bwd_hidden(ln, c.storage, D, last, to_embed, ctx->gv, a);
     }
   }
+  WeightTensor wt[3];
   for (int l = 1; l <= L; ++l) {
-    WeightTensor wt;
-    wt.W = ctx->W[l - 1];
-    wt.m = ctx->mW[l - 1];
-    wt.v = ctx->vW[l - 1];
-    wt.partial = l < L ? ctx->gW_partial[l - 1] : ctx->gwout_partial;
-    wt.grad_out = (!update && gW) ? gW[l - 1] : nullptr;
-    wt.elems = w_elems(ctx, l);
-    launch_adam_w(ln, ctx->gv, ctx->d_pbl_ptr, ctx->d_pbl_list, ctx->Pw, wt, ad, update);
+    wt[l - 1].W = ctx->W[l - 1];
+    wt[l - 1].m = ctx->mW[l - 1];
+    wt[l - 1].v = ctx->vW[l - 1];
+    wt[l - 1].partial = l < L ? ctx->gW_partial[l - 1] : ctx->gwout_partial;
+    wt[l - 1].grad_out = (!update && gW) ? gW[l - 1] : nullptr;
+    wt[l - 1].elems = w_elems(ctx, l);
+    // who wrote the partials: the wide kernels' workgroups, or, on the wave-per-tile path,
+    // its own workgroups (hidden layers) and the narrow ones (scalar layer)
+    const bool wave = ctx->wave_path() && L >= 2;
+    wt[l - 1].blk_ptr = !wave ? ctx->d_pbl_ptr : (l < L ? ctx->d_wpbl_ptr : ctx->d_nwbl_ptr);
+    wt[l - 1].blk_list = !wave ? ctx->d_pbl_list : (l < L ? ctx->d_wpbl_list : ctx->d_nwbl_list);
   }
+  launch_adam_w(ln, ctx->Pw, wt, L, ad, update);
   if (update) ctx->probs_valid = true;  // p is that of the parameters before the step
 }
 

@@ -159,6 +159,7 @@ void launch_bwd_readout(const Launch& ln, const GraphView& g, const float* g_z, 
 //   else write GZ_out = G_Hprev * [Hprev > 0].
 struct BwdArgs {
   const void* GZ_in = nullptr;   // [n, D] storage type (not last)
+  void* GZ_last = nullptr;       // [n, D] bf16: where the wave-per-tile path forms G_Z of the last hidden layer
   const void* Hcur = nullptr;    // [n, D] storage type (last)
   const float* g_t = nullptr;    // [n] (last)
   const float* w_out = nullptr;  // [Pw, D] (last)
@@ -191,6 +192,11 @@ void launch_bwd_hidden_bf16(const Launch& ln, int D, bool last, bool to_embed, c
                             const BwdArgs& a);
 
 // wave-per-tile bf16 kernels (wave_kernels_bf16.hip), width 64
+// last hidden layer: a.GZ_last = G_Z formed from g_t, w_out and Hcur; gw_out partials per
+// narrow workgroup
+void launch_form_gz_last(const Launch& ln, int D, const GraphView& g, const BwdArgs& a);
+// hidden-layer backward on G_Z = a.GZ_in; gW partials per wave-kernel workgroup
+void launch_bwd_hidden_wave(const Launch& ln, int D, bool to_embed, const GraphView& gt, const BwdArgs& a);
 void launch_fwd_hidden_wave(const Launch& ln, int D, const GraphView& g, const void* X, const float* W,
                             int w_stride, void* Y, const float* w_out, int wout_stride, float* t,
                             float* heavy_partial);
@@ -199,17 +205,19 @@ void launch_fwd_hidden_wave(const Launch& ln, int D, const GraphView& g, const v
 void launch_bwd_single(const Launch& ln, int storage, int D, const GraphView& g, const BwdArgs& a);
 
 // Sum the per-workgroup partials of each weight tensor in a fixed order, then
-// apply Adam (or only write the gradient when grad_out != nullptr).
+// apply Adam (or only write the gradient when grad_out != nullptr).  Up to three
+// tensors (one per layer) are served by one launch.
 struct WeightTensor {
   float* W = nullptr;
   float* m = nullptr;
   float* v = nullptr;
-  const float* partial = nullptr;  // [num_blocks, elems]
+  const float* partial = nullptr;  // [workgroups, elems]
+  const int* blk_ptr = nullptr;    // workgroups that hold partials of weight set kw:
+  const int* blk_list = nullptr;   //   blk_list[blk_ptr[kw] .. blk_ptr[kw+1])
   float* grad_out = nullptr;       // [Pw, elems] or nullptr
   int elems = 0;                   // per subgraph
 };
-void launch_adam_w(const Launch& ln, const GraphView& g, const int* part_blk_ptr,
-                   const int* part_blk_list, int Pw, const WeightTensor& wt, const AdamStep& adam,
+void launch_adam_w(const Launch& ln, int Pw, const WeightTensor* tensors, int count, const AdamStep& adam,
                    bool update);
 
 // fp32 -> bf16 copy (round to nearest even).

@@ -1075,6 +1075,21 @@ void fwd_t(const Launch& ln, const GraphView& g, const void* X, const float* W, 
 
 template <int D>
 void bwd_t(const Launch& ln, bool last, bool to_embed, const GraphView& gt, const BwdArgs& a) {
+  if (D == 64) {  // wave-per-tile kernels: G_Z of the last layer is formed first
+    BwdArgs b = a;
+    if (last) {
+      launch_form_gz_last(ln, D, gt, a);
+      b.GZ_in = a.GZ_last;
+    }
+    if (gt.num_chunks > 0) {
+      ln.begin(KK_HEAVY);
+      const PlainB<D> src{static_cast<const bf16_t*>(b.GZ_in), gt.diag};
+      heavy_wide_b_kernel<D, PlainB<D>><<<gt.num_chunks, kBlock, 0, ln.st>>>(gt, src, a.heavy_partial);
+      ln.end(KK_HEAVY);
+    }
+    launch_bwd_hidden_wave(ln, D, to_embed, gt, b);
+    return;
+  }
   if (gt.num_chunks > 0) {
     ln.begin(KK_HEAVY);
     if (last) {

@@ -485,16 +485,40 @@ __global__ __launch_bounds__(kBlock) void loss_reduce_kernel(GraphView g, const 
 // ---------------------------------------------------------------------------
 // Adam on the weight matrices (with the fixed-order reduction of the partials)
 // ---------------------------------------------------------------------------
-__global__ __launch_bounds__(kBlock) void adam_w_kernel(const int* __restrict__ part_blk_ptr,
-                                                        const int* __restrict__ part_blk_list, int Pw,
-                                                        WeightTensor wt, AdamStep ad, int update) {
-  const int64_t gid = static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x;
-  if (gid >= static_cast<int64_t>(Pw) * wt.elems) return;
+struct WeightTensors {
+  WeightTensor t[3];
+  int count = 0;
+};
+
+// One thread per weight of every tensor.  The partials are added in groups of 16
+// (pairwise inside a group, groups in list order) so that 16 loads are in flight.
+__global__ __launch_bounds__(kBlock) void adam_w_kernel(int Pw, WeightTensors wts, AdamStep ad, int update) {
+  int64_t gid = static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x;
+  int which = 0;
+  while (which < wts.count && gid >= static_cast<int64_t>(Pw) * wts.t[which].elems) {
+    gid -= static_cast<int64_t>(Pw) * wts.t[which].elems;
+    ++which;
+  }
+  if (which >= wts.count) return;
+  const WeightTensor& wt = wts.t[which];
   const int k = static_cast<int>(gid / wt.elems);
   const int idx = static_cast<int>(gid % wt.elems);
+  const float* base = wt.partial + idx;
+  const int* __restrict__ part_blk_list = wt.blk_list;
   float gsum = 0.f;
-  for (int q = part_blk_ptr[k]; q < part_blk_ptr[k + 1]; ++q)
-    gsum += wt.partial[static_cast<size_t>(part_blk_list[q]) * wt.elems + idx];
+  int q = wt.blk_ptr[k];
+  const int q1 = wt.blk_ptr[k + 1];
+  for (; q + 16 <= q1; q += 16) {
+    float v[16];
+#pragma unroll
+    for (int u = 0; u < 16; ++u) v[u] = base[static_cast<size_t>(part_blk_list[q + u]) * wt.elems];
+#pragma unroll
+    for (int w = 1; w < 16; w *= 2)
+#pragma unroll
+      for (int u = 0; u < 16; u += 2 * w) v[u] += v[u + w];
+    gsum += v[0];
+  }
+  for (; q < q1; ++q) gsum += base[static_cast<size_t>(part_blk_list[q]) * wt.elems];
   if (wt.grad_out != nullptr) wt.grad_out[gid] = gsum;
   if (update) {
     const float m = ad.b1 * wt.m[gid] + (1.f - ad.b1) * gsum;
@@ -683,14 +707,18 @@ void launch_bwd_single(const Launch& ln, int storage, int D, const GraphView& g,
   ln.end(KK_BWD_EMBED);
 }
 
-void launch_adam_w(const Launch& ln, const GraphView& g, const int* part_blk_ptr,
-                   const int* part_blk_list, int Pw, const WeightTensor& wt, const AdamStep& adam,
+void launch_adam_w(const Launch& ln, int Pw, const WeightTensor* tensors, int count, const AdamStep& adam,
                    bool update) {
-  (void)g;
-  const int64_t total = static_cast<int64_t>(Pw) * wt.elems;
+  WeightTensors wts;
+  wts.count = count;
+  int64_t total = 0;
+  for (int i = 0; i < count; ++i) {
+    wts.t[i] = tensors[i];
+    total += static_cast<int64_t>(Pw) * tensors[i].elems;
+  }
   const int blocks = static_cast<int>((total + kBlock - 1) / kBlock);
   ln.begin(KK_ADAM_W);
-  adam_w_kernel<<<blocks, kBlock, 0, ln.st>>>(part_blk_ptr, part_blk_list, Pw, wt, adam, update ? 1 : 0);
+  adam_w_kernel<<<blocks, kBlock, 0, ln.st>>>(Pw, wts, adam, update ? 1 : 0);
   ln.end(KK_ADAM_W);
 }
 

@@ -58,11 +58,20 @@ struct WG {
   static constexpr int NO = RW / NG;     // output rows per lane group
   static constexpr int XP = SE * 2 + 16; // bytes per feature in the transposed row buffer
   static constexpr int PA = D + 8;       // pitch of the bf16 output tile
-  static constexpr size_t xf_bytes = static_cast<size_t>(D) * XP;
+  static constexpr int GP = RW * 2 + 16; // bytes per feature of a transposed 32-row bf16 tile
+  static constexpr int PF = D + 4;       // pitch (floats) of an fp32 32-row tile
+  // one wave-private LDS region serves, in turn, as the transposed row buffer of a step,
+  // as the two transposed tiles of the weight-gradient product, and as the output tile
+  static constexpr size_t xf_bytes = static_cast<size_t>(D) * XP;  // forward: row buffer / output tile
+  static constexpr size_t region_bytes =                           // backward
+      static_cast<size_t>(D) * (XP > 2 * GP ? XP : 2 * GP) > static_cast<size_t>(RW) * PF * 4
+          ? static_cast<size_t>(D) * (XP > 2 * GP ? XP : 2 * GP)
+          : static_cast<size_t>(RW) * PF * 4;
   static constexpr size_t wts_bytes = static_cast<size_t>(SE) * 4;  // hi halves, then lo halves
   static constexpr size_t ot_bytes = static_cast<size_t>(RW) * PA * 2;
   // the output tile reuses the row buffer: the step's fragments are in registers by then
   static constexpr size_t wave_bytes = xf_bytes + wts_bytes;
+  static constexpr size_t bwd_wave_bytes = region_bytes + wts_bytes;
   static_assert(ot_bytes <= xf_bytes, "the output tile overlays the row buffer");
   static constexpr size_t w_bytes = static_cast<size_t>(D) * D * 2;
   static_assert(SE <= 64, "slot masks are 64 bits wide");
@@ -102,6 +111,26 @@ __device__ __forceinline__ void load_weight_fragments(const float* __restrict__ 
   }
 }
 
+// W^k -> LDS as A operands of G_H^T = W G_T^T:
+// wfr[((ta * KS2 + ks2) * 64 + lane) * 8 + e] = W[32 ta + n][feature_of(ks2, h, e)].
+template <int D>
+__device__ __forceinline__ void load_weight_fragments_t(const float* __restrict__ Wk, bf16_t* wfr) {
+  constexpr int kPer = D * D / 4 / kBlock;
+  float4 v[kPer];
+#pragma unroll
+  for (int q = 0; q < kPer; ++q) v[q] = reinterpret_cast<const float4*>(Wk)[threadIdx.x + q * kBlock];
+#pragma unroll
+  for (int q = 0; q < kPer; ++q) {
+    const int idx = (threadIdx.x + q * kBlock) * 4;
+    const int a = idx / D, b0 = idx % D;  // W[a][b0 .. b0+3]: one run e%4 = 0..3 of feature_of
+    const int ks2 = b0 / 16, h = (b0 / 4) % 2, e0 = ((b0 / 8) % 2) * 4;
+    uint2 pk;
+    pk.x = f32x2_to_bf16x2(v[q].x, v[q].y);
+    pk.y = f32x2_to_bf16x2(v[q].z, v[q].w);
+    *reinterpret_cast<uint2*>(wfr + (((a / 32) * WG<D>::KS2 + ks2) * 64 + h * 32 + a % 32) * 8 + e0) = pk;
+  }
+}
+
 // pair_mask[b] for an 8-bit pattern b: four words whose 16-bit halves are all ones where
 // the corresponding bit of b is set (bit 2d -> lower half of word d).
 __device__ __forceinline__ void fill_pair_masks(uint4* pair_mask) {
@@ -125,19 +154,18 @@ __device__ __forceinline__ uint32_t upper_halves(uint32_t x, uint32_t y) {
 // Calls on_tile(row0, nrows, agg) for every tile tau in [tile0, tile1) of subgraph k, in
 // order.  agg[tn][r] at lane (n, h) is element (row0 + n, acc_feature(tn, h, r)) of
 // A_hat X in fp32 (zero for rows past nrows).  `went` is the light stream of the matrix
-// that is applied (A_hat or its transpose); wave_lds is this wavefront's xf_bytes +
-// wts_bytes of LDS; pair_mask is the workgroup's table from fill_pair_masks.
+// that is applied (A_hat or its transpose); xf (xf_bytes) and wts (wts_bytes) are this
+// wavefront's LDS; pair_mask is the workgroup's table from fill_pair_masks.  on_tile may
+// overwrite xf.
 template <int D, typename OnTile>
 __device__ __forceinline__ void stream_tiles(const GraphView& g, const int2* __restrict__ went,
                                              const bf16_t* __restrict__ X, int k, int tile0, int tile1,
-                                             unsigned char* wave_lds, const uint4* pair_mask,
+                                             unsigned char* xf, uint32_t* wts, const uint4* pair_mask,
                                              const float* __restrict__ heavy_partial, OnTile&& on_tile) {
   using G_ = WG<D>;
   const int lane = threadIdx.x % 64;
   const int n = lane % 32, h = lane / 32;
   const int grp = lane / G_::LPR, sub = lane % G_::LPR;
-  unsigned char* xf = wave_lds;
-  uint32_t* wts = reinterpret_cast<uint32_t*>(wave_lds + G_::xf_bytes);
 
   const int rbeg = g.part_rows[k], rend = g.part_rows[k + 1];
   const int row_end = min(rend, rbeg + tile1 * RW);
@@ -308,7 +336,8 @@ __global__ __launch_bounds__(kBlock, 3) void fwd_wave_kernel(
   if (tiles.x >= tiles.y) return;
   unsigned char* my_lds = wave_mem + wave * G_::wave_bytes;
   bf16_t* ot = reinterpret_cast<bf16_t*>(my_lds);  // overlays the row buffer
-  stream_tiles<D>(g, g.went, X, k, tiles.x, tiles.y, my_lds, pair_mask, heavy_partial,
+  stream_tiles<D>(g, g.went, X, k, tiles.x, tiles.y, my_lds,
+                  reinterpret_cast<uint32_t*>(my_lds + G_::xf_bytes), pair_mask, heavy_partial,
                   [&](int row0, int nrows, const floatx16 (&agg)[G_::NT]) {
     // Z^T = W^T AGG^T: the rounded aggregate is the B operand as it stands
     floatx16 z[G_::NT];
@@ -362,6 +391,299 @@ __global__ __launch_bounds__(kBlock, 3) void fwd_wave_kernel(
   });
 }
 
+// ---------------------------------------------------------------------------
+// G_Z of the last hidden layer, formed row by row from the scalar layer's gradient:
+//   GZ[i, :] = g_t[i] * w_out^k * [Hcur[i, :] > 0]      (rounded to bf16)
+// and the scalar layer's weight gradient, one partial per workgroup:
+//   gwout_partial[workgroup, :] = sum_i Hcur[i, :] g_t[i].
+// One workgroup per 256-row tile of the narrow decomposition.
+// ---------------------------------------------------------------------------
+template <int D>
+__global__ __launch_bounds__(kBlock) void form_gz_last_kernel(
+    GraphView g, const bf16_t* __restrict__ Hcur, const float* __restrict__ g_t,
+    const float* __restrict__ w_out, int wout_stride, bf16_t* __restrict__ GZ,
+    float* __restrict__ gwout_partial) {
+  constexpr int LPR = D / 8, RP = kBlock / LPR;  // lanes per row, rows per pass
+  __shared__ float red[RP][D + 1];
+  const int k = g.nblk_k[blockIdx.x];
+  if (k < 0) return;
+  const int s = g.nblk_s[blockIdx.x];
+  const int rbeg = g.part_rows[k], rend = g.part_rows[k + 1];
+  const int rr = threadIdx.x / LPR, c0 = (threadIdx.x % LPR) * 8;
+  float wv[8], gacc[8];
+#pragma unroll
+  for (int x = 0; x < 8; ++x) {
+    wv[x] = w_out[static_cast<size_t>(k) * wout_stride + c0 + x];
+    gacc[x] = 0.f;
+  }
+  for (int row0 = rbeg + s * kNarrowRows; row0 < rend; row0 += g.nblk_S[blockIdx.x] * kNarrowRows) {
+    const int nrows = min(kNarrowRows, rend - row0);
+    for (int r = rr; r < nrows; r += RP) {
+      const size_t off = static_cast<size_t>(row0 + r) * D + c0;
+      const float gt = g_t[row0 + r];
+      float hv[8], out[8];
+      unpack8(*reinterpret_cast<const uint4*>(Hcur + off), hv);
+#pragma unroll
+      for (int x = 0; x < 8; ++x) {
+        out[x] = hv[x] > 0.f ? gt * wv[x] : 0.f;
+        gacc[x] = fmaf(hv[x], gt, gacc[x]);
+      }
+      *reinterpret_cast<uint4*>(GZ + off) = pack8(out);
+    }
+  }
+#pragma unroll
+  for (int x = 0; x < 8; ++x) red[rr][c0 + x] = gacc[x];
+  __syncthreads();
+  if (threadIdx.x < D) {
+    float acc = 0.f;
+    for (int r = 0; r < RP; ++r) acc += red[r][threadIdx.x];
+    gwout_partial[static_cast<size_t>(blockIdx.x) * D + threadIdx.x] = acc;
+  }
+}
+
+// Positive halves of h select the halves of v (two packed bf16 values each).
+__device__ __forceinline__ uint32_t keep_where_positive(uint32_t v, uint32_t h) {
+  typedef short i16x2_t __attribute__((ext_vector_type(2)));
+  typedef unsigned short u16x2_t __attribute__((ext_vector_type(2)));
+  i16x2_t hs;
+  __builtin_memcpy(&hs, &h, 4);
+  const i16x2_t zero = {0, 0}, one = {1, 1};
+  hs = __builtin_elementwise_min(__builtin_elementwise_max(hs, zero), one);  // 1 where h > 0
+  u16x2_t m, vv;
+  __builtin_memcpy(&m, &hs, 4);
+  __builtin_memcpy(&vv, &v, 4);
+  vv = vv * m;
+  uint32_t r;
+  __builtin_memcpy(&r, &vv, 4);
+  return r;
+}
+
+template <int D>
+constexpr size_t bwd_wave_lds() {
+  return WG<D>::w_bytes + 256 * sizeof(uint4) + 4 * WG<D>::bwd_wave_bytes;
+}
+
+// ---------------------------------------------------------------------------
+// Backward of a hidden layer:  G_T = A_hat^T G_Z  (stream_tiles over the transposed
+// light stream);  gW partial = sum over the workgroup's rows of Hprev^T G_T;
+// G_Hprev = G_T W^T;  then GZ_out = G_Hprev * [Hprev > 0], or, on the embedding
+// (TO_EMBED), Adam on E / writing the gradient.
+// Per tile, in the wave's LDS region: G_T (bf16) and Hprev, both transposed to
+// [feature][row], feed the weight-gradient product (contraction over the 32 rows);
+// the rounded G_T^T in registers is the B operand of G_H^T = W G_T^T; the result is
+// staged once more to reach full rows.  Hprev rows of the next tile are requested
+// while the current one is finished.
+// ---------------------------------------------------------------------------
+template <int D, bool TO_EMBED>
+__global__ __launch_bounds__(kBlock, 2) void bwd_wave_kernel(GraphView g, BwdArgs a) {
+  using G_ = WG<D>;
+  extern __shared__ __align__(16) unsigned char smem[];
+  bf16_t* wfr = reinterpret_cast<bf16_t*>(smem);
+  uint4* pair_mask = reinterpret_cast<uint4*>(smem + G_::w_bytes);
+  unsigned char* wave_mem = reinterpret_cast<unsigned char*>(pair_mask + 256);
+  static_assert(4 * G_::bwd_wave_bytes >= 2 * D * D * sizeof(float), "room for the gradient reduction");
+
+  const int k = g.wblk_k[blockIdx.x];
+  if (k < 0) return;
+  const int tid = threadIdx.x, lane = tid % 64;
+  const int wave = __builtin_amdgcn_readfirstlane(tid / 64);
+  const int n = lane % 32, h = lane / 32;
+  const int grp = lane / G_::LPR, sub = lane % G_::LPR;
+  load_weight_fragments_t<D>(a.W + static_cast<size_t>(k) * a.w_stride, wfr);
+  fill_pair_masks(pair_mask);
+  __syncthreads();
+
+  const bf16_t* GZ = static_cast<const bf16_t*>(a.GZ_in);
+  const bf16_t* Hprev = static_cast<const bf16_t*>(a.Hprev);
+  const int2 tiles = g.wwave_tiles[blockIdx.x * (kBlock / 64) + wave];
+  unsigned char* R = wave_mem + wave * G_::bwd_wave_bytes;
+  const bool need_gh = !(TO_EMBED && a.mode == EMBED_SKIP);
+  floatx16 gw[G_::NT][G_::NT];
+#pragma unroll
+  for (int ta = 0; ta < G_::NT; ++ta)
+#pragma unroll
+    for (int tb = 0; tb < G_::NT; ++tb)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) gw[ta][tb][r] = 0.f;
+
+  if (tiles.x < tiles.y) {
+    const int rbeg = g.part_rows[k];
+    const int row_end = min(g.part_rows[k + 1], rbeg + tiles.y * RW);
+    // rows 4 grp + u (u = 0..3) of a tile, features 8 sub .. + 7: what this lane loads of
+    // Hprev and what it stores of the result
+    constexpr int RPL = RW / G_::NG;
+    uint4 hp_raw[RPL];
+    auto request_hprev = [&](int row0) {
+#pragma unroll
+      for (int u = 0; u < RPL; ++u) {
+        const int r = row0 + RPL * grp + u;
+        hp_raw[u] = make_uint4(0u, 0u, 0u, 0u);
+        if (r < row_end) hp_raw[u] = *reinterpret_cast<const uint4*>(Hprev + static_cast<size_t>(r) * D + sub * 8);
+      }
+    };
+    request_hprev(rbeg + tiles.x * RW);
+    static_assert(RPL == 4, "four rows per lane group");
+
+    stream_tiles<D>(g, g.went, GZ, k, tiles.x, tiles.y, R, reinterpret_cast<uint32_t*>(R + G_::region_bytes),
+                    pair_mask, a.heavy_partial,
+                    [&](int row0, int nrows, const floatx16 (&agg)[G_::NT]) {
+      // G_T^T rounded to bf16: B operands of the second product
+      uint4 bq[G_::KS2];
+#pragma unroll
+      for (int ks2 = 0; ks2 < G_::KS2; ++ks2) {
+        float v[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) v[e] = agg[ks2 / 2][8 * (ks2 % 2) + e];
+        bq[ks2] = pack8(v);
+      }
+      // G_T and Hprev as [feature][row]
+      unsigned char* gtl = R;
+      unsigned char* hpl = R + D * G_::GP;
+#pragma unroll
+      for (int ks2 = 0; ks2 < G_::KS2; ++ks2)
+#pragma unroll
+        for (int d = 0; d < 4; ++d) {
+          const int f = feature_of(ks2, 0, 2 * d) + 4 * h;
+          const uint32_t w = (&bq[ks2].x)[d];
+          *reinterpret_cast<uint16_t*>(gtl + f * G_::GP + n * 2) = static_cast<uint16_t>(w & 0xffffu);
+          *reinterpret_cast<uint16_t*>(gtl + (f + 1) * G_::GP + n * 2) = static_cast<uint16_t>(w >> 16);
+        }
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        const uint32_t x0 = (&hp_raw[0].x)[i / 2], x1 = (&hp_raw[1].x)[i / 2];
+        const uint32_t x2 = (&hp_raw[2].x)[i / 2], x3 = (&hp_raw[3].x)[i / 2];
+        uint2 d;
+        d.x = (i % 2 == 0) ? lower_halves(x0, x1) : upper_halves(x0, x1);
+        d.y = (i % 2 == 0) ? lower_halves(x2, x3) : upper_halves(x2, x3);
+        *reinterpret_cast<uint2*>(hpl + (sub * 8 + i) * G_::GP + grp * (RPL * 2)) = d;
+      }
+      // gW[a, b] += sum over the tile's rows of Hprev[row, a] G_T[row, b]
+#pragma unroll
+      for (int ks = 0; ks < RW / 16; ++ks) {
+        bf16x8 af[G_::NT], bf[G_::NT];
+#pragma unroll
+        for (int t = 0; t < G_::NT; ++t) {
+          af[t] = as_frag(*reinterpret_cast<const uint4*>(hpl + (32 * t + n) * G_::GP + (16 * ks + 8 * h) * 2));
+          bf[t] = as_frag(*reinterpret_cast<const uint4*>(gtl + (32 * t + n) * G_::GP + (16 * ks + 8 * h) * 2));
+        }
+#pragma unroll
+        for (int ta = 0; ta < G_::NT; ++ta)
+#pragma unroll
+          for (int tb = 0; tb < G_::NT; ++tb)
+            gw[ta][tb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[ta], bf[tb], gw[ta][tb], 0, 0, 0);
+      }
+      if (need_gh) {
+        // G_H^T = W G_T^T
+        floatx16 z[G_::NT];
+#pragma unroll
+        for (int ta = 0; ta < G_::NT; ++ta)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) z[ta][r] = 0.f;
+#pragma unroll
+        for (int ks2 = 0; ks2 < G_::KS2; ++ks2)
+#pragma unroll
+          for (int ta = 0; ta < G_::NT; ++ta) {
+            const bf16x8 wa =
+                as_frag(*reinterpret_cast<const uint4*>(wfr + ((ta * G_::KS2 + ks2) * 64 + lane) * 8));
+            z[ta] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wa, as_frag(bq[ks2]), z[ta], 0, 0, 0);
+          }
+        if (TO_EMBED) {
+          // full fp32 rows through the region, then Adam (or the plain gradient)
+          float* st = reinterpret_cast<float*>(R);
+#pragma unroll
+          for (int ta = 0; ta < G_::NT; ++ta)
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+              *reinterpret_cast<float4*>(st + n * G_::PF + acc_feature(ta, 0, 4 * i) + 4 * h) =
+                  make_float4(z[ta][4 * i], z[ta][4 * i + 1], z[ta][4 * i + 2], z[ta][4 * i + 3]);
+          constexpr int LR = D / 4;        // lanes per fp32 row
+          constexpr int RI = 64 / LR;      // rows per instruction
+#pragma unroll
+          for (int q = 0; q < RW / RI; ++q) {
+            const int r = q * RI + lane / LR, cc = (lane % LR) * 4;
+            if (r < nrows) {
+              const float4 gq = *reinterpret_cast<const float4*>(st + r * G_::PF + cc);
+              const size_t off = static_cast<size_t>(row0 + r) * D + cc;
+              if (a.mode == EMBED_WRITE_GRAD) {
+                *reinterpret_cast<float4*>(a.gE + off) = gq;
+              } else {
+                const float4 m0 = *reinterpret_cast<const float4*>(a.mE + off);
+                const float4 v0 = *reinterpret_cast<const float4*>(a.vE + off);
+                const float4 e0 = *reinterpret_cast<const float4*>(a.E + off);
+                const float gv[4] = {gq.x, gq.y, gq.z, gq.w};
+                const float mv[4] = {m0.x, m0.y, m0.z, m0.w};
+                const float vv[4] = {v0.x, v0.y, v0.z, v0.w};
+                const float ev[4] = {e0.x, e0.y, e0.z, e0.w};
+                float mo[4], vo[4], eo[4];
+#pragma unroll
+                for (int x = 0; x < 4; ++x) {
+                  mo[x] = a.adam.b1 * mv[x] + (1.f - a.adam.b1) * gv[x];
+                  vo[x] = a.adam.b2 * vv[x] + (1.f - a.adam.b2) * gv[x] * gv[x];
+                  const float upd =
+                      (mo[x] * a.adam.inv_bc1) / (sqrtf(vo[x]) * a.adam.inv_sqrt_bc2 + a.adam.eps);
+                  eo[x] = ev[x] - a.adam.lr * upd;
+                }
+                *reinterpret_cast<float4*>(a.mE + off) = make_float4(mo[0], mo[1], mo[2], mo[3]);
+                *reinterpret_cast<float4*>(a.vE + off) = make_float4(vo[0], vo[1], vo[2], vo[3]);
+                *reinterpret_cast<float4*>(a.E + off) = make_float4(eo[0], eo[1], eo[2], eo[3]);
+                uint2 eb;
+                eb.x = f32x2_to_bf16x2(eo[0], eo[1]);
+                eb.y = f32x2_to_bf16x2(eo[2], eo[3]);
+                *reinterpret_cast<uint2*>(static_cast<bf16_t*>(a.Eb) + off) = eb;
+              }
+            }
+          }
+        } else {
+          // GZ_out = G_Hprev * [Hprev > 0]: full bf16 rows through the region
+          bf16_t* ot = reinterpret_cast<bf16_t*>(R);
+#pragma unroll
+          for (int ta = 0; ta < G_::NT; ++ta)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+              uint2 pk;
+              pk.x = f32x2_to_bf16x2(z[ta][4 * i], z[ta][4 * i + 1]);
+              pk.y = f32x2_to_bf16x2(z[ta][4 * i + 2], z[ta][4 * i + 3]);
+              *reinterpret_cast<uint2*>(ot + n * G_::PA + acc_feature(ta, 0, 4 * i) + 4 * h) = pk;
+            }
+          bf16_t* GZo = static_cast<bf16_t*>(a.GZ_out);
+#pragma unroll
+          for (int u = 0; u < RPL; ++u) {
+            const int r = RPL * grp + u;
+            uint4 o = *reinterpret_cast<const uint4*>(ot + r * G_::PA + sub * 8);
+            o.x = keep_where_positive(o.x, hp_raw[u].x);
+            o.y = keep_where_positive(o.y, hp_raw[u].y);
+            o.z = keep_where_positive(o.z, hp_raw[u].z);
+            o.w = keep_where_positive(o.w, hp_raw[u].w);
+            if (r < nrows) *reinterpret_cast<uint4*>(GZo + static_cast<size_t>(row0 + r) * D + sub * 8) = o;
+          }
+        }
+      }
+      request_hprev(row0 + RW);
+    });
+  }
+
+  // weight-gradient partial of the workgroup: (wave 0 + wave 2) + (wave 1 + wave 3)
+  __syncthreads();
+  float* buf = reinterpret_cast<float*>(wave_mem);
+  for (int pass = 0; pass < 2; ++pass) {
+    if (wave / 2 == pass) {
+      float* b = buf + (wave % 2) * D * D;
+#pragma unroll
+      for (int ta = 0; ta < G_::NT; ++ta)
+#pragma unroll
+        for (int tb = 0; tb < G_::NT; ++tb)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            float* p = b + acc_feature(ta, h, r) * D + 32 * tb + n;
+            *p = pass == 0 ? gw[ta][tb][r] : *p + gw[ta][tb][r];
+          }
+    }
+    __syncthreads();
+  }
+  float* out = a.gW_partial + static_cast<size_t>(blockIdx.x) * D * D;
+  for (int idx = tid; idx < D * D; idx += kBlock) out[idx] = buf[idx] + buf[D * D + idx];
+}
+
 template <typename K>
 void allow_lds(K kernel, size_t bytes) {
   if (bytes > 48 * 1024)
@@ -370,6 +692,29 @@ void allow_lds(K kernel, size_t bytes) {
 }
 
 }  // namespace
+
+void launch_form_gz_last(const Launch& ln, int D, const GraphView& g, const BwdArgs& a) {
+  if (D != 64) return;
+  ln.begin(KK_BWD_READOUT);
+  form_gz_last_kernel<64><<<g.num_nblocks, kBlock, 0, ln.st>>>(
+      g, static_cast<const bf16_t*>(a.Hcur), a.g_t, a.w_out, a.wout_stride, static_cast<bf16_t*>(a.GZ_last),
+      a.gwout_partial);
+  ln.end(KK_BWD_READOUT);
+}
+
+void launch_bwd_hidden_wave(const Launch& ln, int D, bool to_embed, const GraphView& gt, const BwdArgs& a) {
+  if (D != 64) return;
+  const int kind = to_embed ? KK_BWD_EMBED : KK_BWD_HIDDEN;
+  ln.begin(kind);
+  if (to_embed) {
+    allow_lds(bwd_wave_kernel<64, true>, bwd_wave_lds<64>());
+    bwd_wave_kernel<64, true><<<gt.num_wblocks, kBlock, bwd_wave_lds<64>(), ln.st>>>(gt, a);
+  } else {
+    allow_lds(bwd_wave_kernel<64, false>, bwd_wave_lds<64>());
+    bwd_wave_kernel<64, false><<<gt.num_wblocks, kBlock, bwd_wave_lds<64>(), ln.st>>>(gt, a);
+  }
+  ln.end(kind);
+}
 
 void launch_fwd_hidden_wave(const Launch& ln, int D, const GraphView& g, const void* X, const float* W,
                             int w_stride, void* Y, const float* w_out, int wout_stride, float* t,
