@@ -112,9 +112,10 @@ struct gco_ctx {
   int32_t *d_heavy_of_row = nullptr, *d_heavy_chunk_ptr = nullptr, *d_chunk_begin = nullptr,
           *d_chunk_end = nullptr, *d_chunk_part = nullptr;
   int32_t* d_heavy_rows = nullptr;
-  int32_t *d_wblk_k = nullptr, *d_wrowptr = nullptr;
-  int2* d_wwave_tiles = nullptr;
-  int32_t *d_wpbl_ptr = nullptr, *d_wpbl_list = nullptr;
+  int32_t *d_wblk_k[kWaveMaps] = {}, *d_wrowptr = nullptr;
+  int num_wblocks[kWaveMaps] = {};
+  int2* d_wwave_tiles[kWaveMaps] = {};
+  int32_t *d_wpbl_ptr[kWaveMaps] = {}, *d_wpbl_list[kWaveMaps] = {};
   int2 *d_went = nullptr, *d_went_t = nullptr;
   int32_t *d_wtile_base = nullptr, *d_wtile_hptr = nullptr;
   int2 *d_ent = nullptr, *d_ent_t = nullptr;
@@ -255,14 +256,15 @@ int w_elems(const gco_ctx* ctx, int l /*1..L*/) {
 // round-robin by id); subgraphs are spread over the XCDs longest-first.
 void build_block_map(int P, const std::vector<int>& part_rows, const std::vector<int32_t>& lrowptr,
                      int tile_rows, int target_blocks, int max_tiles_per_block,
-                     std::vector<int>& blk_k, std::vector<int>& blk_s, std::vector<int>& blk_S) {
+                     std::vector<int>& blk_k, std::vector<int>& blk_s, std::vector<int>& blk_S,
+                     double row_cost = 2.0) {
   std::vector<int> tiles(P), Sk(P);
   std::vector<double> work(P);
   double total = 0;
   for (int k = 0; k < P; ++k) {
     const int rows = part_rows[k + 1] - part_rows[k];
     tiles[k] = (rows + tile_rows - 1) / tile_rows;
-    work[k] = 2.0 * rows + (lrowptr[part_rows[k + 1]] - lrowptr[part_rows[k]]);
+    work[k] = row_cost * rows + (lrowptr[part_rows[k + 1]] - lrowptr[part_rows[k]]);
     total += work[k];
   }
   for (int k = 0; k < P; ++k) {
@@ -319,13 +321,16 @@ void build_block_map(int P, const std::vector<int>& part_rows, const std::vector
 
 // Wave-per-tile kernels: workgroups are dealt to the subgraphs as above; the tiles of a
 // subgraph (kWaveRows rows each) are then cut into one contiguous run per wavefront such
-// that every run holds about the same number of light-stream entries (one per row plus
-// the neighbours of rows that are not pre-reduced).
+// that every run costs about the same: a tile costs its light-stream entries (one per row
+// plus the neighbours of rows that are not pre-reduced) plus row_cost per row, which
+// stands for the per-row work of the kernel's dense part and epilogue.
 void build_wave_map(int P, const std::vector<int>& part_rows, const std::vector<int32_t>& lrowptr,
-                    int target_blocks, std::vector<int>& wblk_k, std::vector<int2>& wwave_tiles) {
+                    int target_blocks, double row_cost, std::vector<int>& wblk_k,
+                    std::vector<int2>& wwave_tiles) {
   constexpr int kWaves = kBlock / 64;
   std::vector<int> blk_s, blk_S;
-  build_block_map(P, part_rows, lrowptr, kWaveRows * kWaves, target_blocks, 0, wblk_k, blk_s, blk_S);
+  build_block_map(P, part_rows, lrowptr, kWaveRows * kWaves, target_blocks, 0, wblk_k, blk_s, blk_S,
+                  1.0 + row_cost);
   wwave_tiles.assign(wblk_k.size() * kWaves, make_int2(0, 0));
   std::vector<std::vector<int>> cuts(P);  // cuts[k][v] = first tile of wavefront v of subgraph k
   for (size_t b = 0; b < wblk_k.size(); ++b) {
@@ -334,9 +339,9 @@ void build_wave_map(int P, const std::vector<int>& part_rows, const std::vector<
     if (cuts[k].empty()) {
       const int rows = part_rows[k + 1] - part_rows[k];
       const int tiles = (rows + kWaveRows - 1) / kWaveRows;
-      std::vector<int64_t> pre(static_cast<size_t>(tiles) + 1, 0);  // entries before tile t
+      std::vector<double> pre(static_cast<size_t>(tiles) + 1, 0);  // cost before tile t
       for (int t = 0; t < tiles; ++t) {
-        int64_t c = 0;
+        double c = row_cost * kWaveRows;
         for (int r = part_rows[k] + t * kWaveRows; r < std::min(part_rows[k + 1], part_rows[k] + (t + 1) * kWaveRows); ++r) {
           const int deg = lrowptr[r + 1] - lrowptr[r];
           c += 1 + (deg >= kHeavyMin ? 0 : deg);
@@ -348,7 +353,7 @@ void build_wave_map(int P, const std::vector<int>& part_rows, const std::vector<
       cuts[k][0] = 0;
       int t = 0;
       for (int v = 1; v < V; ++v) {
-        const int64_t want = pre[tiles] * v / V;
+        const double want = pre[tiles] * v / V;
         while (t < tiles && pre[t] < want) ++t;
         cuts[k][v] = t;
       }
@@ -629,20 +634,22 @@ int gco_upload_graph(gco_ctx* ctx, int64_t n64, const int64_t* rowptr, const int
   // work decomposition
   std::vector<int> blk_k, blk_s, blk_S, nblk_k, nblk_s, nblk_S;
   build_block_map(P, part_rows, lrowptr, kTileRows, kWideBlocks, kMaxTilesPerBlock, blk_k, blk_s, blk_S);
-  std::vector<int> wblk_k;
-  std::vector<int2> wwave_tiles;
-  build_wave_map(P, part_rows, lrowptr, kWaveBlocks, wblk_k, wwave_tiles);
-  GALLOC(ctx->d_wblk_k, wblk_k.size());
-  GALLOC(ctx->d_wwave_tiles, wwave_tiles.size());
-  HIPCHK(h2d(ctx, ctx->d_wblk_k, wblk_k.data(), wblk_k.size()));
-  HIPCHK(h2d(ctx, ctx->d_wwave_tiles, wwave_tiles.data(), wwave_tiles.size()));
-  {
+  // one decomposition per kernel kind (different cost per row)
+  for (int v = 0; v < kWaveMaps; ++v) {
+    std::vector<int> wblk_k;
+    std::vector<int2> wwave_tiles;
+    build_wave_map(P, part_rows, lrowptr, kWaveBlocksFor[v], kWaveRowCost[v], wblk_k, wwave_tiles);
+    ctx->num_wblocks[v] = static_cast<int>(wblk_k.size());
+    GALLOC(ctx->d_wwave_tiles[v], wwave_tiles.size());
+    HIPCHK(h2d(ctx, ctx->d_wwave_tiles[v], wwave_tiles.data(), wwave_tiles.size()));
+    GALLOC(ctx->d_wblk_k[v], wblk_k.size());
+    HIPCHK(h2d(ctx, ctx->d_wblk_k[v], wblk_k.data(), wblk_k.size()));
     std::vector<int> ptr, list;
     bucket_blocks(wblk_k, ctx->Pw, ptr, list);
-    GALLOC(ctx->d_wpbl_ptr, ptr.size());
-    GALLOC(ctx->d_wpbl_list, std::max<size_t>(1, list.size()));
-    HIPCHK(h2d(ctx, ctx->d_wpbl_ptr, ptr.data(), ptr.size()));
-    HIPCHK(h2d(ctx, ctx->d_wpbl_list, list.data(), list.size()));
+    GALLOC(ctx->d_wpbl_ptr[v], ptr.size());
+    GALLOC(ctx->d_wpbl_list[v], std::max<size_t>(1, list.size()));
+    HIPCHK(h2d(ctx, ctx->d_wpbl_ptr[v], ptr.data(), ptr.size()));
+    HIPCHK(h2d(ctx, ctx->d_wpbl_list[v], list.data(), list.size()));
   }
   // width-1 kernels: one 256-row tile per workgroup
   build_block_map(P, part_rows, lrowptr, kNarrowRows, std::numeric_limits<int>::max() / 2, 1, nblk_k,
@@ -753,9 +760,11 @@ int gco_upload_graph(gco_ctx* ctx, int64_t n64, const int64_t* rowptr, const int
   g.blk_s = ctx->d_blk_s;
   g.blk_S = ctx->d_blk_S;
   g.num_blocks = static_cast<int>(blk_k.size());
-  g.wblk_k = ctx->d_wblk_k;
-  g.wwave_tiles = ctx->d_wwave_tiles;
-  g.num_wblocks = static_cast<int>(wblk_k.size());
+  for (int v = 0; v < kWaveMaps; ++v) {
+    g.wwave_tiles[v] = ctx->d_wwave_tiles[v];
+    g.wblk_k[v] = ctx->d_wblk_k[v];
+    g.num_wblocks[v] = ctx->num_wblocks[v];
+  }
   g.wrowptr = ctx->d_wrowptr;
   g.wtile_base = ctx->d_wtile_base;
   g.wtile_hptr = ctx->d_wtile_hptr;
@@ -804,7 +813,8 @@ int gco_upload_graph(gco_ctx* ctx, int64_t n64, const int64_t* rowptr, const int
     uint8_t* q = nullptr;
     GALLOC(q, nd * eb);
     ctx->H[l] = q;
-    GALLOC(ctx->gW_partial[l - 1], static_cast<size_t>(std::max(g.num_blocks, g.num_wblocks)) * D * D);
+    GALLOC(ctx->gW_partial[l - 1],
+           static_cast<size_t>(std::max({g.num_blocks, g.num_wblocks[WM_BWD], g.num_wblocks[WM_EMBED]})) * D * D);
   }
   // G_Z between two hidden layers; the wave-per-tile kernels also store that of the last one
   for (int l = 1; l <= (ctx->wave_path() ? L - 1 : L - 2); ++l) {
@@ -818,7 +828,7 @@ int gco_upload_graph(gco_ctx* ctx, int64_t n64, const int64_t* rowptr, const int
   GALLOC(ctx->p, static_cast<size_t>(n));
   GALLOC(ctx->g_z, static_cast<size_t>(n));
   GALLOC(ctx->g_t, static_cast<size_t>(n));
-  GALLOC(ctx->loss_partial, static_cast<size_t>(g.num_nblocks));
+  GALLOC(ctx->loss_partial, static_cast<size_t>(g.num_nblocks) * kLossSets);
   GALLOC(ctx->loss_part, static_cast<size_t>(P));
   GALLOC(ctx->loss_one, 1);
   HIPCHK(hipStreamSynchronize(st));
@@ -969,11 +979,18 @@ static void run_forward(gco_ctx* ctx) {
   ctx->probs_valid = true;
 }
 
-static void run_loss(gco_ctx* ctx, double* loss_out) {
+// Loss kernel; its workgroup partials go to set `slot` (< kLossSets) of loss_partial.
+static void run_loss_partials(gco_ctx* ctx, int slot) {
   const Launch ln = ctx->launch();
   const float q = ctx->cfg.problem == GCO_PROBLEM_MAXCUT ? 2.f : ctx->cfg.alpha;
-  launch_loss(ln, ctx->gv, ctx->p, ctx->d_c, q, ctx->g_z, ctx->loss_partial, ctx->d_heavy_partial);
-  launch_loss_reduce(ln, ctx->gv, ctx->loss_partial, ctx->loss_part, loss_out);
+  launch_loss(ln, ctx->gv, ctx->p, ctx->d_c, q, ctx->g_z,
+              ctx->loss_partial + static_cast<size_t>(slot) * ctx->gv.num_nblocks, ctx->d_heavy_partial);
+}
+
+// Loss at the current parameters: total to loss_out[0], per-subgraph values to ctx->loss_part.
+static void run_loss(gco_ctx* ctx, double* loss_out) {
+  run_loss_partials(ctx, 0);
+  launch_loss_reduce(ctx->launch(), ctx->gv, ctx->loss_partial, 1, 0, ctx->loss_part, loss_out);
 }
 
 // update = true: Adam step t = ++step.  update = false: gradients are written to gE / gW.
@@ -1035,8 +1052,9 @@ static void run_backward(gco_ctx* ctx, bool update, float* gE, float* const* gW)
     // who wrote the partials: the wide kernels' workgroups, or, on the wave-per-tile path,
     // its own workgroups (hidden layers) and the narrow ones (scalar layer)
     const bool wave = ctx->wave_path() && L >= 2;
-    wt[l - 1].blk_ptr = !wave ? ctx->d_pbl_ptr : (l < L ? ctx->d_wpbl_ptr : ctx->d_nwbl_ptr);
-    wt[l - 1].blk_list = !wave ? ctx->d_pbl_list : (l < L ? ctx->d_wpbl_list : ctx->d_nwbl_list);
+    const int wm = l == 1 ? WM_EMBED : WM_BWD;  // the kernel kind that wrote gW_l
+    wt[l - 1].blk_ptr = !wave ? ctx->d_pbl_ptr : (l < L ? ctx->d_wpbl_ptr[wm] : ctx->d_nwbl_ptr);
+    wt[l - 1].blk_list = !wave ? ctx->d_pbl_list : (l < L ? ctx->d_wpbl_list[wm] : ctx->d_nwbl_list);
   }
   launch_adam_w(ln, ctx->Pw, wt, L, ad, update);
   if (update) ctx->probs_valid = true;  // p is that of the parameters before the step
@@ -1053,10 +1071,17 @@ int gco_train(gco_ctx* ctx, int32_t epochs, double* loss_per_epoch) {
     GALLOC(ctx->loss_hist, static_cast<size_t>(epochs));
     ctx->loss_hist_cap = epochs;
   }
+  // the loss partials of up to kLossSets epochs are reduced by one launch
+  int pending = 0;
   for (int e = 0; e < epochs; ++e) {
     run_forward(ctx);
-    run_loss(ctx, ctx->loss_hist + e);
+    run_loss_partials(ctx, pending++);
     run_backward(ctx, true, nullptr, nullptr);
+    if (pending == kLossSets || e + 1 == epochs) {
+      launch_loss_reduce(ctx->launch(), ctx->gv, ctx->loss_partial, pending, ctx->gv.num_nblocks, nullptr,
+                         ctx->loss_hist + (e + 1 - pending));
+      pending = 0;
+    }
   }
   HIPCHK(hipGetLastError());
   if (loss_per_epoch) HIPCHK(d2h(ctx, loss_per_epoch, ctx->loss_hist, static_cast<size_t>(epochs)));

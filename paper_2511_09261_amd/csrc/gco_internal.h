@@ -21,7 +21,11 @@ constexpr int kChunk = 256;      // neighbours per chunk of a pre-reduced row
 constexpr int kWideBlocks = 2048;        // workgroups aimed at by the wide kernels
 constexpr int kMaxTilesPerBlock = 16;     // tiles one wide workgroup may own
 constexpr int kWaveRows = 32;            // rows of a tile in the wave-per-tile kernels
-constexpr int kWaveBlocks = 1536;        // workgroups aimed at by the wave-per-tile kernels
+// cuts of the tiles among the wavefronts, one per kernel kind: cost of a row relative to
+// one light-stream entry (measured per-tile against per-entry time of each kernel)
+enum WaveMap : int { WM_FWD = 0, WM_BWD = 1, WM_EMBED = 2, kWaveMaps = 3 };
+constexpr double kWaveRowCost[kWaveMaps] = {0.7, 1.5, 100.0};
+constexpr int kWaveBlocksFor[kWaveMaps] = {3072, 960, 3072};  // workgroups aimed at (measured best)
 constexpr int kEntPad = 512;             // zero entries appended to the packed entry arrays
 
 enum KernelKind : int {
@@ -60,13 +64,13 @@ struct GraphView {
   const int* blk_s = nullptr;
   const int* blk_S = nullptr;
   int num_blocks = 0;
-  // wave-per-tile kernels: workgroup b serves subgraph wblk_k[b] (< 0: nothing to do);
-  // its wavefront q owns tiles wwave_tiles[4b+q].x .. .y (kWaveRows rows each, counted
-  // from the subgraph's first row) -- contiguous runs, cut so that the wavefronts of a
-  // subgraph stream about equally many entries
-  const int* wblk_k = nullptr;
-  const int2* wwave_tiles = nullptr;
-  int num_wblocks = 0;
+  // wave-per-tile kernels, one decomposition per kernel kind m (WaveMap): workgroup b
+  // serves subgraph wblk_k[m][b] (< 0: nothing to do); its wavefront q owns tiles
+  // wwave_tiles[m][4b+q].x .. .y (kWaveRows rows each, counted from the subgraph's first
+  // row) -- contiguous runs, cut so that the wavefronts have about equal work in that kind
+  const int* wblk_k[kWaveMaps] = {};
+  const int2* wwave_tiles[kWaveMaps] = {};
+  int num_wblocks[kWaveMaps] = {};
   // light stream: per row its diagonal entry {i, A_hat_ii}, then its packed entries unless
   // the row is pre-reduced; row i owns went[wrowptr[i] .. wrowptr[i+1]).  went_t holds the
   // entries of A_hat^T.  kEntPad zero entries follow the last row.
@@ -142,9 +146,12 @@ void launch_fwd_readout(const Launch& ln, const GraphView& g, const float* t, fl
 void launch_loss(const Launch& ln, const GraphView& g, const float* p, const float* c, float q,
                  float* g_z, double* loss_partial, float* heavy_partial);
 
-// loss_part[k] = sum of the partials of subgraph k; loss_out[0] = sum_k loss_part[k].
-void launch_loss_reduce(const Launch& ln, const GraphView& g, const double* loss_partial,
-                        double* loss_part, double* loss_out);
+// For each of `sets` sets of workgroup partials (set s starts at loss_partial + s * set_stride):
+// loss_part[s, k] = sum of the partials of subgraph k (if loss_part != nullptr);
+// loss_out[s] = sum_k of those.  The training loop reduces many epochs with one launch.
+void launch_loss_reduce(const Launch& ln, const GraphView& g, const double* loss_partial, int sets,
+                        int64_t set_stride, double* loss_part, double* loss_out);
+constexpr int kLossSets = 64;  // epochs whose loss partials are kept before they are reduced
 
 // g_t = A_hat^T g_z.
 void launch_bwd_readout(const Launch& ln, const GraphView& g, const float* g_z, float* g_t,

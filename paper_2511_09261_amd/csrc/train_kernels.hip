@@ -456,29 +456,36 @@ __global__ __launch_bounds__(kBlock) void loss_kernel(GraphView g, const float* 
   if (threadIdx.x == 0) loss_partial[blockIdx.x] = ((wred[0] + wred[1]) + wred[2]) + wred[3];
 }
 
-// One workgroup.  Each wavefront takes subgraphs k = wave, wave + 4, ...: its
-// lanes sum the workgroup partials of k in a strided, fixed order, then the
-// wavefront total is formed by a butterfly.  Thread 0 adds the subgraph values.
+// One workgroup per set of partials (one set per epoch).  Each wavefront takes subgraphs
+// k = wave, wave + 4, ...: its lanes sum the workgroup partials of k in a strided, fixed
+// order, then the wavefront total is formed by a butterfly.  Thread 0 adds the subgraph
+// values.  loss_part (per-subgraph values, [sets, P]) may be null.
 __global__ __launch_bounds__(kBlock) void loss_reduce_kernel(GraphView g, const double* __restrict__ partial,
+                                                             int64_t set_stride,
                                                              double* __restrict__ loss_part,
                                                              double* __restrict__ loss_out) {
+  extern __shared__ double part_s[];  // [P]
+  __shared__ double tot[kBlock];
+  partial += static_cast<int64_t>(blockIdx.x) * set_stride;
   const int wave = threadIdx.x / 64, lane = threadIdx.x % 64;
   for (int k = wave; k < g.P; k += kBlock / 64) {
     double acc = 0.0;
     for (int q = g.nblk_ptr[k] + lane; q < g.nblk_ptr[k + 1]; q += 64) acc += partial[g.nblk_list[q]];
     acc = wave_sum(acc);
-    if (lane == 0) loss_part[k] = acc;
+    if (lane == 0) {
+      part_s[k] = acc;
+      if (loss_part != nullptr) loss_part[static_cast<int64_t>(blockIdx.x) * g.P + k] = acc;
+    }
   }
   __syncthreads();
-  __shared__ double tot[kBlock];
   double mine = 0.0;
-  for (int k = threadIdx.x; k < g.P; k += kBlock) mine += loss_part[k];
+  for (int k = threadIdx.x; k < g.P; k += kBlock) mine += part_s[k];
   tot[threadIdx.x] = mine;
   __syncthreads();
   if (threadIdx.x == 0) {
     double acc = 0.0;
     for (int q = 0; q < kBlock; ++q) acc += tot[q];
-    loss_out[0] = acc;
+    loss_out[blockIdx.x] = acc;
   }
 }
 
@@ -637,10 +644,13 @@ void launch_loss(const Launch& ln, const GraphView& g, const float* p, const flo
   ln.end(KK_LOSS);
 }
 
-void launch_loss_reduce(const Launch& ln, const GraphView& g, const double* loss_partial,
-                        double* loss_part, double* loss_out) {
+void launch_loss_reduce(const Launch& ln, const GraphView& g, const double* loss_partial, int sets,
+                        int64_t set_stride, double* loss_part, double* loss_out) {
+  if (sets <= 0) return;
+  const size_t lds = static_cast<size_t>(g.P) * sizeof(double);
+  allow_lds(loss_reduce_kernel, lds);
   ln.begin(KK_LOSS_REDUCE);
-  loss_reduce_kernel<<<1, kBlock, 0, ln.st>>>(g, loss_partial, loss_part, loss_out);
+  loss_reduce_kernel<<<sets, kBlock, lds, ln.st>>>(g, loss_partial, set_stride, loss_part, loss_out);
   ln.end(KK_LOSS_REDUCE);
 }
 

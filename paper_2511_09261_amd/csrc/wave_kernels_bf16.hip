@@ -216,7 +216,10 @@ __device__ __forceinline__ void stream_tiles(const GraphView& g, const int2* __r
         const uint32_t x = (&raw[2 * q].x)[i / 2], y = (&raw[2 * q + 1].x)[i / 2];
         d[q] = (i % 2 == 0) ? lower_halves(x, y) : upper_halves(x, y);
       }
-      *reinterpret_cast<uint4*>(xf + (sub * 8 + i) * G_::XP + grp * 16) = make_uint4(d[0], d[1], d[2], d[3]);
+      // the 16-byte groups of a feature are rotated by feature / 8, so that the lanes of
+      // one store (features 8 apart) fall into different LDS banks
+      *reinterpret_cast<uint4*>(xf + (sub * 8 + i) * G_::XP + ((grp + sub) % G_::NG) * 16) =
+          make_uint4(d[0], d[1], d[2], d[3]);
     }
     if (sub == 0) {  // values of slots 8 grp .. 8 grp + 7: the hi halves, the lo halves
       const uint32_t y[8] = {static_cast<uint32_t>(cur[0].y), static_cast<uint32_t>(cur[1].y),
@@ -235,7 +238,8 @@ __device__ __forceinline__ void stream_tiles(const GraphView& g, const int2* __r
     for (int tn = 0; tn < G_::NT; ++tn)
 #pragma unroll
       for (int ks = 0; ks < G_::KS1; ++ks)
-        xa[tn][ks] = as_frag(*reinterpret_cast<const uint4*>(xf + (tn * 32 + n) * G_::XP + (2 * ks + h) * 16));
+        xa[tn][ks] = as_frag(*reinterpret_cast<const uint4*>(
+            xf + (tn * 32 + n) * G_::XP + ((2 * ks + h + (tn * 32 + n) / 8) % G_::NG) * 16));
     const int b1 = min(b0 + G_::SE, E1);
     while (true) {
       // slots of the step that belong to row n of the current tile, as a bit mask
@@ -264,19 +268,48 @@ __device__ __forceinline__ void stream_tiles(const GraphView& g, const int2* __r
       // the tile is complete: pre-reduced rows take their chunk partials
       const int h0 = __builtin_amdgcn_readlane(factsA, RW + 1), h1 = __builtin_amdgcn_readlane(factsA, RW + 2);
       for (int hh = h0; hh < h1; ++hh) {
-        if (g.heavy_rows[hh] - row0 == n) {
-          for (int ch = g.heavy_chunk_ptr[hh]; ch < g.heavy_chunk_ptr[hh + 1]; ++ch) {
-            const float* pp = heavy_partial + static_cast<size_t>(ch) * D;
+        // the whole wavefront sums the row's chunk partials: lane (cg, fq) = (lane / LQ,
+        // lane % LQ) adds chunks cg, cg + CG, ... for features 4 fq .. 4 fq + 3, four loads
+        // in flight; the CG groups are then added in order
+        constexpr int LQ = D / 4, CG = 64 / LQ;
+        const int c0h = g.heavy_chunk_ptr[hh], c1h = g.heavy_chunk_ptr[hh + 1];
+        float4 tot = make_float4(0.f, 0.f, 0.f, 0.f);
+        for (int ch = c0h + lane / LQ; ch < c1h; ch += 4 * CG) {
+          float4 pv[4];
 #pragma unroll
-            for (int tn = 0; tn < G_::NT; ++tn)
+          for (int c = 0; c < 4; ++c) {
+            pv[c] = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (ch + c * CG < c1h)
+              pv[c] = *reinterpret_cast<const float4*>(heavy_partial + static_cast<size_t>(ch + c * CG) * D +
+                                                       (lane % LQ) * 4);
+          }
 #pragma unroll
-              for (int i = 0; i < 4; ++i) {
-                const float4 pv = *reinterpret_cast<const float4*>(pp + acc_feature(tn, h, 4 * i));
-                agg[tn][4 * i] += pv.x; agg[tn][4 * i + 1] += pv.y;
-                agg[tn][4 * i + 2] += pv.z; agg[tn][4 * i + 3] += pv.w;
-              }
+          for (int c = 0; c < 4; ++c) {
+            tot.x += pv[c].x; tot.y += pv[c].y; tot.z += pv[c].z; tot.w += pv[c].w;
           }
         }
+        float4 sum = make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+        for (int cg = 0; cg < CG; ++cg) {
+          sum.x += __shfl(tot.x, cg * LQ + lane % LQ, 64);
+          sum.y += __shfl(tot.y, cg * LQ + lane % LQ, 64);
+          sum.z += __shfl(tot.z, cg * LQ + lane % LQ, 64);
+          sum.w += __shfl(tot.w, cg * LQ + lane % LQ, 64);
+        }
+        // hand the totals to the two lanes that hold the row
+        const bool mine = g.heavy_rows[hh] - row0 == n;
+#pragma unroll
+        for (int tn = 0; tn < G_::NT; ++tn)
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            const int src = acc_feature(tn, h, 4 * i) / 4;
+            const float x0 = __shfl(sum.x, src, 64), x1 = __shfl(sum.y, src, 64);
+            const float x2 = __shfl(sum.z, src, 64), x3 = __shfl(sum.w, src, 64);
+            if (mine) {
+              agg[tn][4 * i] += x0; agg[tn][4 * i + 1] += x1;
+              agg[tn][4 * i + 2] += x2; agg[tn][4 * i + 3] += x3;
+            }
+          }
       }
       on_tile(row0, nrows, agg);
 #pragma unroll
@@ -321,7 +354,7 @@ __global__ __launch_bounds__(kBlock, 3) void fwd_wave_kernel(
   uint4* pair_mask = reinterpret_cast<uint4*>(smem + G_::w_bytes + D * sizeof(float));
   unsigned char* wave_mem = reinterpret_cast<unsigned char*>(pair_mask + 256);
 
-  const int k = g.wblk_k[blockIdx.x];
+  const int k = g.wblk_k[WM_FWD][blockIdx.x];
   if (k < 0) return;
   const int tid = threadIdx.x, lane = tid % 64;
   const int wave = __builtin_amdgcn_readfirstlane(tid / 64);
@@ -332,7 +365,7 @@ __global__ __launch_bounds__(kBlock, 3) void fwd_wave_kernel(
   if (tid < D) wo[tid] = w_out != nullptr ? w_out[static_cast<size_t>(k) * wout_stride + tid] : 0.f;
   __syncthreads();  // the only workgroup barrier: W^k and w_out are in LDS
 
-  const int2 tiles = g.wwave_tiles[blockIdx.x * (kBlock / 64) + wave];
+  const int2 tiles = g.wwave_tiles[WM_FWD][blockIdx.x * (kBlock / 64) + wave];
   if (tiles.x >= tiles.y) return;
   unsigned char* my_lds = wave_mem + wave * G_::wave_bytes;
   bf16_t* ot = reinterpret_cast<bf16_t*>(my_lds);  // overlays the row buffer
@@ -483,7 +516,8 @@ __global__ __launch_bounds__(kBlock, 2) void bwd_wave_kernel(GraphView g, BwdArg
   unsigned char* wave_mem = reinterpret_cast<unsigned char*>(pair_mask + 256);
   static_assert(4 * G_::bwd_wave_bytes >= 2 * D * D * sizeof(float), "room for the gradient reduction");
 
-  const int k = g.wblk_k[blockIdx.x];
+  constexpr int WM = TO_EMBED ? WM_EMBED : WM_BWD;
+  const int k = g.wblk_k[WM][blockIdx.x];
   if (k < 0) return;
   const int tid = threadIdx.x, lane = tid % 64;
   const int wave = __builtin_amdgcn_readfirstlane(tid / 64);
@@ -495,7 +529,7 @@ __global__ __launch_bounds__(kBlock, 2) void bwd_wave_kernel(GraphView g, BwdArg
 
   const bf16_t* GZ = static_cast<const bf16_t*>(a.GZ_in);
   const bf16_t* Hprev = static_cast<const bf16_t*>(a.Hprev);
-  const int2 tiles = g.wwave_tiles[blockIdx.x * (kBlock / 64) + wave];
+  const int2 tiles = g.wwave_tiles[WM][blockIdx.x * (kBlock / 64) + wave];
   unsigned char* R = wave_mem + wave * G_::bwd_wave_bytes;
   const bool need_gh = !(TO_EMBED && a.mode == EMBED_SKIP);
   floatx16 gw[G_::NT][G_::NT];
@@ -555,7 +589,8 @@ __global__ __launch_bounds__(kBlock, 2) void bwd_wave_kernel(GraphView g, BwdArg
         uint2 d;
         d.x = (i % 2 == 0) ? lower_halves(x0, x1) : upper_halves(x0, x1);
         d.y = (i % 2 == 0) ? lower_halves(x2, x3) : upper_halves(x2, x3);
-        *reinterpret_cast<uint2*>(hpl + (sub * 8 + i) * G_::GP + grp * (RPL * 2)) = d;
+        // 16-byte groups rotated by feature / 8 (LDS banks, as for the row buffer)
+        *reinterpret_cast<uint2*>(hpl + (sub * 8 + i) * G_::GP + ((grp / 2 + sub) % 4) * 16 + (grp % 2) * 8) = d;
       }
       // gW[a, b] += sum over the tile's rows of Hprev[row, a] G_T[row, b]
 #pragma unroll
@@ -563,7 +598,8 @@ __global__ __launch_bounds__(kBlock, 2) void bwd_wave_kernel(GraphView g, BwdArg
         bf16x8 af[G_::NT], bf[G_::NT];
 #pragma unroll
         for (int t = 0; t < G_::NT; ++t) {
-          af[t] = as_frag(*reinterpret_cast<const uint4*>(hpl + (32 * t + n) * G_::GP + (16 * ks + 8 * h) * 2));
+          af[t] = as_frag(*reinterpret_cast<const uint4*>(hpl + (32 * t + n) * G_::GP +
+                                                          ((2 * ks + h + (32 * t + n) / 8) % 4) * 16));
           bf[t] = as_frag(*reinterpret_cast<const uint4*>(gtl + (32 * t + n) * G_::GP + (16 * ks + 8 * h) * 2));
         }
 #pragma unroll
@@ -598,38 +634,63 @@ __global__ __launch_bounds__(kBlock, 2) void bwd_wave_kernel(GraphView g, BwdArg
                   make_float4(z[ta][4 * i], z[ta][4 * i + 1], z[ta][4 * i + 2], z[ta][4 * i + 3]);
           constexpr int LR = D / 4;        // lanes per fp32 row
           constexpr int RI = 64 / LR;      // rows per instruction
+          constexpr int NQ = RW / RI;      // instructions per tile and tensor
+          const int rr = lane / LR, cc = (lane % LR) * 4;
+          if (a.mode == EMBED_WRITE_GRAD) {
 #pragma unroll
-          for (int q = 0; q < RW / RI; ++q) {
-            const int r = q * RI + lane / LR, cc = (lane % LR) * 4;
-            if (r < nrows) {
-              const float4 gq = *reinterpret_cast<const float4*>(st + r * G_::PF + cc);
-              const size_t off = static_cast<size_t>(row0 + r) * D + cc;
-              if (a.mode == EMBED_WRITE_GRAD) {
-                *reinterpret_cast<float4*>(a.gE + off) = gq;
-              } else {
-                const float4 m0 = *reinterpret_cast<const float4*>(a.mE + off);
-                const float4 v0 = *reinterpret_cast<const float4*>(a.vE + off);
-                const float4 e0 = *reinterpret_cast<const float4*>(a.E + off);
+            for (int q = 0; q < NQ; ++q) {
+              const int r = q * RI + rr;
+              if (r < nrows)
+                *reinterpret_cast<float4*>(a.gE + static_cast<size_t>(row0 + r) * D + cc) =
+                    *reinterpret_cast<const float4*>(st + r * G_::PF + cc);
+            }
+          } else {
+            // the state of half a tile is requested at once, so that the loads overlap
+            float* __restrict__ pE = a.E;
+            float* __restrict__ pM = a.mE;
+            float* __restrict__ pV = a.vE;
+            bf16_t* __restrict__ pB = static_cast<bf16_t*>(a.Eb);
+            constexpr int HB = NQ / 2;
+#pragma unroll
+            for (int half = 0; half < 2; ++half) {
+              float4 e0[HB], m0[HB], v0[HB];
+#pragma unroll
+              for (int q = 0; q < HB; ++q) {
+                const int r = (half * HB + q) * RI + rr;
+                const size_t off = static_cast<size_t>(row0 + min(r, nrows - 1)) * D + cc;
+                m0[q] = *reinterpret_cast<const float4*>(pM + off);
+                v0[q] = *reinterpret_cast<const float4*>(pV + off);
+                e0[q] = *reinterpret_cast<const float4*>(pE + off);
+              }
+#pragma unroll
+              for (int q = 0; q < HB; ++q) {
+                const int r = (half * HB + q) * RI + rr;
+                const float4 gq = *reinterpret_cast<const float4*>(st + r * G_::PF + cc);
+                const size_t off = static_cast<size_t>(row0 + r) * D + cc;
                 const float gv[4] = {gq.x, gq.y, gq.z, gq.w};
-                const float mv[4] = {m0.x, m0.y, m0.z, m0.w};
-                const float vv[4] = {v0.x, v0.y, v0.z, v0.w};
-                const float ev[4] = {e0.x, e0.y, e0.z, e0.w};
+                const float mv[4] = {m0[q].x, m0[q].y, m0[q].z, m0[q].w};
+                const float vv[4] = {v0[q].x, v0[q].y, v0[q].z, v0[q].w};
+                const float ev[4] = {e0[q].x, e0[q].y, e0[q].z, e0[q].w};
                 float mo[4], vo[4], eo[4];
 #pragma unroll
                 for (int x = 0; x < 4; ++x) {
                   mo[x] = a.adam.b1 * mv[x] + (1.f - a.adam.b1) * gv[x];
                   vo[x] = a.adam.b2 * vv[x] + (1.f - a.adam.b2) * gv[x] * gv[x];
-                  const float upd =
-                      (mo[x] * a.adam.inv_bc1) / (sqrtf(vo[x]) * a.adam.inv_sqrt_bc2 + a.adam.eps);
+                  // v_sqrt_f32 and v_rcp_f32: 1 ulp each
+                  const float upd = (mo[x] * a.adam.inv_bc1) *
+                                    __builtin_amdgcn_rcpf(__builtin_amdgcn_sqrtf(vo[x]) * a.adam.inv_sqrt_bc2 +
+                                                          a.adam.eps);
                   eo[x] = ev[x] - a.adam.lr * upd;
                 }
-                *reinterpret_cast<float4*>(a.mE + off) = make_float4(mo[0], mo[1], mo[2], mo[3]);
-                *reinterpret_cast<float4*>(a.vE + off) = make_float4(vo[0], vo[1], vo[2], vo[3]);
-                *reinterpret_cast<float4*>(a.E + off) = make_float4(eo[0], eo[1], eo[2], eo[3]);
-                uint2 eb;
-                eb.x = f32x2_to_bf16x2(eo[0], eo[1]);
-                eb.y = f32x2_to_bf16x2(eo[2], eo[3]);
-                *reinterpret_cast<uint2*>(static_cast<bf16_t*>(a.Eb) + off) = eb;
+                if (r < nrows) {
+                  *reinterpret_cast<float4*>(pM + off) = make_float4(mo[0], mo[1], mo[2], mo[3]);
+                  *reinterpret_cast<float4*>(pV + off) = make_float4(vo[0], vo[1], vo[2], vo[3]);
+                  *reinterpret_cast<float4*>(pE + off) = make_float4(eo[0], eo[1], eo[2], eo[3]);
+                  uint2 eb;
+                  eb.x = f32x2_to_bf16x2(eo[0], eo[1]);
+                  eb.y = f32x2_to_bf16x2(eo[2], eo[3]);
+                  *reinterpret_cast<uint2*>(pB + off) = eb;
+                }
               }
             }
           }
@@ -708,10 +769,10 @@ void launch_bwd_hidden_wave(const Launch& ln, int D, bool to_embed, const GraphV
   ln.begin(kind);
   if (to_embed) {
     allow_lds(bwd_wave_kernel<64, true>, bwd_wave_lds<64>());
-    bwd_wave_kernel<64, true><<<gt.num_wblocks, kBlock, bwd_wave_lds<64>(), ln.st>>>(gt, a);
+    bwd_wave_kernel<64, true><<<gt.num_wblocks[WM_EMBED], kBlock, bwd_wave_lds<64>(), ln.st>>>(gt, a);
   } else {
     allow_lds(bwd_wave_kernel<64, false>, bwd_wave_lds<64>());
-    bwd_wave_kernel<64, false><<<gt.num_wblocks, kBlock, bwd_wave_lds<64>(), ln.st>>>(gt, a);
+    bwd_wave_kernel<64, false><<<gt.num_wblocks[WM_BWD], kBlock, bwd_wave_lds<64>(), ln.st>>>(gt, a);
   }
   ln.end(kind);
 }
@@ -722,7 +783,7 @@ void launch_fwd_hidden_wave(const Launch& ln, int D, const GraphView& g, const v
   if (D != 64) return;
   allow_lds(fwd_wave_kernel<64>, fwd_wave_lds<64>());
   ln.begin(KK_FWD_HIDDEN);
-  fwd_wave_kernel<64><<<g.num_wblocks, kBlock, fwd_wave_lds<64>(), ln.st>>>(
+  fwd_wave_kernel<64><<<g.num_wblocks[WM_FWD], kBlock, fwd_wave_lds<64>(), ln.st>>>(
       g, static_cast<const bf16_t*>(X), W, w_stride, static_cast<bf16_t*>(Y), w_out, wout_stride, t,
       heavy_partial);
   ln.end(KK_FWD_HIDDEN);
