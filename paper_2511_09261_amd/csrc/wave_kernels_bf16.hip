@@ -424,6 +424,23 @@ __global__ __launch_bounds__(kBlock, 3) void fwd_wave_kernel(
   });
 }
 
+// 16-byte accesses to data that is streamed once (optimizer state): marked non-temporal,
+// so that they do not displace the gathered rows from the caches.
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ float4 load_streamed(const float* p) {
+  const f32x4_t v = __builtin_nontemporal_load(reinterpret_cast<const f32x4_t*>(p));
+  return make_float4(v.x, v.y, v.z, v.w);
+}
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ uint4 load_streamed(const bf16_t* p) {
+  const u32x4_t v = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(p));
+  return make_uint4(v.x, v.y, v.z, v.w);
+}
+__device__ __forceinline__ void store_streamed(float* p, float a, float b, float c, float d) {
+  const f32x4_t v = {a, b, c, d};
+  __builtin_nontemporal_store(v, reinterpret_cast<f32x4_t*>(p));
+}
+
 // ---------------------------------------------------------------------------
 // G_Z of the last hidden layer, formed row by row from the scalar layer's gradient:
 //   GZ[i, :] = g_t[i] * w_out^k * [Hcur[i, :] > 0]      (rounded to bf16)
@@ -455,7 +472,7 @@ __global__ __launch_bounds__(kBlock) void form_gz_last_kernel(
       const size_t off = static_cast<size_t>(row0 + r) * D + c0;
       const float gt = g_t[row0 + r];
       float hv[8], out[8];
-      unpack8(*reinterpret_cast<const uint4*>(Hcur + off), hv);
+      unpack8(load_streamed(Hcur + off), hv);
 #pragma unroll
       for (int x = 0; x < 8; ++x) {
         out[x] = hv[x] > 0.f ? gt * wv[x] : 0.f;
@@ -552,7 +569,7 @@ __global__ __launch_bounds__(kBlock, 2) void bwd_wave_kernel(GraphView g, BwdArg
       for (int u = 0; u < RPL; ++u) {
         const int r = row0 + RPL * grp + u;
         hp_raw[u] = make_uint4(0u, 0u, 0u, 0u);
-        if (r < row_end) hp_raw[u] = *reinterpret_cast<const uint4*>(Hprev + static_cast<size_t>(r) * D + sub * 8);
+        if (r < row_end) hp_raw[u] = load_streamed(Hprev + static_cast<size_t>(r) * D + sub * 8);
       }
     };
     request_hprev(rbeg + tiles.x * RW);
@@ -658,9 +675,9 @@ __global__ __launch_bounds__(kBlock, 2) void bwd_wave_kernel(GraphView g, BwdArg
               for (int q = 0; q < HB; ++q) {
                 const int r = (half * HB + q) * RI + rr;
                 const size_t off = static_cast<size_t>(row0 + min(r, nrows - 1)) * D + cc;
-                m0[q] = *reinterpret_cast<const float4*>(pM + off);
-                v0[q] = *reinterpret_cast<const float4*>(pV + off);
-                e0[q] = *reinterpret_cast<const float4*>(pE + off);
+                m0[q] = load_streamed(pM + off);
+                v0[q] = load_streamed(pV + off);
+                e0[q] = load_streamed(pE + off);
               }
 #pragma unroll
               for (int q = 0; q < HB; ++q) {
@@ -683,9 +700,9 @@ __global__ __launch_bounds__(kBlock, 2) void bwd_wave_kernel(GraphView g, BwdArg
                   eo[x] = ev[x] - a.adam.lr * upd;
                 }
                 if (r < nrows) {
-                  *reinterpret_cast<float4*>(pM + off) = make_float4(mo[0], mo[1], mo[2], mo[3]);
-                  *reinterpret_cast<float4*>(pV + off) = make_float4(vo[0], vo[1], vo[2], vo[3]);
-                  *reinterpret_cast<float4*>(pE + off) = make_float4(eo[0], eo[1], eo[2], eo[3]);
+                  store_streamed(pM + off, mo[0], mo[1], mo[2], mo[3]);
+                  store_streamed(pV + off, vo[0], vo[1], vo[2], vo[3]);
+                  store_streamed(pE + off, eo[0], eo[1], eo[2], eo[3]);
                   uint2 eb;
                   eb.x = f32x2_to_bf16x2(eo[0], eo[1]);
                   eb.y = f32x2_to_bf16x2(eo[2], eo[3]);
