@@ -23,7 +23,7 @@ namespace {
 
 const char* const kKindNames[KK_COUNT] = {
     "fwd_hidden", "fwd_gemv", "fwd_readout", "loss", "bwd_readout",
-    "bwd_hidden", "bwd_embed_adam", "adam_w", "loss_reduce", "heavy_rows"};
+    "bwd_hidden", "bwd_embed_adam", "adam_w", "loss_reduce", "heavy_rows", "form_gz"};
 
 struct EventPair {
   hipEvent_t a, b;
@@ -395,22 +395,33 @@ void traffic_model(gco_ctx* ctx) {
   kb[KK_FWD_READOUT] = idx + scales + 3 * n * 4;
   kb[KK_LOSS] = idx + 3 * n * 4;
   kb[KK_BWD_READOUT] = idx + scales + 2 * n * 4;
-  const double wpart = Pw * D * D * 4 + NB * D * D * 4;
+  // On the wave-per-tile path the weight-gradient partials come from that path's own
+  // workgroups, the scalar layer's from the narrow ones, and G_Z of the last hidden layer
+  // is formed by a kernel of its own (KK_FORM_GZ) instead of inside the layer's backward.
+  const bool wave = ctx->wave_path() && L >= 2;
+  const double NBh = wave ? ctx->gv.num_wblocks[WM_BWD] : NB, NBe = wave ? ctx->gv.num_wblocks[WM_EMBED] : NB;
+  const double NBo = wave ? ctx->gv.num_nblocks : NB;
+  const double last_extra = wave ? 0 : n * 4 + NBo * D * 4;  // g_t read + gw_out partials
+  if (wave) kb[KK_FORM_GZ] = 2 * n * D * s + n * 4 + Pw * D * 4 + NBo * D * 4;
   // gathered gradient source + Hprev read + GZ write
-  kb[KK_BWD_HIDDEN] = idx + scales + 3 * n * D * s + wpart + (L == 3 ? n * 4 + NB * D * 4 : 0);
+  kb[KK_BWD_HIDDEN] = idx + scales + 3 * n * D * s + Pw * D * D * 4 + NBh * D * D * 4 + (L == 3 ? last_extra : 0);
   // first layer: gathered source + embedding (working copy) read + Adam state in/out
   const double adam_e = ctx->cfg.train_embed ? (6 * n * D * 4 + (s == 2 ? n * D * 2 : 0)) : 0;
   const double hprev_read = (s == 2 || !ctx->cfg.train_embed) ? n * D * s : 0;  // fp32: E is read by Adam already
   if (L >= 2)
-    kb[KK_BWD_EMBED] = idx + scales + n * D * s + hprev_read + wpart + adam_e + (L == 2 ? n * 4 + NB * D * 4 : 0);
+    kb[KK_BWD_EMBED] = idx + scales + n * D * s + hprev_read + Pw * D * D * 4 + NBe * D * D * 4 + adam_e +
+                       (L == 2 ? last_extra : 0);
   else
     kb[KK_BWD_EMBED] = n * 4 + hprev_read + adam_e + NB * D * 4;
+  // one launch serves all weight tensors: W, m, v in and out, and the partials
   double wtot = 0;
   for (int l = 1; l <= L; ++l) {
     const double e = l < L ? D * D : D;
-    wtot += Pw * e * 24 + NB * e * 4;
+    const double nb = l == L ? NBo : (l == 1 ? NBe : NBh);
+    wtot += Pw * e * 24 + nb * e * 4;
   }
-  kb[KK_ADAM_W] = wtot / L;
+  kb[KK_ADAM_W] = wtot;
+  // one set of partials; the training loop reduces many sets per launch
   kb[KK_LOSS_REDUCE] = ctx->gv.num_nblocks * 8.0 + ctx->P * 8.0;
   kb[KK_HEAVY] = 0;  // reported by time only
 }

@@ -39,6 +39,7 @@ enum KernelKind : int {
   KK_ADAM_W,           // gradient reduction + Adam on the weight matrices
   KK_LOSS_REDUCE,      // per-subgraph and total loss
   KK_HEAVY,            // chunked pre-reduction of very long rows
+  KK_FORM_GZ,          // G_Z of the last hidden layer + gradient of the scalar layer's weights
   KK_COUNT
 };
 

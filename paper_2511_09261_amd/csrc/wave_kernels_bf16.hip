@@ -773,11 +773,11 @@ void allow_lds(K kernel, size_t bytes) {
 
 void launch_form_gz_last(const Launch& ln, int D, const GraphView& g, const BwdArgs& a) {
   if (D != 64) return;
-  ln.begin(KK_BWD_READOUT);
+  ln.begin(KK_FORM_GZ);
   form_gz_last_kernel<64><<<g.num_nblocks, kBlock, 0, ln.st>>>(
       g, static_cast<const bf16_t*>(a.Hcur), a.g_t, a.w_out, a.wout_stride, static_cast<bf16_t*>(a.GZ_last),
       a.gwout_partial);
-  ln.end(KK_BWD_READOUT);
+  ln.end(KK_FORM_GZ);
 }
 
 void launch_bwd_hidden_wave(const Launch& ln, int D, bool to_embed, const GraphView& gt, const BwdArgs& a) {
