@@ -84,6 +84,16 @@ struct Store<bf16_t> {
   static __device__ __forceinline__ float as_stored(float x) { return bf16_to_f32(f32_to_bf16(x)); }
 };
 
+// Between LDS writes of some lanes of a wavefront and LDS reads of the same locations by
+// other lanes of that wavefront: the hardware executes a wavefront's LDS operations in
+// program order, so no instruction is needed, but the compiler has to be told that the
+// lanes communicate (otherwise it may forward a lane's own earlier store to its load).
+__device__ __forceinline__ void wave_lds_handoff() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
 // Sum over the 64 lanes of a wavefront in a fixed butterfly order; every lane
 // ends with the total.
 __device__ __forceinline__ float wave_sum(float v) {

@@ -114,9 +114,11 @@ struct gco_ctx {
   int32_t* d_heavy_rows = nullptr;
   int32_t *d_wblk_k[kWaveMaps] = {}, *d_wrowptr = nullptr;
   int num_wblocks[kWaveMaps] = {};
+  int num_loss_slots = 0;
   int2* d_wwave_tiles[kWaveMaps] = {};
   int32_t *d_wpbl_ptr[kWaveMaps] = {}, *d_wpbl_list[kWaveMaps] = {};
   int2 *d_went = nullptr, *d_went_t = nullptr;
+  float *d_wval = nullptr, *d_wval_t = nullptr;
   int32_t *d_wtile_base = nullptr, *d_wtile_hptr = nullptr;
   int2 *d_ent = nullptr, *d_ent_t = nullptr;
   float* d_diag = nullptr;
@@ -422,7 +424,7 @@ void traffic_model(gco_ctx* ctx) {
   }
   kb[KK_ADAM_W] = wtot;
   // one set of partials; the training loop reduces many sets per launch
-  kb[KK_LOSS_REDUCE] = ctx->gv.num_nblocks * 8.0 + ctx->P * 8.0;
+  kb[KK_LOSS_REDUCE] = ctx->gv.num_loss_slots * 8.0 + ctx->P * 8.0;
   kb[KK_HEAVY] = 0;  // reported by time only
 }
 
@@ -631,14 +633,20 @@ int gco_upload_graph(gco_ctx* ctx, int64_t n64, const int64_t* rowptr, const int
     GALLOC(ctx->d_wrowptr, static_cast<size_t>(n) + 1);
     GALLOC(ctx->d_went, static_cast<size_t>(nnz_light) + kEntPad);
     launch_fill_u32(st, ctx->d_went + nnz_light, 2 * kEntPad, 0u);
-    launch_light_fill(st, n, ctx->d_lrowptr, ctx->d_ent, ctx->d_diag, d_wptr64, ctx->d_wrowptr, ctx->d_went);
+    GALLOC(ctx->d_wval, static_cast<size_t>(nnz_light) + kEntPad);
+    launch_fill_u32(st, ctx->d_wval + nnz_light, kEntPad, 0u);
+    launch_light_fill(st, n, ctx->d_lrowptr, ctx->d_ent, ctx->d_diag, d_wptr64, ctx->d_wrowptr, ctx->d_went,
+                      ctx->d_wval);
     if (ctx->d_ent_t == ctx->d_ent) {
       ctx->d_went_t = ctx->d_went;
+      ctx->d_wval_t = ctx->d_wval;
     } else {
+      GALLOC(ctx->d_wval_t, static_cast<size_t>(nnz_light) + kEntPad);
+      launch_fill_u32(st, ctx->d_wval_t + nnz_light, kEntPad, 0u);
       GALLOC(ctx->d_went_t, static_cast<size_t>(nnz_light) + kEntPad);
       launch_fill_u32(st, ctx->d_went_t + nnz_light, 2 * kEntPad, 0u);
       launch_light_fill(st, n, ctx->d_lrowptr, ctx->d_ent_t, ctx->d_diag, d_wptr64, ctx->d_wrowptr,
-                        ctx->d_went_t);
+                        ctx->d_went_t, ctx->d_wval_t);
     }
   }
 
@@ -646,11 +654,13 @@ int gco_upload_graph(gco_ctx* ctx, int64_t n64, const int64_t* rowptr, const int
   std::vector<int> blk_k, blk_s, blk_S, nblk_k, nblk_s, nblk_S;
   build_block_map(P, part_rows, lrowptr, kTileRows, kWideBlocks, kMaxTilesPerBlock, blk_k, blk_s, blk_S);
   // one decomposition per kernel kind (different cost per row)
+  std::vector<int> narrow_wblk_k;
   for (int v = 0; v < kWaveMaps; ++v) {
     std::vector<int> wblk_k;
     std::vector<int2> wwave_tiles;
     build_wave_map(P, part_rows, lrowptr, kWaveBlocksFor[v], kWaveRowCost[v], wblk_k, wwave_tiles);
     ctx->num_wblocks[v] = static_cast<int>(wblk_k.size());
+    if (v == WM_NARROW) narrow_wblk_k = wblk_k;
     GALLOC(ctx->d_wwave_tiles[v], wwave_tiles.size());
     HIPCHK(h2d(ctx, ctx->d_wwave_tiles[v], wwave_tiles.data(), wwave_tiles.size()));
     GALLOC(ctx->d_wblk_k[v], wblk_k.size());
@@ -687,15 +697,6 @@ int gco_upload_graph(gco_ctx* ctx, int64_t n64, const int64_t* rowptr, const int
     HIPCHK(h2d(ctx, ctx->d_pbl_ptr, ptr.data(), ptr.size()));
     HIPCHK(h2d(ctx, ctx->d_pbl_list, list.data(), list.size()));
   }
-  // narrow workgroups of each subgraph (loss reduction)
-  {
-    std::vector<int> ptr, list;
-    bucket_blocks(nblk_k, P, ptr, list);
-    GALLOC(ctx->d_nbl_ptr, ptr.size());
-    GALLOC(ctx->d_nbl_list, std::max<size_t>(1, list.size()));
-    HIPCHK(h2d(ctx, ctx->d_nbl_ptr, ptr.data(), ptr.size()));
-    HIPCHK(h2d(ctx, ctx->d_nbl_list, list.data(), list.size()));
-  }
   {
     std::vector<int> ptr, list;
     bucket_blocks(nblk_k, ctx->Pw, ptr, list);
@@ -726,6 +727,25 @@ int gco_upload_graph(gco_ctx* ctx, int64_t n64, const int64_t* rowptr, const int
     }
   }
   const int num_chunks = static_cast<int>(chunk_begin.size());
+  // loss partials of each subgraph: one slot per pre-reduced row, then one per workgroup of
+  // the width-1 decomposition
+  {
+    std::vector<int> slot_k;
+    int kk = 0;
+    for (int r : heavy_rows) {
+      while (r >= part_rows[kk + 1]) ++kk;
+      slot_k.push_back(kk);
+    }
+    slot_k.insert(slot_k.end(), narrow_wblk_k.begin(), narrow_wblk_k.end());
+    std::vector<int> ptr, list;
+    bucket_blocks(slot_k, P, ptr, list);
+    // bucket_blocks sends every slot to group 0 when there is one group: right for P == 1 too
+    ctx->num_loss_slots = static_cast<int>(slot_k.size());
+    GALLOC(ctx->d_nbl_ptr, ptr.size());
+    GALLOC(ctx->d_nbl_list, std::max<size_t>(1, list.size()));
+    HIPCHK(h2d(ctx, ctx->d_nbl_ptr, ptr.data(), ptr.size()));
+    HIPCHK(h2d(ctx, ctx->d_nbl_list, list.data(), list.size()));
+  }
   {  // pre-reduced rows per wave tile
     std::vector<int> tbase(P + 1, 0);
     for (int kk = 0; kk < P; ++kk)
@@ -781,12 +801,15 @@ int gco_upload_graph(gco_ctx* ctx, int64_t n64, const int64_t* rowptr, const int
   g.wtile_hptr = ctx->d_wtile_hptr;
   g.went = ctx->d_went;
   g.went_t = ctx->d_went_t;
+  g.wval = ctx->d_wval;
+  g.wval_t = ctx->d_wval_t;
   g.nblk_k = ctx->d_nblk_k;
   g.nblk_s = ctx->d_nblk_s;
   g.nblk_S = ctx->d_nblk_S;
   g.num_nblocks = static_cast<int>(nblk_k.size());
-  g.nblk_ptr = ctx->d_nbl_ptr;
-  g.nblk_list = ctx->d_nbl_list;
+  g.num_loss_slots = ctx->num_loss_slots;
+  g.loss_ptr = ctx->d_nbl_ptr;
+  g.loss_list = ctx->d_nbl_list;
   g.num_heavy = num_heavy;
   g.num_chunks = num_chunks;
   g.heavy_of_row = ctx->d_heavy_of_row;
@@ -839,7 +862,7 @@ int gco_upload_graph(gco_ctx* ctx, int64_t n64, const int64_t* rowptr, const int
   GALLOC(ctx->p, static_cast<size_t>(n));
   GALLOC(ctx->g_z, static_cast<size_t>(n));
   GALLOC(ctx->g_t, static_cast<size_t>(n));
-  GALLOC(ctx->loss_partial, static_cast<size_t>(g.num_nblocks) * kLossSets);
+  GALLOC(ctx->loss_partial, static_cast<size_t>(g.num_loss_slots) * kLossSets);
   GALLOC(ctx->loss_part, static_cast<size_t>(P));
   GALLOC(ctx->loss_one, 1);
   HIPCHK(hipStreamSynchronize(st));
@@ -986,7 +1009,7 @@ static void run_forward(gco_ctx* ctx) {
                         last ? ctx->W[L - 1] : nullptr, wos, ctx->t, ctx->d_heavy_partial);
     }
   }
-  launch_fwd_readout(ln, ctx->gv, ctx->t, ctx->z, ctx->p, ctx->d_heavy_partial);
+  launch_fwd_readout(ln, ctx->gv, ctx->t, ctx->z, ctx->p);
   ctx->probs_valid = true;
 }
 
@@ -995,7 +1018,7 @@ static void run_loss_partials(gco_ctx* ctx, int slot) {
   const Launch ln = ctx->launch();
   const float q = ctx->cfg.problem == GCO_PROBLEM_MAXCUT ? 2.f : ctx->cfg.alpha;
   launch_loss(ln, ctx->gv, ctx->p, ctx->d_c, q, ctx->g_z,
-              ctx->loss_partial + static_cast<size_t>(slot) * ctx->gv.num_nblocks, ctx->d_heavy_partial);
+              ctx->loss_partial + static_cast<size_t>(slot) * ctx->gv.num_loss_slots);
 }
 
 // Loss at the current parameters: total to loss_out[0], per-subgraph values to ctx->loss_part.
@@ -1021,7 +1044,7 @@ static void run_backward(gco_ctx* ctx, bool update, float* gE, float* const* gW)
     ad.inv_bc1 = static_cast<float>(1.0 / (1.0 - std::pow(static_cast<double>(c.adam_b1), tt)));
     ad.inv_sqrt_bc2 = static_cast<float>(1.0 / std::sqrt(1.0 - std::pow(static_cast<double>(c.adam_b2), tt)));
   }
-  launch_bwd_readout(ln, ctx->gv, ctx->g_z, ctx->g_t, ctx->d_heavy_partial);
+  launch_bwd_readout(ln, ctx->gv, ctx->g_z, ctx->g_t);
   BwdArgs a;
   a.g_t = ctx->g_t;
   a.w_out = ctx->W[L - 1];
@@ -1089,7 +1112,7 @@ int gco_train(gco_ctx* ctx, int32_t epochs, double* loss_per_epoch) {
     run_loss_partials(ctx, pending++);
     run_backward(ctx, true, nullptr, nullptr);
     if (pending == kLossSets || e + 1 == epochs) {
-      launch_loss_reduce(ctx->launch(), ctx->gv, ctx->loss_partial, pending, ctx->gv.num_nblocks, nullptr,
+      launch_loss_reduce(ctx->launch(), ctx->gv, ctx->loss_partial, pending, ctx->gv.num_loss_slots, nullptr,
                          ctx->loss_hist + (e + 1 - pending));
       pending = 0;
     }

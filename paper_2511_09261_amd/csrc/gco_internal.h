@@ -23,9 +23,9 @@ constexpr int kMaxTilesPerBlock = 16;     // tiles one wide workgroup may own
 constexpr int kWaveRows = 32;            // rows of a tile in the wave-per-tile kernels
 // cuts of the tiles among the wavefronts, one per kernel kind: cost of a row relative to
 // one light-stream entry (measured per-tile against per-entry time of each kernel)
-enum WaveMap : int { WM_FWD = 0, WM_BWD = 1, WM_EMBED = 2, kWaveMaps = 3 };
-constexpr double kWaveRowCost[kWaveMaps] = {0.7, 1.5, 100.0};
-constexpr int kWaveBlocksFor[kWaveMaps] = {3072, 960, 3072};  // workgroups aimed at (measured best)
+enum WaveMap : int { WM_FWD = 0, WM_BWD = 1, WM_EMBED = 2, WM_NARROW = 3, kWaveMaps = 4 };
+constexpr double kWaveRowCost[kWaveMaps] = {0.7, 1.5, 100.0, 1.0};
+constexpr int kWaveBlocksFor[kWaveMaps] = {3072, 960, 3072, 2048};  // workgroups aimed at (measured best)
 constexpr int kEntPad = 512;             // zero entries appended to the packed entry arrays
 
 enum KernelKind : int {
@@ -83,14 +83,20 @@ struct GraphView {
   const int* wtile_hptr = nullptr;  // [tiles+1]
   const int2* went = nullptr;
   const int2* went_t = nullptr;
+  // the same entries' values in fp32 (width-1 kernels)
+  const float* wval = nullptr;
+  const float* wval_t = nullptr;
   // narrow kernels: same scheme with kNarrowRows-row tiles
   const int* nblk_k = nullptr;
   const int* nblk_s = nullptr;
   const int* nblk_S = nullptr;
   int num_nblocks = 0;
-  // narrow workgroups of subgraph k: nblk_list[nblk_ptr[k] .. nblk_ptr[k+1])
-  const int* nblk_ptr = nullptr;
-  const int* nblk_list = nullptr;
+  // loss partials: the width-1 kernels' grid is num_heavy workgroups (one per pre-reduced
+  // row) followed by the workgroups of decomposition WM_NARROW, one partial each; those of
+  // subgraph k are loss_list[loss_ptr[k] .. loss_ptr[k+1])
+  int num_loss_slots = 0;
+  const int* loss_ptr = nullptr;
+  const int* loss_list = nullptr;
   // very long rows, pre-reduced in chunks: row heavy_row[h] owns chunks
   // heavy_chunk_ptr[h] .. heavy_chunk_ptr[h+1]; chunk c covers CSR entries
   // chunk_begin[c] .. chunk_end[c].  heavy_of_row[i] = h or -1.
@@ -103,6 +109,20 @@ struct GraphView {
   const int* chunk_end = nullptr;
   const int* chunk_part = nullptr;    // subgraph of the row that owns the chunk
 };
+
+// The view of the transposed matrix: scale vectors and entry arrays exchanged.
+inline GraphView transposed(const GraphView& g) {
+  GraphView gt = g;
+  gt.sa = g.sb;
+  gt.sb = g.sa;
+  gt.ent = g.ent_t;
+  gt.ent_t = g.ent;
+  gt.went = g.went_t;
+  gt.went_t = g.went;
+  gt.wval = g.wval_t;
+  gt.wval_t = g.wval;
+  return gt;
+}
 
 // Per-call Adam constants (bias corrections evaluated on the host in double).
 struct AdamStep {
@@ -139,13 +159,13 @@ void launch_fwd_hidden(const Launch& ln, int storage, int D, const GraphView& g,
 void launch_fwd_gemv(const Launch& ln, int storage, int D, const GraphView& g, const void* X,
                      const float* w, int w_stride, float* t);
 
+// ---- width-1 kernels (narrow_kernels.hip) ----
 // z = A_hat t, p = sigmoid(z).
-void launch_fwd_readout(const Launch& ln, const GraphView& g, const float* t, float* z, float* p,
-                        float* heavy_partial);
+void launch_fwd_readout(const Launch& ln, const GraphView& g, const float* t, float* z, float* p);
 
-// s = A_loc p; g_z = (c + q s) p (1 - p); loss partial per workgroup.
+// s = A_loc p; g_z = (c + q s) p (1 - p); loss partial per workgroup (g.num_loss_slots of them).
 void launch_loss(const Launch& ln, const GraphView& g, const float* p, const float* c, float q,
-                 float* g_z, double* loss_partial, float* heavy_partial);
+                 float* g_z, double* loss_partial);
 
 // For each of `sets` sets of workgroup partials (set s starts at loss_partial + s * set_stride):
 // loss_part[s, k] = sum of the partials of subgraph k (if loss_part != nullptr);
@@ -155,8 +175,7 @@ void launch_loss_reduce(const Launch& ln, const GraphView& g, const double* loss
 constexpr int kLossSets = 64;  // epochs whose loss partials are kept before they are reduced
 
 // g_t = A_hat^T g_z.
-void launch_bwd_readout(const Launch& ln, const GraphView& g, const float* g_z, float* g_t,
-                        float* heavy_partial);
+void launch_bwd_readout(const Launch& ln, const GraphView& g, const float* g_z, float* g_t);
 
 // Backward of hidden layer l (and of the scalar layer when `last`):
 //   last:  G_Z[j,:] = g_t[j] * w_out^k * [Hcur[j,:] > 0] is formed while gathering,

@@ -31,10 +31,11 @@ void launch_scales(hipStream_t st, int n, const int32_t* lrowptr, int norm, int 
 void launch_pack_entries(hipStream_t st, int n, const int32_t* rowptr, const int32_t* col,
                          const float* row_scale, const float* col_scale, int2* ent, float* diag);
 // Light stream (every row's diagonal entry {i, diag[i]}, followed by its entries unless the
-// row is pre-reduced): per-row entry counts, then the fill at scanned offsets.
+// row is pre-reduced): per-row entry counts, then the fill at scanned offsets; went holds
+// {column, value as a bf16 pair}, wval the value in fp32.
 void launch_light_count(hipStream_t st, int n, const int32_t* rowptr, int64_t* count);
 void launch_light_fill(hipStream_t st, int n, const int32_t* rowptr, const int2* ent, const float* diag,
-                       const int64_t* wptr64, int32_t* wrowptr, int2* went);
+                       const int64_t* wptr64, int32_t* wrowptr, int2* went, float* wval);
 void launch_linear_coeff(hipStream_t st, int n, const float* c_base, const float* extra_orig,
                          const int32_t* perm, float* c);
 

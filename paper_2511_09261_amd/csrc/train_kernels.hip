@@ -316,146 +316,6 @@ __global__ __launch_bounds__(kBlock) void bwd_single_kernel(GraphView g, BwdArgs
 // Width-1 passes: y_i = f_self(i) + sum_{j in N(i)} f(j), then an epilogue per row
 // ---------------------------------------------------------------------------
 
-// Row sums for one 256-row tile into rs[0..256): thread per short row, one
-// wavefront per longer row, chunk partials for the very long ones.
-template <class F>
-__device__ void narrow_row_sums(const GraphView& g, const F& f, int row0, int nrows, float* rs,
-                                int* mlist, const float* __restrict__ heavy_partial) {
-  const int tid = threadIdx.x;
-  if (tid == 0) mlist[0] = 0;
-  __syncthreads();
-  if (tid < nrows) {
-    const int i = row0 + tid;
-    const int e0 = g.rowptr[i], e1 = g.rowptr[i + 1];
-    const int h = g.num_heavy > 0 ? g.heavy_of_row[i] : -1;
-    if (h >= 0) {
-      float acc = 0.f;
-      for (int ch = g.heavy_chunk_ptr[h]; ch < g.heavy_chunk_ptr[h + 1]; ++ch) acc += heavy_partial[ch];
-      rs[tid] = acc;
-    } else if (e1 - e0 > 32) {
-      const int q = atomicAdd(&mlist[0], 1);
-      mlist[1 + q] = tid;
-    } else {
-      float acc = 0.f;
-      for (int e = e0; e < e1; ++e) acc += f(g.col[e]);
-      rs[tid] = acc;
-    }
-  }
-  __syncthreads();
-  const int nm = mlist[0];
-  const int wave = tid / 64, lane = tid % 64;
-  for (int q = wave; q < nm; q += kBlock / 64) {
-    const int r = mlist[1 + q];
-    const int i = row0 + r;
-    float acc = 0.f;
-    for (int e = g.rowptr[i] + lane; e < g.rowptr[i + 1]; e += 64) acc += f(g.col[e]);
-    acc = wave_sum(acc);
-    if (lane == 0) rs[r] = acc;
-  }
-  __syncthreads();
-}
-
-template <class F>
-__global__ __launch_bounds__(kBlock) void heavy_narrow_kernel(GraphView g, F f, float* partial) {
-  __shared__ float red[kBlock / 64];
-  const int ch = blockIdx.x;
-  float acc = 0.f;
-  for (int e = g.chunk_begin[ch] + threadIdx.x; e < g.chunk_end[ch]; e += kBlock) acc += f(g.col[e]);
-  acc = wave_sum(acc);
-  if (threadIdx.x % 64 == 0) red[threadIdx.x / 64] = acc;
-  __syncthreads();
-  if (threadIdx.x == 0) partial[ch] = ((red[0] + red[1]) + red[2]) + red[3];
-}
-
-struct ScaledValue {  // f(j) = sb[j] * x[j]
-  const float* sb;
-  const float* x;
-  __device__ __forceinline__ float operator()(int j) const { return sb[j] * x[j]; }
-};
-struct PlainValue {  // f(j) = x[j]
-  const float* x;
-  __device__ __forceinline__ float operator()(int j) const { return x[j]; }
-};
-
-// z = A_hat t; p = sigmoid(z)
-__global__ __launch_bounds__(kBlock) void fwd_readout_kernel(GraphView g, const float* __restrict__ t,
-                                                             float* __restrict__ z,
-                                                             float* __restrict__ p,
-                                                             const float* __restrict__ heavy_partial) {
-  __shared__ float rs[kNarrowRows];
-  __shared__ int mlist[kNarrowRows + 1];
-  const int k = g.nblk_k[blockIdx.x];
-  if (k < 0) return;
-  const int s = g.nblk_s[blockIdx.x];
-  const int rbeg = g.part_rows[k], rend = g.part_rows[k + 1];
-  ScaledValue f{g.sb, t};
-  for (int row0 = rbeg + s * kNarrowRows; row0 < rend; row0 += g.nblk_S[blockIdx.x] * kNarrowRows) {
-    const int nrows = min(kNarrowRows, rend - row0);
-    narrow_row_sums(g, f, row0, nrows, rs, mlist, heavy_partial);
-    if (threadIdx.x < nrows) {
-      const int i = row0 + threadIdx.x;
-      const float zi = g.sa[i] * (f(i) + rs[threadIdx.x]);
-      z[i] = zi;
-      p[i] = 1.f / (1.f + expf(-zi));
-    }
-    __syncthreads();
-  }
-}
-
-// g_t = A_hat^T g_z  (the view passed in has sa and sb exchanged)
-__global__ __launch_bounds__(kBlock) void bwd_readout_kernel(GraphView g, const float* __restrict__ g_z,
-                                                             float* __restrict__ g_t,
-                                                             const float* __restrict__ heavy_partial) {
-  __shared__ float rs[kNarrowRows];
-  __shared__ int mlist[kNarrowRows + 1];
-  const int k = g.nblk_k[blockIdx.x];
-  if (k < 0) return;
-  const int s = g.nblk_s[blockIdx.x];
-  const int rbeg = g.part_rows[k], rend = g.part_rows[k + 1];
-  ScaledValue f{g.sb, g_z};
-  for (int row0 = rbeg + s * kNarrowRows; row0 < rend; row0 += g.nblk_S[blockIdx.x] * kNarrowRows) {
-    const int nrows = min(kNarrowRows, rend - row0);
-    narrow_row_sums(g, f, row0, nrows, rs, mlist, heavy_partial);
-    if (threadIdx.x < nrows) {
-      const int i = row0 + threadIdx.x;
-      g_t[i] = g.sa[i] * (f(i) + rs[threadIdx.x]);
-    }
-    __syncthreads();
-  }
-}
-
-// s = A_loc p; g_z = (c + q s) p (1 - p); loss partial = sum_i p_i (c_i + q/2 s_i)
-__global__ __launch_bounds__(kBlock) void loss_kernel(GraphView g, const float* __restrict__ p,
-                                                      const float* __restrict__ cl, float q,
-                                                      float* __restrict__ g_z,
-                                                      double* __restrict__ loss_partial,
-                                                      const float* __restrict__ heavy_partial) {
-  __shared__ float rs[kNarrowRows];
-  __shared__ int mlist[kNarrowRows + 1];
-  __shared__ double wred[kBlock / 64];
-  const int k = g.nblk_k[blockIdx.x];
-  if (k < 0) return;
-  const int s = g.nblk_s[blockIdx.x];
-  const int rbeg = g.part_rows[k], rend = g.part_rows[k + 1];
-  PlainValue f{p};
-  double lsum = 0.0;
-  for (int row0 = rbeg + s * kNarrowRows; row0 < rend; row0 += g.nblk_S[blockIdx.x] * kNarrowRows) {
-    const int nrows = min(kNarrowRows, rend - row0);
-    narrow_row_sums(g, f, row0, nrows, rs, mlist, heavy_partial);
-    if (threadIdx.x < nrows) {
-      const int i = row0 + threadIdx.x;
-      const float pi = p[i], ci = cl[i], si = rs[threadIdx.x];
-      g_z[i] = (ci + q * si) * pi * (1.f - pi);
-      lsum += static_cast<double>(pi) * (static_cast<double>(ci) + 0.5 * static_cast<double>(q) * static_cast<double>(si));
-    }
-    __syncthreads();
-  }
-  lsum = wave_sum(lsum);
-  if (threadIdx.x % 64 == 0) wred[threadIdx.x / 64] = lsum;
-  __syncthreads();
-  if (threadIdx.x == 0) loss_partial[blockIdx.x] = ((wred[0] + wred[1]) + wred[2]) + wred[3];
-}
-
 // One workgroup per set of partials (one set per epoch).  Each wavefront takes subgraphs
 // k = wave, wave + 4, ...: its lanes sum the workgroup partials of k in a strided, fixed
 // order, then the wavefront total is formed by a butterfly.  Thread 0 adds the subgraph
@@ -470,7 +330,7 @@ __global__ __launch_bounds__(kBlock) void loss_reduce_kernel(GraphView g, const 
   const int wave = threadIdx.x / 64, lane = threadIdx.x % 64;
   for (int k = wave; k < g.P; k += kBlock / 64) {
     double acc = 0.0;
-    for (int q = g.nblk_ptr[k] + lane; q < g.nblk_ptr[k + 1]; q += 64) acc += partial[g.nblk_list[q]];
+    for (int q = g.loss_ptr[k] + lane; q < g.loss_ptr[k + 1]; q += 64) acc += partial[g.loss_list[q]];
     acc = wave_sum(acc);
     if (lane == 0) {
       part_s[k] = acc;
@@ -555,17 +415,6 @@ void allow_lds(K kernel, size_t bytes) {
                               hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(bytes));
 }
 
-GraphView transposed(const GraphView& g) {
-  GraphView gt = g;
-  gt.sa = g.sb;
-  gt.sb = g.sa;
-  gt.ent = g.ent_t;
-  gt.ent_t = g.ent;
-  gt.went = g.went_t;
-  gt.went_t = g.went;
-  return gt;
-}
-
 }  // namespace
 
 // ---------------------------------------------------------------------------
@@ -620,30 +469,6 @@ void launch_fwd_gemv(const Launch& ln, int storage, int D, const GraphView& g, c
   ln.end(KK_FWD_GEMV);
 }
 
-void launch_fwd_readout(const Launch& ln, const GraphView& g, const float* t, float* z, float* p,
-                        float* heavy_partial) {
-  if (g.num_chunks > 0) {
-    ln.begin(KK_HEAVY);
-    heavy_narrow_kernel<ScaledValue><<<g.num_chunks, kBlock, 0, ln.st>>>(g, ScaledValue{g.sb, t}, heavy_partial);
-    ln.end(KK_HEAVY);
-  }
-  ln.begin(KK_FWD_READOUT);
-  fwd_readout_kernel<<<g.num_nblocks, kBlock, 0, ln.st>>>(g, t, z, p, heavy_partial);
-  ln.end(KK_FWD_READOUT);
-}
-
-void launch_loss(const Launch& ln, const GraphView& g, const float* p, const float* c, float q,
-                 float* g_z, double* loss_partial, float* heavy_partial) {
-  if (g.num_chunks > 0) {
-    ln.begin(KK_HEAVY);
-    heavy_narrow_kernel<PlainValue><<<g.num_chunks, kBlock, 0, ln.st>>>(g, PlainValue{p}, heavy_partial);
-    ln.end(KK_HEAVY);
-  }
-  ln.begin(KK_LOSS);
-  loss_kernel<<<g.num_nblocks, kBlock, 0, ln.st>>>(g, p, c, q, g_z, loss_partial, heavy_partial);
-  ln.end(KK_LOSS);
-}
-
 void launch_loss_reduce(const Launch& ln, const GraphView& g, const double* loss_partial, int sets,
                         int64_t set_stride, double* loss_part, double* loss_out) {
   if (sets <= 0) return;
@@ -652,19 +477,6 @@ void launch_loss_reduce(const Launch& ln, const GraphView& g, const double* loss
   ln.begin(KK_LOSS_REDUCE);
   loss_reduce_kernel<<<sets, kBlock, lds, ln.st>>>(g, loss_partial, set_stride, loss_part, loss_out);
   ln.end(KK_LOSS_REDUCE);
-}
-
-void launch_bwd_readout(const Launch& ln, const GraphView& g, const float* g_z, float* g_t,
-                        float* heavy_partial) {
-  const GraphView gt = transposed(g);
-  if (g.num_chunks > 0) {
-    ln.begin(KK_HEAVY);
-    heavy_narrow_kernel<ScaledValue><<<g.num_chunks, kBlock, 0, ln.st>>>(gt, ScaledValue{gt.sb, g_z}, heavy_partial);
-    ln.end(KK_HEAVY);
-  }
-  ln.begin(KK_BWD_READOUT);
-  bwd_readout_kernel<<<g.num_nblocks, kBlock, 0, ln.st>>>(gt, g_z, g_t, heavy_partial);
-  ln.end(KK_BWD_READOUT);
 }
 
 template <typename T, int D>

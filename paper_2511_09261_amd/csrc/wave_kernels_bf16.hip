@@ -232,6 +232,7 @@ __device__ __forceinline__ void stream_tiles(const GraphView& g, const int2* __r
           make_uint4(lower_halves(y[0], y[1]), lower_halves(y[2], y[3]), lower_halves(y[4], y[5]),
                      lower_halves(y[6], y[7]));
     }
+    wave_lds_handoff();
     // fragments of the step: slots 16 ks + 8h .. + 7 of feature 32 tn + n, and their values
     bf16x8 xa[G_::NT][G_::KS1];
 #pragma unroll
@@ -312,6 +313,7 @@ __device__ __forceinline__ void stream_tiles(const GraphView& g, const int2* __r
           }
       }
       on_tile(row0, nrows, agg);
+      wave_lds_handoff();
 #pragma unroll
       for (int tn = 0; tn < G_::NT; ++tn)
 #pragma unroll
@@ -331,6 +333,7 @@ __device__ __forceinline__ void stream_tiles(const GraphView& g, const int2* __r
     }
 #pragma unroll
     for (int j = 0; j < 8; ++j) cur[j] = nxt[j];
+    wave_lds_handoff();
   }
 }
 
@@ -410,6 +413,7 @@ __global__ __launch_bounds__(kBlock, 3) void fwd_wave_kernel(
         *reinterpret_cast<uint2*>(ot + n * G_::PA + f0) = pk;
       }
     // full rows, 16 bytes per lane
+    wave_lds_handoff();
 #pragma unroll
     for (int u = 0; u < G_::NO; ++u) {
       const int r = u * G_::NG + grp;
@@ -417,6 +421,7 @@ __global__ __launch_bounds__(kBlock, 3) void fwd_wave_kernel(
         *reinterpret_cast<uint4*>(Y + static_cast<size_t>(row0 + r) * D + c0) =
             *reinterpret_cast<const uint4*>(ot + r * G_::PA + c0);
     }
+    wave_lds_handoff();
     if (w_out != nullptr) {  // t[r] = sum_c Y[r, c] * w_out[c]
       part += __shfl_xor(part, 32, 64);
       if (h == 0 && n < nrows) t[row0 + n] = part;
@@ -609,6 +614,7 @@ __global__ __launch_bounds__(kBlock, 2) void bwd_wave_kernel(GraphView g, BwdArg
         // 16-byte groups rotated by feature / 8 (LDS banks, as for the row buffer)
         *reinterpret_cast<uint2*>(hpl + (sub * 8 + i) * G_::GP + ((grp / 2 + sub) % 4) * 16 + (grp % 2) * 8) = d;
       }
+      wave_lds_handoff();
       // gW[a, b] += sum over the tile's rows of Hprev[row, a] G_T[row, b]
 #pragma unroll
       for (int ks = 0; ks < RW / 16; ++ks) {
@@ -625,6 +631,7 @@ __global__ __launch_bounds__(kBlock, 2) void bwd_wave_kernel(GraphView g, BwdArg
           for (int tb = 0; tb < G_::NT; ++tb)
             gw[ta][tb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[ta], bf[tb], gw[ta][tb], 0, 0, 0);
       }
+      wave_lds_handoff();
       if (need_gh) {
         // G_H^T = W G_T^T
         floatx16 z[G_::NT];
@@ -649,6 +656,7 @@ __global__ __launch_bounds__(kBlock, 2) void bwd_wave_kernel(GraphView g, BwdArg
             for (int i = 0; i < 4; ++i)
               *reinterpret_cast<float4*>(st + n * G_::PF + acc_feature(ta, 0, 4 * i) + 4 * h) =
                   make_float4(z[ta][4 * i], z[ta][4 * i + 1], z[ta][4 * i + 2], z[ta][4 * i + 3]);
+          wave_lds_handoff();
           constexpr int LR = D / 4;        // lanes per fp32 row
           constexpr int RI = 64 / LR;      // rows per instruction
           constexpr int NQ = RW / RI;      // instructions per tile and tensor
@@ -723,6 +731,7 @@ __global__ __launch_bounds__(kBlock, 2) void bwd_wave_kernel(GraphView g, BwdArg
               pk.y = f32x2_to_bf16x2(z[ta][4 * i + 2], z[ta][4 * i + 3]);
               *reinterpret_cast<uint2*>(ot + n * G_::PA + acc_feature(ta, 0, 4 * i) + 4 * h) = pk;
             }
+          wave_lds_handoff();
           bf16_t* GZo = static_cast<bf16_t*>(a.GZ_out);
 #pragma unroll
           for (int u = 0; u < RPL; ++u) {
@@ -736,6 +745,7 @@ __global__ __launch_bounds__(kBlock, 2) void bwd_wave_kernel(GraphView g, BwdArg
           }
         }
       }
+      wave_lds_handoff();
       request_hprev(row0 + RW);
     });
   }
