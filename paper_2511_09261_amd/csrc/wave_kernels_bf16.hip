@@ -337,6 +337,30 @@ __device__ __forceinline__ void stream_tiles(const GraphView& g, const int2* __r
   }
 }
 
+// 16-byte accesses marked non-temporal: loads of data that is streamed once (optimizer
+// state, own rows read once), so that they do not displace the gathered rows from the
+// caches, and the stores of whole output rows, which complete sooner that way (a
+// wavefront's next wait for loads also waits for its earlier stores).
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ float4 load_streamed(const float* p) {
+  const f32x4_t v = __builtin_nontemporal_load(reinterpret_cast<const f32x4_t*>(p));
+  return make_float4(v.x, v.y, v.z, v.w);
+}
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ uint4 load_streamed(const bf16_t* p) {
+  const u32x4_t v = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(p));
+  return make_uint4(v.x, v.y, v.z, v.w);
+}
+__device__ __forceinline__ void store_streamed(float* p, float a, float b, float c, float d) {
+  const f32x4_t v = {a, b, c, d};
+  __builtin_nontemporal_store(v, reinterpret_cast<f32x4_t*>(p));
+}
+
+__device__ __forceinline__ void store_streamed(bf16_t* p, const uint4& q) {
+  const u32x4_t v = {q.x, q.y, q.z, q.w};
+  __builtin_nontemporal_store(v, reinterpret_cast<u32x4_t*>(p));
+}
+
 template <int D>
 constexpr size_t fwd_wave_lds() {
   return WG<D>::w_bytes + D * sizeof(float) + 256 * sizeof(uint4) + 4 * WG<D>::wave_bytes;
@@ -381,17 +405,25 @@ __global__ __launch_bounds__(kBlock, 3) void fwd_wave_kernel(
     for (int tj = 0; tj < G_::NT; ++tj)
 #pragma unroll
       for (int r = 0; r < 16; ++r) z[tj][r] = 0.f;
+    uint4 bq[G_::KS2];
 #pragma unroll
     for (int ks2 = 0; ks2 < G_::KS2; ++ks2) {
       float v[8];
 #pragma unroll
       for (int e = 0; e < 8; ++e) v[e] = agg[ks2 / 2][8 * (ks2 % 2) + e];
-      const bf16x8 b = as_frag(pack8(v));
+      bq[ks2] = pack8(v);
+    }
+    // per output tile: all fragments of W first, then the chain of products, so that the
+    // products do not wait for one LDS read each
 #pragma unroll
-      for (int tj = 0; tj < G_::NT; ++tj) {
-        const bf16x8 a = as_frag(*reinterpret_cast<const uint4*>(wfr + ((tj * G_::KS2 + ks2) * 64 + lane) * 8));
-        z[tj] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, z[tj], 0, 0, 0);
-      }
+    for (int tj = 0; tj < G_::NT; ++tj) {
+      uint4 wa[G_::KS2];
+#pragma unroll
+      for (int ks2 = 0; ks2 < G_::KS2; ++ks2)
+        wa[ks2] = *reinterpret_cast<const uint4*>(wfr + ((tj * G_::KS2 + ks2) * 64 + lane) * 8);
+#pragma unroll
+      for (int ks2 = 0; ks2 < G_::KS2; ++ks2)
+        z[tj] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_frag(wa[ks2]), as_frag(bq[ks2]), z[tj], 0, 0, 0);
     }
     // ReLU, round; lane (n, h) holds features acc_feature(tj, h, r) of row n
     float part = 0.f;
@@ -418,8 +450,8 @@ __global__ __launch_bounds__(kBlock, 3) void fwd_wave_kernel(
     for (int u = 0; u < G_::NO; ++u) {
       const int r = u * G_::NG + grp;
       if (r < nrows)
-        *reinterpret_cast<uint4*>(Y + static_cast<size_t>(row0 + r) * D + c0) =
-            *reinterpret_cast<const uint4*>(ot + r * G_::PA + c0);
+        store_streamed(Y + static_cast<size_t>(row0 + r) * D + c0,
+                       *reinterpret_cast<const uint4*>(ot + r * G_::PA + c0));
     }
     wave_lds_handoff();
     if (w_out != nullptr) {  // t[r] = sum_c Y[r, c] * w_out[c]
@@ -427,23 +459,6 @@ __global__ __launch_bounds__(kBlock, 3) void fwd_wave_kernel(
       if (h == 0 && n < nrows) t[row0 + n] = part;
     }
   });
-}
-
-// 16-byte accesses to data that is streamed once (optimizer state): marked non-temporal,
-// so that they do not displace the gathered rows from the caches.
-typedef float f32x4_t __attribute__((ext_vector_type(4)));
-__device__ __forceinline__ float4 load_streamed(const float* p) {
-  const f32x4_t v = __builtin_nontemporal_load(reinterpret_cast<const f32x4_t*>(p));
-  return make_float4(v.x, v.y, v.z, v.w);
-}
-typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
-__device__ __forceinline__ uint4 load_streamed(const bf16_t* p) {
-  const u32x4_t v = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(p));
-  return make_uint4(v.x, v.y, v.z, v.w);
-}
-__device__ __forceinline__ void store_streamed(float* p, float a, float b, float c, float d) {
-  const f32x4_t v = {a, b, c, d};
-  __builtin_nontemporal_store(v, reinterpret_cast<f32x4_t*>(p));
 }
 
 // ---------------------------------------------------------------------------
@@ -741,7 +756,7 @@ __global__ __launch_bounds__(kBlock, 2) void bwd_wave_kernel(GraphView g, BwdArg
             o.y = keep_where_positive(o.y, hp_raw[u].y);
             o.z = keep_where_positive(o.z, hp_raw[u].z);
             o.w = keep_where_positive(o.w, hp_raw[u].w);
-            if (r < nrows) *reinterpret_cast<uint4*>(GZo + static_cast<size_t>(row0 + r) * D + sub * 8) = o;
+            if (r < nrows) store_streamed(GZo + static_cast<size_t>(row0 + r) * D + sub * 8, o);
           }
         }
       }
