@@ -111,6 +111,13 @@ def main():
     t0 = time.perf_counter(); u, v = ctx.cut_edges(); t_cut = time.perf_counter() - t0
     info = ctx.graph_info()
 
+    # fine-tune step of Sec. 3.3 on one eighth of the subgraphs (not part of `value`)
+    listed = list(range(0, wl.num_parts, 8))
+    ctx.train_subset(3, listed, return_loss=False)
+    ctx.sync()
+    t0 = time.perf_counter(); ctx.train_subset(20, listed, return_loss=False); ctx.sync()
+    t_sub = (time.perf_counter() - t0) / 20
+
     L = wl.num_layers
     nnz = 2 * info["m_local"]
     ea_per_epoch = 2 * L * (nnz + g.n) + nnz
@@ -138,6 +145,7 @@ def main():
                                  / (per_epoch[k] * 1e-3) / 1e9 for k in per_epoch if per_epoch[k] > 0},
                   "generate_s": t_gen, "upload_preprocess_s": t_upload,
                   "forward_and_read_probs_s": t_fwd, "round_repair_s": t_rr, "cut_edges_s": t_cut,
+                  "fine_tune_subset": {"subgraphs": len(listed), "of": wl.num_parts, "ms_per_epoch": t_sub * 1e3},
                   "set_size_or_cut": obj, "conflicts_before": c_before, "conflicts_after": c_after,
                   "cut_edges": int(len(u))},
     }

@@ -134,6 +134,25 @@ int gco_set_linear_penalty(gco_ctx* ctx, const float* extra);
  * NULL (use gco_sync); otherwise returns after the stream has drained. */
 int gco_train(gco_ctx* ctx, int32_t epochs, double* loss_per_epoch);
 
+/* The same for a subset of the subgraphs: the fine-tuning step of Sec. 3.3 / Alg. 1
+ * stage 3 retrains only the subgraphs involved in a conflict, warm-started from their
+ * current parameters and optimizer state, usually after gco_set_linear_penalty.
+ * parts is int32[num_listed] of subgraph ids (host; duplicates allowed).  Subgraphs that
+ * are not listed keep their embeddings, weights, Adam moments, step counts and
+ * probabilities bit for bit.  With shared weights the one weight set is updated from the
+ * gradients of the listed subgraphs only.  loss_per_epoch[e] is the sum of the listed
+ * subgraphs' losses.  Every subgraph (and weight set) counts its own Adam steps, so the
+ * bias correction of a subgraph depends only on how often that subgraph was trained.
+ * ERANGE for an id outside [0, num_parts). */
+int gco_train_subset(gco_ctx* ctx, int32_t epochs, const int32_t* parts, int32_t num_listed,
+                     double* loss_per_epoch);
+
+/* Adam step counts: steps_embed is int64[num_parts] (embedding rows of each subgraph),
+ * steps_weights int64[Pw] (weight sets).  gco_set_params zeroes them; gco_set_opt_state
+ * sets all of them to its `step`; gco_get_opt_state reports the largest.  Host arrays. */
+int gco_get_steps(gco_ctx* ctx, int64_t* steps_embed, int64_t* steps_weights);
+int gco_set_steps(gco_ctx* ctx, const int64_t* steps_embed, const int64_t* steps_weights);
+
 /* Forward pass at the current parameters (Alg. 1 stage 2: "run forward to get p"). */
 int gco_forward(gco_ctx* ctx);
 /* Probabilities of the last forward / the forward of the last epoch: float[n]. */

@@ -180,7 +180,8 @@ def loss(lg: LocalGraph, p, spec: Spec, extra_linear=None):
     return float(per_part.sum()), per_part
 
 
-def backward(lg: LocalGraph, cache: dict, Ws, spec: Spec, extra_linear=None, relu_on=None):
+def backward(lg: LocalGraph, cache: dict, Ws, spec: Spec, extra_linear=None, relu_on=None,
+             active=None):
     """Exact chain rule through Eq. 5, Eq. 4 and the layers of Eq. 3.
 
     Returns (gE [n, d], [gW_1 .. gW_L]) with gW_l shaped like W_l.
@@ -189,7 +190,12 @@ def backward(lg: LocalGraph, cache: dict, Ws, spec: Spec, extra_linear=None, rel
     where the ReLU of layer l passes the gradient; it replaces the checker's own
     decision Z_l > 0.  Tests of reduced-precision runs pass the decisions the
     device took, because a unit whose pre-activation is zero to within rounding
-    may legitimately fall on either side."""
+    may legitimately fall on either side.
+
+    active, if given, is a boolean array over the subgraphs: only the listed subgraphs
+    contribute to the weight gradients (this matters only when the weights are shared;
+    with per-subgraph weights a subgraph's gradient never depends on the others)."""
+    on_k = np.ones(lg.num_parts, dtype=bool) if active is None else np.asarray(active, dtype=bool)
     L = spec.num_layers
     c, q = qubo_coefficients(lg, spec)
     if extra_linear is not None:
@@ -204,7 +210,8 @@ def backward(lg: LocalGraph, cache: dict, Ws, spec: Spec, extra_linear=None, rel
     g_agg = np.zeros_like(cache["Agg"][L])
     for k, idx in enumerate(lg.members):
         kk = 0 if spec.weight_sharing else k
-        gWs[L - 1][kk, :, 0] += cache["Agg"][L][idx].T @ g_z[idx]
+        if on_k[k]:
+            gWs[L - 1][kk, :, 0] += cache["Agg"][L][idx].T @ g_z[idx]
         g_agg[idx] = np.outer(g_z[idx], WL[kk, :, 0])
     g_H = lg.A_hat.T @ g_agg
     for l in range(L - 1, 0, -1):
@@ -216,7 +223,8 @@ def backward(lg: LocalGraph, cache: dict, Ws, spec: Spec, extra_linear=None, rel
         g_agg = np.zeros_like(cache["Agg"][l])
         for k, idx in enumerate(lg.members):
             kk = 0 if spec.weight_sharing else k
-            gWs[l - 1][kk] += cache["Agg"][l][idx].T @ g_Z[idx]
+            if on_k[k]:
+                gWs[l - 1][kk] += cache["Agg"][l][idx].T @ g_Z[idx]
             g_agg[idx] = g_Z[idx] @ Wl[kk].T
         g_H = lg.A_hat.T @ g_agg
     return g_H, gWs
@@ -234,35 +242,55 @@ def adam_update(theta, g, m, v, t, spec: Spec):
 
 @dataclass
 class TrainState:
+    """Parameters, Adam moments and Adam step counts.  Every subgraph is a model of its
+    own (Alg. 1 trains and stores them one by one), so the embedding rows of subgraph k
+    count their steps in tE[k] and weight set kw in tW[kw]."""
     E: np.ndarray
     Ws: list
     mE: np.ndarray
     vE: np.ndarray
     mW: list
     vW: list
-    t: int = 0
+    tE: np.ndarray = None
+    tW: np.ndarray = None
 
 
 def init_state(E, Ws) -> TrainState:
     E = np.array(E, dtype=np.float64)
     Ws = [np.array(W, dtype=np.float64) for W in Ws]
     return TrainState(E, Ws, np.zeros_like(E), np.zeros_like(E),
-                      [np.zeros_like(W) for W in Ws], [np.zeros_like(W) for W in Ws], 0)
+                      [np.zeros_like(W) for W in Ws], [np.zeros_like(W) for W in Ws])
 
 
-def train(lg: LocalGraph, st: TrainState, spec: Spec, epochs: int, extra_linear=None):
-    """`epochs` full-batch steps.  Returns the loss at the parameters each epoch
-    started from, and per-subgraph losses [epochs, P]."""
+def train(lg: LocalGraph, st: TrainState, spec: Spec, epochs: int, extra_linear=None, active=None):
+    """`epochs` full-batch steps of the subgraphs listed in `active` (boolean array over the
+    subgraphs; None = all): Sec. 3.2 for all of them, the fine-tuning step of Sec. 3.3 /
+    Alg. 1 stage 3 for a subset.  Subgraphs that are not listed keep parameters, moments
+    and step counts.  Returns the loss (summed over the listed subgraphs) at the parameters
+    each epoch started from, and per-subgraph losses [epochs, P]."""
+    P, Pw = lg.num_parts, st.Ws[0].shape[0]
+    if st.tE is None:
+        st.tE = np.zeros(P, dtype=np.int64)
+        st.tW = np.zeros(Pw, dtype=np.int64)
+    on_k = np.ones(P, dtype=bool) if active is None else np.asarray(active, dtype=bool)
+    on_w = on_k if Pw == P else np.array([on_k.any()])
     losses, per_part = [], []
     for _ in range(epochs):
         cache = forward(lg, st.E, st.Ws, spec)
-        tot, pp = loss(lg, cache["p"], spec, extra_linear)
-        losses.append(tot)
+        _, pp = loss(lg, cache["p"], spec, extra_linear)
+        losses.append(pp[on_k].sum())
         per_part.append(pp)
-        gE, gWs = backward(lg, cache, st.Ws, spec, extra_linear)
-        st.t += 1
+        gE, gWs = backward(lg, cache, st.Ws, spec, extra_linear, active=on_k)
+        st.tE[on_k] += 1
+        st.tW[on_w] += 1
         if spec.train_embed:
-            st.E, st.mE, st.vE = adam_update(st.E, gE, st.mE, st.vE, st.t, spec)
+            for k, idx in enumerate(lg.members):
+                if on_k[k]:
+                    st.E[idx], st.mE[idx], st.vE[idx] = adam_update(
+                        st.E[idx], gE[idx], st.mE[idx], st.vE[idx], int(st.tE[k]), spec)
         for l in range(spec.num_layers):
-            st.Ws[l], st.mW[l], st.vW[l] = adam_update(st.Ws[l], gWs[l], st.mW[l], st.vW[l], st.t, spec)
+            for kw in range(Pw):
+                if on_w[kw]:
+                    st.Ws[l][kw], st.mW[l][kw], st.vW[l][kw] = adam_update(
+                        st.Ws[l][kw], gWs[l][kw], st.mW[l][kw], st.vW[l][kw], int(st.tW[kw]), spec)
     return np.array(losses), np.array(per_part)

@@ -61,6 +61,9 @@ _PROTOTYPES = {
                                     C.POINTER(C.c_void_p), C.c_int64]),
     "gco_set_linear_penalty": (C.c_int, [C.c_void_p, C.c_void_p]),
     "gco_train": (C.c_int, [C.c_void_p, C.c_int32, C.c_void_p]),
+    "gco_train_subset": (C.c_int, [C.c_void_p, C.c_int32, C.c_void_p, C.c_int32, C.c_void_p]),
+    "gco_get_steps": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p]),
+    "gco_set_steps": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p]),
     "gco_forward": (C.c_int, [C.c_void_p]),
     "gco_get_probs": (C.c_int, [C.c_void_p, C.c_void_p]),
     "gco_loss": (C.c_int, [C.c_void_p, C.POINTER(C.c_double), C.c_void_p]),
@@ -256,6 +259,28 @@ class Context:
         out = np.empty(epochs, dtype=np.float64) if return_loss else None
         self._check(self.lib.gco_train(self.h, epochs, _ptr(out)))
         return out
+
+    @property
+    def num_weight_sets(self):
+        return 1 if self.weight_sharing else self.num_parts
+
+    def train_subset(self, epochs, parts, return_loss=True):
+        parts = np.ascontiguousarray(parts, dtype=np.int32)
+        out = np.empty(epochs, dtype=np.float64) if return_loss else None
+        self._check(self.lib.gco_train_subset(self.h, epochs, _ptr(parts), parts.shape[0], _ptr(out)))
+        return out
+
+    def get_steps(self):
+        se = np.empty(self.num_parts, dtype=np.int64)
+        sw = np.empty(self.num_weight_sets, dtype=np.int64)
+        self._check(self.lib.gco_get_steps(self.h, _ptr(se), _ptr(sw)))
+        return se, sw
+
+    def set_steps(self, steps_embed, steps_weights):
+        se = np.ascontiguousarray(steps_embed, dtype=np.int64)
+        sw = np.ascontiguousarray(steps_weights, dtype=np.int64)
+        assert se.shape[0] == self.num_parts and sw.shape[0] == self.num_weight_sets
+        self._check(self.lib.gco_set_steps(self.h, _ptr(se), _ptr(sw)))
 
     def forward(self):
         self._check(self.lib.gco_forward(self.h))

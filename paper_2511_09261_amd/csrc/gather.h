@@ -166,6 +166,7 @@ __global__ __launch_bounds__(kBlock) void heavy_wide_kernel(GraphView g, Src src
   const int tid = threadIdx.x;
   const int grp = tid / LPR;
   const int c0 = (tid % LPR) * VEC;
+  if (g.chunk_part[ch] < 0) return;  // the row's subgraph sits out
   src.set_part(g.chunk_part[ch], c0);
   float acc[VEC];
 #pragma unroll

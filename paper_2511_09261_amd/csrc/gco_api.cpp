@@ -104,19 +104,32 @@ struct gco_ctx {
   int32_t* d_lcol = nullptr;
   float *d_sa = nullptr, *d_sb = nullptr, *d_cbase = nullptr, *d_c = nullptr;
   int32_t* d_part_rows = nullptr;
-  int32_t *d_blk_k = nullptr, *d_blk_s = nullptr, *d_nblk_k = nullptr, *d_nblk_s = nullptr;
+  int32_t *d_blk_s = nullptr, *d_nblk_s = nullptr;
   int32_t *d_blk_S = nullptr, *d_nblk_S = nullptr;
-  int32_t *d_pbl_ptr = nullptr, *d_pbl_list = nullptr;
-  int32_t *d_nbl_ptr = nullptr, *d_nbl_list = nullptr;
-  int32_t *d_nwbl_ptr = nullptr, *d_nwbl_list = nullptr;  // narrow workgroups per weight set
   int32_t *d_heavy_of_row = nullptr, *d_heavy_chunk_ptr = nullptr, *d_chunk_begin = nullptr,
-          *d_chunk_end = nullptr, *d_chunk_part = nullptr;
-  int32_t* d_heavy_rows = nullptr;
-  int32_t *d_wblk_k[kWaveMaps] = {}, *d_wrowptr = nullptr;
+          *d_chunk_end = nullptr;
+  int32_t* d_wrowptr = nullptr;
+  // Everything that names which subgraph a unit of work belongs to, on the host (as built
+  // at upload) and on the device twice: for all subgraphs (`full`) and for the subset of
+  // the current gco_train_subset call (`sub`, units of the other subgraphs marked -1).
+  struct HostMaps {
+    std::vector<int> blk_k, nblk_k, wblk_k[kWaveMaps], chunk_part, heavy_rows, heavy_part;
+  } hm;
+  struct ActiveMaps {
+    int32_t *blk_k = nullptr, *nblk_k = nullptr, *wblk_k[kWaveMaps] = {}, *chunk_part = nullptr,
+            *heavy_rows = nullptr;
+    // workgroups that hold partials, per weight set: wide kernels, wave kernels, narrow tiles
+    int32_t *pbl_ptr = nullptr, *pbl_list = nullptr;
+    int32_t *wpbl_ptr[kWaveMaps] = {}, *wpbl_list[kWaveMaps] = {};
+    int32_t *nwbl_ptr = nullptr, *nwbl_list = nullptr;
+    // loss partial slots per subgraph
+    int32_t *loss_ptr = nullptr, *loss_list = nullptr;
+    bool allocated = false;
+  } full, sub;
+  GraphView gv_sub;
   int num_wblocks[kWaveMaps] = {};
   int num_loss_slots = 0;
   int2* d_wwave_tiles[kWaveMaps] = {};
-  int32_t *d_wpbl_ptr[kWaveMaps] = {}, *d_wpbl_list[kWaveMaps] = {};
   int2 *d_went = nullptr, *d_went_t = nullptr;
   float *d_wval = nullptr, *d_wval_t = nullptr;
   int32_t *d_wtile_base = nullptr, *d_wtile_hptr = nullptr;
@@ -129,7 +142,9 @@ struct gco_ctx {
   // ---- parameters and activations (new order) ----
   bool has_params = false;
   bool probs_valid = false;
-  int64_t step = 0;
+  // Adam step counts: one per subgraph (embedding rows) and one per weight set
+  std::vector<int64_t> stepE, stepW;
+  float2* d_bc = nullptr;  // bias corrections of up to kLossSets epochs, [epoch][P + Pw]
   float *E = nullptr, *mE = nullptr, *vE = nullptr;
   void* Eb = nullptr;
   float *W[3] = {}, *mW[3] = {}, *vW[3] = {};
@@ -379,6 +394,76 @@ void bucket_blocks(const std::vector<int>& blk_k, int num_sets, std::vector<int>
   std::vector<int> cursor(ptr.begin(), ptr.end() - 1);
   for (size_t b = 0; b < blk_k.size(); ++b)
     if (blk_k[b] >= 0) list[cursor[num_sets == 1 ? 0 : blk_k[b]]++] = static_cast<int>(b);
+}
+
+// Builds the subgraph-naming arrays of `m` from the host copies: units of subgraphs with
+// active[k] == 0 are marked -1 and left out of the lists (active == nullptr: all take part).
+int upload_active_maps(gco_ctx* ctx, gco_ctx::ActiveMaps& m, const uint8_t* active) {
+  const gco_ctx::HostMaps& h = ctx->hm;
+  const int P = ctx->P, Pw = ctx->Pw;
+  auto filtered = [&](const std::vector<int>& src) {
+    std::vector<int> out(src);
+    if (active != nullptr)
+      for (int& k : out)
+        if (k >= 0 && !active[k]) k = -1;
+    return out;
+  };
+  const bool first = !m.allocated;
+  auto put = [&](int32_t*& dst, const std::vector<int>& v, size_t capacity) -> int {
+    if (first) GALLOC(dst, std::max<size_t>(1, capacity));
+    HIPCHK(h2d(ctx, dst, v.data(), v.size()));
+    return GCO_OK;
+  };
+  auto put_lists = [&](int32_t*& ptr, int32_t*& list, const std::vector<int>& ks, int sets) -> int {
+    std::vector<int> pv, lv;
+    bucket_blocks(ks, sets, pv, lv);
+    int rc = put(ptr, pv, pv.size());
+    if (rc != GCO_OK) return rc;
+    return put(list, lv, ks.size());
+  };
+#define PUT(expr)                 \
+  do {                            \
+    const int rc_ = (expr);       \
+    if (rc_ != GCO_OK) return rc_; \
+  } while (0)
+  const std::vector<int> blk_k = filtered(h.blk_k), nblk_k = filtered(h.nblk_k);
+  PUT(put(m.blk_k, blk_k, blk_k.size()));
+  PUT(put(m.nblk_k, nblk_k, nblk_k.size()));
+  PUT(put_lists(m.pbl_ptr, m.pbl_list, blk_k, Pw));
+  PUT(put_lists(m.nwbl_ptr, m.nwbl_list, nblk_k, Pw));
+  std::vector<int> narrow;
+  for (int v = 0; v < kWaveMaps; ++v) {
+    const std::vector<int> wk = filtered(h.wblk_k[v]);
+    PUT(put(m.wblk_k[v], wk, wk.size()));
+    PUT(put_lists(m.wpbl_ptr[v], m.wpbl_list[v], wk, Pw));
+    if (v == WM_NARROW) narrow = wk;
+  }
+  const std::vector<int> chunk_part = filtered(h.chunk_part), heavy_part = filtered(h.heavy_part);
+  PUT(put(m.chunk_part, chunk_part, chunk_part.size()));
+  std::vector<int> heavy_rows(h.heavy_rows);
+  for (size_t q = 0; q < heavy_rows.size(); ++q)
+    if (heavy_part[q] < 0) heavy_rows[q] = -1;
+  PUT(put(m.heavy_rows, heavy_rows, heavy_rows.size()));
+  // loss partial slots: one per pre-reduced row, then one per workgroup of the width-1 kernels
+  std::vector<int> slot_k(heavy_part);
+  slot_k.insert(slot_k.end(), narrow.begin(), narrow.end());
+  PUT(put_lists(m.loss_ptr, m.loss_list, slot_k, P));
+#undef PUT
+  m.allocated = true;
+  return GCO_OK;
+}
+
+// The graph view with the subgraph-naming arrays of `m`.
+GraphView view_with(const gco_ctx* ctx, const gco_ctx::ActiveMaps& m) {
+  GraphView g = ctx->gv;
+  g.blk_k = m.blk_k;
+  g.nblk_k = m.nblk_k;
+  for (int v = 0; v < kWaveMaps; ++v) g.wblk_k[v] = m.wblk_k[v];
+  g.chunk_part = m.chunk_part;
+  g.heavy_rows = m.heavy_rows;
+  g.loss_ptr = m.loss_ptr;
+  g.loss_list = m.loss_list;
+  return g;
 }
 
 void traffic_model(gco_ctx* ctx) {
@@ -654,57 +739,26 @@ int gco_upload_graph(gco_ctx* ctx, int64_t n64, const int64_t* rowptr, const int
   std::vector<int> blk_k, blk_s, blk_S, nblk_k, nblk_s, nblk_S;
   build_block_map(P, part_rows, lrowptr, kTileRows, kWideBlocks, kMaxTilesPerBlock, blk_k, blk_s, blk_S);
   // one decomposition per kernel kind (different cost per row)
-  std::vector<int> narrow_wblk_k;
   for (int v = 0; v < kWaveMaps; ++v) {
-    std::vector<int> wblk_k;
     std::vector<int2> wwave_tiles;
-    build_wave_map(P, part_rows, lrowptr, kWaveBlocksFor[v], kWaveRowCost[v], wblk_k, wwave_tiles);
-    ctx->num_wblocks[v] = static_cast<int>(wblk_k.size());
-    if (v == WM_NARROW) narrow_wblk_k = wblk_k;
+    build_wave_map(P, part_rows, lrowptr, kWaveBlocksFor[v], kWaveRowCost[v], ctx->hm.wblk_k[v], wwave_tiles);
+    ctx->num_wblocks[v] = static_cast<int>(ctx->hm.wblk_k[v].size());
     GALLOC(ctx->d_wwave_tiles[v], wwave_tiles.size());
     HIPCHK(h2d(ctx, ctx->d_wwave_tiles[v], wwave_tiles.data(), wwave_tiles.size()));
-    GALLOC(ctx->d_wblk_k[v], wblk_k.size());
-    HIPCHK(h2d(ctx, ctx->d_wblk_k[v], wblk_k.data(), wblk_k.size()));
-    std::vector<int> ptr, list;
-    bucket_blocks(wblk_k, ctx->Pw, ptr, list);
-    GALLOC(ctx->d_wpbl_ptr[v], ptr.size());
-    GALLOC(ctx->d_wpbl_list[v], std::max<size_t>(1, list.size()));
-    HIPCHK(h2d(ctx, ctx->d_wpbl_ptr[v], ptr.data(), ptr.size()));
-    HIPCHK(h2d(ctx, ctx->d_wpbl_list[v], list.data(), list.size()));
   }
   // width-1 kernels: one 256-row tile per workgroup
   build_block_map(P, part_rows, lrowptr, kNarrowRows, std::numeric_limits<int>::max() / 2, 1, nblk_k,
                   nblk_s, nblk_S);
-  GALLOC(ctx->d_blk_k, blk_k.size());
   GALLOC(ctx->d_blk_s, blk_s.size());
-  GALLOC(ctx->d_nblk_k, nblk_k.size());
   GALLOC(ctx->d_nblk_s, nblk_s.size());
   GALLOC(ctx->d_blk_S, blk_S.size());
   GALLOC(ctx->d_nblk_S, nblk_S.size());
   HIPCHK(h2d(ctx, ctx->d_blk_S, blk_S.data(), blk_S.size()));
   HIPCHK(h2d(ctx, ctx->d_nblk_S, nblk_S.data(), nblk_S.size()));
-  HIPCHK(h2d(ctx, ctx->d_blk_k, blk_k.data(), blk_k.size()));
   HIPCHK(h2d(ctx, ctx->d_blk_s, blk_s.data(), blk_s.size()));
-  HIPCHK(h2d(ctx, ctx->d_nblk_k, nblk_k.data(), nblk_k.size()));
   HIPCHK(h2d(ctx, ctx->d_nblk_s, nblk_s.data(), nblk_s.size()));
-  // workgroups whose weight-gradient partials belong to weight set kw
-  {
-    const int Pw = ctx->Pw;
-    std::vector<int> ptr, list;
-    bucket_blocks(blk_k, Pw, ptr, list);
-    GALLOC(ctx->d_pbl_ptr, ptr.size());
-    GALLOC(ctx->d_pbl_list, std::max<size_t>(1, list.size()));
-    HIPCHK(h2d(ctx, ctx->d_pbl_ptr, ptr.data(), ptr.size()));
-    HIPCHK(h2d(ctx, ctx->d_pbl_list, list.data(), list.size()));
-  }
-  {
-    std::vector<int> ptr, list;
-    bucket_blocks(nblk_k, ctx->Pw, ptr, list);
-    GALLOC(ctx->d_nwbl_ptr, ptr.size());
-    GALLOC(ctx->d_nwbl_list, std::max<size_t>(1, list.size()));
-    HIPCHK(h2d(ctx, ctx->d_nwbl_ptr, ptr.data(), ptr.size()));
-    HIPCHK(h2d(ctx, ctx->d_nwbl_list, list.data(), list.size()));
-  }
+  ctx->hm.blk_k = blk_k;
+  ctx->hm.nblk_k = nblk_k;
   // very long rows
   std::vector<int> heavy_of_row, heavy_rows, heavy_chunk_ptr(1, 0), chunk_begin, chunk_end, chunk_part;
   int num_heavy = 0;
@@ -727,24 +781,22 @@ int gco_upload_graph(gco_ctx* ctx, int64_t n64, const int64_t* rowptr, const int
     }
   }
   const int num_chunks = static_cast<int>(chunk_begin.size());
-  // loss partials of each subgraph: one slot per pre-reduced row, then one per workgroup of
-  // the width-1 decomposition
-  {
-    std::vector<int> slot_k;
+  {  // subgraph of every pre-reduced row
+    ctx->hm.heavy_part.clear();
     int kk = 0;
     for (int r : heavy_rows) {
       while (r >= part_rows[kk + 1]) ++kk;
-      slot_k.push_back(kk);
+      ctx->hm.heavy_part.push_back(kk);
     }
-    slot_k.insert(slot_k.end(), narrow_wblk_k.begin(), narrow_wblk_k.end());
-    std::vector<int> ptr, list;
-    bucket_blocks(slot_k, P, ptr, list);
-    // bucket_blocks sends every slot to group 0 when there is one group: right for P == 1 too
-    ctx->num_loss_slots = static_cast<int>(slot_k.size());
-    GALLOC(ctx->d_nbl_ptr, ptr.size());
-    GALLOC(ctx->d_nbl_list, std::max<size_t>(1, list.size()));
-    HIPCHK(h2d(ctx, ctx->d_nbl_ptr, ptr.data(), ptr.size()));
-    HIPCHK(h2d(ctx, ctx->d_nbl_list, list.data(), list.size()));
+    ctx->hm.heavy_rows = heavy_rows;
+    ctx->hm.chunk_part = chunk_part;
+    ctx->num_loss_slots = static_cast<int>(heavy_rows.size() + ctx->hm.wblk_k[WM_NARROW].size());
+  }
+  ctx->full.allocated = false;
+  ctx->sub.allocated = false;
+  {
+    const int rc = upload_active_maps(ctx, ctx->full, nullptr);
+    if (rc != GCO_OK) return rc;
   }
   {  // pre-reduced rows per wave tile
     std::vector<int> tbase(P + 1, 0);
@@ -764,18 +816,14 @@ int gco_upload_graph(gco_ctx* ctx, int64_t n64, const int64_t* rowptr, const int
   }
   if (num_heavy > 0) {
     GALLOC(ctx->d_heavy_of_row, static_cast<size_t>(n));
-    GALLOC(ctx->d_heavy_rows, heavy_rows.size());
-    HIPCHK(h2d(ctx, ctx->d_heavy_rows, heavy_rows.data(), heavy_rows.size()));
     GALLOC(ctx->d_heavy_chunk_ptr, heavy_chunk_ptr.size());
     GALLOC(ctx->d_chunk_begin, chunk_begin.size());
     GALLOC(ctx->d_chunk_end, chunk_end.size());
-    GALLOC(ctx->d_chunk_part, chunk_part.size());
     GALLOC(ctx->d_heavy_partial, static_cast<size_t>(num_chunks) * D);
     HIPCHK(h2d(ctx, ctx->d_heavy_of_row, heavy_of_row.data(), heavy_of_row.size()));
     HIPCHK(h2d(ctx, ctx->d_heavy_chunk_ptr, heavy_chunk_ptr.data(), heavy_chunk_ptr.size()));
     HIPCHK(h2d(ctx, ctx->d_chunk_begin, chunk_begin.data(), chunk_begin.size()));
     HIPCHK(h2d(ctx, ctx->d_chunk_end, chunk_end.data(), chunk_end.size()));
-    HIPCHK(h2d(ctx, ctx->d_chunk_part, chunk_part.data(), chunk_part.size()));
   }
 
   GraphView& g = ctx->gv;
@@ -787,13 +835,13 @@ int gco_upload_graph(gco_ctx* ctx, int64_t n64, const int64_t* rowptr, const int
   g.sa = ctx->d_sa;
   g.sb = ctx->d_sb;
   g.part_rows = ctx->d_part_rows;
-  g.blk_k = ctx->d_blk_k;
+  g.blk_k = ctx->full.blk_k;
   g.blk_s = ctx->d_blk_s;
   g.blk_S = ctx->d_blk_S;
   g.num_blocks = static_cast<int>(blk_k.size());
   for (int v = 0; v < kWaveMaps; ++v) {
     g.wwave_tiles[v] = ctx->d_wwave_tiles[v];
-    g.wblk_k[v] = ctx->d_wblk_k[v];
+    g.wblk_k[v] = ctx->full.wblk_k[v];
     g.num_wblocks[v] = ctx->num_wblocks[v];
   }
   g.wrowptr = ctx->d_wrowptr;
@@ -803,24 +851,24 @@ int gco_upload_graph(gco_ctx* ctx, int64_t n64, const int64_t* rowptr, const int
   g.went_t = ctx->d_went_t;
   g.wval = ctx->d_wval;
   g.wval_t = ctx->d_wval_t;
-  g.nblk_k = ctx->d_nblk_k;
+  g.nblk_k = ctx->full.nblk_k;
   g.nblk_s = ctx->d_nblk_s;
   g.nblk_S = ctx->d_nblk_S;
   g.num_nblocks = static_cast<int>(nblk_k.size());
   g.num_loss_slots = ctx->num_loss_slots;
-  g.loss_ptr = ctx->d_nbl_ptr;
-  g.loss_list = ctx->d_nbl_list;
+  g.loss_ptr = ctx->full.loss_ptr;
+  g.loss_list = ctx->full.loss_list;
   g.num_heavy = num_heavy;
   g.num_chunks = num_chunks;
   g.heavy_of_row = ctx->d_heavy_of_row;
-  g.heavy_rows = ctx->d_heavy_rows;
+  g.heavy_rows = ctx->full.heavy_rows;
   g.ent = ctx->d_ent;
   g.ent_t = ctx->d_ent_t;
   g.diag = ctx->d_diag;
   g.heavy_chunk_ptr = ctx->d_heavy_chunk_ptr;
   g.chunk_begin = ctx->d_chunk_begin;
   g.chunk_end = ctx->d_chunk_end;
-  g.chunk_part = ctx->d_chunk_part;
+  g.chunk_part = ctx->full.chunk_part;
 
   // parameters, optimizer state, activations
   const size_t nd = static_cast<size_t>(n) * D;
@@ -857,6 +905,7 @@ int gco_upload_graph(gco_ctx* ctx, int64_t n64, const int64_t* rowptr, const int
     ctx->GZ[l] = q;
   }
   GALLOC(ctx->gwout_partial, static_cast<size_t>(std::max(g.num_blocks, g.num_nblocks)) * D);
+  GALLOC(ctx->d_bc, static_cast<size_t>(kLossSets) * (P + ctx->Pw));
   GALLOC(ctx->t, static_cast<size_t>(n));
   GALLOC(ctx->z, static_cast<size_t>(n));
   GALLOC(ctx->p, static_cast<size_t>(n));
@@ -868,7 +917,8 @@ int gco_upload_graph(gco_ctx* ctx, int64_t n64, const int64_t* rowptr, const int
   HIPCHK(hipStreamSynchronize(st));
   traffic_model(ctx);
   ctx->has_graph = true;
-  ctx->step = 0;
+  ctx->stepE.assign(static_cast<size_t>(ctx->P), 0);
+  ctx->stepW.assign(static_cast<size_t>(ctx->Pw), 0);
   return GCO_OK;
 }
 
@@ -923,7 +973,8 @@ int gco_set_params(gco_ctx* ctx, const float* E, const float* const* W) {
   }
   if (ctx->Eb) launch_to_bf16(ctx->launch(), ctx->E, ctx->Eb, static_cast<int64_t>(nd));
   HIPCHK(hipStreamSynchronize(ctx->st));
-  ctx->step = 0;
+  ctx->stepE.assign(static_cast<size_t>(ctx->P), 0);
+  ctx->stepW.assign(static_cast<size_t>(ctx->Pw), 0);
   ctx->has_params = true;
   ctx->probs_valid = false;
   return GCO_OK;
@@ -955,7 +1006,11 @@ int gco_get_opt_state(gco_ctx* ctx, float* mE, float* vE, float* const* mW, floa
     if (mW && mW[l - 1]) HIPCHK(d2h(ctx, mW[l - 1], ctx->mW[l - 1], cnt));
     if (vW && vW[l - 1]) HIPCHK(d2h(ctx, vW[l - 1], ctx->vW[l - 1], cnt));
   }
-  if (step) *step = ctx->step;
+  if (step) {  // the largest count; gco_get_steps gives all of them
+    *step = 0;
+    for (int64_t t : ctx->stepE) *step = std::max(*step, t);
+    for (int64_t t : ctx->stepW) *step = std::max(*step, t);
+  }
   return GCO_OK;
 }
 
@@ -974,7 +1029,8 @@ int gco_set_opt_state(gco_ctx* ctx, const float* mE, const float* vE, const floa
     HIPCHK(h2d(ctx, ctx->vW[l - 1], vW[l - 1], cnt));
   }
   HIPCHK(hipStreamSynchronize(ctx->st));
-  ctx->step = step;
+  ctx->stepE.assign(static_cast<size_t>(ctx->P), step);
+  ctx->stepW.assign(static_cast<size_t>(ctx->Pw), step);
   return GCO_OK;
 }
 
@@ -995,56 +1051,64 @@ int gco_set_linear_penalty(gco_ctx* ctx, const float* extra) {
 
 // ---- one epoch ------------------------------------------------------------------
 
-static void run_forward(gco_ctx* ctx) {
+static void run_forward(gco_ctx* ctx, const GraphView& gv) {
   const Launch ln = ctx->launch();
   const gco_config& c = ctx->cfg;
   const int D = c.dim, L = c.num_layers;
   const int ws = ctx->Pw == 1 ? 0 : D * D, wos = ctx->Pw == 1 ? 0 : D;
   if (L == 1) {
-    launch_fwd_gemv(ln, c.storage, D, ctx->gv, ctx->H[0], ctx->W[0], wos, ctx->t);
+    launch_fwd_gemv(ln, c.storage, D, gv, ctx->H[0], ctx->W[0], wos, ctx->t);
   } else {
     for (int l = 1; l <= L - 1; ++l) {
       const bool last = l == L - 1;
-      launch_fwd_hidden(ln, c.storage, D, ctx->gv, ctx->H[l - 1], ctx->W[l - 1], ws, ctx->H[l],
+      launch_fwd_hidden(ln, c.storage, D, gv, ctx->H[l - 1], ctx->W[l - 1], ws, ctx->H[l],
                         last ? ctx->W[L - 1] : nullptr, wos, ctx->t, ctx->d_heavy_partial);
     }
   }
-  launch_fwd_readout(ln, ctx->gv, ctx->t, ctx->z, ctx->p);
+  launch_fwd_readout(ln, gv, ctx->t, ctx->z, ctx->p);
   ctx->probs_valid = true;
 }
 
+static void run_forward(gco_ctx* ctx) { run_forward(ctx, ctx->gv); }
+
 // Loss kernel; its workgroup partials go to set `slot` (< kLossSets) of loss_partial.
-static void run_loss_partials(gco_ctx* ctx, int slot) {
+static void run_loss_partials(gco_ctx* ctx, const GraphView& gv, int slot) {
   const Launch ln = ctx->launch();
   const float q = ctx->cfg.problem == GCO_PROBLEM_MAXCUT ? 2.f : ctx->cfg.alpha;
-  launch_loss(ln, ctx->gv, ctx->p, ctx->d_c, q, ctx->g_z,
-              ctx->loss_partial + static_cast<size_t>(slot) * ctx->gv.num_loss_slots);
+  launch_loss(ln, gv, ctx->p, ctx->d_c, q, ctx->g_z,
+              ctx->loss_partial + static_cast<size_t>(slot) * gv.num_loss_slots);
 }
 
 // Loss at the current parameters: total to loss_out[0], per-subgraph values to ctx->loss_part.
 static void run_loss(gco_ctx* ctx, double* loss_out) {
-  run_loss_partials(ctx, 0);
+  run_loss_partials(ctx, ctx->gv, 0);
   launch_loss_reduce(ctx->launch(), ctx->gv, ctx->loss_partial, 1, 0, ctx->loss_part, loss_out);
 }
 
-// update = true: Adam step t = ++step.  update = false: gradients are written to gE / gW.
-static void run_backward(gco_ctx* ctx, bool update, float* gE, float* const* gW) {
+// Adam constants for one more step when every subgraph and weight set has seen `step` steps.
+static AdamStep adam_constants(const gco_config& c, int64_t step) {
+  AdamStep ad{};
+  const double tt = static_cast<double>(step);
+  ad.lr = c.lr;
+  ad.b1 = c.adam_b1;
+  ad.b2 = c.adam_b2;
+  ad.eps = c.adam_eps;
+  ad.inv_bc1 = static_cast<float>(1.0 / (1.0 - std::pow(static_cast<double>(c.adam_b1), tt)));
+  ad.inv_sqrt_bc2 = static_cast<float>(1.0 / std::sqrt(1.0 - std::pow(static_cast<double>(c.adam_b2), tt)));
+  return ad;
+}
+
+// update = true: an Adam step with the constants adE (embedding rows) and adW (weights);
+// update = false: gradients are written to gE / gW.  gv and maps name the subgraphs that
+// take part.
+static void run_backward(gco_ctx* ctx, const GraphView& gv, const gco_ctx::ActiveMaps& maps, bool update,
+                         const AdamStep& adE, const AdamStep& adW, float* gE, float* const* gW) {
   const Launch ln = ctx->launch();
   const gco_config& c = ctx->cfg;
   const int D = c.dim, L = c.num_layers;
   const int ws = ctx->Pw == 1 ? 0 : D * D, wos = ctx->Pw == 1 ? 0 : D;
-  AdamStep ad{};
-  if (update) {
-    ctx->step += 1;
-    const double tt = static_cast<double>(ctx->step);
-    ad.lr = c.lr;
-    ad.b1 = c.adam_b1;
-    ad.b2 = c.adam_b2;
-    ad.eps = c.adam_eps;
-    ad.inv_bc1 = static_cast<float>(1.0 / (1.0 - std::pow(static_cast<double>(c.adam_b1), tt)));
-    ad.inv_sqrt_bc2 = static_cast<float>(1.0 / std::sqrt(1.0 - std::pow(static_cast<double>(c.adam_b2), tt)));
-  }
-  launch_bwd_readout(ln, ctx->gv, ctx->g_z, ctx->g_t);
+  const AdamStep& ad = adE;
+  launch_bwd_readout(ln, gv, ctx->g_z, ctx->g_t);
   BwdArgs a;
   a.g_t = ctx->g_t;
   a.w_out = ctx->W[L - 1];
@@ -1061,7 +1125,7 @@ static void run_backward(gco_ctx* ctx, bool update, float* gE, float* const* gW)
   a.mode = update ? (c.train_embed ? EMBED_ADAM : EMBED_SKIP) : (gE ? EMBED_WRITE_GRAD : EMBED_SKIP);
   if (L == 1) {
     a.Hprev = ctx->H[0];
-    launch_bwd_single(ln, c.storage, D, ctx->gv, a);
+    launch_bwd_single(ln, c.storage, D, gv, a);
   } else {
     for (int l = L - 1; l >= 1; --l) {
       const bool last = l == L - 1, to_embed = l == 1;
@@ -1072,7 +1136,7 @@ static void run_backward(gco_ctx* ctx, bool update, float* gE, float* const* gW)
       a.w_stride = ws;
       a.gW_partial = ctx->gW_partial[l - 1];
       a.GZ_out = to_embed ? nullptr : ctx->GZ[l - 1];
-      launch_bwd_hidden(ln, c.storage, D, last, to_embed, ctx->gv, a);
+      launch_bwd_hidden(ln, c.storage, D, last, to_embed, gv, a);
     }
   }
   WeightTensor wt[3];
@@ -1087,11 +1151,71 @@ static void run_backward(gco_ctx* ctx, bool update, float* gE, float* const* gW)
     // its own workgroups (hidden layers) and the narrow ones (scalar layer)
     const bool wave = ctx->wave_path() && L >= 2;
     const int wm = l == 1 ? WM_EMBED : WM_BWD;  // the kernel kind that wrote gW_l
-    wt[l - 1].blk_ptr = !wave ? ctx->d_pbl_ptr : (l < L ? ctx->d_wpbl_ptr[wm] : ctx->d_nwbl_ptr);
-    wt[l - 1].blk_list = !wave ? ctx->d_pbl_list : (l < L ? ctx->d_wpbl_list[wm] : ctx->d_nwbl_list);
+    wt[l - 1].blk_ptr = !wave ? maps.pbl_ptr : (l < L ? maps.wpbl_ptr[wm] : maps.nwbl_ptr);
+    wt[l - 1].blk_list = !wave ? maps.pbl_list : (l < L ? maps.wpbl_list[wm] : maps.nwbl_list);
   }
-  launch_adam_w(ln, ctx->Pw, wt, L, ad, update);
+  launch_adam_w(ln, ctx->Pw, wt, L, adW, update);
   if (update) ctx->probs_valid = true;  // p is that of the parameters before the step
+}
+
+// `epochs` training epochs of the subgraphs with active[k] != 0 (nullptr: all of them); the
+// others keep their parameters, optimizer state, step counts and probabilities.
+static int train_impl(gco_ctx* ctx, int32_t epochs, const uint8_t* active, double* loss_per_epoch) {
+  const int P = ctx->P, Pw = ctx->Pw;
+  const GraphView& gv = active ? ctx->gv_sub : ctx->gv;
+  const gco_ctx::ActiveMaps& maps = active ? ctx->sub : ctx->full;
+  if (ctx->loss_hist_cap < epochs) {
+    // the old array (if any) stays owned by the graph allocation list
+    ctx->loss_hist = nullptr;
+    GALLOC(ctx->loss_hist, static_cast<size_t>(epochs));
+    ctx->loss_hist_cap = epochs;
+  }
+  // which weight sets take part: a subgraph's own, or the shared one if any subgraph does
+  std::vector<uint8_t> actE(P, 1), actW(Pw, 0);
+  if (active) actE.assign(active, active + P);
+  for (int k = 0; k < P; ++k)
+    if (actE[k]) actW[Pw == 1 ? 0 : k] = 1;
+  // one set of Adam constants serves all while every step count is the same
+  bool uniform = active == nullptr;
+  for (int64_t t : ctx->stepE) uniform = uniform && t == ctx->stepE[0];
+  for (int64_t t : ctx->stepW) uniform = uniform && t == ctx->stepE[0];
+  const gco_config& c = ctx->cfg;
+  std::vector<float2> bc;
+  // the loss partials of up to kLossSets epochs are reduced by one launch; so are the
+  // per-subgraph bias corrections of those epochs uploaded at once
+  for (int e0 = 0; e0 < epochs; e0 += kLossSets) {
+    const int ne = std::min<int>(kLossSets, epochs - e0);
+    if (!uniform) {
+      bc.assign(static_cast<size_t>(ne) * (P + Pw), make_float2(1.f, 1.f));
+      for (int e = 0; e < ne; ++e)
+        for (int q = 0; q < P + Pw; ++q) {
+          const bool on = q < P ? actE[q] : actW[q - P];
+          if (!on) continue;
+          const int64_t t0 = q < P ? ctx->stepE[q] : ctx->stepW[q - P];
+          const AdamStep ad = adam_constants(c, t0 + e0 + e + 1);
+          bc[static_cast<size_t>(e) * (P + Pw) + q] = make_float2(ad.inv_bc1, ad.inv_sqrt_bc2);
+        }
+      HIPCHK(h2d(ctx, ctx->d_bc, bc.data(), bc.size()));
+    }
+    for (int e = 0; e < ne; ++e) {
+      AdamStep adE = adam_constants(c, ctx->stepE.empty() ? 1 : ctx->stepE[0] + e0 + e + 1), adW = adE;
+      if (!uniform) {
+        adE.per_part = ctx->d_bc + static_cast<size_t>(e) * (P + Pw);
+        adW.per_part = adE.per_part + P;
+      }
+      run_forward(ctx, gv);
+      run_loss_partials(ctx, gv, e);
+      run_backward(ctx, gv, maps, true, adE, adW, nullptr, nullptr);
+    }
+    launch_loss_reduce(ctx->launch(), gv, ctx->loss_partial, ne, gv.num_loss_slots, nullptr, ctx->loss_hist + e0);
+  }
+  for (int k = 0; k < P; ++k)
+    if (actE[k]) ctx->stepE[k] += epochs;
+  for (int k = 0; k < Pw; ++k)
+    if (actW[k]) ctx->stepW[k] += epochs;
+  HIPCHK(hipGetLastError());
+  if (loss_per_epoch) HIPCHK(d2h(ctx, loss_per_epoch, ctx->loss_hist, static_cast<size_t>(epochs)));
+  return GCO_OK;
 }
 
 int gco_train(gco_ctx* ctx, int32_t epochs, double* loss_per_epoch) {
@@ -1099,26 +1223,49 @@ int gco_train(gco_ctx* ctx, int32_t epochs, double* loss_per_epoch) {
   NEED(ctx->has_params, GCO_ESTATE, "set_params must precede train");
   NEED(epochs >= 0, GCO_EINVAL, "negative epoch count");
   if (epochs == 0) return GCO_OK;
-  if (ctx->loss_hist_cap < epochs) {
-    // the old array (if any) stays owned by the graph allocation list
-    ctx->loss_hist = nullptr;
-    GALLOC(ctx->loss_hist, static_cast<size_t>(epochs));
-    ctx->loss_hist_cap = epochs;
+  return train_impl(ctx, epochs, nullptr, loss_per_epoch);
+}
+
+int gco_train_subset(gco_ctx* ctx, int32_t epochs, const int32_t* parts, int32_t num_listed,
+                     double* loss_per_epoch) {
+  if (!ctx) return GCO_EINVAL;
+  NEED(ctx->has_params, GCO_ESTATE, "set_params must precede train");
+  NEED(epochs >= 0, GCO_EINVAL, "negative epoch count");
+  NEED(num_listed >= 0 && (parts != nullptr || num_listed == 0), GCO_EINVAL, "bad subgraph list");
+  std::vector<uint8_t> active(static_cast<size_t>(ctx->P), 0);
+  for (int q = 0; q < num_listed; ++q) {
+    NEED(parts[q] >= 0 && parts[q] < ctx->P, GCO_ERANGE, "subgraph id %d out of range", parts[q]);
+    active[parts[q]] = 1;
   }
-  // the loss partials of up to kLossSets epochs are reduced by one launch
-  int pending = 0;
-  for (int e = 0; e < epochs; ++e) {
-    run_forward(ctx);
-    run_loss_partials(ctx, pending++);
-    run_backward(ctx, true, nullptr, nullptr);
-    if (pending == kLossSets || e + 1 == epochs) {
-      launch_loss_reduce(ctx->launch(), ctx->gv, ctx->loss_partial, pending, ctx->gv.num_loss_slots, nullptr,
-                         ctx->loss_hist + (e + 1 - pending));
-      pending = 0;
-    }
+  if (epochs == 0 || num_listed == 0) {
+    if (loss_per_epoch)
+      for (int e = 0; e < epochs; ++e) loss_per_epoch[e] = 0.0;
+    return GCO_OK;
   }
-  HIPCHK(hipGetLastError());
-  if (loss_per_epoch) HIPCHK(d2h(ctx, loss_per_epoch, ctx->loss_hist, static_cast<size_t>(epochs)));
+  {
+    const int rc = upload_active_maps(ctx, ctx->sub, active.data());
+    if (rc != GCO_OK) return rc;
+  }
+  ctx->gv_sub = view_with(ctx, ctx->sub);
+  return train_impl(ctx, epochs, active.data(), loss_per_epoch);
+}
+
+int gco_get_steps(gco_ctx* ctx, int64_t* steps_embed, int64_t* steps_weights) {
+  if (!ctx) return GCO_EINVAL;
+  NEED(ctx->has_params, GCO_ESTATE, "set_params must precede get_steps");
+  if (steps_embed) std::copy(ctx->stepE.begin(), ctx->stepE.end(), steps_embed);
+  if (steps_weights) std::copy(ctx->stepW.begin(), ctx->stepW.end(), steps_weights);
+  return GCO_OK;
+}
+
+int gco_set_steps(gco_ctx* ctx, const int64_t* steps_embed, const int64_t* steps_weights) {
+  if (!ctx) return GCO_EINVAL;
+  NEED(ctx->has_params, GCO_ESTATE, "set_params must precede set_steps");
+  NEED(steps_embed && steps_weights, GCO_EINVAL, "NULL step array");
+  for (int k = 0; k < ctx->P; ++k) NEED(steps_embed[k] >= 0, GCO_EINVAL, "negative step count");
+  for (int k = 0; k < ctx->Pw; ++k) NEED(steps_weights[k] >= 0, GCO_EINVAL, "negative step count");
+  ctx->stepE.assign(steps_embed, steps_embed + ctx->P);
+  ctx->stepW.assign(steps_weights, steps_weights + ctx->Pw);
   return GCO_OK;
 }
 
@@ -1168,7 +1315,7 @@ int gco_get_grads(gco_ctx* ctx, float* gE, float* const* gW) {
   }
   run_forward(ctx);
   run_loss(ctx, ctx->loss_one);
-  run_backward(ctx, false, d_gE, d_gW);
+  run_backward(ctx, ctx->gv, ctx->full, false, AdamStep{}, AdamStep{}, d_gE, d_gW);
   HIPCHK(hipGetLastError());
   if (gE) {
     int rc = download_node_matrix(ctx, gE, d_gE);

@@ -103,11 +103,11 @@ struct GraphView {
   int num_heavy = 0;
   int num_chunks = 0;
   const int* heavy_of_row = nullptr;  // [n]
-  const int* heavy_rows = nullptr;    // [num_heavy] ascending row ids
+  const int* heavy_rows = nullptr;    // [num_heavy] ascending row ids (< 0: a row of a subgraph that sits out)
   const int* heavy_chunk_ptr = nullptr;
   const int* chunk_begin = nullptr;
   const int* chunk_end = nullptr;
-  const int* chunk_part = nullptr;    // subgraph of the row that owns the chunk
+  const int* chunk_part = nullptr;    // subgraph of the row that owns the chunk (< 0: skip the chunk)
 };
 
 // The view of the transposed matrix: scale vectors and entry arrays exchanged.
@@ -129,6 +129,22 @@ struct AdamStep {
   float lr, b1, b2, eps;
   float inv_bc1;       // 1 / (1 - b1^t)
   float inv_sqrt_bc2;  // 1 / sqrt(1 - b2^t)
+  // When the subgraphs (weight sets) have seen different numbers of steps: the two bias
+  // corrections per subgraph, {inv_bc1, inv_sqrt_bc2}[k]; nullptr = the values above.
+  const float2* per_part = nullptr;
+  __host__ __device__ AdamStep for_part(int k) const {
+    AdamStep r = *this;
+#if defined(__HIP_DEVICE_COMPILE__)
+    if (per_part != nullptr) {
+      const float2 bc = per_part[k];
+      r.inv_bc1 = bc.x;
+      r.inv_sqrt_bc2 = bc.y;
+    }
+#else
+    (void)k;
+#endif
+    return r;
+  }
 };
 
 // Where to enqueue, and an optional per-kernel timer: begin/end bracket exactly
@@ -245,7 +261,7 @@ struct WeightTensor {
   int elems = 0;                   // per subgraph
 };
 void launch_adam_w(const Launch& ln, int Pw, const WeightTensor* tensors, int count, const AdamStep& adam,
-                   bool update);
+                   bool update);  // adam.per_part, if set, is indexed by weight set; sets without partials are left alone
 
 // fp32 -> bf16 copy (round to nearest even).
 void launch_to_bf16(const Launch& ln, const float* src, void* dst, int64_t count);

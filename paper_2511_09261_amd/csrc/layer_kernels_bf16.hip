@@ -316,6 +316,7 @@ __global__ __launch_bounds__(kBlock) void heavy_wide_b_kernel(GraphView g, Src s
   const int ch = blockIdx.x;
   const int tid = threadIdx.x;
   const int grp = tid / M::LPR, c0 = (tid % M::LPR) * 8;
+  if (g.chunk_part[ch] < 0) return;  // the row's subgraph sits out
   src.set_part(g.chunk_part[ch], c0);
   float a8[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
   const int eb = g.chunk_end[ch];
@@ -845,6 +846,7 @@ __global__ __launch_bounds__(kBlock) void bwd_hidden_bf16_kernel(GraphView g, Bw
 
   const int k = g.blk_k[blockIdx.x];
   if (k < 0) return;
+  const AdamStep ad = a.adam.for_part(k);
   const int s = g.blk_s[blockIdx.x], S = g.blk_S[blockIdx.x];
   const int tid = threadIdx.x, lane = tid % 64, wave = tid / 64;
   const int tn = wave % M::NT, tm0 = wave / M::NT;
@@ -977,10 +979,10 @@ __global__ __launch_bounds__(kBlock) void bwd_hidden_bf16_kernel(GraphView g, Bw
             float mo[4], vo[4], eo[4];
 #pragma unroll
             for (int x = 0; x < 4; ++x) {
-              mo[x] = a.adam.b1 * mv[x] + (1.f - a.adam.b1) * gv[x];
-              vo[x] = a.adam.b2 * vv[x] + (1.f - a.adam.b2) * gv[x] * gv[x];
-              const float upd = (mo[x] * a.adam.inv_bc1) / (sqrtf(vo[x]) * a.adam.inv_sqrt_bc2 + a.adam.eps);
-              eo[x] = ev[x] - a.adam.lr * upd;
+              mo[x] = ad.b1 * mv[x] + (1.f - ad.b1) * gv[x];
+              vo[x] = ad.b2 * vv[x] + (1.f - ad.b2) * gv[x] * gv[x];
+              const float upd = (mo[x] * ad.inv_bc1) / (sqrtf(vo[x]) * ad.inv_sqrt_bc2 + ad.eps);
+              eo[x] = ev[x] - ad.lr * upd;
             }
             *reinterpret_cast<float4*>(a.mE + off) = make_float4(mo[0], mo[1], mo[2], mo[3]);
             *reinterpret_cast<float4*>(a.vE + off) = make_float4(vo[0], vo[1], vo[2], vo[3]);

@@ -132,6 +132,7 @@ __global__ __launch_bounds__(kBlock) void narrow_stream_kernel(GraphView g, Op o
     // one row with very many neighbours: CSR entries {column, A_hat value};
     // 32 entries per thread and pass: first all entries, then all gathered values
     const int i = g.heavy_rows[blockIdx.x];
+    if (i < 0) return;  // the row's subgraph sits out
     const int e0 = g.rowptr[i], e1 = g.rowptr[i + 1];
     constexpr int kU = 32;
     float acc = 0.f;

@@ -179,6 +179,7 @@ __global__ __launch_bounds__(kBlock) void bwd_hidden_kernel(GraphView g, BwdArgs
 
   const int k = g.blk_k[blockIdx.x];
   if (k < 0) return;
+  const AdamStep ad = a.adam.for_part(k);
   const int s = g.blk_s[blockIdx.x];
   const int tid = threadIdx.x;
   const T* Hprev = static_cast<const T*>(a.Hprev);
@@ -244,10 +245,10 @@ __global__ __launch_bounds__(kBlock) void bwd_hidden_kernel(GraphView g, BwdArgs
             a.gE[idx] = gh[i];
           } else {
             const float gq = gh[i];
-            const float m = a.adam.b1 * a.mE[idx] + (1.f - a.adam.b1) * gq;
-            const float v = a.adam.b2 * a.vE[idx] + (1.f - a.adam.b2) * gq * gq;
-            const float upd = (m * a.adam.inv_bc1) / (sqrtf(v) * a.adam.inv_sqrt_bc2 + a.adam.eps);
-            const float e = a.E[idx] - a.adam.lr * upd;
+            const float m = ad.b1 * a.mE[idx] + (1.f - ad.b1) * gq;
+            const float v = ad.b2 * a.vE[idx] + (1.f - ad.b2) * gq * gq;
+            const float upd = (m * ad.inv_bc1) / (sqrtf(v) * ad.inv_sqrt_bc2 + ad.eps);
+            const float e = a.E[idx] - ad.lr * upd;
             a.mE[idx] = m;
             a.vE[idx] = v;
             a.E[idx] = e;
@@ -274,6 +275,7 @@ __global__ __launch_bounds__(kBlock) void bwd_single_kernel(GraphView g, BwdArgs
   constexpr int RG = kBlock / D;
   const int k = g.blk_k[blockIdx.x];
   if (k < 0) return;
+  const AdamStep ad = a.adam.for_part(k);
   const int s = g.blk_s[blockIdx.x];
   const int tid = threadIdx.x;
   const int c = tid % D, rg = tid / D;
@@ -292,10 +294,10 @@ __global__ __launch_bounds__(kBlock) void bwd_single_kernel(GraphView g, BwdArgs
       if (a.mode == EMBED_WRITE_GRAD) {
         a.gE[idx] = gq;
       } else if (a.mode == EMBED_ADAM) {
-        const float m = a.adam.b1 * a.mE[idx] + (1.f - a.adam.b1) * gq;
-        const float v = a.adam.b2 * a.vE[idx] + (1.f - a.adam.b2) * gq * gq;
-        const float upd = (m * a.adam.inv_bc1) / (sqrtf(v) * a.adam.inv_sqrt_bc2 + a.adam.eps);
-        const float e = a.E[idx] - a.adam.lr * upd;
+        const float m = ad.b1 * a.mE[idx] + (1.f - ad.b1) * gq;
+        const float v = ad.b2 * a.vE[idx] + (1.f - ad.b2) * gq * gq;
+        const float upd = (m * ad.inv_bc1) / (sqrtf(v) * ad.inv_sqrt_bc2 + ad.eps);
+        const float e = a.E[idx] - ad.lr * upd;
         a.mE[idx] = m;
         a.vE[idx] = v;
         a.E[idx] = e;
@@ -375,6 +377,11 @@ __global__ __launch_bounds__(kBlock) void adam_w_kernel(int Pw, WeightTensors wt
   float gsum = 0.f;
   int q = wt.blk_ptr[k];
   const int q1 = wt.blk_ptr[k + 1];
+  if (q == q1) {  // no workgroup produced a gradient for this weight set: it sits out
+    if (wt.grad_out != nullptr) wt.grad_out[gid] = 0.f;
+    return;
+  }
+  const AdamStep adk = ad.for_part(k);
   for (; q + 16 <= q1; q += 16) {
     float v[16];
 #pragma unroll
@@ -388,11 +395,11 @@ __global__ __launch_bounds__(kBlock) void adam_w_kernel(int Pw, WeightTensors wt
   for (; q < q1; ++q) gsum += base[static_cast<size_t>(part_blk_list[q]) * wt.elems];
   if (wt.grad_out != nullptr) wt.grad_out[gid] = gsum;
   if (update) {
-    const float m = ad.b1 * wt.m[gid] + (1.f - ad.b1) * gsum;
-    const float v = ad.b2 * wt.v[gid] + (1.f - ad.b2) * gsum * gsum;
+    const float m = adk.b1 * wt.m[gid] + (1.f - adk.b1) * gsum;
+    const float v = adk.b2 * wt.v[gid] + (1.f - adk.b2) * gsum * gsum;
     wt.m[gid] = m;
     wt.v[gid] = v;
-    wt.W[gid] -= ad.lr * (m * ad.inv_bc1) / (sqrtf(v) * ad.inv_sqrt_bc2 + ad.eps);
+    wt.W[gid] -= adk.lr * (m * adk.inv_bc1) / (sqrtf(v) * adk.inv_sqrt_bc2 + adk.eps);
   }
 }
 

@@ -556,6 +556,7 @@ __global__ __launch_bounds__(kBlock, 2) void bwd_wave_kernel(GraphView g, BwdArg
   constexpr int WM = TO_EMBED ? WM_EMBED : WM_BWD;
   const int k = g.wblk_k[WM][blockIdx.x];
   if (k < 0) return;
+  const AdamStep ad = a.adam.for_part(k);
   const int tid = threadIdx.x, lane = tid % 64;
   const int wave = __builtin_amdgcn_readfirstlane(tid / 64);
   const int n = lane % 32, h = lane / 32;
@@ -714,13 +715,13 @@ __global__ __launch_bounds__(kBlock, 2) void bwd_wave_kernel(GraphView g, BwdArg
                 float mo[4], vo[4], eo[4];
 #pragma unroll
                 for (int x = 0; x < 4; ++x) {
-                  mo[x] = a.adam.b1 * mv[x] + (1.f - a.adam.b1) * gv[x];
-                  vo[x] = a.adam.b2 * vv[x] + (1.f - a.adam.b2) * gv[x] * gv[x];
+                  mo[x] = ad.b1 * mv[x] + (1.f - ad.b1) * gv[x];
+                  vo[x] = ad.b2 * vv[x] + (1.f - ad.b2) * gv[x] * gv[x];
                   // v_sqrt_f32 and v_rcp_f32: 1 ulp each
-                  const float upd = (mo[x] * a.adam.inv_bc1) *
-                                    __builtin_amdgcn_rcpf(__builtin_amdgcn_sqrtf(vo[x]) * a.adam.inv_sqrt_bc2 +
-                                                          a.adam.eps);
-                  eo[x] = ev[x] - a.adam.lr * upd;
+                  const float upd = (mo[x] * ad.inv_bc1) *
+                                    __builtin_amdgcn_rcpf(__builtin_amdgcn_sqrtf(vo[x]) * ad.inv_sqrt_bc2 +
+                                                          ad.eps);
+                  eo[x] = ev[x] - ad.lr * upd;
                 }
                 if (r < nrows) {
                   store_streamed(pM + off, mo[0], mo[1], mo[2], mo[3]);

@@ -182,6 +182,78 @@ def test_frozen_embeddings_and_shared_weights_train(gco):
     ctx.destroy()
 
 
+# ------------------------------------------------------------------ subset fine-tune
+
+@pytest.mark.parametrize("kind,L,D,storage,share", [
+    ("bfs12", 2, 16, "fp32", False),     # block kernels
+    ("bfs12", 3, 64, "bf16", False),     # wave-per-tile kernels
+    ("hubs_parts", 3, 64, "bf16", False),  # with pre-reduced rows in a subgraph that sits out
+    ("random", 2, 16, "fp32", True),     # one weight set for all subgraphs
+    ("random", 1, 16, "fp32", False),    # no hidden layer
+])
+def test_subset_fine_tune(gco, kind, L, D, storage, share):
+    """Sec. 3.3 / Alg. 1 stage 3: after some epochs on everything, a penalty is put on a
+    few nodes and only the listed subgraphs are trained on.  Listed subgraphs follow the
+    checker (loss trajectory; each subgraph counts its own Adam steps), the others keep
+    parameters, optimizer state and probabilities bit for bit."""
+    g, part, P = make_case(kind, seed=17)
+    ctx, spec, lg, E, Ws = run_pair(gco, g, part, P, L=L, D=D, storage=storage, share=share)
+    tol = 1e-4 if storage == "fp32" else 2e-2
+    st = gcn.init_state(E, Ws)
+    got0 = ctx.train(3)
+    want0, _ = gcn.train(lg, st, spec, 3)
+    assert np.abs(got0 - want0).max() <= tol * np.abs(want0).max()
+    rs = np.random.RandomState(3)
+    lam = ((rs.random_sample(g.n) < 0.2) * 0.9).astype(np.float32)
+    ctx.set_linear_penalty(lam)
+    listed = [0, P - 1] if P > 2 else [P - 1]
+    active = np.zeros(P, dtype=bool)
+    active[listed] = True
+    E1, W1 = ctx.get_params()
+    s1 = ctx.get_opt_state()
+    ctx.forward()
+    p1 = ctx.get_probs()
+    got = ctx.train_subset(4, listed)
+    want, _ = gcn.train(lg, st, spec, 4, lam.astype(np.float64), active=active)
+    assert np.abs(got - want).max() <= tol * np.abs(want).max()
+    se, sw = ctx.get_steps()
+    np.testing.assert_array_equal(se, st.tE)
+    np.testing.assert_array_equal(sw, st.tW)
+    E2, W2 = ctx.get_params()
+    s2 = ctx.get_opt_state()
+    part_arr = np.zeros(g.n, dtype=np.int64) if part is None else np.asarray(part)
+    off = ~active[part_arr]
+    np.testing.assert_array_equal(E2[off], E1[off])
+    np.testing.assert_array_equal(s2[0][off], s1[0][off])
+    np.testing.assert_array_equal(s2[1][off], s1[1][off])
+    assert np.abs(E2[~off] - E1[~off]).max() > 0
+    if not share:
+        for a, b in zip(W2, W1):
+            np.testing.assert_array_equal(a[~active], b[~active])
+    assert rel(E2, st.E) <= (5e-3 if storage == "fp32" else 5e-2)
+    # probabilities of the subgraphs that sat out are those of before
+    p2 = ctx.get_probs()
+    np.testing.assert_array_equal(p2[off], p1[off])
+    # back to everything: per-subgraph step counts keep the trajectory on the checker's
+    got3 = ctx.train(2)
+    want3, _ = gcn.train(lg, st, spec, 2, lam.astype(np.float64))
+    assert np.abs(got3 - want3).max() <= tol * np.abs(want3).max()
+    np.testing.assert_array_equal(ctx.get_steps()[0], st.tE)
+    ctx.destroy()
+
+
+def test_subset_errors_and_empty_list(gco):
+    g, part, P = make_case("random", seed=2)
+    ctx, spec, lg, E, Ws = run_pair(gco, g, part, P)
+    with pytest.raises(gco.GcoError):
+        ctx.train_subset(1, [P])
+    with pytest.raises(gco.GcoError):
+        ctx.train_subset(1, [-1])
+    np.testing.assert_array_equal(ctx.train_subset(2, []), np.zeros(2))
+    np.testing.assert_array_equal(ctx.get_params()[0], E)
+    ctx.destroy()
+
+
 def test_parameter_round_trip_and_checkpoint_resume(gco):
     g, part, P = make_case("bfs12", seed=3)
     ctx, spec, lg, E, Ws = run_pair(gco, g, part, P, L=3, D=32)

@@ -414,6 +414,82 @@ def test_batched_training_equals_training_each_subgraph_alone(problem):
     np.testing.assert_array_equal(l2, losses)
 
 
+def _subgraph_alone(n, edges, part, k, E, Ws, shared=False):
+    idx = np.flatnonzero(part == k)
+    pos = -np.ones(n, dtype=int)
+    pos[idx] = np.arange(len(idx))
+    sub_edges = [(pos[u], pos[v]) for u, v in edges if part[u] == k and part[v] == k]
+    rp, cl = hp.csr_from_edges(len(idx), sub_edges)
+    lgk = gcn.local_graph(len(idx), rp, cl, None, 1, "sym")
+    stk = gcn.init_state(E[idx], [W[0:1] if shared else W[k:k + 1] for W in Ws])
+    return idx, lgk, stk
+
+
+def test_subset_fine_tune_touches_only_the_listed_subgraphs_and_counts_their_steps():
+    """Sec. 3.3 / Alg. 1 stage 3: the fine-tune retrains only the subgraphs involved,
+    with the penalty added to their loss.  Pins: 2 epochs of subgraphs {0, 2} with a
+    penalty followed by 3 epochs of all subgraphs equals, for each subgraph, the run of
+    that subgraph alone with its own number of steps (5 for listed, 3 for the others),
+    so the Adam step count is per subgraph; unlisted subgraphs do not move at all."""
+    rs = np.random.RandomState(21)
+    n, d, P, L = 40, 4, 4, 2
+    edges = hp.random_graph(n, 0.2, rs)
+    part = rs.randint(0, P, n)
+    rowptr, col = hp.csr_from_edges(n, edges)
+    spec = gcn.Spec(problem="mis", num_layers=L)
+    E, Ws = rand_params(rs, n, d, L, P)
+    lam = (rs.random_sample(n) < 0.3) * 0.8          # lambda on some nodes (Eq. for L_new)
+    lg = gcn.local_graph(n, rowptr, col, part, P, "sym")
+    st = gcn.init_state(E, Ws)
+    active = np.array([True, False, True, False])
+    before = (st.E.copy(), [W.copy() for W in st.Ws])
+    l_sub, per_sub = gcn.train(lg, st, spec, 2, lam, active=active)
+    np.testing.assert_allclose(l_sub, per_sub[:, active].sum(axis=1), rtol=1e-14)
+    for k in (1, 3):                                 # unlisted: bit for bit
+        idx = np.flatnonzero(part == k)
+        np.testing.assert_array_equal(st.E[idx], before[0][idx])
+        for l in range(L):
+            np.testing.assert_array_equal(st.Ws[l][k], before[1][l][k])
+    np.testing.assert_array_equal(st.tE, [2, 0, 2, 0])
+    gcn.train(lg, st, spec, 3, lam)
+    np.testing.assert_array_equal(st.tE, [5, 3, 5, 3])
+    for k in range(P):
+        idx, lgk, stk = _subgraph_alone(n, edges, part, k, E, Ws)
+        gcn.train(lgk, stk, spec, 5 if active[k] else 3, lam[idx])
+        np.testing.assert_allclose(stk.E, st.E[idx], rtol=1e-9, atol=1e-12)
+        for l in range(L):
+            np.testing.assert_allclose(stk.Ws[l][0], st.Ws[l][k], rtol=1e-9, atol=1e-12)
+
+
+def test_subset_fine_tune_with_shared_weights_uses_the_listed_gradients_only():
+    """With one weight set for all subgraphs, a step on subgraphs {1, 2} is a step on the
+    graph made of those two subgraphs alone."""
+    rs = np.random.RandomState(22)
+    n, d, P, L = 30, 3, 3, 2
+    edges = hp.random_graph(n, 0.25, rs)
+    part = rs.randint(0, P, n)
+    rowptr, col = hp.csr_from_edges(n, edges)
+    spec = gcn.Spec(problem="maxcut", num_layers=L, weight_sharing=True)
+    E, Ws = rand_params(rs, n, d, L, 1)
+    lg = gcn.local_graph(n, rowptr, col, part, P, "sym")
+    st = gcn.init_state(E, Ws)
+    active = np.array([False, True, True])
+    gcn.train(lg, st, spec, 4, active=active)
+    keep = np.flatnonzero(part != 0)
+    pos = -np.ones(n, dtype=int)
+    pos[keep] = np.arange(len(keep))
+    sub_edges = [(pos[u], pos[v]) for u, v in edges if part[u] != 0 and part[v] != 0]
+    rp, cl = hp.csr_from_edges(len(keep), sub_edges)
+    lg2 = gcn.local_graph(len(keep), rp, cl, part[keep] - 1, 2, "sym")
+    st2 = gcn.init_state(E[keep], Ws)
+    gcn.train(lg2, st2, spec, 4)
+    np.testing.assert_allclose(st2.E, st.E[keep], rtol=1e-9, atol=1e-12)
+    for l in range(L):
+        np.testing.assert_allclose(st2.Ws[l], st.Ws[l], rtol=1e-9, atol=1e-12)
+    np.testing.assert_array_equal(st.E[part == 0], E[part == 0])
+    np.testing.assert_array_equal(st.tW, [4])
+
+
 def test_relabelling_nodes_permutes_probabilities():
     rs = np.random.RandomState(12)
     n, d, P, L = 30, 4, 2, 3
