@@ -267,14 +267,17 @@ int w_elems(const gco_ctx* ctx, int l /*1..L*/) {
 // Workgroup -> (subgraph k, first tile s, stride S_k) tables: workgroup b walks
 // tiles s, s + S_k, s + 2 S_k, ... of subgraph k.  S_k is proportional to the
 // subgraph's share of the work (rows and CSR entries), at least
-// ceil(tiles_k / max_tiles_per_block), at most tiles_k.  With 8 subgraphs or
-// more, all workgroups of a subgraph get ids that are equal modulo 8, so that
-// they land on one XCD and share its L2 (workgroups are dealt to the 8 XCDs
-// round-robin by id); subgraphs are spread over the XCDs longest-first.
+// ceil(tiles_k / max_tiles_per_block), at most tiles_k.  With group_by_xcd, all
+// workgroups of a subgraph get ids that are equal modulo 8, so that they land on
+// one XCD and share its L2 (workgroups are dealt to the 8 XCDs round-robin by id);
+// subgraphs are spread over the XCDs longest-first.  The caller asks for that when
+// the feature matrix does not fit the Infinity Cache: while it fits, grouping gains
+// nothing measurable (c4: 0.977 against 0.973 ms per epoch) and costs the balance of
+// runs in which only some subgraphs train.
 void build_block_map(int P, const std::vector<int>& part_rows, const std::vector<int32_t>& lrowptr,
                      int tile_rows, int target_blocks, int max_tiles_per_block,
                      std::vector<int>& blk_k, std::vector<int>& blk_s, std::vector<int>& blk_S,
-                     double row_cost = 2.0) {
+                     bool group_by_xcd, double row_cost = 2.0) {
   std::vector<int> tiles(P), Sk(P);
   std::vector<double> work(P);
   double total = 0;
@@ -294,7 +297,7 @@ void build_block_map(int P, const std::vector<int>& part_rows, const std::vector
   blk_k.clear();
   blk_s.clear();
   blk_S.clear();
-  if (P >= 8) {
+  if (group_by_xcd && P >= 8) {
     std::vector<int> order(P);
     for (int k = 0; k < P; ++k) order[k] = k;
     std::stable_sort(order.begin(), order.end(), [&](int x, int y) { return Sk[x] > Sk[y]; });
@@ -342,12 +345,12 @@ void build_block_map(int P, const std::vector<int>& part_rows, const std::vector
 // plus the neighbours of rows that are not pre-reduced) plus row_cost per row, which
 // stands for the per-row work of the kernel's dense part and epilogue.
 void build_wave_map(int P, const std::vector<int>& part_rows, const std::vector<int32_t>& lrowptr,
-                    int target_blocks, double row_cost, std::vector<int>& wblk_k,
+                    int target_blocks, double row_cost, bool group_by_xcd, std::vector<int>& wblk_k,
                     std::vector<int2>& wwave_tiles) {
   constexpr int kWaves = kBlock / 64;
   std::vector<int> blk_s, blk_S;
   build_block_map(P, part_rows, lrowptr, kWaveRows * kWaves, target_blocks, 0, wblk_k, blk_s, blk_S,
-                  1.0 + row_cost);
+                  group_by_xcd, 1.0 + row_cost);
   wwave_tiles.assign(wblk_k.size() * kWaves, make_int2(0, 0));
   std::vector<std::vector<int>> cuts(P);  // cuts[k][v] = first tile of wavefront v of subgraph k
   for (size_t b = 0; b < wblk_k.size(); ++b) {
@@ -737,18 +740,23 @@ int gco_upload_graph(gco_ctx* ctx, int64_t n64, const int64_t* rowptr, const int
 
   // work decomposition
   std::vector<int> blk_k, blk_s, blk_S, nblk_k, nblk_s, nblk_S;
-  build_block_map(P, part_rows, lrowptr, kTileRows, kWideBlocks, kMaxTilesPerBlock, blk_k, blk_s, blk_S);
+  // subgraph -> XCD affinity only when one feature matrix exceeds the 256 MB Infinity Cache
+  const bool group_by_xcd =
+      static_cast<double>(n) * ctx->cfg.dim * ctx->elem_bytes() > 256.0 * 1024 * 1024;
+  build_block_map(P, part_rows, lrowptr, kTileRows, kWideBlocks, kMaxTilesPerBlock, blk_k, blk_s, blk_S,
+                  group_by_xcd);
   // one decomposition per kernel kind (different cost per row)
   for (int v = 0; v < kWaveMaps; ++v) {
     std::vector<int2> wwave_tiles;
-    build_wave_map(P, part_rows, lrowptr, kWaveBlocksFor[v], kWaveRowCost[v], ctx->hm.wblk_k[v], wwave_tiles);
+    build_wave_map(P, part_rows, lrowptr, kWaveBlocksFor[v], kWaveRowCost[v], group_by_xcd, ctx->hm.wblk_k[v],
+                   wwave_tiles);
     ctx->num_wblocks[v] = static_cast<int>(ctx->hm.wblk_k[v].size());
     GALLOC(ctx->d_wwave_tiles[v], wwave_tiles.size());
     HIPCHK(h2d(ctx, ctx->d_wwave_tiles[v], wwave_tiles.data(), wwave_tiles.size()));
   }
   // width-1 kernels: one 256-row tile per workgroup
   build_block_map(P, part_rows, lrowptr, kNarrowRows, std::numeric_limits<int>::max() / 2, 1, nblk_k,
-                  nblk_s, nblk_S);
+                  nblk_s, nblk_S, group_by_xcd);
   GALLOC(ctx->d_blk_s, blk_s.size());
   GALLOC(ctx->d_nblk_s, nblk_s.size());
   GALLOC(ctx->d_blk_S, blk_S.size());
