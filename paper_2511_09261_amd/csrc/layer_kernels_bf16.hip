@@ -387,106 +387,13 @@ constexpr size_t kGatherLds = kBlock * 8 * sizeof(float)                      //
                               + kMaxTilesPerBlock * (R + 1) * sizeof(int)     // rp
                               + (R + 4) * sizeof(int);                        // hlist
 template <int D>
-constexpr size_t fwd_lds() {
-  return MG<D>::at_bytes + kGatherLds + D * sizeof(float);
-}
-template <int D>
 constexpr size_t bwd_lds() {
   return MG<D>::at_bytes + 2 * MG<D>::tt_bytes + kGatherLds;
 }
 
 // ---------------------------------------------------------------------------
-// Forward: Y = relu((A_hat X) W^k)  [+ t = Y w_out^k]
-// ---------------------------------------------------------------------------
-template <int D>
-__global__ __launch_bounds__(kBlock) void fwd_hidden_bf16_kernel(
-    GraphView g, const bf16_t* __restrict__ X, const float* __restrict__ W, int w_stride,
-    bf16_t* __restrict__ Y, const float* __restrict__ w_out, int wout_stride, float* __restrict__ t,
-    const float* __restrict__ heavy_partial) {
-  using M = MG<D>;
-  extern __shared__ __align__(16) unsigned char smem[];
-  bf16_t* at = reinterpret_cast<bf16_t*>(smem);
-  float* red = reinterpret_cast<float*>(smem + M::at_bytes);
-  int2* ents = reinterpret_cast<int2*>(red + kBlock * 8);
-  int* rp = reinterpret_cast<int*>(ents + kEntCap);
-  int* hlist = rp + kMaxTilesPerBlock * (R + 1);
-  float* wo = reinterpret_cast<float*>(hlist + R + 4);
-
-  const int k = g.blk_k[blockIdx.x];
-  if (k < 0) return;
-  const int s = g.blk_s[blockIdx.x], S = g.blk_S[blockIdx.x];
-  const int tid = threadIdx.x, lane = tid % 64, wave = tid / 64;
-  const int tn = wave % M::NT, tm0 = wave / M::NT;
-  const int rbeg = g.part_rows[k], rend = g.part_rows[k + 1];
-  const int Q = preload_row_pointers(g, rbeg, rend, s, S, rp);
-  const float* Wk = W + static_cast<size_t>(k) * w_stride;
-  // B operand: B[kk][j] = W[kk][j], j = tn * 32 + lane % 32, kept in registers
-  bf16x8 bfrag[M::KS];
-#pragma unroll
-  for (int ks = 0; ks < M::KS; ++ks) {
-    float v[8];
-#pragma unroll
-    for (int x = 0; x < 8; ++x) v[x] = Wk[(ks * 16 + 8 * (lane / 32) + x) * D + tn * 32 + lane % 32];
-    bfrag[ks] = as_frag(pack8(v));
-  }
-  if (w_out != nullptr && tid < D) wo[tid] = w_out[static_cast<size_t>(k) * wout_stride + tid];
-  const PlainB<D> src{X, g.diag};
-  const BfSink<D, false> sink{at, nullptr};
-  __syncthreads();  // row pointers are in LDS
-  TileRegs<D> next;
-  if (Q > 0) prefetch_tile<D>(g, src, rbeg + s * R, min(R, rend - (rbeg + s * R)), rp, next);
-  for (int q = 0; q < Q; ++q) {
-    const int row0 = rbeg + (s + q * S) * R;
-    const int nrows = min(R, rend - row0);
-    const int* rpq = rp + q * (R + 1);
-    uint4 own[M::NCH];
-#pragma unroll
-    for (int u = 0; u < M::NCH; ++u) own[u] = next.own[u];
-    const bool in_lds = next.in_lds;
-    commit_entries<D>(next, ents);
-    if (tid == 0) hlist[0] = 0;
-    __syncthreads();
-    if (q + 1 < Q) {
-      const int row1 = row0 + S * R;
-      prefetch_tile<D>(g, src, row1, min(R, rend - row1), rpq + (R + 1), next);
-    }
-    gather_tile<D>(g, src, sink, row0, nrows, rpq, ents, in_lds, own, red, hlist, heavy_partial);
-    floatx16 acc[M::NTM];
-    tile_product<D>(at, bfrag, tm0, acc);
-    __syncthreads();  // every wave has read its A fragments: the tile can be reused for Y
-#pragma unroll
-    for (int qq = 0; qq < M::NTM; ++qq) {
-      const int tm = tm0 + qq * M::WPC;
-      if (tm < M::MT) {
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int i = tm * 32 + (r / 4) * 8 + (lane / 32) * 4 + r % 4;
-          at[i * M::PA + tn * 32 + lane % 32] = f32_to_bf16(fmaxf(acc[qq][r], 0.f));
-        }
-      }
-    }
-    __syncthreads();
-    for (int idx = tid; idx < R * M::LPR; idx += kBlock) {
-      const int r = idx / M::LPR, c0 = (idx % M::LPR) * 8;
-      if (r < nrows)
-        *reinterpret_cast<uint4*>(Y + static_cast<size_t>(row0 + r) * D + c0) =
-            *reinterpret_cast<const uint4*>(at + r * M::PA + c0);
-    }
-    if (w_out != nullptr) {  // t[r] = sum_c Y[r, c] * w_out[c]: four lanes per row
-      const int r = tid / 4, qd = tid % 4;
-      float part = 0.f;
-      for (int c = qd * (D / 4); c < (qd + 1) * (D / 4); ++c)
-        part = fmaf(bf16_to_f32(at[r * M::PA + c]), wo[c], part);
-      part += __shfl_xor(part, 1, 64);
-      part += __shfl_xor(part, 2, 64);
-      if (qd == 0 && r < nrows) t[row0 + r] = part;
-    }
-    __syncthreads();
-  }
-}
-
-// ---------------------------------------------------------------------------
-// Forward with asynchronous global -> LDS copies
+// Forward: Y = relu((A_hat X) W^k)  [+ t = Y w_out^k], with asynchronous global -> LDS
+// copies.  (Width 64 runs on the wave-per-tile kernels instead.)
 // ---------------------------------------------------------------------------
 // A tile moves 16 KB and a memory round trip takes about 2 us, so a workgroup
 // that waits for its own loads keeps far too few bytes in flight.  Here the
