@@ -109,6 +109,12 @@ FWD_BWD_CASES = [
     ("hubs_parts", "mis", 2, 128, "sym", "bf16", False),
     ("bfs12", "maxcut", 3, 128, "sym", "bf16", True),
     ("bfs12", "mis", 1, 64, "sym", "bf16", False),
+    # width 64 in bf16 runs on the wave-per-tile kernels: the non-symmetric normalisation
+    # (separate streams for A_hat and its transpose), two layers (the last hidden layer is
+    # also the first), shared weights, long rows in several subgraphs
+    ("random", "maxcut", 2, 64, "mean", "bf16", False),
+    ("hubs_parts", "mis", 3, 64, "mean", "bf16", True),
+    ("bfs12", "maxcut", 2, 64, "sym", "bf16", True),
 ]
 
 
