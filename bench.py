@@ -158,6 +158,14 @@ def main():
     t0 = time.perf_counter(); ctx.train_subset(20, listed, return_loss=False); ctx.sync()
     t_sub = (time.perf_counter() - t0) / 20
 
+    # best-by-loss snapshot of Alg. 1 stage 1 switched on (not part of `value`)
+    ctx.keep_best(True)
+    ctx.train(3, return_loss=False)
+    ctx.sync()
+    t0 = time.perf_counter(); ctx.train(20, return_loss=False); ctx.sync()
+    t_best = (time.perf_counter() - t0) / 20
+    ctx.keep_best(False)
+
     L = wl.num_layers
     nnz = 2 * info["m_local"]
     ea_per_epoch = 2 * L * (nnz + g.n) + nnz
@@ -187,6 +195,7 @@ def main():
                   "generate_s": t_gen, "upload_preprocess_s": t_upload,
                   "forward_and_read_probs_s": t_fwd, "round_repair_s": t_rr, "cut_edges_s": t_cut,
                   "fine_tune_subset": {"subgraphs": len(listed), "of": wl.num_parts, "ms_per_epoch": t_sub * 1e3},
+                  "epoch_with_best_snapshot_ms": t_best * 1e3,
                   "set_size_or_cut": obj, "conflicts_before": c_before, "conflicts_after": c_after,
                   "cut_edges": int(len(u))},
     }

@@ -153,6 +153,23 @@ int gco_train_subset(gco_ctx* ctx, int32_t epochs, const int32_t* parts, int32_t
 int gco_get_steps(gco_ctx* ctx, int64_t* steps_embed, int64_t* steps_weights);
 int gco_set_steps(gco_ctx* ctx, const int64_t* steps_embed, const int64_t* steps_weights);
 
+/* Best-by-loss snapshot (Alg. 1 stage 1 stores, per subgraph, the network of the lowest
+ * loss).  A model is one subgraph with its embedding rows and its own weight set; with
+ * shared weights the whole batch is one model judged by the total loss.  While enabled,
+ * every epoch of gco_train / gco_train_subset compares each trained model's loss (the one
+ * reported for that epoch, i.e. at the parameters the epoch started from) with the lowest
+ * seen so far and, where it is lower, copies those parameters into a device-side
+ * snapshot before the update.  enable != 0 starts tracking and forgets earlier snapshots
+ * (allocates one more copy of the parameters, fp32); enable == 0 stops tracking and keeps
+ * the snapshots.  gco_set_params and a new graph forget them too.  Optimizer state is not
+ * part of the snapshot. */
+int gco_keep_best(gco_ctx* ctx, int32_t enable);
+/* Lowest loss per model: double[Pw] (host), +infinity for a model never offered. */
+int gco_get_best_loss(gco_ctx* ctx, double* best_loss);
+/* Copy the snapshots back into the current parameters (models without one keep theirs).
+ * Adam moments and step counts are left as they are.  ESTATE if tracking was never on. */
+int gco_restore_best(gco_ctx* ctx);
+
 /* Forward pass at the current parameters (Alg. 1 stage 2: "run forward to get p"). */
 int gco_forward(gco_ctx* ctx);
 /* Probabilities of the last forward / the forward of the last epoch: float[n]. */

@@ -262,12 +262,58 @@ def init_state(E, Ws) -> TrainState:
                       [np.zeros_like(W) for W in Ws], [np.zeros_like(W) for W in Ws])
 
 
-def train(lg: LocalGraph, st: TrainState, spec: Spec, epochs: int, extra_linear=None, active=None):
+class BestState:
+    """Parameters of the lowest loss seen so far, per model (Alg. 1 stage 1: each worker
+    stores the best network of its subgraph).  A model is one subgraph with its own
+    weights, or, with shared weights, the whole batch judged by the total loss.  A
+    subgraph without nodes has no model."""
+
+    def __init__(self, lg: LocalGraph, st: "TrainState"):
+        self.num_models = st.Ws[0].shape[0]
+        self.loss = np.full(self.num_models, np.inf)
+        self.E = np.zeros_like(st.E)
+        self.Ws = [np.zeros_like(W) for W in st.Ws]
+
+    def offer(self, lg: LocalGraph, st: "TrainState", per_part, on_k):
+        """Called with the losses of the parameters `st` holds right now."""
+        if self.num_models == lg.num_parts:
+            for k, idx in enumerate(lg.members):
+                if on_k[k] and len(idx) and per_part[k] < self.loss[k]:
+                    self.loss[k] = per_part[k]
+                    self.E[idx] = st.E[idx]
+                    for l, W in enumerate(st.Ws):
+                        self.Ws[l][k] = W[k]
+        else:
+            total = per_part[on_k].sum()
+            if on_k.any() and total < self.loss[0]:
+                self.loss[0] = total
+                self.E[...] = st.E
+                for l, W in enumerate(st.Ws):
+                    self.Ws[l][...] = W
+
+    def restore(self, lg: LocalGraph, st: "TrainState"):
+        """Put the stored parameters back (models without a snapshot keep theirs)."""
+        if self.num_models == lg.num_parts:
+            for k, idx in enumerate(lg.members):
+                if np.isfinite(self.loss[k]):
+                    st.E[idx] = self.E[idx]
+                    for l in range(len(st.Ws)):
+                        st.Ws[l][k] = self.Ws[l][k]
+        elif np.isfinite(self.loss[0]):
+            st.E[...] = self.E
+            for l in range(len(st.Ws)):
+                st.Ws[l][...] = self.Ws[l]
+
+
+def train(lg: LocalGraph, st: TrainState, spec: Spec, epochs: int, extra_linear=None, active=None,
+          best: BestState = None):
     """`epochs` full-batch steps of the subgraphs listed in `active` (boolean array over the
     subgraphs; None = all): Sec. 3.2 for all of them, the fine-tuning step of Sec. 3.3 /
     Alg. 1 stage 3 for a subset.  Subgraphs that are not listed keep parameters, moments
     and step counts.  Returns the loss (summed over the listed subgraphs) at the parameters
-    each epoch started from, and per-subgraph losses [epochs, P]."""
+    each epoch started from, and per-subgraph losses [epochs, P].  With `best`, every
+    epoch's losses are offered to it together with the parameters they belong to (those
+    the epoch started from)."""
     P, Pw = lg.num_parts, st.Ws[0].shape[0]
     if st.tE is None:
         st.tE = np.zeros(P, dtype=np.int64)
@@ -280,6 +326,8 @@ def train(lg: LocalGraph, st: TrainState, spec: Spec, epochs: int, extra_linear=
         _, pp = loss(lg, cache["p"], spec, extra_linear)
         losses.append(pp[on_k].sum())
         per_part.append(pp)
+        if best is not None:
+            best.offer(lg, st, pp, on_k)
         gE, gWs = backward(lg, cache, st.Ws, spec, extra_linear, active=on_k)
         st.tE[on_k] += 1
         st.tW[on_w] += 1

@@ -64,6 +64,9 @@ _PROTOTYPES = {
     "gco_train_subset": (C.c_int, [C.c_void_p, C.c_int32, C.c_void_p, C.c_int32, C.c_void_p]),
     "gco_get_steps": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p]),
     "gco_set_steps": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p]),
+    "gco_keep_best": (C.c_int, [C.c_void_p, C.c_int32]),
+    "gco_get_best_loss": (C.c_int, [C.c_void_p, C.c_void_p]),
+    "gco_restore_best": (C.c_int, [C.c_void_p]),
     "gco_forward": (C.c_int, [C.c_void_p]),
     "gco_get_probs": (C.c_int, [C.c_void_p, C.c_void_p]),
     "gco_loss": (C.c_int, [C.c_void_p, C.POINTER(C.c_double), C.c_void_p]),
@@ -281,6 +284,17 @@ class Context:
         sw = np.ascontiguousarray(steps_weights, dtype=np.int64)
         assert se.shape[0] == self.num_parts and sw.shape[0] == self.num_weight_sets
         self._check(self.lib.gco_set_steps(self.h, _ptr(se), _ptr(sw)))
+
+    def keep_best(self, enable=True):
+        self._check(self.lib.gco_keep_best(self.h, 1 if enable else 0))
+
+    def get_best_loss(self):
+        best = np.empty(self.num_weight_sets, dtype=np.float64)
+        self._check(self.lib.gco_get_best_loss(self.h, _ptr(best)))
+        return best
+
+    def restore_best(self):
+        self._check(self.lib.gco_restore_best(self.h))
 
     def forward(self):
         self._check(self.lib.gco_forward(self.h))

@@ -23,7 +23,8 @@ namespace {
 
 const char* const kKindNames[KK_COUNT] = {
     "fwd_hidden", "fwd_gemv", "fwd_readout", "loss", "bwd_readout",
-    "bwd_hidden", "bwd_embed_adam", "adam_w", "loss_reduce", "heavy_rows", "form_gz"};
+    "bwd_hidden", "bwd_embed_adam", "adam_w", "loss_reduce", "heavy_rows", "form_gz",
+    "best_snapshot"};
 
 struct EventPair {
   hipEvent_t a, b;
@@ -156,6 +157,13 @@ struct gco_ctx {
   double *loss_partial = nullptr, *loss_part = nullptr, *loss_hist = nullptr, *loss_one = nullptr;
   int64_t loss_hist_cap = 0;
 
+  // best-by-loss snapshot: one model per weight set (Pw of them)
+  bool best_on = false, best_alloc = false;
+  float* E_best = nullptr;
+  float* W_best[3] = {};
+  double* d_best_loss = nullptr;
+  int32_t *d_improved = nullptr, *d_has_best = nullptr;
+
   double kind_bytes[KK_COUNT] = {};
 
   int fail(int code, const char* fmt, ...) {
@@ -197,6 +205,7 @@ struct gco_ctx {
     for (void* q : graph_allocs) raw_free(q);
     graph_allocs.clear();
     has_graph = has_params = probs_valid = false;
+    best_on = best_alloc = false;
     loss_hist_cap = 0;
     loss_hist = nullptr;
   }
@@ -514,6 +523,7 @@ void traffic_model(gco_ctx* ctx) {
   // one set of partials; the training loop reduces many sets per launch
   kb[KK_LOSS_REDUCE] = ctx->gv.num_loss_slots * 8.0 + ctx->P * 8.0;
   kb[KK_HEAVY] = 0;  // reported by time only
+  kb[KK_BEST] = 0;   // depends on how many models improved
 }
 
 }  // namespace
@@ -962,6 +972,15 @@ static int download_node_matrix(gco_ctx* ctx, float* host_orig, const float* dev
   return GCO_OK;
 }
 
+// Forget every snapshot: lowest loss +infinity, no model has one.
+static int reset_best(gco_ctx* ctx) {
+  const std::vector<double> inf(static_cast<size_t>(ctx->Pw), std::numeric_limits<double>::infinity());
+  HIPCHK(h2d(ctx, ctx->d_best_loss, inf.data(), inf.size()));
+  HIPCHK(hipMemsetAsync(ctx->d_has_best, 0, static_cast<size_t>(ctx->Pw) * sizeof(int32_t), ctx->st));
+  HIPCHK(hipMemsetAsync(ctx->d_improved, 0, static_cast<size_t>(ctx->Pw) * sizeof(int32_t), ctx->st));
+  return GCO_OK;
+}
+
 int gco_set_params(gco_ctx* ctx, const float* E, const float* const* W) {
   if (!ctx) return GCO_EINVAL;
   NEED(ctx->has_graph, GCO_ESTATE, "no graph uploaded");
@@ -980,6 +999,10 @@ int gco_set_params(gco_ctx* ctx, const float* E, const float* const* W) {
     HIPCHK(hipMemsetAsync(ctx->vW[l - 1], 0, cnt * sizeof(float), ctx->st));
   }
   if (ctx->Eb) launch_to_bf16(ctx->launch(), ctx->E, ctx->Eb, static_cast<int64_t>(nd));
+  if (ctx->best_alloc) {
+    rc = reset_best(ctx);
+    if (rc != GCO_OK) return rc;
+  }
   HIPCHK(hipStreamSynchronize(ctx->st));
   ctx->stepE.assign(static_cast<size_t>(ctx->P), 0);
   ctx->stepW.assign(static_cast<size_t>(ctx->Pw), 0);
@@ -1166,6 +1189,20 @@ static void run_backward(gco_ctx* ctx, const GraphView& gv, const gco_ctx::Activ
   if (update) ctx->probs_valid = true;  // p is that of the parameters before the step
 }
 
+// Copies the parameters of the models flagged on the device between the live set and the
+// snapshot.
+static void copy_params(gco_ctx* ctx, const GraphView& gv, const int32_t* flag, bool to_best) {
+  const int L = ctx->cfg.num_layers;
+  int elems[3] = {};
+  for (int l = 1; l <= L; ++l) elems[l - 1] = static_cast<int>(w_elems(ctx, l));
+  if (to_best)
+    launch_param_copy(ctx->launch(), gv, ctx->Pw, ctx->cfg.dim, flag, ctx->E, ctx->E_best, ctx->W,
+                      ctx->W_best, elems, L);
+  else
+    launch_param_copy(ctx->launch(), gv, ctx->Pw, ctx->cfg.dim, flag, ctx->E_best, ctx->E, ctx->W_best,
+                      ctx->W, elems, L);
+}
+
 // `epochs` training epochs of the subgraphs with active[k] != 0 (nullptr: all of them); the
 // others keep their parameters, optimizer state, step counts and probabilities.
 static int train_impl(gco_ctx* ctx, int32_t epochs, const uint8_t* active, double* loss_per_epoch) {
@@ -1213,6 +1250,12 @@ static int train_impl(gco_ctx* ctx, int32_t epochs, const uint8_t* active, doubl
       }
       run_forward(ctx, gv);
       run_loss_partials(ctx, gv, e);
+      if (ctx->best_on) {
+        // the parameters still are the ones this loss belongs to
+        launch_best_update(ctx->launch(), gv, ctx->loss_partial + static_cast<size_t>(e) * gv.num_loss_slots,
+                           Pw, ctx->d_best_loss, ctx->d_improved, ctx->d_has_best);
+        copy_params(ctx, gv, ctx->d_improved, /*to_best=*/true);
+      }
       run_backward(ctx, gv, maps, true, adE, adW, nullptr, nullptr);
     }
     launch_loss_reduce(ctx->launch(), gv, ctx->loss_partial, ne, gv.num_loss_slots, nullptr, ctx->loss_hist + e0);
@@ -1256,6 +1299,49 @@ int gco_train_subset(gco_ctx* ctx, int32_t epochs, const int32_t* parts, int32_t
   }
   ctx->gv_sub = view_with(ctx, ctx->sub);
   return train_impl(ctx, epochs, active.data(), loss_per_epoch);
+}
+
+int gco_keep_best(gco_ctx* ctx, int32_t enable) {
+  if (!ctx) return GCO_EINVAL;
+  NEED(ctx->has_graph, GCO_ESTATE, "no graph uploaded");
+  if (!enable) {
+    ctx->best_on = false;
+    return GCO_OK;
+  }
+  if (!ctx->best_alloc) {
+    GALLOC(ctx->E_best, static_cast<size_t>(ctx->n) * ctx->cfg.dim);
+    for (int l = 1; l <= ctx->cfg.num_layers; ++l)
+      GALLOC(ctx->W_best[l - 1], static_cast<size_t>(ctx->Pw) * w_elems(ctx, l));
+    GALLOC(ctx->d_best_loss, static_cast<size_t>(ctx->Pw));
+    GALLOC(ctx->d_improved, static_cast<size_t>(ctx->Pw));
+    GALLOC(ctx->d_has_best, static_cast<size_t>(ctx->Pw));
+    ctx->best_alloc = true;
+  }
+  const int rc = reset_best(ctx);
+  if (rc != GCO_OK) return rc;
+  HIPCHK(hipStreamSynchronize(ctx->st));
+  ctx->best_on = true;
+  return GCO_OK;
+}
+
+int gco_get_best_loss(gco_ctx* ctx, double* best_loss) {
+  if (!ctx) return GCO_EINVAL;
+  NEED(ctx->best_alloc, GCO_ESTATE, "gco_keep_best was never enabled");
+  NEED(best_loss, GCO_EINVAL, "best_loss is NULL");
+  HIPCHK(d2h(ctx, best_loss, ctx->d_best_loss, static_cast<size_t>(ctx->Pw)));
+  return GCO_OK;
+}
+
+int gco_restore_best(gco_ctx* ctx) {
+  if (!ctx) return GCO_EINVAL;
+  NEED(ctx->best_alloc, GCO_ESTATE, "gco_keep_best was never enabled");
+  NEED(ctx->has_params, GCO_ESTATE, "no parameters set");
+  copy_params(ctx, ctx->gv, ctx->d_has_best, /*to_best=*/false);
+  if (ctx->Eb)
+    launch_to_bf16(ctx->launch(), ctx->E, ctx->Eb, static_cast<int64_t>(ctx->n) * ctx->cfg.dim);
+  HIPCHK(hipGetLastError());
+  ctx->probs_valid = false;
+  return GCO_OK;
 }
 
 int gco_get_steps(gco_ctx* ctx, int64_t* steps_embed, int64_t* steps_weights) {

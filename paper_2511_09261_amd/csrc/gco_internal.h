@@ -40,6 +40,7 @@ enum KernelKind : int {
   KK_LOSS_REDUCE,      // per-subgraph and total loss
   KK_HEAVY,            // chunked pre-reduction of very long rows
   KK_FORM_GZ,          // G_Z of the last hidden layer + gradient of the scalar layer's weights
+  KK_BEST,             // best-by-loss snapshot: decision per model + copy of the improved ones
   KK_COUNT
 };
 
@@ -189,6 +190,19 @@ void launch_loss(const Launch& ln, const GraphView& g, const float* p, const flo
 void launch_loss_reduce(const Launch& ln, const GraphView& g, const double* loss_partial, int sets,
                         int64_t set_stride, double* loss_part, double* loss_out);
 constexpr int kLossSets = 64;  // epochs whose loss partials are kept before they are reduced
+
+// Best-by-loss snapshot (Alg. 1 stage 1).  `models` = number of weight sets: P (a subgraph
+// with its own weights is a model) or 1 (shared weights: the batch is one model, judged by
+// the total loss).  From one epoch's loss partials, summed as launch_loss_reduce sums
+// them: improved[u] = 1 and best_loss[u], has_best[u] updated where model u was trained
+// this epoch and its loss is below best_loss[u]; improved[u] = 0 otherwise.
+void launch_best_update(const Launch& ln, const GraphView& g, const double* loss_partial, int models,
+                        double* best_loss, int* improved, int* has_best);
+// Copies the embedding rows (width D) and the weight tensors (w_elems[l] floats per model)
+// of every model with flag[u] != 0 from *_src to *_dst.
+void launch_param_copy(const Launch& ln, const GraphView& g, int models, int D, const int* flag,
+                       const float* E_src, float* E_dst, const float* const* W_src, float* const* W_dst,
+                       const int* w_elems, int num_w);
 
 // g_t = A_hat^T g_z.
 void launch_bwd_readout(const Launch& ln, const GraphView& g, const float* g_z, float* g_t);

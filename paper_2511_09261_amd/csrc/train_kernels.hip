@@ -318,10 +318,32 @@ __global__ __launch_bounds__(kBlock) void bwd_single_kernel(GraphView g, BwdArgs
 // Width-1 passes: y_i = f_self(i) + sum_{j in N(i)} f(j), then an epilogue per row
 // ---------------------------------------------------------------------------
 
+// Loss of subgraph k from the workgroup partials of one epoch: the lanes of a wavefront add
+// the partials of k in a strided, fixed order, then a butterfly forms the total (every lane
+// returns it).
+__device__ inline double subgraph_loss(const GraphView& g, const double* __restrict__ partial, int k,
+                                       int lane) {
+  double acc = 0.0;
+  for (int q = g.loss_ptr[k] + lane; q < g.loss_ptr[k + 1]; q += 64) acc += partial[g.loss_list[q]];
+  return wave_sum(acc);
+}
+
+// Sum of part_s[0..P) in a fixed order (per-thread strided sums, then thread 0 adds them);
+// valid in thread 0.  Contains workgroup barriers.
+__device__ inline double total_loss(const double* part_s, int P, double* tot) {
+  __syncthreads();
+  double mine = 0.0;
+  for (int k = threadIdx.x; k < P; k += kBlock) mine += part_s[k];
+  tot[threadIdx.x] = mine;
+  __syncthreads();
+  double acc = 0.0;
+  if (threadIdx.x == 0)
+    for (int q = 0; q < kBlock; ++q) acc += tot[q];
+  return acc;
+}
+
 // One workgroup per set of partials (one set per epoch).  Each wavefront takes subgraphs
-// k = wave, wave + 4, ...: its lanes sum the workgroup partials of k in a strided, fixed
-// order, then the wavefront total is formed by a butterfly.  Thread 0 adds the subgraph
-// values.  loss_part (per-subgraph values, [sets, P]) may be null.
+// k = wave, wave + 4, ...  loss_part (per-subgraph values, [sets, P]) may be null.
 __global__ __launch_bounds__(kBlock) void loss_reduce_kernel(GraphView g, const double* __restrict__ partial,
                                                              int64_t set_stride,
                                                              double* __restrict__ loss_part,
@@ -331,23 +353,99 @@ __global__ __launch_bounds__(kBlock) void loss_reduce_kernel(GraphView g, const 
   partial += static_cast<int64_t>(blockIdx.x) * set_stride;
   const int wave = threadIdx.x / 64, lane = threadIdx.x % 64;
   for (int k = wave; k < g.P; k += kBlock / 64) {
-    double acc = 0.0;
-    for (int q = g.loss_ptr[k] + lane; q < g.loss_ptr[k + 1]; q += 64) acc += partial[g.loss_list[q]];
-    acc = wave_sum(acc);
+    const double acc = subgraph_loss(g, partial, k, lane);
     if (lane == 0) {
       part_s[k] = acc;
       if (loss_part != nullptr) loss_part[static_cast<int64_t>(blockIdx.x) * g.P + k] = acc;
     }
   }
-  __syncthreads();
-  double mine = 0.0;
-  for (int k = threadIdx.x; k < g.P; k += kBlock) mine += part_s[k];
-  tot[threadIdx.x] = mine;
-  __syncthreads();
-  if (threadIdx.x == 0) {
-    double acc = 0.0;
-    for (int q = 0; q < kBlock; ++q) acc += tot[q];
-    loss_out[blockIdx.x] = acc;
+  const double total = total_loss(part_s, g.P, tot);
+  if (threadIdx.x == 0) loss_out[blockIdx.x] = total;
+}
+
+// ---------------------------------------------------------------------------
+// Best-by-loss snapshot (Alg. 1 stage 1: the best network of every subgraph is kept)
+// ---------------------------------------------------------------------------
+
+// One workgroup.  The losses of this epoch, summed exactly as loss_reduce_kernel sums them,
+// are compared with the lowest seen so far, per model: a subgraph (models == P) or the
+// whole batch (models == 1).  A subgraph without loss partials is not being trained and is
+// not offered.  improved[u] tells the copy kernel which models to store.
+__global__ __launch_bounds__(kBlock) void best_update_kernel(GraphView g, const double* __restrict__ partial,
+                                                             int models, double* __restrict__ best_loss,
+                                                             int* __restrict__ improved,
+                                                             int* __restrict__ has_best) {
+  extern __shared__ double part_s[];  // [P]
+  __shared__ double tot[kBlock];
+  const int wave = threadIdx.x / 64, lane = threadIdx.x % 64;
+  for (int k = wave; k < g.P; k += kBlock / 64) {
+    const double acc = subgraph_loss(g, partial, k, lane);
+    if (lane == 0) {
+      part_s[k] = acc;
+      if (models != 1) {
+        const bool better = g.loss_ptr[k + 1] > g.loss_ptr[k] && acc < best_loss[k];
+        improved[k] = better ? 1 : 0;
+        if (better) {
+          best_loss[k] = acc;
+          has_best[k] = 1;
+        }
+      }
+    }
+  }
+  const double total = total_loss(part_s, g.P, tot);
+  if (models == 1 && threadIdx.x == 0) {
+    const bool better = g.loss_ptr[g.P] > g.loss_ptr[0] && total < best_loss[0];
+    improved[0] = better ? 1 : 0;
+    if (better) {
+      best_loss[0] = total;
+      has_best[0] = 1;
+    }
+  }
+}
+
+struct ParamCopy {
+  const float* E_src = nullptr;
+  float* E_dst = nullptr;
+  const float* W_src[3] = {};
+  float* W_dst[3] = {};
+  int w_elems[3] = {};  // per weight set
+  int num_w = 0;
+};
+
+// Copies the parameters of the models with flag[u] != 0.  blockIdx.y < P: the embedding
+// rows of subgraph y (row width D floats, D % 4 == 0); blockIdx.y = P + l: weight tensor l
+// of every flagged model.  The workgroups of one y share the work in a strided loop, four
+// 16-byte accesses in flight per lane; the embedding is read and written past the caches.
+__global__ __launch_bounds__(kBlock) void param_copy_kernel(GraphView g, int models, int D,
+                                                            const int* __restrict__ flag, ParamCopy c) {
+  const int y = blockIdx.y;
+  const int64_t stride = static_cast<int64_t>(gridDim.x) * kBlock;
+  const int64_t first = static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x;
+  if (y < g.P) {
+    if (!flag[models == 1 ? 0 : y]) return;
+    const int64_t i0 = static_cast<int64_t>(g.part_rows[y]) * (D / 4);
+    const int64_t i1 = static_cast<int64_t>(g.part_rows[y + 1]) * (D / 4);
+    for (int64_t i = i0 + first; i < i1; i += 4 * stride) {
+      typedef float f32x4_t __attribute__((ext_vector_type(4)));
+      const f32x4_t* src = reinterpret_cast<const f32x4_t*>(c.E_src);
+      f32x4_t* dst = reinterpret_cast<f32x4_t*>(c.E_dst);
+      f32x4_t v[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u)
+        if (i + u * stride < i1) v[u] = __builtin_nontemporal_load(src + i + u * stride);
+#pragma unroll
+      for (int u = 0; u < 4; ++u)
+        if (i + u * stride < i1) __builtin_nontemporal_store(v[u], dst + i + u * stride);
+    }
+  } else {
+    const int l = y - g.P;
+    if (l >= c.num_w) return;
+    const int elems = c.w_elems[l];
+    for (int u = 0; u < models; ++u) {
+      if (!flag[u]) continue;
+      const int64_t base = static_cast<int64_t>(u) * elems;
+      for (int64_t e = first; e < elems; e += stride) c.W_dst[l][base + e] = c.W_src[l][base + e];
+    }
   }
 }
 
@@ -474,6 +572,33 @@ void launch_fwd_gemv(const Launch& ln, int storage, int D, const GraphView& g, c
     GCO_DISPATCH_D(float, D, (fwd_gemv_kernel<float, DD><<<g.num_nblocks, kBlock, 0, ln.st>>>(g, static_cast<const float*>(X), w, w_stride, t)))
   }
   ln.end(KK_FWD_GEMV);
+}
+
+void launch_best_update(const Launch& ln, const GraphView& g, const double* loss_partial, int models,
+                        double* best_loss, int* improved, int* has_best) {
+  const size_t lds = static_cast<size_t>(g.P) * sizeof(double);
+  allow_lds(best_update_kernel, lds);
+  ln.begin(KK_BEST);
+  best_update_kernel<<<1, kBlock, lds, ln.st>>>(g, loss_partial, models, best_loss, improved, has_best);
+  ln.end(KK_BEST);
+}
+
+void launch_param_copy(const Launch& ln, const GraphView& g, int models, int D, const int* flag,
+                       const float* E_src, float* E_dst, const float* const* W_src, float* const* W_dst,
+                       const int* w_elems, int num_w) {
+  ParamCopy c;
+  c.E_src = E_src;
+  c.E_dst = E_dst;
+  c.num_w = num_w;
+  for (int l = 0; l < num_w; ++l) {
+    c.W_src[l] = W_src[l];
+    c.W_dst[l] = W_dst[l];
+    c.w_elems[l] = w_elems[l];
+  }
+  const int per_part = std::max(1, (kWideBlocks + g.P - 1) / g.P);
+  ln.begin(KK_BEST);
+  param_copy_kernel<<<dim3(per_part, g.P + num_w), kBlock, 0, ln.st>>>(g, models, D, flag, c);
+  ln.end(KK_BEST);
 }
 
 void launch_loss_reduce(const Launch& ln, const GraphView& g, const double* loss_partial, int sets,

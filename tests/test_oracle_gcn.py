@@ -544,3 +544,68 @@ def test_training_on_the_small_workload_behaves():
     st = gcn.init_state(E, Ws)
     losses, _ = gcn.train(lg, st, spec, 200)
     assert losses[-1] < losses[0] and losses[-1] < 0
+
+
+@pytest.mark.parametrize("shared", [False, True])
+def test_best_snapshot_holds_the_parameters_of_the_lowest_loss_per_model(shared):
+    """Alg. 1 stage 1 stores the best network of every subgraph.  Pins, on a run whose
+    losses go up and down (large step size): the stored loss is the minimum of the
+    model's own trajectory; the stored parameters are those of a fresh run stopped after
+    exactly argmin steps (so the snapshot is taken before the update of that epoch, not
+    after); evaluating the restored parameters reproduces the stored loss; different
+    models pick different epochs."""
+    rs = np.random.RandomState(31)
+    n, d, P, L = 48, 4, 4, 2
+    edges = hp.random_graph(n, 0.2, rs)
+    part = rs.randint(0, P, n)
+    rowptr, col = hp.csr_from_edges(n, edges)
+    spec = gcn.Spec(problem="mis", num_layers=L, lr=0.5, weight_sharing=shared)
+    E, Ws = rand_params(rs, n, d, L, 1 if shared else P)
+    lg = gcn.local_graph(n, rowptr, col, part, P, "sym")
+    st = gcn.init_state(E, Ws)
+    best = gcn.BestState(lg, st)
+    epochs = 12
+    total, per = gcn.train(lg, st, spec, epochs, best=best)
+    traj = total[:, None] if shared else per
+    arg = traj.argmin(axis=0)
+    np.testing.assert_array_equal(best.loss, traj.min(axis=0))
+    assert np.all(np.diff(traj, axis=0).max(axis=0) > 0), "trajectory must not be monotone"
+    assert np.all(arg > 0) and np.all(arg < epochs - 1)
+    if not shared:
+        assert len(set(arg.tolist())) > 1
+    for u in range(traj.shape[1]):
+        ref = gcn.init_state(E, Ws)
+        gcn.train(lg, ref, spec, int(arg[u]))
+        idx = np.arange(n) if shared else np.flatnonzero(part == u)
+        np.testing.assert_array_equal(best.E[idx], ref.E[idx])
+        for l in range(L):
+            np.testing.assert_array_equal(best.Ws[l][u], ref.Ws[l][u])
+    best.restore(lg, st)
+    _, pp = gcn.loss(lg, gcn.forward(lg, st.E, st.Ws, spec)["p"], spec)
+    np.testing.assert_allclose(pp.sum() if shared else pp, best.loss[0] if shared else best.loss,
+                               rtol=1e-13)
+
+
+def test_best_snapshot_leaves_unlisted_and_unseen_models_alone():
+    """A subset run offers only the listed subgraphs; restoring touches nothing else."""
+    rs = np.random.RandomState(32)
+    n, d, P, L = 36, 3, 3, 2
+    edges = hp.random_graph(n, 0.25, rs)
+    part = rs.randint(0, P, n)
+    rowptr, col = hp.csr_from_edges(n, edges)
+    spec = gcn.Spec(problem="maxcut", num_layers=L, lr=0.3)
+    E, Ws = rand_params(rs, n, d, L, P)
+    lg = gcn.local_graph(n, rowptr, col, part, P, "sym")
+    st = gcn.init_state(E, Ws)
+    best = gcn.BestState(lg, st)
+    active = np.array([False, True, False])
+    _, per = gcn.train(lg, st, spec, 6, active=active, best=best)
+    assert np.isinf(best.loss[0]) and np.isinf(best.loss[2])
+    assert best.loss[1] == per[:, 1].min()
+    moved = (st.E.copy(), [W.copy() for W in st.Ws])
+    best.restore(lg, st)
+    for k in (0, 2):
+        idx = np.flatnonzero(part == k)
+        np.testing.assert_array_equal(st.E[idx], moved[0][idx])
+        for l in range(L):
+            np.testing.assert_array_equal(st.Ws[l][k], moved[1][l][k])
