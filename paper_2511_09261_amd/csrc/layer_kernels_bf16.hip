@@ -970,7 +970,7 @@ void fwd_t(const Launch& ln, const GraphView& g, const void* X, const float* W, 
     heavy_wide_b_kernel<D, PlainB<D>><<<g.num_chunks, kBlock, 0, ln.st>>>(g, src, heavy_partial);
     ln.end(KK_HEAVY);
   }
-  if (D == 64) {  // wave-per-tile kernel
+  if (D == 64 || D == 128) {  // wave-per-tile kernel
     launch_fwd_hidden_wave(ln, D, g, X, W, w_stride, Y, w_out, wout_stride, t, heavy_partial);
     return;
   }

@@ -370,7 +370,7 @@ constexpr size_t fwd_wave_lds() {
 // Forward: Y = relu((A_hat X) W^k)  [+ t = Y w_out^k]
 // ---------------------------------------------------------------------------
 template <int D>
-__global__ __launch_bounds__(kBlock, 3) void fwd_wave_kernel(
+__global__ __launch_bounds__(kBlock, D == 64 ? 3 : 2) void fwd_wave_kernel(
     GraphView g, const bf16_t* __restrict__ X, const float* __restrict__ W, int w_stride,
     bf16_t* __restrict__ Y, const float* __restrict__ w_out, int wout_stride, float* __restrict__ t,
     const float* __restrict__ heavy_partial) {
@@ -823,12 +823,18 @@ void launch_bwd_hidden_wave(const Launch& ln, int D, bool to_embed, const GraphV
 void launch_fwd_hidden_wave(const Launch& ln, int D, const GraphView& g, const void* X, const float* W,
                             int w_stride, void* Y, const float* w_out, int wout_stride, float* t,
                             float* heavy_partial) {
-  if (D != 64) return;
-  allow_lds(fwd_wave_kernel<64>, fwd_wave_lds<64>());
   ln.begin(KK_FWD_HIDDEN);
-  fwd_wave_kernel<64><<<g.num_wblocks[WM_FWD], kBlock, fwd_wave_lds<64>(), ln.st>>>(
-      g, static_cast<const bf16_t*>(X), W, w_stride, static_cast<bf16_t*>(Y), w_out, wout_stride, t,
-      heavy_partial);
+  if (D == 64) {
+    allow_lds(fwd_wave_kernel<64>, fwd_wave_lds<64>());
+    fwd_wave_kernel<64><<<g.num_wblocks[WM_FWD], kBlock, fwd_wave_lds<64>(), ln.st>>>(
+        g, static_cast<const bf16_t*>(X), W, w_stride, static_cast<bf16_t*>(Y), w_out, wout_stride, t,
+        heavy_partial);
+  } else if (D == 128) {
+    allow_lds(fwd_wave_kernel<128>, fwd_wave_lds<128>());
+    fwd_wave_kernel<128><<<g.num_wblocks[WM_FWD], kBlock, fwd_wave_lds<128>(), ln.st>>>(
+        g, static_cast<const bf16_t*>(X), W, w_stride, static_cast<bf16_t*>(Y), w_out, wout_stride, t,
+        heavy_partial);
+  }
   ln.end(KK_FWD_HIDDEN);
 }
 
