@@ -24,7 +24,7 @@ namespace {
 const char* const kKindNames[KK_COUNT] = {
     "fwd_hidden", "fwd_gemv", "fwd_readout", "loss", "bwd_readout",
     "bwd_hidden", "bwd_embed_adam", "adam_w", "loss_reduce", "heavy_rows", "form_gz",
-    "best_snapshot"};
+    "best_snapshot", "grad_w"};
 
 struct EventPair {
   hipEvent_t a, b;
@@ -153,6 +153,7 @@ struct gco_ctx {
   float* gwout_partial = nullptr;
   void* H[3] = {};            // H[0] aliases the embedding in storage type
   void* GZ[3] = {};
+  void* GT = nullptr;         // rows of A_hat^T G_Z of the layer in hand (split_grad_w())
   float *t = nullptr, *z = nullptr, *p = nullptr, *g_z = nullptr, *g_t = nullptr;
   double *loss_partial = nullptr, *loss_part = nullptr, *loss_hist = nullptr, *loss_one = nullptr;
   int64_t loss_hist_cap = 0;
@@ -210,8 +211,12 @@ struct gco_ctx {
     loss_hist = nullptr;
   }
   int elem_bytes() const { return cfg.storage == GCO_STORAGE_BF16 ? 2 : 4; }
-  // the hidden layers run on the wave-per-tile kernels (bf16 storage, width 64)
-  bool wave_path() const { return cfg.storage == GCO_STORAGE_BF16 && cfg.dim == 64; }
+  // the hidden layers run on the wave-per-tile kernels (bf16 storage, width 64 or 128)
+  bool wave_path() const { return cfg.storage == GCO_STORAGE_BF16 && (cfg.dim == 64 || cfg.dim == 128); }
+  // width 128: the weight gradients come from a kernel of their own, fed with stored G_T rows
+  bool split_grad_w() const { return wave_path() && cfg.dim == 128; }
+  // decomposition whose workgroups wrote the weight-gradient partials of hidden layer l
+  int grad_map(int l) const { return (l == 1 && !split_grad_w()) ? WM_EMBED : WM_BWD; }
   Launch launch() { return Launch{st, prof.mode ? &prof : nullptr}; }
 };
 
@@ -498,16 +503,25 @@ void traffic_model(gco_ctx* ctx) {
   // workgroups, the scalar layer's from the narrow ones, and G_Z of the last hidden layer
   // is formed by a kernel of its own (KK_FORM_GZ) instead of inside the layer's backward.
   const bool wave = ctx->wave_path() && L >= 2;
-  const double NBh = wave ? ctx->gv.num_wblocks[WM_BWD] : NB, NBe = wave ? ctx->gv.num_wblocks[WM_EMBED] : NB;
+  const bool split = ctx->split_grad_w() && L >= 2;
+  const double NBh = wave ? ctx->gv.num_wblocks[WM_BWD] : NB;
+  const double NBe = wave ? ctx->gv.num_wblocks[ctx->grad_map(1)] : NB;
   const double NBo = wave ? ctx->gv.num_nblocks : NB;
   const double last_extra = wave ? 0 : n * 4 + NBo * D * 4;  // g_t read + gw_out partials
   if (wave) kb[KK_FORM_GZ] = 2 * n * D * s + n * 4 + Pw * D * 4 + NBo * D * 4;
   // gathered gradient source + Hprev read + GZ write
   kb[KK_BWD_HIDDEN] = idx + scales + 3 * n * D * s + Pw * D * D * 4 + NBh * D * D * 4 + (L == 3 ? last_extra : 0);
+  if (split) {
+    // the partials move to grad_w, which reads Hprev and the stored rows of G_T
+    kb[KK_BWD_HIDDEN] += n * D * s - NBh * D * D * 4;
+    kb[KK_GRAD_W] = 2 * n * D * s + NBh * D * D * 4;
+  }
   // first layer: gathered source + embedding (working copy) read + Adam state in/out
   const double adam_e = ctx->cfg.train_embed ? (6 * n * D * 4 + (s == 2 ? n * D * 2 : 0)) : 0;
   const double hprev_read = (s == 2 || !ctx->cfg.train_embed) ? n * D * s : 0;  // fp32: E is read by Adam already
-  if (L >= 2)
+  if (L >= 2 && split)  // gathered source + G_T rows out + Adam; the working copy is read by grad_w
+    kb[KK_BWD_EMBED] = idx + scales + 2 * n * D * s + Pw * D * D * 4 + adam_e;
+  else if (L >= 2)
     kb[KK_BWD_EMBED] = idx + scales + n * D * s + hprev_read + Pw * D * D * 4 + NBe * D * D * 4 + adam_e +
                        (L == 2 ? last_extra : 0);
   else
@@ -524,6 +538,7 @@ void traffic_model(gco_ctx* ctx) {
   kb[KK_LOSS_REDUCE] = ctx->gv.num_loss_slots * 8.0 + ctx->P * 8.0;
   kb[KK_HEAVY] = 0;  // reported by time only
   kb[KK_BEST] = 0;   // depends on how many models improved
+  if (!split) kb[KK_GRAD_W] = 0;
 }
 
 }  // namespace
@@ -922,6 +937,11 @@ int gco_upload_graph(gco_ctx* ctx, int64_t n64, const int64_t* rowptr, const int
     GALLOC(q, nd * eb);
     ctx->GZ[l] = q;
   }
+  if (ctx->split_grad_w() && L >= 2) {
+    uint8_t* q = nullptr;
+    GALLOC(q, nd * eb);
+    ctx->GT = q;
+  }
   GALLOC(ctx->gwout_partial, static_cast<size_t>(std::max(g.num_blocks, g.num_nblocks)) * D);
   GALLOC(ctx->d_bc, static_cast<size_t>(kLossSets) * (P + ctx->Pw));
   GALLOC(ctx->t, static_cast<size_t>(n));
@@ -1153,6 +1173,7 @@ static void run_backward(gco_ctx* ctx, const GraphView& gv, const gco_ctx::Activ
   a.adam = ad;
   a.heavy_partial = ctx->d_heavy_partial;
   a.GZ_last = L >= 2 ? ctx->GZ[L - 1] : nullptr;
+  a.GT = ctx->GT;
   a.mode = update ? (c.train_embed ? EMBED_ADAM : EMBED_SKIP) : (gE ? EMBED_WRITE_GRAD : EMBED_SKIP);
   if (L == 1) {
     a.Hprev = ctx->H[0];
@@ -1181,7 +1202,7 @@ static void run_backward(gco_ctx* ctx, const GraphView& gv, const gco_ctx::Activ
     // who wrote the partials: the wide kernels' workgroups, or, on the wave-per-tile path,
     // its own workgroups (hidden layers) and the narrow ones (scalar layer)
     const bool wave = ctx->wave_path() && L >= 2;
-    const int wm = l == 1 ? WM_EMBED : WM_BWD;  // the kernel kind that wrote gW_l
+    const int wm = ctx->grad_map(l);  // the decomposition whose workgroups wrote gW_l
     wt[l - 1].blk_ptr = !wave ? maps.pbl_ptr : (l < L ? maps.wpbl_ptr[wm] : maps.nwbl_ptr);
     wt[l - 1].blk_list = !wave ? maps.pbl_list : (l < L ? maps.wpbl_list[wm] : maps.nwbl_list);
   }

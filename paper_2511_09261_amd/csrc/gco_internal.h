@@ -41,6 +41,7 @@ enum KernelKind : int {
   KK_HEAVY,            // chunked pre-reduction of very long rows
   KK_FORM_GZ,          // G_Z of the last hidden layer + gradient of the scalar layer's weights
   KK_BEST,             // best-by-loss snapshot: decision per model + copy of the improved ones
+  KK_GRAD_W,           // weight gradient of a hidden layer from stored rows (bf16, width 128)
   KK_COUNT
 };
 
@@ -227,6 +228,7 @@ struct BwdArgs {
   int w_stride = 0;
   float* gW_partial = nullptr;   // [num_blocks, D*D]
   void* GZ_out = nullptr;        // [n, D] storage type (not to_embed)
+  void* GT = nullptr;            // [n, D] bf16: rows of G_T = A_hat^T G_Z (wave-per-tile path, width 128)
   // to_embed
   int mode = EMBED_ADAM;
   float* E = nullptr;            // fp32 master embeddings [n, D]
@@ -248,11 +250,13 @@ void launch_fwd_hidden_bf16(const Launch& ln, int D, const GraphView& g, const v
 void launch_bwd_hidden_bf16(const Launch& ln, int D, bool last, bool to_embed, const GraphView& gt,
                             const BwdArgs& a);
 
-// wave-per-tile bf16 kernels (wave_kernels_bf16.hip), width 64
+// wave-per-tile bf16 kernels (wave_kernels_bf16.hip), widths 64 and 128
 // last hidden layer: a.GZ_last = G_Z formed from g_t, w_out and Hcur; gw_out partials per
 // narrow workgroup
 void launch_form_gz_last(const Launch& ln, int D, const GraphView& g, const BwdArgs& a);
-// hidden-layer backward on G_Z = a.GZ_in; gW partials per wave-kernel workgroup
+// hidden-layer backward on G_Z = a.GZ_in; gW partials per wave-kernel workgroup (width 64:
+// of this kernel's own decomposition; width 128: of the hidden-backward decomposition,
+// written by a second kernel from a.Hprev and the rows of G_T stored in a.GT)
 void launch_bwd_hidden_wave(const Launch& ln, int D, bool to_embed, const GraphView& gt, const BwdArgs& a);
 void launch_fwd_hidden_wave(const Launch& ln, int D, const GraphView& g, const void* X, const float* W,
                             int w_stride, void* Y, const float* w_out, int wout_stride, float* t,

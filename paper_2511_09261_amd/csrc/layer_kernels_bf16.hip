@@ -984,7 +984,7 @@ void fwd_t(const Launch& ln, const GraphView& g, const void* X, const float* W, 
 
 template <int D>
 void bwd_t(const Launch& ln, bool last, bool to_embed, const GraphView& gt, const BwdArgs& a) {
-  if (D == 64) {  // wave-per-tile kernels: G_Z of the last layer is formed first
+  if (D == 64 || D == 128) {  // wave-per-tile kernels: G_Z of the last layer is formed first
     BwdArgs b = a;
     if (last) {
       launch_form_gz_last(ln, D, gt, a);

@@ -60,19 +60,27 @@ struct WG {
   static constexpr int PA = D + 8;       // pitch of the bf16 output tile
   static constexpr int GP = RW * 2 + 16; // bytes per feature of a transposed 32-row bf16 tile
   static constexpr int PF = D + 4;       // pitch (floats) of an fp32 32-row tile
+  // Width 64: the weight-gradient accumulators (D*D/64 registers per lane) stay in the
+  // backward kernel.  Width 128: they do not fit, the backward kernel stores G_T and a
+  // kernel of its own forms the weight gradient.
+  static constexpr bool GW_INLINE = D <= 64;
   // one wave-private LDS region serves, in turn, as the transposed row buffer of a step,
   // as the two transposed tiles of the weight-gradient product, and as the output tile
   static constexpr size_t xf_bytes = static_cast<size_t>(D) * XP;  // forward: row buffer / output tile
+  static constexpr size_t two_tiles = static_cast<size_t>(D) * (XP > 2 * GP ? XP : 2 * GP);
   static constexpr size_t region_bytes =                           // backward
-      static_cast<size_t>(D) * (XP > 2 * GP ? XP : 2 * GP) > static_cast<size_t>(RW) * PF * 4
-          ? static_cast<size_t>(D) * (XP > 2 * GP ? XP : 2 * GP)
-          : static_cast<size_t>(RW) * PF * 4;
+      !GW_INLINE ? xf_bytes
+                 : (two_tiles > static_cast<size_t>(RW) * PF * 4 ? two_tiles : static_cast<size_t>(RW) * PF * 4);
+  // the fp32 gradient rows of the embedding pass through the region whole, or in two halves
+  static constexpr int SP = static_cast<size_t>(RW) * PF * 4 <= region_bytes ? 1 : 2;
+  static constexpr int RS = RW / SP;
+  static_assert(static_cast<size_t>(RS) * PF * 4 <= region_bytes, "staging of the embedding gradient");
   static constexpr size_t wts_bytes = static_cast<size_t>(SE) * 4;  // hi halves, then lo halves
   static constexpr size_t ot_bytes = static_cast<size_t>(RW) * PA * 2;
   // the output tile reuses the row buffer: the step's fragments are in registers by then
   static constexpr size_t wave_bytes = xf_bytes + wts_bytes;
   static constexpr size_t bwd_wave_bytes = region_bytes + wts_bytes;
-  static_assert(ot_bytes <= xf_bytes, "the output tile overlays the row buffer");
+  static_assert(ot_bytes <= xf_bytes && ot_bytes <= region_bytes, "the output tile overlays the row buffer");
   static constexpr size_t w_bytes = static_cast<size_t>(D) * D * 2;
   static_assert(SE <= 64, "slot masks are 64 bits wide");
   static_assert(wave_bytes % 16 == 0 && w_bytes % 16 == 0 && XP % 16 == 0, "alignment");
@@ -538,20 +546,23 @@ constexpr size_t bwd_wave_lds() {
 // light stream);  gW partial = sum over the workgroup's rows of Hprev^T G_T;
 // G_Hprev = G_T W^T;  then GZ_out = G_Hprev * [Hprev > 0], or, on the embedding
 // (TO_EMBED), Adam on E / writing the gradient.
-// Per tile, in the wave's LDS region: G_T (bf16) and Hprev, both transposed to
-// [feature][row], feed the weight-gradient product (contraction over the 32 rows);
-// the rounded G_T^T in registers is the B operand of G_H^T = W G_T^T; the result is
-// staged once more to reach full rows.  Hprev rows of the next tile are requested
-// while the current one is finished.
+// Width 64, per tile, in the wave's LDS region: G_T (bf16) and Hprev, both transposed to
+// [feature][row], feed the weight-gradient product (contraction over the 32 rows).
+// Width 128: the rows of G_T (bf16) are stored to a.GT instead and grad_w_wave_kernel
+// forms the weight gradient.  The rounded G_T^T in registers is the B operand of
+// G_H^T = W G_T^T; the result is staged once more to reach full rows.  Hprev rows of the
+// next tile are requested while the current one is finished.
 // ---------------------------------------------------------------------------
 template <int D, bool TO_EMBED>
 __global__ __launch_bounds__(kBlock, 2) void bwd_wave_kernel(GraphView g, BwdArgs a) {
   using G_ = WG<D>;
+  constexpr bool GWI = G_::GW_INLINE;
+  constexpr bool NEED_HP = GWI || !TO_EMBED;  // Hprev: operand of the weight gradient, ReLU mask
   extern __shared__ __align__(16) unsigned char smem[];
   bf16_t* wfr = reinterpret_cast<bf16_t*>(smem);
   uint4* pair_mask = reinterpret_cast<uint4*>(smem + G_::w_bytes);
   unsigned char* wave_mem = reinterpret_cast<unsigned char*>(pair_mask + 256);
-  static_assert(4 * G_::bwd_wave_bytes >= 2 * D * D * sizeof(float), "room for the gradient reduction");
+  static_assert(!GWI || 4 * G_::bwd_wave_bytes >= 2 * D * D * sizeof(float), "room for the gradient reduction");
 
   constexpr int WM = TO_EMBED ? WM_EMBED : WM_BWD;
   const int k = g.wblk_k[WM][blockIdx.x];
@@ -570,31 +581,33 @@ __global__ __launch_bounds__(kBlock, 2) void bwd_wave_kernel(GraphView g, BwdArg
   const int2 tiles = g.wwave_tiles[WM][blockIdx.x * (kBlock / 64) + wave];
   unsigned char* R = wave_mem + wave * G_::bwd_wave_bytes;
   const bool need_gh = !(TO_EMBED && a.mode == EMBED_SKIP);
-  floatx16 gw[G_::NT][G_::NT];
+  constexpr int NTW = GWI ? G_::NT : 1;
+  floatx16 gw[NTW][NTW];
 #pragma unroll
-  for (int ta = 0; ta < G_::NT; ++ta)
+  for (int ta = 0; ta < NTW; ++ta)
 #pragma unroll
-    for (int tb = 0; tb < G_::NT; ++tb)
+    for (int tb = 0; tb < NTW; ++tb)
 #pragma unroll
       for (int r = 0; r < 16; ++r) gw[ta][tb][r] = 0.f;
 
   if (tiles.x < tiles.y) {
     const int rbeg = g.part_rows[k];
     const int row_end = min(g.part_rows[k + 1], rbeg + tiles.y * RW);
-    // rows 4 grp + u (u = 0..3) of a tile, features 8 sub .. + 7: what this lane loads of
+    // rows RPL grp + u (u < RPL) of a tile, features 8 sub .. + 7: what this lane loads of
     // Hprev and what it stores of the result
     constexpr int RPL = RW / G_::NG;
-    uint4 hp_raw[RPL];
+    uint4 hp_raw[NEED_HP ? RPL : 1];
     auto request_hprev = [&](int row0) {
+      if (NEED_HP) {
 #pragma unroll
-      for (int u = 0; u < RPL; ++u) {
-        const int r = row0 + RPL * grp + u;
-        hp_raw[u] = make_uint4(0u, 0u, 0u, 0u);
-        if (r < row_end) hp_raw[u] = load_streamed(Hprev + static_cast<size_t>(r) * D + sub * 8);
+        for (int u = 0; u < RPL; ++u) {
+          const int r = row0 + RPL * grp + u;
+          hp_raw[u] = make_uint4(0u, 0u, 0u, 0u);
+          if (r < row_end) hp_raw[u] = load_streamed(Hprev + static_cast<size_t>(r) * D + sub * 8);
+        }
       }
     };
     request_hprev(rbeg + tiles.x * RW);
-    static_assert(RPL == 4, "four rows per lane group");
 
     stream_tiles<D>(g, g.went, GZ, k, tiles.x, tiles.y, R, reinterpret_cast<uint32_t*>(R + G_::region_bytes),
                     pair_mask, a.heavy_partial,
@@ -608,46 +621,70 @@ __global__ __launch_bounds__(kBlock, 2) void bwd_wave_kernel(GraphView g, BwdArg
         for (int e = 0; e < 8; ++e) v[e] = agg[ks2 / 2][8 * (ks2 % 2) + e];
         bq[ks2] = pack8(v);
       }
-      // G_T and Hprev as [feature][row]
-      unsigned char* gtl = R;
-      unsigned char* hpl = R + D * G_::GP;
+      if constexpr (GWI) {
+        static_assert(!GWI || RPL == 4, "four rows per lane group");
+        // G_T and Hprev as [feature][row]
+        unsigned char* gtl = R;
+        unsigned char* hpl = R + D * G_::GP;
 #pragma unroll
-      for (int ks2 = 0; ks2 < G_::KS2; ++ks2)
+        for (int ks2 = 0; ks2 < G_::KS2; ++ks2)
 #pragma unroll
-        for (int d = 0; d < 4; ++d) {
-          const int f = feature_of(ks2, 0, 2 * d) + 4 * h;
-          const uint32_t w = (&bq[ks2].x)[d];
-          *reinterpret_cast<uint16_t*>(gtl + f * G_::GP + n * 2) = static_cast<uint16_t>(w & 0xffffu);
-          *reinterpret_cast<uint16_t*>(gtl + (f + 1) * G_::GP + n * 2) = static_cast<uint16_t>(w >> 16);
+          for (int d = 0; d < 4; ++d) {
+            const int f = feature_of(ks2, 0, 2 * d) + 4 * h;
+            const uint32_t w = (&bq[ks2].x)[d];
+            *reinterpret_cast<uint16_t*>(gtl + f * G_::GP + n * 2) = static_cast<uint16_t>(w & 0xffffu);
+            *reinterpret_cast<uint16_t*>(gtl + (f + 1) * G_::GP + n * 2) = static_cast<uint16_t>(w >> 16);
+          }
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          const uint32_t x0 = (&hp_raw[0].x)[i / 2], x1 = (&hp_raw[1 % RPL].x)[i / 2];
+          const uint32_t x2 = (&hp_raw[2 % RPL].x)[i / 2], x3 = (&hp_raw[3 % RPL].x)[i / 2];
+          uint2 d;
+          d.x = (i % 2 == 0) ? lower_halves(x0, x1) : upper_halves(x0, x1);
+          d.y = (i % 2 == 0) ? lower_halves(x2, x3) : upper_halves(x2, x3);
+          // 16-byte groups rotated by feature / 8 (LDS banks, as for the row buffer)
+          *reinterpret_cast<uint2*>(hpl + (sub * 8 + i) * G_::GP + ((grp / 2 + sub) % 4) * 16 + (grp % 2) * 8) = d;
         }
+        wave_lds_handoff();
+        // gW[a, b] += sum over the tile's rows of Hprev[row, a] G_T[row, b]
 #pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        const uint32_t x0 = (&hp_raw[0].x)[i / 2], x1 = (&hp_raw[1].x)[i / 2];
-        const uint32_t x2 = (&hp_raw[2].x)[i / 2], x3 = (&hp_raw[3].x)[i / 2];
-        uint2 d;
-        d.x = (i % 2 == 0) ? lower_halves(x0, x1) : upper_halves(x0, x1);
-        d.y = (i % 2 == 0) ? lower_halves(x2, x3) : upper_halves(x2, x3);
-        // 16-byte groups rotated by feature / 8 (LDS banks, as for the row buffer)
-        *reinterpret_cast<uint2*>(hpl + (sub * 8 + i) * G_::GP + ((grp / 2 + sub) % 4) * 16 + (grp % 2) * 8) = d;
-      }
-      wave_lds_handoff();
-      // gW[a, b] += sum over the tile's rows of Hprev[row, a] G_T[row, b]
+        for (int ks = 0; ks < RW / 16; ++ks) {
+          bf16x8 af[G_::NT], bf[G_::NT];
 #pragma unroll
-      for (int ks = 0; ks < RW / 16; ++ks) {
-        bf16x8 af[G_::NT], bf[G_::NT];
+          for (int t = 0; t < G_::NT; ++t) {
+            af[t] = as_frag(*reinterpret_cast<const uint4*>(hpl + (32 * t + n) * G_::GP +
+                                                            ((2 * ks + h + (32 * t + n) / 8) % 4) * 16));
+            bf[t] = as_frag(*reinterpret_cast<const uint4*>(gtl + (32 * t + n) * G_::GP + (16 * ks + 8 * h) * 2));
+          }
 #pragma unroll
-        for (int t = 0; t < G_::NT; ++t) {
-          af[t] = as_frag(*reinterpret_cast<const uint4*>(hpl + (32 * t + n) * G_::GP +
-                                                          ((2 * ks + h + (32 * t + n) / 8) % 4) * 16));
-          bf[t] = as_frag(*reinterpret_cast<const uint4*>(gtl + (32 * t + n) * G_::GP + (16 * ks + 8 * h) * 2));
+          for (int ta = 0; ta < NTW; ++ta)
+#pragma unroll
+            for (int tb = 0; tb < NTW; ++tb)
+              gw[ta][tb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[ta], bf[tb], gw[ta][tb], 0, 0, 0);
         }
+        wave_lds_handoff();
+      } else {
+        // the rows of G_T go to memory: lane (n, h) holds, per contraction step, features
+        // feature_of(ks2, h, 0..3) and feature_of(ks2, h, 4..7) of row n
+        bf16_t* ot = reinterpret_cast<bf16_t*>(R);
 #pragma unroll
-        for (int ta = 0; ta < G_::NT; ++ta)
+        for (int ks2 = 0; ks2 < G_::KS2; ++ks2) {
+          *reinterpret_cast<uint2*>(ot + n * G_::PA + feature_of(ks2, 0, 0) + 4 * h) =
+              make_uint2(bq[ks2].x, bq[ks2].y);
+          *reinterpret_cast<uint2*>(ot + n * G_::PA + feature_of(ks2, 0, 4) + 4 * h) =
+              make_uint2(bq[ks2].z, bq[ks2].w);
+        }
+        wave_lds_handoff();
+        bf16_t* GT = static_cast<bf16_t*>(a.GT);
 #pragma unroll
-          for (int tb = 0; tb < G_::NT; ++tb)
-            gw[ta][tb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[ta], bf[tb], gw[ta][tb], 0, 0, 0);
+        for (int u = 0; u < RPL; ++u) {
+          const int r = RPL * grp + u;
+          if (r < nrows)
+            store_streamed(GT + static_cast<size_t>(row0 + r) * D + sub * 8,
+                           *reinterpret_cast<const uint4*>(ot + r * G_::PA + sub * 8));
+        }
+        wave_lds_handoff();
       }
-      wave_lds_handoff();
       if (need_gh) {
         // G_H^T = W G_T^T
         floatx16 z[G_::NT];
@@ -664,76 +701,84 @@ __global__ __launch_bounds__(kBlock, 2) void bwd_wave_kernel(GraphView g, BwdArg
             z[ta] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wa, as_frag(bq[ks2]), z[ta], 0, 0, 0);
           }
         if (TO_EMBED) {
-          // full fp32 rows through the region, then Adam (or the plain gradient)
+          // full fp32 rows through the region (RS rows at a time), then Adam (or the plain
+          // gradient)
           float* st = reinterpret_cast<float*>(R);
-#pragma unroll
-          for (int ta = 0; ta < G_::NT; ++ta)
-#pragma unroll
-            for (int i = 0; i < 4; ++i)
-              *reinterpret_cast<float4*>(st + n * G_::PF + acc_feature(ta, 0, 4 * i) + 4 * h) =
-                  make_float4(z[ta][4 * i], z[ta][4 * i + 1], z[ta][4 * i + 2], z[ta][4 * i + 3]);
-          wave_lds_handoff();
-          constexpr int LR = D / 4;        // lanes per fp32 row
-          constexpr int RI = 64 / LR;      // rows per instruction
-          constexpr int NQ = RW / RI;      // instructions per tile and tensor
+          constexpr int LR = D / 4;          // lanes per fp32 row
+          constexpr int RI = 64 / LR;        // rows per instruction
+          constexpr int NQ = G_::RS / RI;    // instructions per pass and tensor
+          constexpr int HB = 4;              // rows of state requested at once, per lane
+          static_assert(NQ % HB == 0, "whole groups of requests");
           const int rr = lane / LR, cc = (lane % LR) * 4;
-          if (a.mode == EMBED_WRITE_GRAD) {
 #pragma unroll
-            for (int q = 0; q < NQ; ++q) {
-              const int r = q * RI + rr;
-              if (r < nrows)
-                *reinterpret_cast<float4*>(a.gE + static_cast<size_t>(row0 + r) * D + cc) =
-                    *reinterpret_cast<const float4*>(st + r * G_::PF + cc);
+          for (int sp = 0; sp < G_::SP; ++sp) {
+            if (n / G_::RS == sp) {
+#pragma unroll
+              for (int ta = 0; ta < G_::NT; ++ta)
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+                  *reinterpret_cast<float4*>(st + (n % G_::RS) * G_::PF + acc_feature(ta, 0, 4 * i) + 4 * h) =
+                      make_float4(z[ta][4 * i], z[ta][4 * i + 1], z[ta][4 * i + 2], z[ta][4 * i + 3]);
             }
-          } else {
-            // the state of half a tile is requested at once, so that the loads overlap
-            float* __restrict__ pE = a.E;
-            float* __restrict__ pM = a.mE;
-            float* __restrict__ pV = a.vE;
-            bf16_t* __restrict__ pB = static_cast<bf16_t*>(a.Eb);
-            constexpr int HB = NQ / 2;
+            wave_lds_handoff();
+            if (a.mode == EMBED_WRITE_GRAD) {
 #pragma unroll
-            for (int half = 0; half < 2; ++half) {
-              float4 e0[HB], m0[HB], v0[HB];
-#pragma unroll
-              for (int q = 0; q < HB; ++q) {
-                const int r = (half * HB + q) * RI + rr;
-                const size_t off = static_cast<size_t>(row0 + min(r, nrows - 1)) * D + cc;
-                m0[q] = load_streamed(pM + off);
-                v0[q] = load_streamed(pV + off);
-                e0[q] = load_streamed(pE + off);
+              for (int q = 0; q < NQ; ++q) {
+                const int r = sp * G_::RS + q * RI + rr;
+                if (r < nrows)
+                  *reinterpret_cast<float4*>(a.gE + static_cast<size_t>(row0 + r) * D + cc) =
+                      *reinterpret_cast<const float4*>(st + (q * RI + rr) * G_::PF + cc);
               }
+            } else {
+              // the state of HB * RI rows is requested at once, so that the loads overlap
+              float* __restrict__ pE = a.E;
+              float* __restrict__ pM = a.mE;
+              float* __restrict__ pV = a.vE;
+              bf16_t* __restrict__ pB = static_cast<bf16_t*>(a.Eb);
 #pragma unroll
-              for (int q = 0; q < HB; ++q) {
-                const int r = (half * HB + q) * RI + rr;
-                const float4 gq = *reinterpret_cast<const float4*>(st + r * G_::PF + cc);
-                const size_t off = static_cast<size_t>(row0 + r) * D + cc;
-                const float gv[4] = {gq.x, gq.y, gq.z, gq.w};
-                const float mv[4] = {m0[q].x, m0[q].y, m0[q].z, m0[q].w};
-                const float vv[4] = {v0[q].x, v0[q].y, v0[q].z, v0[q].w};
-                const float ev[4] = {e0[q].x, e0[q].y, e0[q].z, e0[q].w};
-                float mo[4], vo[4], eo[4];
+              for (int part = 0; part < NQ / HB; ++part) {
+                float4 e0[HB], m0[HB], v0[HB];
 #pragma unroll
-                for (int x = 0; x < 4; ++x) {
-                  mo[x] = ad.b1 * mv[x] + (1.f - ad.b1) * gv[x];
-                  vo[x] = ad.b2 * vv[x] + (1.f - ad.b2) * gv[x] * gv[x];
-                  // v_sqrt_f32 and v_rcp_f32: 1 ulp each
-                  const float upd = (mo[x] * ad.inv_bc1) *
-                                    __builtin_amdgcn_rcpf(__builtin_amdgcn_sqrtf(vo[x]) * ad.inv_sqrt_bc2 +
-                                                          ad.eps);
-                  eo[x] = ev[x] - ad.lr * upd;
+                for (int q = 0; q < HB; ++q) {
+                  const int r = sp * G_::RS + (part * HB + q) * RI + rr;
+                  const size_t off = static_cast<size_t>(row0 + min(r, nrows - 1)) * D + cc;
+                  m0[q] = load_streamed(pM + off);
+                  v0[q] = load_streamed(pV + off);
+                  e0[q] = load_streamed(pE + off);
                 }
-                if (r < nrows) {
-                  store_streamed(pM + off, mo[0], mo[1], mo[2], mo[3]);
-                  store_streamed(pV + off, vo[0], vo[1], vo[2], vo[3]);
-                  store_streamed(pE + off, eo[0], eo[1], eo[2], eo[3]);
-                  uint2 eb;
-                  eb.x = f32x2_to_bf16x2(eo[0], eo[1]);
-                  eb.y = f32x2_to_bf16x2(eo[2], eo[3]);
-                  *reinterpret_cast<uint2*>(pB + off) = eb;
+#pragma unroll
+                for (int q = 0; q < HB; ++q) {
+                  const int rl = (part * HB + q) * RI + rr, r = sp * G_::RS + rl;
+                  const float4 gq = *reinterpret_cast<const float4*>(st + rl * G_::PF + cc);
+                  const size_t off = static_cast<size_t>(row0 + r) * D + cc;
+                  const float gv[4] = {gq.x, gq.y, gq.z, gq.w};
+                  const float mv[4] = {m0[q].x, m0[q].y, m0[q].z, m0[q].w};
+                  const float vv[4] = {v0[q].x, v0[q].y, v0[q].z, v0[q].w};
+                  const float ev[4] = {e0[q].x, e0[q].y, e0[q].z, e0[q].w};
+                  float mo[4], vo[4], eo[4];
+#pragma unroll
+                  for (int x = 0; x < 4; ++x) {
+                    mo[x] = ad.b1 * mv[x] + (1.f - ad.b1) * gv[x];
+                    vo[x] = ad.b2 * vv[x] + (1.f - ad.b2) * gv[x] * gv[x];
+                    // v_sqrt_f32 and v_rcp_f32: 1 ulp each
+                    const float upd = (mo[x] * ad.inv_bc1) *
+                                      __builtin_amdgcn_rcpf(__builtin_amdgcn_sqrtf(vo[x]) * ad.inv_sqrt_bc2 +
+                                                            ad.eps);
+                    eo[x] = ev[x] - ad.lr * upd;
+                  }
+                  if (r < nrows) {
+                    store_streamed(pM + off, mo[0], mo[1], mo[2], mo[3]);
+                    store_streamed(pV + off, vo[0], vo[1], vo[2], vo[3]);
+                    store_streamed(pE + off, eo[0], eo[1], eo[2], eo[3]);
+                    uint2 eb;
+                    eb.x = f32x2_to_bf16x2(eo[0], eo[1]);
+                    eb.y = f32x2_to_bf16x2(eo[2], eo[3]);
+                    *reinterpret_cast<uint2*>(pB + off) = eb;
+                  }
                 }
               }
             }
+            if (sp + 1 < G_::SP) wave_lds_handoff();  // the next rows overwrite the staging area
           }
         } else {
           // GZ_out = G_Hprev * [Hprev > 0]: full bf16 rows through the region
@@ -753,10 +798,10 @@ __global__ __launch_bounds__(kBlock, 2) void bwd_wave_kernel(GraphView g, BwdArg
           for (int u = 0; u < RPL; ++u) {
             const int r = RPL * grp + u;
             uint4 o = *reinterpret_cast<const uint4*>(ot + r * G_::PA + sub * 8);
-            o.x = keep_where_positive(o.x, hp_raw[u].x);
-            o.y = keep_where_positive(o.y, hp_raw[u].y);
-            o.z = keep_where_positive(o.z, hp_raw[u].z);
-            o.w = keep_where_positive(o.w, hp_raw[u].w);
+            o.x = keep_where_positive(o.x, hp_raw[NEED_HP ? u : 0].x);
+            o.y = keep_where_positive(o.y, hp_raw[NEED_HP ? u : 0].y);
+            o.z = keep_where_positive(o.z, hp_raw[NEED_HP ? u : 0].z);
+            o.w = keep_where_positive(o.w, hp_raw[NEED_HP ? u : 0].w);
             if (r < nrows) store_streamed(GZo + static_cast<size_t>(row0 + r) * D + sub * 8, o);
           }
         }
@@ -766,26 +811,145 @@ __global__ __launch_bounds__(kBlock, 2) void bwd_wave_kernel(GraphView g, BwdArg
     });
   }
 
-  // weight-gradient partial of the workgroup: (wave 0 + wave 2) + (wave 1 + wave 3)
-  __syncthreads();
-  float* buf = reinterpret_cast<float*>(wave_mem);
-  for (int pass = 0; pass < 2; ++pass) {
-    if (wave / 2 == pass) {
-      float* b = buf + (wave % 2) * D * D;
+  if constexpr (GWI) {
+    // weight-gradient partial of the workgroup: (wave 0 + wave 2) + (wave 1 + wave 3)
+    __syncthreads();
+    float* buf = reinterpret_cast<float*>(wave_mem);
+    for (int pass = 0; pass < 2; ++pass) {
+      if (wave / 2 == pass) {
+        float* b = buf + (wave % 2) * D * D;
+#pragma unroll
+        for (int ta = 0; ta < NTW; ++ta)
+#pragma unroll
+          for (int tb = 0; tb < NTW; ++tb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+              float* p = b + acc_feature(ta, h, r) * D + 32 * tb + n;
+              *p = pass == 0 ? gw[ta][tb][r] : *p + gw[ta][tb][r];
+            }
+      }
+      __syncthreads();
+    }
+    float* out = a.gW_partial + static_cast<size_t>(blockIdx.x) * D * D;
+    for (int idx = tid; idx < D * D; idx += kBlock) out[idx] = buf[idx] + buf[D * D + idx];
+  }
+}
+
+// ---------------------------------------------------------------------------
+// Weight gradient of a hidden layer of width 128, from stored rows:
+//   gW partial[workgroup] = sum over the workgroup's rows of Hprev[row, :]^T GT[row, :].
+// Same decomposition as the hidden backward kernel (a wavefront owns a run of 32-row
+// tiles).  Per tile both operands are loaded as full rows (16 bytes per lane, 8 rows per
+// lane), transposed in the lane and parked in LDS as [feature][row]; the contraction over
+// the 32 rows runs on the matrix cores.  The D*D/64 = 256 accumulator registers per lane
+// leave room for one wavefront per SIMD; the next tile's rows are requested before the
+// products of the current one.  The four wavefronts' sums are added in order at the end.
+// ---------------------------------------------------------------------------
+template <int D>
+constexpr size_t grad_w_lds() {
+  return 4 * 2 * static_cast<size_t>(D) * WG<D>::GP;
+}
+
+template <int D>
+__global__ __launch_bounds__(kBlock, 1) void grad_w_wave_kernel(GraphView g, const bf16_t* __restrict__ Hprev,
+                                                                const bf16_t* __restrict__ GT,
+                                                                float* __restrict__ gW_partial) {
+  using G_ = WG<D>;
+  static_assert(RW / G_::NG == 8 && G_::NG == 4, "8 rows per lane, four 16-byte row groups per feature");
+  static_assert(grad_w_lds<D>() >= static_cast<size_t>(D) * D * sizeof(float), "room for the reduction");
+  extern __shared__ __align__(16) unsigned char smem[];
+  const int k = g.wblk_k[WM_BWD][blockIdx.x];
+  if (k < 0) return;
+  const int tid = threadIdx.x, lane = tid % 64;
+  const int wave = __builtin_amdgcn_readfirstlane(tid / 64);
+  const int n = lane % 32, h = lane / 32;
+  const int grp = lane / G_::LPR, sub = lane % G_::LPR;
+  const int2 tiles = g.wwave_tiles[WM_BWD][blockIdx.x * (kBlock / 64) + wave];
+  unsigned char* hl = smem + wave * (2 * D * G_::GP);
+  unsigned char* gl = hl + D * G_::GP;
+  floatx16 acc[G_::NT][G_::NT];
+#pragma unroll
+  for (int ta = 0; ta < G_::NT; ++ta)
+#pragma unroll
+    for (int tb = 0; tb < G_::NT; ++tb)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[ta][tb][r] = 0.f;
+
+  if (tiles.x < tiles.y) {
+    const int rbeg = g.part_rows[k];
+    const int row_end = min(g.part_rows[k + 1], rbeg + tiles.y * RW);
+    uint4 hr[8], gr[8];
+    auto request = [&](int row0) {
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        const int r = row0 + 8 * grp + u;
+        hr[u] = make_uint4(0u, 0u, 0u, 0u);
+        gr[u] = make_uint4(0u, 0u, 0u, 0u);
+        if (r < row_end) {
+          hr[u] = load_streamed(Hprev + static_cast<size_t>(r) * D + sub * 8);
+          gr[u] = load_streamed(GT + static_cast<size_t>(r) * D + sub * 8);
+        }
+      }
+    };
+    // rows 8 grp .. + 7 x features 8 sub .. + 7 of a tile -> [feature][row], the 16-byte row
+    // groups of a feature rotated by feature / 8 (LDS banks)
+    auto park = [&](const uint4 (&raw)[8], unsigned char* dst) {
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        uint32_t d[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const uint32_t x = (&raw[2 * q].x)[i / 2], y = (&raw[2 * q + 1].x)[i / 2];
+          d[q] = (i % 2 == 0) ? lower_halves(x, y) : upper_halves(x, y);
+        }
+        *reinterpret_cast<uint4*>(dst + (sub * 8 + i) * G_::GP + ((grp + sub) % 4) * 16) =
+            make_uint4(d[0], d[1], d[2], d[3]);
+      }
+    };
+    request(rbeg + tiles.x * RW);
+    for (int tau = tiles.x; tau < tiles.y; ++tau) {
+      park(hr, hl);
+      park(gr, gl);
+      request(rbeg + (tau + 1) * RW);  // rows past the wavefront's run read as zero
+      wave_lds_handoff();
+#pragma unroll
+      for (int ks = 0; ks < RW / 16; ++ks) {
+        bf16x8 af[G_::NT], bf[G_::NT];
+#pragma unroll
+        for (int t = 0; t < G_::NT; ++t) {
+          const int off = (32 * t + n) * G_::GP + ((2 * ks + h + (32 * t + n) / 8) % 4) * 16;
+          af[t] = as_frag(*reinterpret_cast<const uint4*>(hl + off));
+          bf[t] = as_frag(*reinterpret_cast<const uint4*>(gl + off));
+        }
+#pragma unroll
+        for (int ta = 0; ta < G_::NT; ++ta)
+#pragma unroll
+          for (int tb = 0; tb < G_::NT; ++tb)
+            acc[ta][tb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[ta], bf[tb], acc[ta][tb], 0, 0, 0);
+      }
+      wave_lds_handoff();
+    }
+  }
+
+  // ((wave 0 + wave 1) + wave 2) + wave 3
+  float* buf = reinterpret_cast<float*>(smem);
+  for (int w = 0; w < kBlock / 64; ++w) {
+    __syncthreads();
+    if (wave == w) {
 #pragma unroll
       for (int ta = 0; ta < G_::NT; ++ta)
 #pragma unroll
         for (int tb = 0; tb < G_::NT; ++tb)
 #pragma unroll
           for (int r = 0; r < 16; ++r) {
-            float* p = b + acc_feature(ta, h, r) * D + 32 * tb + n;
-            *p = pass == 0 ? gw[ta][tb][r] : *p + gw[ta][tb][r];
+            float* p = buf + acc_feature(ta, h, r) * D + 32 * tb + n;
+            *p = w == 0 ? acc[ta][tb][r] : *p + acc[ta][tb][r];
           }
     }
-    __syncthreads();
   }
-  float* out = a.gW_partial + static_cast<size_t>(blockIdx.x) * D * D;
-  for (int idx = tid; idx < D * D; idx += kBlock) out[idx] = buf[idx] + buf[D * D + idx];
+  __syncthreads();
+  float* out = gW_partial + static_cast<size_t>(blockIdx.x) * D * D;
+  for (int idx = tid; idx < D * D; idx += kBlock) out[idx] = buf[idx];
 }
 
 template <typename K>
@@ -798,26 +962,44 @@ void allow_lds(K kernel, size_t bytes) {
 }  // namespace
 
 void launch_form_gz_last(const Launch& ln, int D, const GraphView& g, const BwdArgs& a) {
-  if (D != 64) return;
   ln.begin(KK_FORM_GZ);
-  form_gz_last_kernel<64><<<g.num_nblocks, kBlock, 0, ln.st>>>(
-      g, static_cast<const bf16_t*>(a.Hcur), a.g_t, a.w_out, a.wout_stride, static_cast<bf16_t*>(a.GZ_last),
-      a.gwout_partial);
+  if (D == 64)
+    form_gz_last_kernel<64><<<g.num_nblocks, kBlock, 0, ln.st>>>(
+        g, static_cast<const bf16_t*>(a.Hcur), a.g_t, a.w_out, a.wout_stride, static_cast<bf16_t*>(a.GZ_last),
+        a.gwout_partial);
+  else if (D == 128)
+    form_gz_last_kernel<128><<<g.num_nblocks, kBlock, 0, ln.st>>>(
+        g, static_cast<const bf16_t*>(a.Hcur), a.g_t, a.w_out, a.wout_stride, static_cast<bf16_t*>(a.GZ_last),
+        a.gwout_partial);
   ln.end(KK_FORM_GZ);
 }
 
-void launch_bwd_hidden_wave(const Launch& ln, int D, bool to_embed, const GraphView& gt, const BwdArgs& a) {
-  if (D != 64) return;
+template <int D>
+static void bwd_wave_t(const Launch& ln, bool to_embed, const GraphView& gt, const BwdArgs& a) {
   const int kind = to_embed ? KK_BWD_EMBED : KK_BWD_HIDDEN;
   ln.begin(kind);
   if (to_embed) {
-    allow_lds(bwd_wave_kernel<64, true>, bwd_wave_lds<64>());
-    bwd_wave_kernel<64, true><<<gt.num_wblocks[WM_EMBED], kBlock, bwd_wave_lds<64>(), ln.st>>>(gt, a);
+    allow_lds(bwd_wave_kernel<D, true>, bwd_wave_lds<D>());
+    bwd_wave_kernel<D, true><<<gt.num_wblocks[WM_EMBED], kBlock, bwd_wave_lds<D>(), ln.st>>>(gt, a);
   } else {
-    allow_lds(bwd_wave_kernel<64, false>, bwd_wave_lds<64>());
-    bwd_wave_kernel<64, false><<<gt.num_wblocks[WM_BWD], kBlock, bwd_wave_lds<64>(), ln.st>>>(gt, a);
+    allow_lds(bwd_wave_kernel<D, false>, bwd_wave_lds<D>());
+    bwd_wave_kernel<D, false><<<gt.num_wblocks[WM_BWD], kBlock, bwd_wave_lds<D>(), ln.st>>>(gt, a);
   }
   ln.end(kind);
+}
+
+void launch_bwd_hidden_wave(const Launch& ln, int D, bool to_embed, const GraphView& gt, const BwdArgs& a) {
+  if (D == 64) {
+    bwd_wave_t<64>(ln, to_embed, gt, a);
+  } else if (D == 128) {
+    bwd_wave_t<128>(ln, to_embed, gt, a);
+    // the weight gradient from the stored rows of G_T
+    allow_lds(grad_w_wave_kernel<128>, grad_w_lds<128>());
+    ln.begin(KK_GRAD_W);
+    grad_w_wave_kernel<128><<<gt.num_wblocks[WM_BWD], kBlock, grad_w_lds<128>(), ln.st>>>(
+        gt, static_cast<const bf16_t*>(a.Hprev), static_cast<const bf16_t*>(a.GT), a.gW_partial);
+    ln.end(KK_GRAD_W);
+  }
 }
 
 void launch_fwd_hidden_wave(const Launch& ln, int D, const GraphView& g, const void* X, const float* W,
