@@ -1206,7 +1206,10 @@ static void run_backward(gco_ctx* ctx, const GraphView& gv, const gco_ctx::Activ
     wt[l - 1].blk_ptr = !wave ? maps.pbl_ptr : (l < L ? maps.wpbl_ptr[wm] : maps.nwbl_ptr);
     wt[l - 1].blk_list = !wave ? maps.pbl_list : (l < L ? maps.wpbl_list[wm] : maps.nwbl_list);
   }
-  launch_adam_w(ln, ctx->Pw, wt, L, adW, update);
+  const int writers = (ctx->wave_path() && L >= 2)
+                          ? std::max({gv.num_wblocks[WM_BWD], gv.num_wblocks[WM_EMBED], gv.num_nblocks})
+                          : gv.num_blocks;
+  launch_adam_w(ln, ctx->Pw, wt, L, adW, update, /*many_partials=*/writers / ctx->Pw >= 512);
   if (update) ctx->probs_valid = true;  // p is that of the parameters before the step
 }
 

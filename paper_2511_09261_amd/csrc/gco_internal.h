@@ -278,8 +278,10 @@ struct WeightTensor {
   float* grad_out = nullptr;       // [Pw, elems] or nullptr
   int elems = 0;                   // per subgraph
 };
+// many_partials: few weight sets with hundreds of partials each; the sum over a set's
+// partials is then shared by 16 wavefronts per 64 weights.
 void launch_adam_w(const Launch& ln, int Pw, const WeightTensor* tensors, int count, const AdamStep& adam,
-                   bool update);  // adam.per_part, if set, is indexed by weight set; sets without partials are left alone
+                   bool update, bool many_partials);  // adam.per_part, if set, is indexed by weight set; sets without partials are left alone
 
 // fp32 -> bf16 copy (round to nearest even).
 void launch_to_bf16(const Launch& ln, const float* src, void* dst, int64_t count);

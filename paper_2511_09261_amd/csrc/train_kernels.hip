@@ -412,15 +412,16 @@ struct ParamCopy {
   int num_w = 0;
 };
 
-// Copies the parameters of the models with flag[u] != 0.  blockIdx.y < P: the embedding
-// rows of subgraph y (row width D floats, D % 4 == 0); blockIdx.y = P + l: weight tensor l
-// of every flagged model.  The workgroups of one y share the work in a strided loop, four
-// 16-byte accesses in flight per lane; the embedding is read and written past the caches.
+// Copies the parameters of the models with flag[u] != 0.  blockIdx.x < P: the embedding
+// rows of subgraph x (row width D floats, D % 4 == 0); blockIdx.x = P + l: weight tensor l
+// of every flagged model.  The gridDim.y workgroups of one x share the work in a strided
+// loop, four 16-byte accesses in flight per lane; the embedding is read and written past
+// the caches.
 __global__ __launch_bounds__(kBlock) void param_copy_kernel(GraphView g, int models, int D,
                                                             const int* __restrict__ flag, ParamCopy c) {
-  const int y = blockIdx.y;
-  const int64_t stride = static_cast<int64_t>(gridDim.x) * kBlock;
-  const int64_t first = static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x;
+  const int y = blockIdx.x;
+  const int64_t stride = static_cast<int64_t>(gridDim.y) * kBlock;
+  const int64_t first = static_cast<int64_t>(blockIdx.y) * kBlock + threadIdx.x;
   if (y < g.P) {
     if (!flag[models == 1 ? 0 : y]) return;
     const int64_t i0 = static_cast<int64_t>(g.part_rows[y]) * (D / 4);
@@ -457,40 +458,39 @@ struct WeightTensors {
   int count = 0;
 };
 
-// One thread per weight of every tensor.  The partials are added in groups of 16
-// (pairwise inside a group, groups in list order) so that 16 loads are in flight.
-__global__ __launch_bounds__(kBlock) void adam_w_kernel(int Pw, WeightTensors wts, AdamStep ad, int update) {
-  int64_t gid = static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x;
+// Which tensor, weight set and element a global element index stands for.
+struct WeightElem {
+  int which, k, idx;
+  int64_t gid;  // index inside the tensor
+};
+__device__ inline WeightElem locate_weight(int Pw, const WeightTensors& wts, int64_t gid) {
   int which = 0;
   while (which < wts.count && gid >= static_cast<int64_t>(Pw) * wts.t[which].elems) {
     gid -= static_cast<int64_t>(Pw) * wts.t[which].elems;
     ++which;
   }
-  if (which >= wts.count) return;
-  const WeightTensor& wt = wts.t[which];
-  const int k = static_cast<int>(gid / wt.elems);
-  const int idx = static_cast<int>(gid % wt.elems);
-  const float* base = wt.partial + idx;
-  const int* __restrict__ part_blk_list = wt.blk_list;
-  float gsum = 0.f;
-  int q = wt.blk_ptr[k];
-  const int q1 = wt.blk_ptr[k + 1];
-  if (q == q1) {  // no workgroup produced a gradient for this weight set: it sits out
-    if (wt.grad_out != nullptr) wt.grad_out[gid] = 0.f;
-    return;
+  WeightElem e{which, 0, 0, gid};
+  if (which < wts.count) {
+    e.k = static_cast<int>(gid / wts.t[which].elems);
+    e.idx = static_cast<int>(gid % wts.t[which].elems);
   }
-  const AdamStep adk = ad.for_part(k);
-  for (; q + 16 <= q1; q += 16) {
-    float v[16];
+  return e;
+}
+
+// Sum of 16 partials of one element, pairwise: 16 loads in flight.
+__device__ inline float sum16(const float* base, const int* __restrict__ list, int elems) {
+  float v[16];
 #pragma unroll
-    for (int u = 0; u < 16; ++u) v[u] = base[static_cast<size_t>(part_blk_list[q + u]) * wt.elems];
+  for (int u = 0; u < 16; ++u) v[u] = base[static_cast<size_t>(list[u]) * elems];
 #pragma unroll
-    for (int w = 1; w < 16; w *= 2)
+  for (int w = 1; w < 16; w *= 2)
 #pragma unroll
-      for (int u = 0; u < 16; u += 2 * w) v[u] += v[u + w];
-    gsum += v[0];
-  }
-  for (; q < q1; ++q) gsum += base[static_cast<size_t>(part_blk_list[q]) * wt.elems];
+    for (int u = 0; u < 16; u += 2 * w) v[u] += v[u + w];
+  return v[0];
+}
+
+__device__ inline void adam_on_weight(const WeightTensor& wt, int64_t gid, float gsum, const AdamStep& adk,
+                                      int update) {
   if (wt.grad_out != nullptr) wt.grad_out[gid] = gsum;
   if (update) {
     const float m = adk.b1 * wt.m[gid] + (1.f - adk.b1) * gsum;
@@ -499,6 +499,59 @@ __global__ __launch_bounds__(kBlock) void adam_w_kernel(int Pw, WeightTensors wt
     wt.v[gid] = v;
     wt.W[gid] -= adk.lr * (m * adk.inv_bc1) / (sqrtf(v) * adk.inv_sqrt_bc2 + adk.eps);
   }
+}
+
+// One thread per weight of every tensor.  The partials are added in groups of 16
+// (pairwise inside a group, groups in list order) so that 16 loads are in flight.
+__global__ __launch_bounds__(kBlock) void adam_w_kernel(int Pw, WeightTensors wts, AdamStep ad, int update) {
+  const WeightElem e = locate_weight(Pw, wts, static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x);
+  if (e.which >= wts.count) return;
+  const WeightTensor& wt = wts.t[e.which];
+  const float* base = wt.partial + e.idx;
+  float gsum = 0.f;
+  int q = wt.blk_ptr[e.k];
+  const int q1 = wt.blk_ptr[e.k + 1];
+  if (q == q1) {  // no workgroup produced a gradient for this weight set: it sits out
+    if (wt.grad_out != nullptr) wt.grad_out[e.gid] = 0.f;
+    return;
+  }
+  for (; q + 16 <= q1; q += 16) gsum += sum16(base, wt.blk_list + q, wt.elems);
+  for (; q < q1; ++q) gsum += base[static_cast<size_t>(wt.blk_list[q]) * wt.elems];
+  adam_on_weight(wt, e.gid, gsum, ad.for_part(e.k), update);
+}
+
+// The same for few weight sets with very many partials each (one subgraph holding the whole
+// graph): a workgroup of S wavefronts serves 64 weights; wavefront w adds the groups of 16
+// partials number w, w + S, ...; the S sums are then added in order, the leftover partials
+// (fewer than 16) last.
+constexpr int kAdamSplit = 16;
+__global__ __launch_bounds__(64 * kAdamSplit) void adam_w_split_kernel(int Pw, WeightTensors wts, AdamStep ad,
+                                                                       int update) {
+  __shared__ float red[kAdamSplit][64];
+  const int lane = threadIdx.x % 64, w = threadIdx.x / 64;
+  const WeightElem e = locate_weight(Pw, wts, static_cast<int64_t>(blockIdx.x) * 64 + lane);
+  const bool live = e.which < wts.count;
+  const WeightTensor& wt = wts.t[live ? e.which : 0];
+  int q0 = 0, q1 = 0;
+  if (live) {
+    q0 = wt.blk_ptr[e.k];
+    q1 = wt.blk_ptr[e.k + 1];
+  }
+  const float* base = wt.partial + e.idx;
+  const int groups = (q1 - q0) / 16;
+  float mine = 0.f;
+  for (int gq = w; gq < groups; gq += kAdamSplit) mine += sum16(base, wt.blk_list + q0 + gq * 16, wt.elems);
+  red[w][lane] = mine;
+  __syncthreads();
+  if (w != 0 || !live) return;
+  if (q0 == q1) {
+    if (wt.grad_out != nullptr) wt.grad_out[e.gid] = 0.f;
+    return;
+  }
+  float gsum = 0.f;
+  for (int u = 0; u < kAdamSplit; ++u) gsum += red[u][lane];
+  for (int q = q0 + groups * 16; q < q1; ++q) gsum += base[static_cast<size_t>(wt.blk_list[q]) * wt.elems];
+  adam_on_weight(wt, e.gid, gsum, ad.for_part(e.k), update);
 }
 
 __global__ __launch_bounds__(kBlock) void to_bf16_kernel(const float* __restrict__ src,
@@ -597,7 +650,7 @@ void launch_param_copy(const Launch& ln, const GraphView& g, int models, int D, 
   }
   const int per_part = std::max(1, (kWideBlocks + g.P - 1) / g.P);
   ln.begin(KK_BEST);
-  param_copy_kernel<<<dim3(per_part, g.P + num_w), kBlock, 0, ln.st>>>(g, models, D, flag, c);
+  param_copy_kernel<<<dim3(g.P + num_w, per_part), kBlock, 0, ln.st>>>(g, models, D, flag, c);
   ln.end(KK_BEST);
 }
 
@@ -662,7 +715,7 @@ void launch_bwd_single(const Launch& ln, int storage, int D, const GraphView& g,
 }
 
 void launch_adam_w(const Launch& ln, int Pw, const WeightTensor* tensors, int count, const AdamStep& adam,
-                   bool update) {
+                   bool update, bool many_partials) {
   WeightTensors wts;
   wts.count = count;
   int64_t total = 0;
@@ -670,9 +723,14 @@ void launch_adam_w(const Launch& ln, int Pw, const WeightTensor* tensors, int co
     wts.t[i] = tensors[i];
     total += static_cast<int64_t>(Pw) * tensors[i].elems;
   }
-  const int blocks = static_cast<int>((total + kBlock - 1) / kBlock);
   ln.begin(KK_ADAM_W);
-  adam_w_kernel<<<blocks, kBlock, 0, ln.st>>>(Pw, wts, adam, update ? 1 : 0);
+  if (many_partials) {
+    const int blocks = static_cast<int>((total + 63) / 64);
+    adam_w_split_kernel<<<blocks, 64 * kAdamSplit, 0, ln.st>>>(Pw, wts, adam, update ? 1 : 0);
+  } else {
+    const int blocks = static_cast<int>((total + kBlock - 1) / kBlock);
+    adam_w_kernel<<<blocks, kBlock, 0, ln.st>>>(Pw, wts, adam, update ? 1 : 0);
+  }
   ln.end(KK_ADAM_W);
 }
 

@@ -163,6 +163,25 @@ def test_c4_youtube_shaped_full_size(gco):
     ctx.destroy()
 
 
+@pytest.mark.timeout(600)
+def test_c4_as_one_subgraph_scaled(gco):
+    """The stress variant with nothing cut (one subgraph holds the whole graph: more and
+    longer pre-reduced rows, one weight set fed by hundreds of workgroup partials), at a
+    tenth of c4's size so that the checker's full comparison stays short."""
+    wl = inputs.make_workload("c4p1", scale=0.1)
+    print("c4p1/10", inputs.describe(wl), flush=True)
+    ctx, spec, lg, E, Ws = setup(gco, wl)
+    fixed_weight_checks(ctx, spec, lg, E, Ws)
+    got = ctx.train(5)
+    st = gcn.init_state(E, Ws)
+    want, _ = gcn.train(lg, st, spec, 5)
+    assert np.abs(got - want).max() <= 2e-2 * np.abs(want).max()
+    ctx.set_params(E, Ws)
+    np.testing.assert_array_equal(ctx.train(5), got)
+    check_readout(ctx, wl, "local")
+    ctx.destroy()
+
+
 @pytest.mark.timeout(900)
 def test_c5_regular_graph_sampled_subgraphs(gco):
     """2 M nodes, 50-regular, 256 subgraphs, width 128.  The checker runs four
