@@ -130,10 +130,10 @@ struct gco_ctx {
   GraphView gv_sub;
   int num_wblocks[kWaveMaps] = {};
   int num_loss_slots = 0;
-  int2* d_wwave_tiles[kWaveMaps] = {};
+  WaveRun* d_wave_runs[kWaveMaps] = {};
   int2 *d_went = nullptr, *d_went_t = nullptr;
   float *d_wval = nullptr, *d_wval_t = nullptr;
-  int32_t *d_wtile_base = nullptr, *d_wtile_hptr = nullptr;
+  int32_t* d_wtile_hptr = nullptr;
   int2 *d_ent = nullptr, *d_ent_t = nullptr;
   float* d_diag = nullptr;
   float* d_heavy_partial = nullptr;
@@ -360,12 +360,22 @@ void build_block_map(int P, const std::vector<int>& part_rows, const std::vector
 // stands for the per-row work of the kernel's dense part and epilogue.
 void build_wave_map(int P, const std::vector<int>& part_rows, const std::vector<int32_t>& lrowptr,
                     int target_blocks, double row_cost, bool group_by_xcd, std::vector<int>& wblk_k,
-                    std::vector<int2>& wwave_tiles) {
+                    std::vector<WaveRun>& wave_runs) {
   constexpr int kWaves = kBlock / 64;
   std::vector<int> blk_s, blk_S;
   build_block_map(P, part_rows, lrowptr, kWaveRows * kWaves, target_blocks, 0, wblk_k, blk_s, blk_S,
                   group_by_xcd, 1.0 + row_cost);
-  wwave_tiles.assign(wblk_k.size() * kWaves, make_int2(0, 0));
+  wave_runs.assign(wblk_k.size() * kWaves, WaveRun{});
+  // light-stream offset of every row (one entry per row plus the neighbours of rows that
+  // are not pre-reduced) and global number of every subgraph's first tile
+  const int n = part_rows[P];
+  std::vector<int> wrow(static_cast<size_t>(n) + 1, 0), tbase(static_cast<size_t>(P) + 1, 0);
+  for (int r = 0; r < n; ++r) {
+    const int deg = lrowptr[r + 1] - lrowptr[r];
+    wrow[r + 1] = wrow[r] + 1 + (deg >= kHeavyMin ? 0 : deg);
+  }
+  for (int k = 0; k < P; ++k)
+    tbase[k + 1] = tbase[k] + (part_rows[k + 1] - part_rows[k] + kWaveRows - 1) / kWaveRows;
   std::vector<std::vector<int>> cuts(P);  // cuts[k][v] = first tile of wavefront v of subgraph k
   for (size_t b = 0; b < wblk_k.size(); ++b) {
     const int k = wblk_k[b];
@@ -394,7 +404,14 @@ void build_wave_map(int P, const std::vector<int>& part_rows, const std::vector<
     }
     for (int q = 0; q < kWaves; ++q) {
       const int v = blk_s[b] * kWaves + q;
-      wwave_tiles[b * kWaves + q] = make_int2(cuts[k][v], cuts[k][v + 1]);
+      WaveRun& run = wave_runs[b * kWaves + q];
+      run.tile0 = cuts[k][v];
+      run.tile1 = cuts[k][v + 1];
+      run.rbeg = part_rows[k];
+      run.rend = part_rows[k + 1];
+      run.e0 = wrow[std::min(run.rend, run.rbeg + run.tile0 * kWaveRows)];
+      run.e1 = wrow[std::min(run.rend, run.rbeg + run.tile1 * kWaveRows)];
+      run.tglob = tbase[k];
     }
   }
 }
@@ -772,12 +789,12 @@ int gco_upload_graph(gco_ctx* ctx, int64_t n64, const int64_t* rowptr, const int
                   group_by_xcd);
   // one decomposition per kernel kind (different cost per row)
   for (int v = 0; v < kWaveMaps; ++v) {
-    std::vector<int2> wwave_tiles;
+    std::vector<WaveRun> wave_runs;
     build_wave_map(P, part_rows, lrowptr, kWaveBlocksFor[v], kWaveRowCost[v], group_by_xcd, ctx->hm.wblk_k[v],
-                   wwave_tiles);
+                   wave_runs);
     ctx->num_wblocks[v] = static_cast<int>(ctx->hm.wblk_k[v].size());
-    GALLOC(ctx->d_wwave_tiles[v], wwave_tiles.size());
-    HIPCHK(h2d(ctx, ctx->d_wwave_tiles[v], wwave_tiles.data(), wwave_tiles.size()));
+    GALLOC(ctx->d_wave_runs[v], wave_runs.size());
+    HIPCHK(h2d(ctx, ctx->d_wave_runs[v], wave_runs.data(), wave_runs.size()));
   }
   // width-1 kernels: one 256-row tile per workgroup
   build_block_map(P, part_rows, lrowptr, kNarrowRows, std::numeric_limits<int>::max() / 2, 1, nblk_k,
@@ -842,9 +859,7 @@ int gco_upload_graph(gco_ctx* ctx, int64_t n64, const int64_t* rowptr, const int
       hptr[tbase[kk] + (r - part_rows[kk]) / kWaveRows + 1]++;
     }
     for (size_t q = 1; q < hptr.size(); ++q) hptr[q] += hptr[q - 1];
-    GALLOC(ctx->d_wtile_base, tbase.size());
     GALLOC(ctx->d_wtile_hptr, hptr.size());
-    HIPCHK(h2d(ctx, ctx->d_wtile_base, tbase.data(), tbase.size()));
     HIPCHK(h2d(ctx, ctx->d_wtile_hptr, hptr.data(), hptr.size()));
   }
   if (num_heavy > 0) {
@@ -873,12 +888,11 @@ int gco_upload_graph(gco_ctx* ctx, int64_t n64, const int64_t* rowptr, const int
   g.blk_S = ctx->d_blk_S;
   g.num_blocks = static_cast<int>(blk_k.size());
   for (int v = 0; v < kWaveMaps; ++v) {
-    g.wwave_tiles[v] = ctx->d_wwave_tiles[v];
+    g.wave_runs[v] = ctx->d_wave_runs[v];
     g.wblk_k[v] = ctx->full.wblk_k[v];
     g.num_wblocks[v] = ctx->num_wblocks[v];
   }
   g.wrowptr = ctx->d_wrowptr;
-  g.wtile_base = ctx->d_wtile_base;
   g.wtile_hptr = ctx->d_wtile_hptr;
   g.went = ctx->d_went;
   g.went_t = ctx->d_went_t;

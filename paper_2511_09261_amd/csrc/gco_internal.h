@@ -45,6 +45,17 @@ enum KernelKind : int {
   KK_COUNT
 };
 
+// One wavefront's share of a wave-per-tile kernel.  Everything the wavefront needs before
+// its first loads of the stream sits in this one 32-byte record, so that it starts them
+// after a single lookup.
+struct __attribute__((aligned(16))) WaveRun {
+  int tile0, tile1;  // tiles [tile0, tile1) of its subgraph (kWaveRows rows each, from the subgraph's first row)
+  int rbeg, rend;    // rows of the subgraph
+  int e0, e1;        // light-stream range of the run's rows
+  int tglob;         // global number of the subgraph's first tile
+  int pad;
+};
+
 // Device view of the local (trained-on) graph in subgraph-contiguous node order,
 // plus the static work decomposition.  All pointers are device pointers.
 struct GraphView {
@@ -68,20 +79,19 @@ struct GraphView {
   const int* blk_S = nullptr;
   int num_blocks = 0;
   // wave-per-tile kernels, one decomposition per kernel kind m (WaveMap): workgroup b
-  // serves subgraph wblk_k[m][b] (< 0: nothing to do); its wavefront q owns tiles
-  // wwave_tiles[m][4b+q].x .. .y (kWaveRows rows each, counted from the subgraph's first
-  // row) -- contiguous runs, cut so that the wavefronts have about equal work in that kind
+  // serves subgraph wblk_k[m][b] (< 0: nothing to do); its wavefront q owns the tiles of
+  // wave_runs[m][4b+q] -- contiguous runs, cut so that the wavefronts have about equal work
+  // in that kind
   const int* wblk_k[kWaveMaps] = {};
-  const int2* wwave_tiles[kWaveMaps] = {};
+  const WaveRun* wave_runs[kWaveMaps] = {};
   int num_wblocks[kWaveMaps] = {};
   // light stream: per row its diagonal entry {i, A_hat_ii}, then its packed entries unless
   // the row is pre-reduced; row i owns went[wrowptr[i] .. wrowptr[i+1]).  went_t holds the
   // entries of A_hat^T.  kEntPad zero entries follow the last row.
   const int* wrowptr = nullptr;   // [n+1]
   // wave tiles are numbered subgraph by subgraph: tile tau of subgraph k has the global
-  // number wtile_base[k] + tau; the pre-reduced rows inside global tile T are
-  // heavy_rows[wtile_hptr[T] .. wtile_hptr[T+1])
-  const int* wtile_base = nullptr;  // [P+1]
+  // number (WaveRun::tglob of the subgraph) + tau; the pre-reduced rows inside global tile
+  // T are heavy_rows[wtile_hptr[T] .. wtile_hptr[T+1])
   const int* wtile_hptr = nullptr;  // [tiles+1]
   const int2* went = nullptr;
   const int2* went_t = nullptr;

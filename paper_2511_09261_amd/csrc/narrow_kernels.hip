@@ -167,9 +167,8 @@ __global__ __launch_bounds__(kBlock) void narrow_stream_kernel(GraphView g, Op o
   const int b = blockIdx.x - g.num_heavy;
   const int k = g.wblk_k[WM_NARROW][b];
   if (k < 0) return;
-  const int2 tiles = g.wwave_tiles[WM_NARROW][b * kWaves + wave];
-  const int rbeg = g.part_rows[k], rend = g.part_rows[k + 1];
-  const int r0 = rbeg + tiles.x * kWaveRows, r1 = min(rend, rbeg + tiles.y * kWaveRows);
+  const WaveRun run = g.wave_runs[WM_NARROW][b * kWaves + wave];
+  const int r0 = run.rbeg + run.tile0 * kWaveRows, r1 = min(run.rend, run.rbeg + run.tile1 * kWaveRows);
   int* mark = mark_s[wave];
   int* rp = rp_s[wave];
   float* rowacc = rowacc_s[wave];

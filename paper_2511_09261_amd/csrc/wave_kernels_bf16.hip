@@ -159,15 +159,14 @@ __device__ __forceinline__ uint32_t upper_halves(uint32_t x, uint32_t y) {
   return __builtin_amdgcn_perm(y, x, 0x07060302u);
 }
 
-// Calls on_tile(row0, nrows, agg) for every tile tau in [tile0, tile1) of subgraph k, in
-// order.  agg[tn][r] at lane (n, h) is element (row0 + n, acc_feature(tn, h, r)) of
+// Calls on_tile(row0, nrows, agg) for every tile of the wavefront's run, in order.  agg[tn][r] at lane (n, h) is element (row0 + n, acc_feature(tn, h, r)) of
 // A_hat X in fp32 (zero for rows past nrows).  `went` is the light stream of the matrix
 // that is applied (A_hat or its transpose); xf (xf_bytes) and wts (wts_bytes) are this
 // wavefront's LDS; pair_mask is the workgroup's table from fill_pair_masks.  on_tile may
 // overwrite xf.
 template <int D, typename OnTile>
 __device__ __forceinline__ void stream_tiles(const GraphView& g, const int2* __restrict__ went,
-                                             const bf16_t* __restrict__ X, int k, int tile0, int tile1,
+                                             const bf16_t* __restrict__ X, const WaveRun& run,
                                              unsigned char* xf, uint32_t* wts, const uint4* pair_mask,
                                              const float* __restrict__ heavy_partial, OnTile&& on_tile) {
   using G_ = WG<D>;
@@ -175,10 +174,10 @@ __device__ __forceinline__ void stream_tiles(const GraphView& g, const int2* __r
   const int n = lane % 32, h = lane / 32;
   const int grp = lane / G_::LPR, sub = lane % G_::LPR;
 
-  const int rbeg = g.part_rows[k], rend = g.part_rows[k + 1];
-  const int row_end = min(rend, rbeg + tile1 * RW);
-  const int E0 = g.wrowptr[rbeg + tile0 * RW], E1 = g.wrowptr[row_end];
-  const int tglob = g.wtile_base[k];
+  const int tile0 = run.tile0, tile1 = run.tile1;
+  const int rbeg = run.rbeg, rend = run.rend;
+  const int E0 = run.e0, E1 = run.e1;
+  const int tglob = run.tglob;
   // Lane-held facts of tile tau: lanes 0..32 the stream offsets of its rows (clamped to
   // the tile's end), lanes 33 and 34 its range in the list of pre-reduced rows.
   auto tile_facts = [&](int tau) -> int {
@@ -400,11 +399,11 @@ __global__ __launch_bounds__(kBlock, D == 64 ? 3 : 2) void fwd_wave_kernel(
   if (tid < D) wo[tid] = w_out != nullptr ? w_out[static_cast<size_t>(k) * wout_stride + tid] : 0.f;
   __syncthreads();  // the only workgroup barrier: W^k and w_out are in LDS
 
-  const int2 tiles = g.wwave_tiles[WM_FWD][blockIdx.x * (kBlock / 64) + wave];
-  if (tiles.x >= tiles.y) return;
+  const WaveRun run = g.wave_runs[WM_FWD][blockIdx.x * (kBlock / 64) + wave];
+  if (run.tile0 >= run.tile1) return;
   unsigned char* my_lds = wave_mem + wave * G_::wave_bytes;
   bf16_t* ot = reinterpret_cast<bf16_t*>(my_lds);  // overlays the row buffer
-  stream_tiles<D>(g, g.went, X, k, tiles.x, tiles.y, my_lds,
+  stream_tiles<D>(g, g.went, X, run, my_lds,
                   reinterpret_cast<uint32_t*>(my_lds + G_::xf_bytes), pair_mask, heavy_partial,
                   [&](int row0, int nrows, const floatx16 (&agg)[G_::NT]) {
     // Z^T = W^T AGG^T: the rounded aggregate is the B operand as it stands
@@ -578,7 +577,7 @@ __global__ __launch_bounds__(kBlock, 2) void bwd_wave_kernel(GraphView g, BwdArg
 
   const bf16_t* GZ = static_cast<const bf16_t*>(a.GZ_in);
   const bf16_t* Hprev = static_cast<const bf16_t*>(a.Hprev);
-  const int2 tiles = g.wwave_tiles[WM][blockIdx.x * (kBlock / 64) + wave];
+  const WaveRun run = g.wave_runs[WM][blockIdx.x * (kBlock / 64) + wave];
   unsigned char* R = wave_mem + wave * G_::bwd_wave_bytes;
   const bool need_gh = !(TO_EMBED && a.mode == EMBED_SKIP);
   constexpr int NTW = GWI ? G_::NT : 1;
@@ -590,9 +589,9 @@ __global__ __launch_bounds__(kBlock, 2) void bwd_wave_kernel(GraphView g, BwdArg
 #pragma unroll
       for (int r = 0; r < 16; ++r) gw[ta][tb][r] = 0.f;
 
-  if (tiles.x < tiles.y) {
-    const int rbeg = g.part_rows[k];
-    const int row_end = min(g.part_rows[k + 1], rbeg + tiles.y * RW);
+  if (run.tile0 < run.tile1) {
+    const int rbeg = run.rbeg;
+    const int row_end = min(run.rend, rbeg + run.tile1 * RW);
     // rows RPL grp + u (u < RPL) of a tile, features 8 sub .. + 7: what this lane loads of
     // Hprev and what it stores of the result
     constexpr int RPL = RW / G_::NG;
@@ -607,9 +606,9 @@ __global__ __launch_bounds__(kBlock, 2) void bwd_wave_kernel(GraphView g, BwdArg
         }
       }
     };
-    request_hprev(rbeg + tiles.x * RW);
+    request_hprev(rbeg + run.tile0 * RW);
 
-    stream_tiles<D>(g, g.went, GZ, k, tiles.x, tiles.y, R, reinterpret_cast<uint32_t*>(R + G_::region_bytes),
+    stream_tiles<D>(g, g.went, GZ, run, R, reinterpret_cast<uint32_t*>(R + G_::region_bytes),
                     pair_mask, a.heavy_partial,
                     [&](int row0, int nrows, const floatx16 (&agg)[G_::NT]) {
       // G_T^T rounded to bf16: B operands of the second product
@@ -864,7 +863,7 @@ __global__ __launch_bounds__(kBlock, 1) void grad_w_wave_kernel(GraphView g, con
   const int wave = __builtin_amdgcn_readfirstlane(tid / 64);
   const int n = lane % 32, h = lane / 32;
   const int grp = lane / G_::LPR, sub = lane % G_::LPR;
-  const int2 tiles = g.wwave_tiles[WM_BWD][blockIdx.x * (kBlock / 64) + wave];
+  const WaveRun run = g.wave_runs[WM_BWD][blockIdx.x * (kBlock / 64) + wave];
   unsigned char* hl = smem + wave * (2 * D * G_::GP);
   unsigned char* gl = hl + D * G_::GP;
   floatx16 acc[G_::NT][G_::NT];
@@ -875,9 +874,9 @@ __global__ __launch_bounds__(kBlock, 1) void grad_w_wave_kernel(GraphView g, con
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[ta][tb][r] = 0.f;
 
-  if (tiles.x < tiles.y) {
-    const int rbeg = g.part_rows[k];
-    const int row_end = min(g.part_rows[k + 1], rbeg + tiles.y * RW);
+  if (run.tile0 < run.tile1) {
+    const int rbeg = run.rbeg;
+    const int row_end = min(run.rend, rbeg + run.tile1 * RW);
     uint4 hr[8], gr[8];
     auto request = [&](int row0) {
 #pragma unroll
@@ -906,8 +905,8 @@ __global__ __launch_bounds__(kBlock, 1) void grad_w_wave_kernel(GraphView g, con
             make_uint4(d[0], d[1], d[2], d[3]);
       }
     };
-    request(rbeg + tiles.x * RW);
-    for (int tau = tiles.x; tau < tiles.y; ++tau) {
+    request(rbeg + run.tile0 * RW);
+    for (int tau = run.tile0; tau < run.tile1; ++tau) {
       park(hr, hl);
       park(gr, gl);
       request(rbeg + (tau + 1) * RW);  // rows past the wavefront's run read as zero
