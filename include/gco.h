@@ -115,6 +115,16 @@ int gco_graph_info(gco_ctx* ctx, int64_t* n, int64_t* m, int64_t* m_local, int64
 int gco_set_params(gco_ctx* ctx, const float* E, const float* const* W);
 int gco_get_params(gco_ctx* ctx, float* E, float* const* W);
 
+/* The same with the input processing of Sec. 3.2: the initial embeddings pass once through
+ * the Gumbel-softmax, which turns every row into a distribution close to a one-hot vector:
+ *   X[i, :] = softmax((E[i, :] + g[i, :]) / tau),   g = -log(-log(U)),
+ * U is float[n * dim] of uniforms in the open interval (0, 1) supplied by the caller
+ * (original node order), tau > 0.  X takes the place of E as the embedding (it is what
+ * gco_get_params returns and, if train_embed is set, what is trained); the noise is used
+ * this once.  Computed in fp32 on the device.  EINVAL for tau <= 0 or a NULL pointer. */
+int gco_set_params_gumbel(gco_ctx* ctx, const float* E, const float* U, float tau,
+                          const float* const* W);
+
 /* Adam state ("store net/optimizer states", Alg. 1 stage 1): first and second
  * moments shaped like the parameters, and the step counter t. */
 int gco_get_opt_state(gco_ctx* ctx, float* mE, float* vE, float* const* mW, float* const* vW,

@@ -93,6 +93,21 @@ def _operand(x, spec):
     return round_bf16(x) if (spec.storage == "bf16" and spec.matrix_core_operands) else x
 
 
+def gumbel_softmax_rows(E, U, tau):
+    """Sec. 3.2: the initial embeddings are passed once through the Gumbel-softmax, which
+    turns every row into a distribution close to a one-hot vector.  With noise
+    g = -log(-log(u)) from given uniforms u in (0, 1) and temperature tau,
+        x[i, :] = softmax((E[i, :] + g[i, :]) / tau).
+    The noise is drawn once (it is an input here) and stays fixed during training."""
+    E = np.asarray(E, dtype=np.float64)
+    U = np.asarray(U, dtype=np.float64)
+    g = -np.log(-np.log(U))
+    y = (E + g) / float(tau)
+    y = y - y.max(axis=1, keepdims=True)
+    w = np.exp(y)
+    return w / w.sum(axis=1, keepdims=True)
+
+
 @dataclass
 class LocalGraph:
     """What the training step sees of (graph, partition ids)."""

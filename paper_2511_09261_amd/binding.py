@@ -54,6 +54,7 @@ _PROTOTYPES = {
     "gco_upload_graph": (C.c_int, [C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32]),
     "gco_graph_info": (C.c_int, [C.c_void_p] + [C.POINTER(C.c_int64)] * 4),
     "gco_set_params": (C.c_int, [C.c_void_p, C.c_void_p, C.POINTER(C.c_void_p)]),
+    "gco_set_params_gumbel": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_float, C.POINTER(C.c_void_p)]),
     "gco_get_params": (C.c_int, [C.c_void_p, C.c_void_p, C.POINTER(C.c_void_p)]),
     "gco_get_opt_state": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.POINTER(C.c_void_p),
                                     C.POINTER(C.c_void_p), C.POINTER(C.c_int64)]),
@@ -230,6 +231,14 @@ class Context:
         if len(Ws) != self.num_layers:
             raise ValueError("one weight array per layer expected")
         self._check(self.lib.gco_set_params(self.h, _ptr(E), self._ptr_array(Ws)))
+
+    def set_params_gumbel(self, E, U, tau, Ws):
+        E = _f32(E, (self.n, self.dim))
+        U = _f32(U, (self.n, self.dim))
+        Ws = [_f32(W, s) for W, s in zip(Ws, self._w_shapes())]
+        if len(Ws) != self.num_layers:
+            raise ValueError("one weight array per layer expected")
+        self._check(self.lib.gco_set_params_gumbel(self.h, _ptr(E), _ptr(U), tau, self._ptr_array(Ws)))
 
     def get_params(self):
         E = np.empty((self.n, self.dim), dtype=np.float32)

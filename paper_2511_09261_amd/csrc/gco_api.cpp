@@ -1015,8 +1015,9 @@ static int reset_best(gco_ctx* ctx) {
   return GCO_OK;
 }
 
-int gco_set_params(gco_ctx* ctx, const float* E, const float* const* W) {
-  if (!ctx) return GCO_EINVAL;
+// Parameters from the host; with U != nullptr the embeddings pass through the
+// Gumbel-softmax of Sec. 3.2 first.
+static int set_params_impl(gco_ctx* ctx, const float* E, const float* U, float tau, const float* const* W) {
   NEED(ctx->has_graph, GCO_ESTATE, "no graph uploaded");
   NEED(E && W, GCO_EINVAL, "NULL parameter pointer");
   const int L = ctx->cfg.num_layers;
@@ -1024,6 +1025,15 @@ int gco_set_params(gco_ctx* ctx, const float* E, const float* const* W) {
   const size_t nd = static_cast<size_t>(ctx->n) * ctx->cfg.dim;
   int rc = upload_node_matrix(ctx, E, ctx->E);
   if (rc != GCO_OK) return rc;
+  if (U != nullptr) {
+    Scratch tmp(ctx);
+    float* d_u = tmp.get<float>(nd);
+    NEED(d_u, GCO_ENOMEM, "device scratch allocation failed");
+    rc = upload_node_matrix(ctx, U, d_u);
+    if (rc != GCO_OK) return rc;
+    launch_gumbel_softmax_rows(ctx->launch(), ctx->n, ctx->cfg.dim, ctx->E, d_u, tau);
+    HIPCHK(hipStreamSynchronize(ctx->st));  // d_u is released on return
+  }
   HIPCHK(hipMemsetAsync(ctx->mE, 0, nd * sizeof(float), ctx->st));
   HIPCHK(hipMemsetAsync(ctx->vE, 0, nd * sizeof(float), ctx->st));
   for (int l = 1; l <= L; ++l) {
@@ -1043,6 +1053,18 @@ int gco_set_params(gco_ctx* ctx, const float* E, const float* const* W) {
   ctx->has_params = true;
   ctx->probs_valid = false;
   return GCO_OK;
+}
+
+int gco_set_params(gco_ctx* ctx, const float* E, const float* const* W) {
+  if (!ctx) return GCO_EINVAL;
+  return set_params_impl(ctx, E, nullptr, 1.f, W);
+}
+
+int gco_set_params_gumbel(gco_ctx* ctx, const float* E, const float* U, float tau, const float* const* W) {
+  if (!ctx) return GCO_EINVAL;
+  NEED(U, GCO_EINVAL, "U is NULL");
+  NEED(tau > 0.f, GCO_EINVAL, "tau must be positive");
+  return set_params_impl(ctx, E, U, tau, W);
 }
 
 int gco_get_params(gco_ctx* ctx, float* E, float* const* W) {

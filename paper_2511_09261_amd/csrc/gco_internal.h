@@ -294,6 +294,8 @@ void launch_adam_w(const Launch& ln, int Pw, const WeightTensor* tensors, int co
                    bool update, bool many_partials);  // adam.per_part, if set, is indexed by weight set; sets without partials are left alone
 
 // fp32 -> bf16 copy (round to nearest even).
+// X[i, :] <- softmax((X[i, :] - log(-log(U[i, :]))) / tau), rows of width D (Sec. 3.2).
+void launch_gumbel_softmax_rows(const Launch& ln, int n, int D, float* X, const float* U, float tau);
 void launch_to_bf16(const Launch& ln, const float* src, void* dst, int64_t count);
 // bf16 -> fp32 copy (exact).
 void launch_from_bf16(const Launch& ln, const void* src, float* dst, int64_t count);

@@ -554,6 +554,30 @@ __global__ __launch_bounds__(64 * kAdamSplit) void adam_w_split_kernel(int Pw, W
   adam_on_weight(wt, e.gid, gsum, ad.for_part(e.k), update);
 }
 
+// Sec. 3.2, input processing: X[i, :] = softmax((X[i, :] + g[i, :]) / tau) in place, with
+// g = -log(-log(U[i, :])).  One thread per row (runs once per parameter upload).
+__global__ __launch_bounds__(kBlock) void gumbel_softmax_rows_kernel(int n, int D, float* __restrict__ X,
+                                                                     const float* __restrict__ U, float inv_tau) {
+  const int i = blockIdx.x * kBlock + threadIdx.x;
+  if (i >= n) return;
+  float* x = X + static_cast<size_t>(i) * D;
+  const float* u = U + static_cast<size_t>(i) * D;
+  float top = -INFINITY;
+  for (int c = 0; c < D; ++c) {
+    const float y = (x[c] - logf(-logf(u[c]))) * inv_tau;
+    x[c] = y;
+    top = fmaxf(top, y);
+  }
+  float sum = 0.f;
+  for (int c = 0; c < D; ++c) {
+    const float w = expf(x[c] - top);
+    x[c] = w;
+    sum += w;
+  }
+  const float inv = 1.f / sum;
+  for (int c = 0; c < D; ++c) x[c] *= inv;
+}
+
 __global__ __launch_bounds__(kBlock) void to_bf16_kernel(const float* __restrict__ src,
                                                          bf16_t* __restrict__ dst, int64_t count) {
   const int64_t i = static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x;
@@ -732,6 +756,11 @@ void launch_adam_w(const Launch& ln, int Pw, const WeightTensor* tensors, int co
     adam_w_kernel<<<blocks, kBlock, 0, ln.st>>>(Pw, wts, adam, update ? 1 : 0);
   }
   ln.end(KK_ADAM_W);
+}
+
+void launch_gumbel_softmax_rows(const Launch& ln, int n, int D, float* X, const float* U, float tau) {
+  const int blocks = (n + kBlock - 1) / kBlock;
+  if (blocks > 0) gumbel_softmax_rows_kernel<<<blocks, kBlock, 0, ln.st>>>(n, D, X, U, 1.f / tau);
 }
 
 void launch_to_bf16(const Launch& ln, const float* src, void* dst, int64_t count) {

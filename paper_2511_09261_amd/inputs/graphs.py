@@ -203,6 +203,15 @@ def init_params(n: int, part: np.ndarray, num_parts_w: int, num_layers: int,
     return E, Ws
 
 
+def gumbel_uniforms(n: int, dim: int, seed: int) -> np.ndarray:
+    """float32 uniforms strictly inside (0, 1), one per embedding element, from a stream
+    indexed by the ORIGINAL node id: the noise source of the Gumbel-softmax input
+    processing (23 random bits, offset by half a step: every value is an exact float32 in
+    [2^-24, 1 - 2^-24])."""
+    k = rng.u64(rng.stream_key(seed, 12), n * dim) >> np.uint64(41)
+    return ((k.astype(np.float64) + 0.5) / float(1 << 23)).astype(np.float32).reshape(n, dim)
+
+
 # --- the five workload configurations ---------------------------------------
 
 @dataclass

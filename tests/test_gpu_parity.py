@@ -524,3 +524,41 @@ def test_malformed_inputs_are_rejected_with_codes(gco):
         gco.Context(dim=24)
     with pytest.raises(gco.GcoError):
         gco.Context(dim=16, storage="bf16")
+
+
+# ------------------------------------------------------------------ paper-literal model
+
+@pytest.mark.parametrize("storage,D,tau", [("fp32", 16, 0.5), ("fp32", 64, 1.0), ("bf16", 64, 0.5)])
+def test_gumbel_softmax_input_and_the_one_layer_model(gco, storage, D, tau):
+    """Sec. 3.2 as printed: Gumbel-softmax-processed initial embeddings, one graph
+    convolution with the mean normalisation of Eq. 3, sigmoid, only W trained."""
+    g, part, P = make_case("bfs12", seed=8)
+    E, Ws = inputs.init_params(g.n, part, P, 1, D, 3)
+    E = (E * 10).astype(np.float32)
+    U = inputs.gumbel_uniforms(g.n, D, 3)
+    ctx = gco.Context(problem="mis", num_layers=1, dim=D, norm="mean", storage=storage,
+                      train_embed=False, lr=1e-2)
+    ctx.upload_graph(g.n, g.rowptr, g.col, part, P)
+    with pytest.raises(gco.GcoError):
+        ctx.set_params_gumbel(E, U, 0.0, Ws)
+    ctx.set_params_gumbel(E, U, tau, Ws)
+    X = gcn.gumbel_softmax_rows(E, U, tau)
+    X_dev, _ = ctx.get_params()
+    assert rel(X_dev, X) <= 1e-5
+    np.testing.assert_allclose(X_dev.sum(axis=1), 1.0, rtol=1e-5)
+    # the model on top of it, from the device's own X (fp32) so that only the model differs
+    spec = gcn.Spec(problem="mis", num_layers=1, norm="mean", train_embed=False, lr=1e-2,
+                    storage="bf16" if storage == "bf16" else "exact", matrix_core_operands=True)
+    lg = gcn.local_graph(g.n, g.rowptr, g.col, part, P, "mean")
+    tol = 1e-5 if storage == "fp32" else 2e-2
+    cache = gcn.forward(lg, X_dev, Ws, spec)
+    ctx.forward()
+    assert rel(ctx.get_probs(), cache["p"]) <= tol
+    got = ctx.train(10)
+    st = gcn.init_state(X_dev, Ws)
+    want, _ = gcn.train(lg, st, spec, 10)
+    assert np.abs(got - want).max() <= (1e-4 if storage == "fp32" else 2e-2) * np.abs(want).max()
+    X_after, W_after = ctx.get_params()
+    np.testing.assert_array_equal(X_after, X_dev)        # only W is trained
+    assert rel(W_after[0], st.Ws[0]) <= (1e-3 if storage == "fp32" else 5e-2)
+    ctx.destroy()

@@ -609,3 +609,35 @@ def test_best_snapshot_leaves_unlisted_and_unseen_models_alone():
         np.testing.assert_array_equal(st.E[idx], moved[0][idx])
         for l in range(L):
             np.testing.assert_array_equal(st.Ws[l][k], moved[1][l][k])
+
+
+def test_gumbel_softmax_rows_against_closed_forms():
+    """Sec. 3.2 input processing.  Pins: rows are distributions; with u = exp(-exp(-a)) the
+    noise is exactly a; two columns reduce to the logistic function of the difference
+    (written out here, with the sign of the noise that a dropped minus would flip); adding
+    a constant to a row changes nothing; tau -> 0 gives the one-hot vector of
+    argmax(E + g), a large tau the uniform distribution."""
+    rs = np.random.RandomState(41)
+    n, d = 50, 6
+    E = rs.standard_normal((n, d))
+    U = rs.uniform(0.02, 0.98, (n, d))
+    x = gcn.gumbel_softmax_rows(E, U, 0.7)
+    assert x.shape == (n, d) and np.all(x > 0)
+    np.testing.assert_allclose(x.sum(axis=1), 1.0, rtol=1e-14)
+    np.testing.assert_allclose(gcn.gumbel_softmax_rows(E + rs.standard_normal((n, 1)), U, 0.7), x, rtol=1e-12)
+    # known noise: u = exp(-exp(-a))  <=>  g = a
+    a = rs.standard_normal((n, 2))
+    E2 = rs.standard_normal((n, 2))
+    x2 = gcn.gumbel_softmax_rows(E2, np.exp(-np.exp(-a)), 0.5)
+    diff = (E2[:, 0] + a[:, 0]) - (E2[:, 1] + a[:, 1])
+    np.testing.assert_allclose(x2[:, 0], 1.0 / (1.0 + np.exp(-diff / 0.5)), rtol=1e-12)
+    # a u close to 1 is a large positive g: that column wins
+    Uw = np.full((1, d), 0.5)
+    Uw[0, 3] = 1.0 - 1e-9
+    assert gcn.gumbel_softmax_rows(np.zeros((1, d)), Uw, 1.0).argmax() == 3
+    # temperature limits
+    g = -np.log(-np.log(U))
+    cold = gcn.gumbel_softmax_rows(E, U, 1e-3)
+    np.testing.assert_array_equal(cold.argmax(axis=1), (E + g).argmax(axis=1))
+    assert np.all(cold.max(axis=1) > 1 - 1e-6)
+    np.testing.assert_allclose(gcn.gumbel_softmax_rows(E, U, 1e9), 1.0 / d, rtol=1e-6)
