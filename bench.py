@@ -170,6 +170,19 @@ def main():
         t_best = (time.perf_counter() - t0) / 20
         ctx.keep_best(False)
 
+    # what a plain device-to-device copy reaches on this GPU (read + write bytes per second)
+    src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
+    dst = torch.empty_like(src)
+    dst.copy_(src)
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    ev0.record()
+    for _ in range(5):
+        dst.copy_(src)
+    ev1.record()
+    torch.cuda.synchronize()
+    copy_gbs = 5 * 2 * src.numel() * 4 / (ev0.elapsed_time(ev1) * 1e-3) / 1e9
+    del src, dst
+
     L = wl.num_layers
     nnz = 2 * info["m_local"]
     ea_per_epoch = 2 * L * (nnz + g.n) + nnz
@@ -190,6 +203,7 @@ def main():
         "roofline": {"bound": "hbm", "kernel": dominant, "achieved": achieved, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                      "traffic": recorded_traffic(dominant) if args.workload == "c4" else None,
+                     "copy_kernel_GBps": copy_gbs, "frac_of_copy": achieved / copy_gbs,
                      "avg_launch_ms": avg_ms, "algorithmic_bytes_per_launch": tim["bytes_per_launch"],
                      "launches_timed": tim["launches"]},
         "extra": {"edge_aggregations_per_s": ea_per_epoch * eps, "edge_aggregations_per_epoch": ea_per_epoch,
