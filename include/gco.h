@@ -221,6 +221,27 @@ int gco_cross_mask(gco_ctx* ctx, uint8_t* c);
  * same order and two-call pattern as gco_cut_edges.  x is uint8[n]. */
 int gco_conflict_edges(gco_ctx* ctx, const uint8_t* x, int64_t* count, int32_t* u, int32_t* v);
 
+/* Graph partitioning by modularity (Sec. 3.1): the Louvain heuristic, on the host (no
+ * context, no device).  Same graph format as gco_upload_graph (symmetric CSR, no self
+ * loops; symmetry is not verified).  Writes part_id[n] (int32, host): community ids
+ * 0 .. *num_parts - 1, numbered by smallest member, ready to be passed to
+ * gco_upload_graph; *modularity (may be NULL) receives Q of that partition.  Gains are the
+ * integers 2 m^2 dQ of Eq. 2, so the result is free of rounding: nodes are visited in
+ * ascending id until a sweep moves nothing, a node moves only to a strictly better
+ * community (ties: smallest id), communities are merged into nodes level by level, at most
+ * max_levels levels.  EINVAL for a malformed graph, ERANGE for 2^31 or more CSR entries. */
+int gco_louvain(int64_t n, const int64_t* rowptr, const int32_t* col, int32_t max_levels,
+                int32_t* part_id, int32_t* num_parts, double* modularity);
+
+/* Merge the communities of part_id (values in [0, num_parts)) into at most max_parts groups
+ * without splitting any, for a bounded number of subgraphs of similar size (merging never
+ * cuts an edge; isolated nodes and tiny communities are the usual case).  Communities are
+ * taken in the order (size descending, id ascending) and each goes to the group with the
+ * fewest nodes so far (ties: smallest group id).  part_out may alias part_id.  Host only.
+ * *num_out = min(num_parts, max_parts); with num_parts <= max_parts ids are copied. */
+int gco_pack_parts(int64_t n, const int32_t* part_id, int32_t num_parts, int32_t max_parts,
+                   int32_t* part_out, int32_t* num_out);
+
 /* Wait for the context's stream. */
 int gco_sync(gco_ctx* ctx);
 

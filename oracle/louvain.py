@@ -129,3 +129,24 @@ def louvain(n, rowptr, col, max_levels=32):
             final[c] = len(final)
         part[i] = final[c]
     return part, len(final)
+
+
+def pack_parts(part, num_parts, max_parts):
+    """Merge communities into at most max_parts groups without splitting any (merging never
+    cuts an edge): communities in the order (size descending, id ascending), each to the
+    group with the fewest nodes so far (ties: smallest group id).  Returns the group of every
+    node and the number of groups; with num_parts <= max_parts nothing changes."""
+    n = len(part)
+    if num_parts <= max_parts:
+        return list(part), num_parts
+    size = [0] * num_parts
+    for c in part:
+        size[c] += 1
+    order = sorted(range(num_parts), key=lambda c: (-size[c], c))
+    load = [0] * max_parts
+    group = [0] * num_parts
+    for c in order:
+        b = min(range(max_parts), key=lambda x: (load[x], x))
+        group[c] = b
+        load[b] += size[c]
+    return [group[c] for c in part], max_parts

@@ -77,6 +77,9 @@ _PROTOTYPES = {
     "gco_cut_edges": (C.c_int, [C.c_void_p, C.POINTER(C.c_int64), C.c_void_p, C.c_void_p]),
     "gco_cross_mask": (C.c_int, [C.c_void_p, C.c_void_p]),
     "gco_conflict_edges": (C.c_int, [C.c_void_p, C.c_void_p, C.POINTER(C.c_int64), C.c_void_p, C.c_void_p]),
+    "gco_louvain": (C.c_int, [C.c_int64, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p,
+                              C.POINTER(C.c_int32), C.POINTER(C.c_double)]),
+    "gco_pack_parts": (C.c_int, [C.c_int64, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.POINTER(C.c_int32)]),
     "gco_sync": (C.c_int, [C.c_void_p]),
     "gco_set_profiling": (C.c_int, [C.c_void_p, C.c_int32, C.c_uint64]),
     "gco_num_kernel_kinds": (C.c_int, []),
@@ -108,6 +111,31 @@ def exported_symbols():
 
 def _ptr(a):
     return None if a is None else a.ctypes.data
+
+
+def louvain(n, rowptr, col, max_levels=32):
+    """gco_louvain: (part_id int32[n], number of communities, modularity).  Host only."""
+    lib = load()
+    rowptr = np.ascontiguousarray(rowptr, dtype=np.int64)
+    col = np.ascontiguousarray(col, dtype=np.int32)
+    part = np.empty(n, dtype=np.int32)
+    P, q = C.c_int32(), C.c_double()
+    rc = lib.gco_louvain(n, _ptr(rowptr), _ptr(col), max_levels, _ptr(part), C.byref(P), C.byref(q))
+    if rc != 0:
+        raise GcoError(rc, "gco_louvain failed (malformed graph or size out of range)")
+    return part, P.value, q.value
+
+
+def pack_parts(part, num_parts, max_parts):
+    """gco_pack_parts: (group of every node int32[n], number of groups).  Host only."""
+    lib = load()
+    part = np.ascontiguousarray(part, dtype=np.int32)
+    out = np.empty_like(part)
+    P = C.c_int32()
+    rc = lib.gco_pack_parts(part.shape[0], _ptr(part), num_parts, max_parts, _ptr(out), C.byref(P))
+    if rc != 0:
+        raise GcoError(rc, "gco_pack_parts failed (bad ids or counts)")
+    return out, P.value
 
 
 def _f32(a, shape=None):

@@ -138,3 +138,25 @@ def test_louvain_levels_never_lower_modularity():
         assert q >= q_prev - 1e-12
         q_prev = q
     assert q_prev > 0.2
+
+
+def test_pack_parts_keeps_communities_whole_and_balances():
+    """Pins: no community is split; at most max_parts groups; the heaviest group exceeds the
+    lightest by at most the largest community (the greedy rule's bound); untouched when
+    there are few enough communities; a worked case by hand."""
+    rs = np.random.RandomState(3)
+    part = rs.randint(0, 40, 500).tolist()
+    part = [min(c, 39) for c in part]
+    out, P = lv.pack_parts(part, 40, 6)
+    assert P == 6 and set(out) <= set(range(6))
+    for c in range(40):
+        assert len({out[i] for i in range(500) if part[i] == c}) <= 1
+    sizes = np.bincount(part, minlength=40)
+    loads = np.bincount(out, minlength=6)
+    assert loads.max() - loads.min() <= sizes.max()
+    same, P2 = lv.pack_parts(part, 40, 64)
+    assert same == part and P2 == 40
+    # sizes 5,4,3,3,1 into 2 groups: 5->g0, 4->g1, 3->g1 (4<5), 3->g0 (5<7), 1->g1 (7<8)
+    hand = [0] * 5 + [1] * 4 + [2] * 3 + [3] * 3 + [4]
+    out2, _ = lv.pack_parts(hand, 5, 2)
+    assert [out2[0], out2[5], out2[9], out2[12], out2[15]] == [0, 1, 1, 0, 1]
