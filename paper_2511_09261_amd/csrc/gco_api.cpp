@@ -128,6 +128,7 @@ struct gco_ctx {
     bool allocated = false;
   } full, sub;
   GraphView gv_sub;
+  std::vector<uint8_t> sub_active;  // the subset `sub` was built for
   int num_wblocks[kWaveMaps] = {};
   int num_loss_slots = 0;
   WaveRun* d_wave_runs[kWaveMaps] = {};
@@ -1353,9 +1354,12 @@ int gco_train_subset(gco_ctx* ctx, int32_t epochs, const int32_t* parts, int32_t
       for (int e = 0; e < epochs; ++e) loss_per_epoch[e] = 0.0;
     return GCO_OK;
   }
-  {
+  // the maps of the previous call serve again when the same subgraphs are listed (the
+  // fine-tuning rounds of Alg. 1 stage 3 come back with the same set many times)
+  if (!ctx->sub.allocated || ctx->sub_active != active) {
     const int rc = upload_active_maps(ctx, ctx->sub, active.data());
     if (rc != GCO_OK) return rc;
+    ctx->sub_active = active;
   }
   ctx->gv_sub = view_with(ctx, ctx->sub);
   return train_impl(ctx, epochs, active.data(), loss_per_epoch);

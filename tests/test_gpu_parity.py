@@ -562,3 +562,24 @@ def test_gumbel_softmax_input_and_the_one_layer_model(gco, storage, D, tau):
     np.testing.assert_array_equal(X_after, X_dev)        # only W is trained
     assert rel(W_after[0], st.Ws[0]) <= (1e-3 if storage == "fp32" else 5e-2)
     ctx.destroy()
+
+
+def test_repeated_subset_calls_same_list_then_another(gco):
+    """The fine-tuning rounds of Alg. 1 stage 3 list the same subgraphs again and again (the
+    library keeps the decomposition of the previous call) and then others."""
+    g, part, P = make_case("bfs12", seed=23)
+    ctx, spec, lg, E, Ws = run_pair(gco, g, part, P, L=3, D=64, storage="bf16", lr=5e-3)
+    st = gcn.init_state(E, Ws)
+    got, want = [], []
+    for listed in ([0, 2], [0, 2], [5], [0, 2]):
+        active = np.zeros(P, dtype=bool)
+        active[listed] = True
+        got.append(ctx.train_subset(2, listed))
+        want.append(gcn.train(lg, st, spec, 2, active=active)[0])
+    got, want = np.concatenate(got), np.concatenate(want)
+    assert np.abs(got - want).max() <= 2e-2 * np.abs(want).max()
+    np.testing.assert_array_equal(ctx.get_steps()[0], st.tE)
+    E2, _ = ctx.get_params()
+    untouched = ~np.isin(np.asarray(part), [0, 2, 5])
+    np.testing.assert_array_equal(E2[untouched], E[untouched])
+    ctx.destroy()
