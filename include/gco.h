@@ -94,7 +94,8 @@ const char* gco_last_error(gco_ctx* ctx);
  *   col      int32[rowptr[n]]: symmetric CSR of a simple undirected graph: both
  *            directions present, columns ascending within a row, no self loops,
  *            no duplicates
- *   part_id  int32[n] with values in [0, num_parts), or NULL for one subgraph
+ *   part_id  int32[n] with values in [0, num_parts), or NULL for one subgraph;
+ *            num_parts <= 16384 (ERANGE beyond)
  * Builds on the device: the subgraph-contiguous node order, the CSR of local
  * edges (both ends in one subgraph; only these are trained on, Sec. 3.3), local
  * degrees and the normalisation of Eq. 3, and keeps the full CSR for the

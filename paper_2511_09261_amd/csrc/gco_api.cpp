@@ -636,6 +636,9 @@ int gco_upload_graph(gco_ctx* ctx, int64_t n64, const int64_t* rowptr, const int
   const int n = static_cast<int>(n64);
   if (!part_id) num_parts = 1;
   NEED(num_parts >= 1 && num_parts <= n, GCO_EINVAL, "num_parts = %d not in [1, n]", num_parts);
+  // the per-subgraph loss sums of an epoch are held in one workgroup's LDS
+  NEED(num_parts <= kMaxParts, GCO_ERANGE, "num_parts = %d exceeds %d (merge small subgraphs, e.g. gco_pack_parts)",
+       num_parts, kMaxParts);
   NEED(rowptr[0] == 0, GCO_EINVAL, "rowptr[0] != 0");
   for (int i = 0; i < n; ++i)
     NEED(rowptr[i + 1] >= rowptr[i], GCO_EINVAL, "rowptr decreases at row %d", i);

@@ -27,6 +27,7 @@ enum WaveMap : int { WM_FWD = 0, WM_BWD = 1, WM_EMBED = 2, WM_NARROW = 3, kWaveM
 constexpr double kWaveRowCost[kWaveMaps] = {0.7, 1.5, 100.0, 1.0};
 constexpr int kWaveBlocksFor[kWaveMaps] = {3072, 960, 3072, 2048};  // workgroups aimed at (measured best)
 constexpr int kEntPad = 512;             // zero entries appended to the packed entry arrays
+constexpr int kMaxParts = 16384;         // subgraphs per graph (their loss sums share 128 KB of LDS)
 
 enum KernelKind : int {
   KK_FWD_HIDDEN = 0,   // aggregate + transform + ReLU of one hidden layer (Eq. 3)

@@ -514,6 +514,11 @@ def test_malformed_inputs_are_rejected_with_codes(gco):
     with pytest.raises(gco.GcoError) as e:
         ctx.upload_graph(n, good_rp, good_col, np.array([0, 1, 2, 7]), 3)
     assert e.value.code == gco.EINVAL
+    big_n = 20000                                       # more subgraphs than the library takes
+    with pytest.raises(gco.GcoError) as e:
+        ctx.upload_graph(big_n, np.zeros(big_n + 1, dtype=np.int64), np.zeros(0, dtype=np.int32),
+                         np.arange(big_n, dtype=np.int32), big_n)
+    assert e.value.code == gco.ERANGE
     ctx.upload_graph(n, good_rp, good_col, np.array([0, 0, 1, 1]), 2)    # still usable
     assert ctx.graph_info() == {"n": 4, "m": 2, "m_local": 1, "m_cut": 1}
     with pytest.raises(gco.GcoError) as e:
