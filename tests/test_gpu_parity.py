@@ -64,6 +64,13 @@ def make_case(kind, seed):
         g = graph_with_long_rows(9000, seed, hubs=(5000, 2300, 300))
         part = (np.arange(9000) % 2).astype(np.int32)
         return g, part, 2
+    if kind == "tiny_parts":    # hundreds of subgraphs of 1..5 nodes, some of them empty
+        rs = np.random.RandomState(seed)
+        n = 2000
+        part = np.sort(rs.randint(0, 700, n)).astype(np.int32)
+        u = rs.randint(0, n, 6000)
+        v = np.clip(u + rs.randint(-4, 5, 6000), 0, n - 1)     # mostly inside or next to a subgraph
+        return inputs.from_edges(n, u, v), part, 700
     if kind == "bfs12":         # more than 8 subgraphs: the XCD-grouped block map
         g = inputs.random_regular(3000, 6, seed)
         return g, inputs.bfs_partition(g, 12, seed), 12
@@ -115,6 +122,10 @@ FWD_BWD_CASES = [
     ("random", "maxcut", 2, 64, "mean", "bf16", False),
     ("hubs_parts", "mis", 3, 64, "mean", "bf16", True),
     ("bfs12", "maxcut", 2, 64, "sym", "bf16", True),
+    # many subgraphs smaller than a tile
+    ("tiny_parts", "mis", 2, 16, "sym", "fp32", False),
+    ("tiny_parts", "maxcut", 3, 64, "sym", "bf16", False),
+    ("tiny_parts", "mis", 3, 128, "mean", "bf16", False),
     # width 128: the weight gradient comes from stored rows of A_hat^T G_Z
     ("hubs", "mis", 3, 128, "mean", "bf16", False),
     ("random", "maxcut", 3, 128, "sym", "bf16", False),
