@@ -1,4 +1,4 @@
-// Wave-per-tile bf16 layer kernels.
+// Wave-per-tile bf16 layer kernels (widths 64 and 128).
 //
 // Every 64-lane wavefront owns a contiguous run of 32-row tiles of one subgraph
 // and works through it alone: there is no workgroup barrier after the prologue,
