@@ -202,6 +202,8 @@ def main():
     eps = args.steps / dt
     avg_ms = tim["total_ms"] / max(1, tim["launches"])
     achieved = tim["bytes_per_launch"] / (avg_ms * 1e-3) / 1e9 if avg_ms > 0 else 0.0
+    gb_epoch = sum(v["bytes_per_launch"] * v["launches"] / 5 for v in breakdown.values()) / 1e9
+    launches_epoch = sum(v["launches"] for v in breakdown.values()) / 5
     out = {
         "metric": "GNN train epochs/s (edge-aggregations/s in extra), Youtube-shaped 1.1M-node graph, 1 GPU",
         "value": eps, "unit": "epochs/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -222,6 +224,10 @@ def main():
                      "avg_launch_ms": avg_ms, "algorithmic_bytes_per_launch": tim["bytes_per_launch"],
                      "launches_timed": tim["launches"]},
         "extra": {"edge_aggregations_per_s": ea_per_epoch * eps, "edge_aggregations_per_epoch": ea_per_epoch,
+                  # every kernel's algorithmic bytes x its launches per epoch, against the epoch time
+                  "algorithmic_GB_per_epoch": gb_epoch, "epoch_GBps": gb_epoch * eps,
+                  "epoch_frac_of_copy": gb_epoch * eps / copy_gbs,
+                  "kernel_launches_per_epoch": launches_epoch,
                   "kernel_ms_per_epoch": per_epoch,
                   "kernel_gbs": {k: (breakdown[k]["bytes_per_launch"] * breakdown[k]["launches"] / 5)
                                  / (per_epoch[k] * 1e-3) / 1e9 for k in per_epoch if per_epoch[k] > 0},
