@@ -89,7 +89,7 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: every subgraph of the graph is batched on a single "
-              "MI355X and no multi-GPU path exists in this build; run with --gpus 1.", file=sys.stderr)
+              "MI355X and the library has no multi-GPU path; run with --gpus 1.", file=sys.stderr)
         sys.exit(2)
 
     import numpy as np
