@@ -706,7 +706,7 @@ __global__ __launch_bounds__(kBlock, 2) void bwd_wave_kernel(GraphView g, BwdArg
           constexpr int LR = D / 4;          // lanes per fp32 row
           constexpr int RI = 64 / LR;        // rows per instruction
           constexpr int NQ = G_::RS / RI;    // instructions per pass and tensor
-          constexpr int HB = 4;              // rows of state requested at once, per lane
+          constexpr int HB = D == 64 ? 4 : 2;  // rows of state requested at once, per lane
           static_assert(NQ % HB == 0, "whole groups of requests");
           const int rr = lane / LR, cc = (lane % LR) * 4;
 #pragma unroll
