@@ -31,17 +31,15 @@ Readings taken where the paper is open (listed with reasons in the design notes)
     weights are declared shared.
 
 Reduced-precision storage.  Three of the workloads prescribe "bf16 features with
-fp32 accumulate".  With Spec.storage = "bf16" the checker keeps its fp64
-arithmetic but rounds to bfloat16 (8 significant bits, round to nearest even)
-exactly the tensors that such a run stores in bf16: the working copy of the
-embeddings, every hidden activation H_l, and the stored activation gradients.
-With Spec.matrix_core_operands it also rounds the two operands of each hidden
-layer's dense transform (the aggregated rows and W_l), as a bf16 matrix-core
-multiply with fp32 accumulation does.  This matters because ReLU turns a
-floating-point value into a yes/no decision: the device and the checker must
-take that decision on values of the same precision, otherwise a handful of
-units near zero flip and the gradients of whole rows differ by O(1).
-Spec.storage = "exact" (default) rounds nothing.
+fp32 accumulate" (one of them "X.W on bf16 MFMA").  With Spec.storage = "bf16" the
+checker keeps its fp64 arithmetic but rounds to bfloat16 (8 significant bits, round
+to nearest even) the tensors that such a run holds in bf16: the working copy of the
+embeddings, every hidden activation H_l, the activation gradient kept between two
+hidden layers, and the two operands of each hidden layer's dense transform (a bf16
+matrix multiply takes bf16 operands by definition; accumulation stays unrounded).
+This matters because ReLU turns a floating-point value into a yes/no decision, and a
+decision has to be taken on values of the same precision on both sides of a
+comparison.  Spec.storage = "exact" (default) rounds nothing.
 
 A library routine is used for two steps only: dense matmul (numpy @) and sparse
 matrix times dense matrix (scipy.sparse CSR @).
@@ -68,7 +66,6 @@ class Spec:
     adam_b2: float = 0.999
     adam_eps: float = 1e-8
     storage: str = "exact"        # "exact" | "bf16" (see the module docstring)
-    matrix_core_operands: bool = False
 
 
 def round_bf16(x):
@@ -90,7 +87,8 @@ def _stored(x, spec):
 
 
 def _operand(x, spec):
-    return round_bf16(x) if (spec.storage == "bf16" and spec.matrix_core_operands) else x
+    """An operand of a hidden layer's dense transform."""
+    return round_bf16(x) if spec.storage == "bf16" else x
 
 
 def gumbel_softmax_rows(E, U, tau):
@@ -195,21 +193,18 @@ def loss(lg: LocalGraph, p, spec: Spec, extra_linear=None):
     return float(per_part.sum()), per_part
 
 
-def backward(lg: LocalGraph, cache: dict, Ws, spec: Spec, extra_linear=None, relu_on=None,
-             active=None):
+def backward(lg: LocalGraph, cache: dict, Ws, spec: Spec, extra_linear=None, active=None,
+             trace: dict = None):
     """Exact chain rule through Eq. 5, Eq. 4 and the layers of Eq. 3.
 
     Returns (gE [n, d], [gW_1 .. gW_L]) with gW_l shaped like W_l.
 
-    relu_on, if given, is a list indexed by layer l of boolean arrays that say
-    where the ReLU of layer l passes the gradient; it replaces the checker's own
-    decision Z_l > 0.  Tests of reduced-precision runs pass the decisions the
-    device took, because a unit whose pre-activation is zero to within rounding
-    may legitimately fall on either side.
-
     active, if given, is a boolean array over the subgraphs: only the listed subgraphs
     contribute to the weight gradients (this matters only when the weights are shared;
-    with per-subgraph weights a subgraph's gradient never depends on the others)."""
+    with per-subgraph weights a subgraph's gradient never depends on the others).
+
+    trace, if given, receives "G_H": the list, indexed by hidden layer l, of dL/dH_l (the
+    gradient that arrives at the ReLU of layer l)."""
     on_k = np.ones(lg.num_parts, dtype=bool) if active is None else np.asarray(active, dtype=bool)
     L = spec.num_layers
     c, q = qubo_coefficients(lg, spec)
@@ -229,9 +224,10 @@ def backward(lg: LocalGraph, cache: dict, Ws, spec: Spec, extra_linear=None, rel
             gWs[L - 1][kk, :, 0] += cache["Agg"][L][idx].T @ g_z[idx]
         g_agg[idx] = np.outer(g_z[idx], WL[kk, :, 0])
     g_H = lg.A_hat.T @ g_agg
+    G_H = [None] * L
     for l in range(L - 1, 0, -1):
-        on = (cache["Z"][l] > 0.0) if relu_on is None else relu_on[l]
-        g_Z = g_H * on                                # ReLU, derivative 0 at 0
+        G_H[l] = g_H
+        g_Z = g_H * (cache["Z"][l] > 0.0)             # ReLU, derivative 0 at 0
         if l < L - 1:
             g_Z = _stored(g_Z, spec)                  # kept in memory between two layers
         Wl = np.asarray(Ws[l - 1], dtype=np.float64)
@@ -242,6 +238,8 @@ def backward(lg: LocalGraph, cache: dict, Ws, spec: Spec, extra_linear=None, rel
                 gWs[l - 1][kk] += cache["Agg"][l][idx].T @ g_Z[idx]
             g_agg[idx] = g_Z[idx] @ Wl[kk].T
         g_H = lg.A_hat.T @ g_agg
+    if trace is not None:
+        trace["G_H"] = G_H
     return g_H, gWs
 
 

@@ -323,25 +323,23 @@ def test_bf16_storage_mode_stays_close_and_rounds_the_right_tensors():
     lg = make(n, edges, part, P)
     E, Ws = rand_params(rs, n, d, L, P)
     exact = gcn.forward(lg, E, Ws, gcn.Spec(num_layers=L))
-    for mc in (False, True):
-        spec = gcn.Spec(num_layers=L, storage="bf16", matrix_core_operands=mc)
-        out = gcn.forward(lg, E, Ws, spec)
-        assert 0 < np.abs(out["p"] - exact["p"]).max() < 3e-2
-        for H in out["H"]:
-            np.testing.assert_array_equal(gcn.round_bf16(H), H)      # stored tensors are bf16 values
-        np.testing.assert_array_equal(out["H"][0], gcn.round_bf16(E))
-        if mc:
-            np.testing.assert_array_equal(gcn.round_bf16(out["Agg"][1]), out["Agg"][1])
-        # the gradient is the exact derivative of the rounded forward wherever no
-        # rounding intervenes: check dL/dW_L (last layer sees only exact operations)
-        gE, gWs = gcn.backward(lg, out, Ws, spec)
-        h = 1e-6
-        for k in range(P):
-            Wp = [W.copy() for W in Ws]; Wp[L - 1][k, 0, 0] += h
-            Wm = [W.copy() for W in Ws]; Wm[L - 1][k, 0, 0] -= h
-            fd = (gcn.loss(lg, gcn.forward(lg, E, Wp, spec)["p"], spec)[0] -
-                  gcn.loss(lg, gcn.forward(lg, E, Wm, spec)["p"], spec)[0]) / (2 * h)
-            assert abs(fd - gWs[L - 1][k, 0, 0]) < 1e-6 * max(1, abs(fd))
+    spec = gcn.Spec(num_layers=L, storage="bf16")
+    out = gcn.forward(lg, E, Ws, spec)
+    assert 0 < np.abs(out["p"] - exact["p"]).max() < 3e-2
+    for H in out["H"]:
+        np.testing.assert_array_equal(gcn.round_bf16(H), H)      # stored tensors are bf16 values
+    np.testing.assert_array_equal(out["H"][0], gcn.round_bf16(E))
+    np.testing.assert_array_equal(gcn.round_bf16(out["Agg"][1]), out["Agg"][1])
+    # the gradient is the exact derivative of the rounded forward wherever no
+    # rounding intervenes: check dL/dW_L (last layer sees only exact operations)
+    gE, gWs = gcn.backward(lg, out, Ws, spec)
+    h = 1e-6
+    for k in range(P):
+        Wp = [W.copy() for W in Ws]; Wp[L - 1][k, 0, 0] += h
+        Wm = [W.copy() for W in Ws]; Wm[L - 1][k, 0, 0] -= h
+        fd = (gcn.loss(lg, gcn.forward(lg, E, Wp, spec)["p"], spec)[0] -
+              gcn.loss(lg, gcn.forward(lg, E, Wm, spec)["p"], spec)[0]) / (2 * h)
+        assert abs(fd - gWs[L - 1][k, 0, 0]) < 1e-6 * max(1, abs(fd))
 
 
 # ---------------------------------------------------------------- Adam
