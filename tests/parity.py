@@ -14,10 +14,12 @@ from oracle import gcn
 from oracle import precision as pr
 
 TOL_BF16 = 2e-2
-# share of hidden units whose ReLU decision the arithmetic model cannot settle; a property
-# of the inputs alone (computed by the checker): asserted so that the comparison cannot
-# silently turn vacuous
-MAX_AMBIGUOUS_SHARE = 1e-2
+# share of hidden units whose ReLU decision the arithmetic model cannot settle: a property
+# of the inputs alone (computed by the checker), asserted so that the comparison cannot
+# silently turn vacuous.  First hidden layer: a few in ten thousand to a few in a thousand;
+# later layers gather stored values that may already sit one bf16 step apart: several in a
+# hundred, and a fifth where thousands of rows gather the row of one long-row hub.
+MAX_AMBIGUOUS_SHARE = (None, 1e-2, 0.5)
 
 
 def rel(a, b):
@@ -56,7 +58,7 @@ def compare_hidden(want, H_dev, l, rows=None, tol=TOL_BF16, label=""):
     wrong = differ & ~amb
     assert not wrong.any(), f"{label} layer {l}: {int(wrong.sum())} certain ReLU decisions differ"
     share = float(amb.mean())
-    assert share <= MAX_AMBIGUOUS_SHARE, f"{label} layer {l}: {share:.2e} of the units are undecidable"
+    assert share <= MAX_AMBIGUOUS_SHARE[min(l, 2)], f"{label} layer {l}: {share:.2e} of the units are undecidable"
     outside = np.abs(H_dev - H_ref) > dH * (1 + 1e-6) + 1e-30
     print(f"{label} H_{l}: rel {rel(H_dev, H_ref):.2e} l2 {rel_l2(H_dev, H_ref):.2e}; undecidable "
           f"{int(amb.sum())} of {amb.size} ({share:.1e}), of which the device took {int(differ.sum())} "
@@ -64,7 +66,9 @@ def compare_hidden(want, H_dev, l, rows=None, tol=TOL_BF16, label=""):
     return int(outside.sum())
 
 
-def compare_gradient(name, got, ref, slack, tol=TOL_BF16, label=""):
+def compare_gradient(name, got, ref, slack, tol=TOL_BF16, label="", plain=False):
+    """plain: the entries must also match within the tolerance alone, slack or not (for inputs
+    on which the undecidable units carry too little gradient to matter)."""
     got = np.asarray(got, dtype=np.float64)
     scale = np.abs(ref).max()
     excess = np.abs(got - ref) - slack
@@ -73,9 +77,11 @@ def compare_gradient(name, got, ref, slack, tol=TOL_BF16, label=""):
           f"{int((slack > 0).sum())} of {slack.size}, with slack above the tolerance {int(loose.sum())}; "
           f"largest excess over the slack {excess.max() / max(scale, 1e-300):.2e} of max|g|", flush=True)
     assert excess.max() <= tol * scale, f"{label} {name}"
+    if plain:
+        assert rel(got, ref) <= tol, f"{label} {name} (without slack)"
 
 
-def compare_bf16_run(ctx, lg, E, Ws, spec, extra=None, tol=TOL_BF16, label=""):
+def compare_bf16_run(ctx, lg, E, Ws, spec, extra=None, tol=TOL_BF16, label="", plain=False):
     """Forward probabilities, loss, hidden activations with their ReLU decisions, and all
     gradients of the device context ctx (parameters already set) against the checker."""
     import dataclasses
@@ -98,10 +104,11 @@ def compare_bf16_run(ctx, lg, E, Ws, spec, extra=None, tol=TOL_BF16, label=""):
     for l in range(1, L):
         outside += compare_hidden(want, ctx.get_hidden(l), l, tol=tol, label=label)
     dE, dWs = ctx.get_grads()
-    compare_gradient("dL/dE", dE, want["gE"], want["sE"], tol, label)
+    compare_gradient("dL/dE", dE, want["gE"], want["sE"], tol, label, plain)
     for l in range(L):
-        compare_gradient(f"dL/dW_{l + 1}", dWs[l], want["gWs"][l], want["sWs"][l], tol, label)
-    return want, outside
+        compare_gradient(f"dL/dW_{l + 1}", dWs[l], want["gWs"][l], want["sWs"][l], tol, label, plain)
+    assert outside == 0, f"{label}: {outside} stored activations lie outside the arithmetic model's bound"
+    return want
 
 
 def power_of_two_case(seed, d, L, hubs=(63, 255, 1023, 1023), ring_blocks=6, ring_size=500):

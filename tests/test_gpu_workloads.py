@@ -94,8 +94,8 @@ def test_fp32_workloads_full_training(gco, name):
     ctx.destroy()
 
 
-def fixed_weight_checks(ctx, spec, lg, E, Ws, label):
-    parity.compare_bf16_run(ctx, lg, E, Ws, spec, label=label)
+def fixed_weight_checks(ctx, spec, lg, E, Ws, label, plain=False):
+    parity.compare_bf16_run(ctx, lg, E, Ws, spec, label=label, plain=plain)
 
 
 def test_c3_bf16_workload(gco):
@@ -129,7 +129,9 @@ def test_c4_youtube_shaped_full_size(gco):
     print("c4", inputs.describe(wl), flush=True)
     g = wl.graph
     ctx, spec, lg, E, Ws = setup(gco, wl)
-    fixed_weight_checks(ctx, spec, lg, E, Ws, "c4")
+    # at the workload's own initialisation the undecidable units carry so little gradient
+    # that every entry also matches within 2e-2 without any slack
+    fixed_weight_checks(ctx, spec, lg, E, Ws, "c4", plain=True)
     print("c4 fixed-weight checks done", flush=True)
     got = ctx.train(10)
     st = gcn.init_state(E, Ws)
@@ -249,21 +251,34 @@ def test_c5_regular_graph_sampled_subgraphs(gco):
     np.testing.assert_array_equal(u, wu)
     np.testing.assert_array_equal(v, wv)
     del u, v, wu, wv
-    # ten epochs of all 256 subgraphs, one at a time (the per-subgraph loss belongs to the
-    # parameters before the step); the checker trains each sampled subgraph alone
+    # the configured 50 epochs of all 256 subgraphs, one at a time (the per-subgraph loss
+    # belongs to the parameters before the step); the checker trains each sampled subgraph
+    # alone.  Trajectory within 2e-2 throughout; at the end the loss within 1 %.
     got = []
-    for e in range(10):
+    for e in range(wl.epochs):
         got.append(ctx.loss()[1][list(C5_SAMPLE)])
         ctx.train(1, return_loss=False)
     got = np.array(got)
+    _, per_end = ctx.loss()
+    x, obj, _, _ = ctx.round_repair(0.5, "local")
+    assert obj == cb.cut_value(g.n, g.rowptr, g.col, wl.part, x, "all")
     for q, k in enumerate(C5_SAMPLE):
         idx, lgk, Ek, Wk = alone[k]
+        _, sub = subgraph_alone(wl, k)
         st = gcn.init_state(Ek, Wk)
-        want, _ = gcn.train(lgk, st, spec, 10)
-        print(f"c5 subgraph {k}: loss {want[0]:.2f} -> {want[-1]:.2f} (device {got[0, q]:.2f} -> {got[-1, q]:.2f}), "
-              f"worst rel {np.abs(got[:, q] - want).max() / np.abs(want).max():.2e}", flush=True)
+        want, _ = gcn.train(lgk, st, spec, wl.epochs)
+        p_ref = gcn.forward(lgk, st.E, st.Ws, spec)["p"]
+        end_ref, _ = gcn.loss(lgk, p_ref, spec)
+        cut_ref = cb.cut_value(sub.n, sub.rowptr, sub.col, None, cb.round_probs(p_ref.astype(np.float32)), "all")
+        cut_dev = cb.cut_value(sub.n, sub.rowptr, sub.col, None, x[idx], "all")
+        print(f"c5 subgraph {k}: loss {want[0]:.2f} -> {end_ref:.2f} (device {got[0, q]:.2f} -> {per_end[k]:.2f}), "
+              f"worst rel over the trajectory {np.abs(got[:, q] - want).max() / np.abs(want).max():.2e}; "
+              f"cut {cut_ref} device {cut_dev}", flush=True)
         assert np.abs(got[:, q] - want).max() <= 2e-2 * np.abs(want).max()
-        assert want[-1] != want[0]
+        assert abs(per_end[k] - end_ref) <= 1e-2 * abs(end_ref)
+        # (the cut values are printed only: at this workload's initialisation and learning
+        # rate 50 epochs leave every p within about 1e-2 of 0.5, so which side of 0.5 a
+        # node falls on is decided by rounding noise on both sides)
     x, obj, _, _ = ctx.round_repair(0.5, "local")
     assert obj == cb.cut_value(g.n, g.rowptr, g.col, wl.part, x, "all")
     ctx.destroy()
@@ -283,9 +298,10 @@ def test_louvain_partition_end_to_end(gco):
     want, wantC = lv.louvain(g.n, g.rowptr, g.col)
     np.testing.assert_array_equal(comm, want)
     assert C == wantC
+    want = np.asarray(want)
     assert abs(q - lv.modularity(g.n, g.rowptr, g.col, want)) <= 1e-12
     part, P = gco.pack_parts(comm, C, 16)
-    want_part, wantP = lv.pack_parts(want.tolist(), wantC, 16)
+    want_part, wantP = lv.pack_parts(list(want), wantC, 16)
     np.testing.assert_array_equal(part, want_part)
     assert P == wantP and P <= 16
     E, Ws = inputs.init_params(g.n, part, P, wl.num_layers, wl.dim, wl.seed)
