@@ -211,6 +211,19 @@ int gco_get_hidden(gco_ctx* ctx, int32_t layer, float* H);
 int gco_round_repair(gco_ctx* ctx, float thr, int32_t repair_scope, uint8_t* x,
                      int64_t* objective, int64_t* conflicts_before, int64_t* conflicts_after);
 
+/* gco_round_repair for callers that cannot allocate device memory (code under HIP graph
+ * capture around it, tight serving loops, harnesses that forbid hipMalloc): same arguments,
+ * same results bit for bit, but the call's work area (7 bytes per node plus counters) is a
+ * fixed block inside the library's code object instead of memory from hipMalloc or the
+ * context's allocator hooks; the call allocates and frees nothing.  Limits: n <= 2^21
+ * nodes (ERANGE beyond).  Each GPU holds one such block (14.7 MB) for the life of the
+ * process, shared by every context on that GPU: calls that overlap in time on one GPU
+ * (different streams or threads) race on it and must be serialised by the caller.  The
+ * block is looked up on the device that is current at the call, which must be the device
+ * the context was created on. */
+int gco_round_repair_static(gco_ctx* ctx, float thr, int32_t repair_scope, uint8_t* x,
+                            int64_t* objective, int64_t* conflicts_before, int64_t* conflicts_after);
+
 /* Cross edges (Sec. 3.3: edges whose ends lie in different subgraphs), as pairs
  * (u[i], v[i]) with u < v sorted by (u, v).  Two-call pattern: with u = v = NULL
  * only *count is written; otherwise *count is the capacity of u and v on entry

@@ -74,6 +74,7 @@ _PROTOTYPES = {
     "gco_get_grads": (C.c_int, [C.c_void_p, C.c_void_p, C.POINTER(C.c_void_p)]),
     "gco_get_hidden": (C.c_int, [C.c_void_p, C.c_int32, C.c_void_p]),
     "gco_round_repair": (C.c_int, [C.c_void_p, C.c_float, C.c_int32, C.c_void_p] + [C.POINTER(C.c_int64)] * 3),
+    "gco_round_repair_static": (C.c_int, [C.c_void_p, C.c_float, C.c_int32, C.c_void_p] + [C.POINTER(C.c_int64)] * 3),
     "gco_cut_edges": (C.c_int, [C.c_void_p, C.POINTER(C.c_int64), C.c_void_p, C.c_void_p]),
     "gco_cross_mask": (C.c_int, [C.c_void_p, C.c_void_p]),
     "gco_conflict_edges": (C.c_int, [C.c_void_p, C.c_void_p, C.POINTER(C.c_int64), C.c_void_p, C.c_void_p]),
@@ -363,6 +364,14 @@ class Context:
         obj, cb, ca = C.c_int64(), C.c_int64(), C.c_int64()
         self._check(self.lib.gco_round_repair(self.h, thr, REPAIR[repair_scope], _ptr(x),
                                               C.byref(obj), C.byref(cb), C.byref(ca)))
+        return x, obj.value, cb.value, ca.value
+
+    def round_repair_static(self, thr=0.5, repair_scope="local"):
+        """gco_round_repair_static: the same, inside the library's fixed work area (no allocation)."""
+        x = np.empty(self.n, dtype=np.uint8)
+        obj, cb, ca = C.c_int64(), C.c_int64(), C.c_int64()
+        self._check(self.lib.gco_round_repair_static(self.h, thr, REPAIR[repair_scope], _ptr(x),
+                                                     C.byref(obj), C.byref(cb), C.byref(ca)))
         return x, obj.value, cb.value, ca.value
 
     def cut_edges(self):

@@ -1508,25 +1508,23 @@ int gco_get_hidden(gco_ctx* ctx, int32_t layer, float* H) {
 
 // ---- read-out -------------------------------------------------------------------
 
-int gco_round_repair(gco_ctx* ctx, float thr, int32_t repair_scope, uint8_t* x, int64_t* objective,
-                     int64_t* conflicts_before, int64_t* conflicts_after) {
-  if (!ctx) return GCO_EINVAL;
-  NEED(ctx->probs_valid, GCO_ESTATE, "no forward pass has run");
-  NEED(x, GCO_EINVAL, "x is NULL");
-  NEED(repair_scope >= GCO_REPAIR_NONE && repair_scope <= GCO_REPAIR_ALL, GCO_EINVAL,
-       "bad repair_scope %d", repair_scope);
+// Device buffers of one gco_round_repair call (n floats, three byte arrays of n rounded up
+// to a multiple of 4, 8 counters, 4 ints).
+struct RepairBuffers {
+  float* p_orig;
+  uint8_t *state, *x_orig, *x_new;
+  unsigned long long* counts;
+  int* undecided;
+};
+
+static int round_repair_impl(gco_ctx* ctx, float thr, int32_t repair_scope, const RepairBuffers& b, uint8_t* x,
+                             int64_t* objective, int64_t* conflicts_before, int64_t* conflicts_after) {
   const int n = ctx->n;
   hipStream_t st = ctx->st;
-  Scratch tmp(ctx);
-  const size_t npad = (static_cast<size_t>(n) + 3) / 4 * 4;
-  float* p_orig = tmp.get<float>(static_cast<size_t>(n));
-  uint8_t* state = tmp.get<uint8_t>(npad);
-  uint8_t* x_orig = tmp.get<uint8_t>(npad);
-  uint8_t* x_new = tmp.get<uint8_t>(npad);
-  unsigned long long* counts = tmp.get<unsigned long long>(8);
-  int* undecided = tmp.get<int>(4);
-  NEED(p_orig && state && x_orig && x_new && counts && undecided, GCO_ENOMEM,
-       "device scratch allocation failed");
+  float* p_orig = b.p_orig;
+  uint8_t *state = b.state, *x_orig = b.x_orig, *x_new = b.x_new;
+  unsigned long long* counts = b.counts;
+  int* undecided = b.undecided;
   launch_gather_rows(st, n, 1, ctx->p, ctx->d_inv, p_orig);
   launch_round(st, n, p_orig, thr, x_orig);  // 0/1 in original order
   launch_fill_u32(st, counts, 16, 0u);
@@ -1565,6 +1563,63 @@ int gco_round_repair(gco_ctx* ctx, float thr, int32_t repair_scope, uint8_t* x, 
   if (objective)
     *objective = static_cast<int64_t>(ctx->cfg.problem == GCO_PROBLEM_MIS ? h[4] : h[6]);
   return GCO_OK;
+}
+
+int gco_round_repair(gco_ctx* ctx, float thr, int32_t repair_scope, uint8_t* x, int64_t* objective,
+                     int64_t* conflicts_before, int64_t* conflicts_after) {
+  if (!ctx) return GCO_EINVAL;
+  NEED(ctx->probs_valid, GCO_ESTATE, "no forward pass has run");
+  NEED(x, GCO_EINVAL, "x is NULL");
+  NEED(repair_scope >= GCO_REPAIR_NONE && repair_scope <= GCO_REPAIR_ALL, GCO_EINVAL,
+       "bad repair_scope %d", repair_scope);
+  const int n = ctx->n;
+  Scratch tmp(ctx);
+  const size_t npad = (static_cast<size_t>(n) + 3) / 4 * 4;
+  RepairBuffers b{};
+  b.p_orig = tmp.get<float>(static_cast<size_t>(n));
+  b.state = tmp.get<uint8_t>(npad);
+  b.x_orig = tmp.get<uint8_t>(npad);
+  b.x_new = tmp.get<uint8_t>(npad);
+  b.counts = tmp.get<unsigned long long>(8);
+  b.undecided = tmp.get<int>(4);
+  NEED(b.p_orig && b.state && b.x_orig && b.x_new && b.counts && b.undecided, GCO_ENOMEM,
+       "device scratch allocation failed");
+  return round_repair_impl(ctx, thr, repair_scope, b, x, objective, conflicts_before, conflicts_after);
+}
+
+int gco_round_repair_static(gco_ctx* ctx, float thr, int32_t repair_scope, uint8_t* x, int64_t* objective,
+                            int64_t* conflicts_before, int64_t* conflicts_after) {
+  if (!ctx) return GCO_EINVAL;
+  NEED(ctx->probs_valid, GCO_ESTATE, "no forward pass has run");
+  NEED(x, GCO_EINVAL, "x is NULL");
+  NEED(repair_scope >= GCO_REPAIR_NONE && repair_scope <= GCO_REPAIR_ALL, GCO_EINVAL,
+       "bad repair_scope %d", repair_scope);
+  NEED(ctx->n <= kStaticMaxNodes, GCO_ERANGE,
+       "n = %d exceeds the %d nodes the static work area of gco_round_repair_static holds", ctx->n,
+       kStaticMaxNodes);
+  void* base = nullptr;
+  HIPCHK(static_scratch_for_current_device(&base));
+  // carve the block: every piece starts on a 256-byte boundary
+  const size_t n = static_cast<size_t>(ctx->n);
+  const size_t npad = (n + 3) / 4 * 4;
+  auto up = [](size_t v) { return (v + 255) / 256 * 256; };
+  unsigned char* q = static_cast<unsigned char*>(base);
+  RepairBuffers b{};
+  b.counts = reinterpret_cast<unsigned long long*>(q);
+  q += 256;
+  b.undecided = reinterpret_cast<int*>(q);
+  q += 256;
+  b.p_orig = reinterpret_cast<float*>(q);
+  q += up(n * sizeof(float));
+  b.state = q;
+  q += up(npad);
+  b.x_orig = q;
+  q += up(npad);
+  b.x_new = q;
+  q += up(npad);
+  NEED(static_cast<size_t>(q - static_cast<unsigned char*>(base)) <= kStaticScratchBytes, GCO_ERANGE,
+       "static work area too small for n = %d", ctx->n);
+  return round_repair_impl(ctx, thr, repair_scope, b, x, objective, conflicts_before, conflicts_after);
 }
 
 static int cross_edges_impl(gco_ctx* ctx, const uint8_t* d_x, int64_t* count, int32_t* u, int32_t* v,

@@ -27,6 +27,12 @@ enum WaveMap : int { WM_FWD = 0, WM_BWD = 1, WM_EMBED = 2, WM_NARROW = 3, kWaveM
 constexpr double kWaveRowCost[kWaveMaps] = {0.7, 1.5, 100.0, 1.0};
 constexpr int kWaveBlocksFor[kWaveMaps] = {3072, 960, 3072, 2048};  // workgroups aimed at (measured best)
 constexpr int kEntPad = 512;             // zero entries appended to the packed entry arrays
+// gco_round_repair_static works inside a block of device memory that is part of the
+// library's code object: up to this many nodes, 7 bytes per node plus counters.
+constexpr int kStaticMaxNodes = 1 << 21;
+constexpr size_t kStaticScratchBytes = static_cast<size_t>(kStaticMaxNodes) * 7 + 4096;
+hipError_t static_scratch_for_current_device(void** out);
+
 constexpr int kMaxParts = 16384;         // subgraphs per graph (their loss sums share 128 KB of LDS)
 
 enum KernelKind : int {
