@@ -24,7 +24,7 @@ namespace {
 const char* const kKindNames[KK_COUNT] = {
     "fwd_hidden", "fwd_gemv", "fwd_readout", "loss", "bwd_readout",
     "bwd_hidden", "bwd_embed_adam", "adam_w", "loss_reduce", "heavy_rows", "form_gz",
-    "best_snapshot", "grad_w"};
+    "best_snapshot", "grad_w", "scalar_layer"};
 
 struct EventPair {
   hipEvent_t a, b;
@@ -131,9 +131,16 @@ struct gco_ctx {
   std::vector<uint8_t> sub_active;  // the subset `sub` was built for
   int num_wblocks[kWaveMaps] = {};
   int num_loss_slots = 0;
+  // the three width-1 passes as one launch with a workgroup per subgraph: possible when
+  // two float vectors of the largest subgraph fit the LDS of a compute unit
+  bool fused_scalar = false;
+  int fused_waves = 0, fused_cap = 0;
+  int2* d_fused_cuts = nullptr;
+  int32_t* d_heavy_ptr = nullptr;
   WaveRun* d_wave_runs[kWaveMaps] = {};
   int2 *d_went = nullptr, *d_went_t = nullptr;
   float *d_wval = nullptr, *d_wval_t = nullptr;
+  int32_t* d_wrowid = nullptr;
   int32_t* d_wtile_hptr = nullptr;
   int2 *d_ent = nullptr, *d_ent_t = nullptr;
   float* d_diag = nullptr;
@@ -479,9 +486,14 @@ int upload_active_maps(gco_ctx* ctx, gco_ctx::ActiveMaps& m, const uint8_t* acti
   for (size_t q = 0; q < heavy_rows.size(); ++q)
     if (heavy_part[q] < 0) heavy_rows[q] = -1;
   PUT(put(m.heavy_rows, heavy_rows, heavy_rows.size()));
-  // loss partial slots: one per pre-reduced row, then one per workgroup of the width-1 kernels
+  // loss partial slots: one per pre-reduced row, then one per workgroup of the width-1
+  // kernels; with the one-launch scalar layer, one per subgraph
   std::vector<int> slot_k(heavy_part);
   slot_k.insert(slot_k.end(), narrow.begin(), narrow.end());
+  if (ctx->fused_scalar) {
+    slot_k.resize(static_cast<size_t>(P));
+    for (int k = 0; k < P; ++k) slot_k[k] = (active == nullptr || active[k]) ? k : -1;
+  }
   PUT(put_lists(m.loss_ptr, m.loss_list, slot_k, P));
 #undef PUT
   m.allocated = true;
@@ -517,6 +529,8 @@ void traffic_model(gco_ctx* ctx) {
   kb[KK_FWD_READOUT] = idx + scales + 3 * n * 4;
   kb[KK_LOSS] = idx + 3 * n * 4;
   kb[KK_BWD_READOUT] = idx + scales + 2 * n * 4;
+  // the three passes in one launch: t and c in, p and g_t out; z and dL/dz never travel
+  kb[KK_SCALAR_FUSED] = 3 * idx + 2 * scales + 4 * n * 4;
   // On the wave-per-tile path the weight-gradient partials come from that path's own
   // workgroups, the scalar layer's from the narrow ones, and G_Z of the last hidden layer
   // is formed by a kernel of its own (KK_FORM_GZ) instead of inside the layer's backward.
@@ -769,8 +783,10 @@ int gco_upload_graph(gco_ctx* ctx, int64_t n64, const int64_t* rowptr, const int
     launch_fill_u32(st, ctx->d_went + nnz_light, 2 * kEntPad, 0u);
     GALLOC(ctx->d_wval, static_cast<size_t>(nnz_light) + kEntPad);
     launch_fill_u32(st, ctx->d_wval + nnz_light, kEntPad, 0u);
+    GALLOC(ctx->d_wrowid, static_cast<size_t>(nnz_light) + kEntPad);
+    launch_fill_u32(st, ctx->d_wrowid + nnz_light, kEntPad, 0xffffffffu);
     launch_light_fill(st, n, ctx->d_lrowptr, ctx->d_ent, ctx->d_diag, d_wptr64, ctx->d_wrowptr, ctx->d_went,
-                      ctx->d_wval);
+                      ctx->d_wval, ctx->d_wrowid);
     if (ctx->d_ent_t == ctx->d_ent) {
       ctx->d_went_t = ctx->d_went;
       ctx->d_wval_t = ctx->d_wval;
@@ -780,7 +796,7 @@ int gco_upload_graph(gco_ctx* ctx, int64_t n64, const int64_t* rowptr, const int
       GALLOC(ctx->d_went_t, static_cast<size_t>(nnz_light) + kEntPad);
       launch_fill_u32(st, ctx->d_went_t + nnz_light, 2 * kEntPad, 0u);
       launch_light_fill(st, n, ctx->d_lrowptr, ctx->d_ent_t, ctx->d_diag, d_wptr64, ctx->d_wrowptr,
-                        ctx->d_went_t, ctx->d_wval_t);
+                        ctx->d_went_t, ctx->d_wval_t, nullptr);
     }
   }
 
@@ -846,6 +862,64 @@ int gco_upload_graph(gco_ctx* ctx, int64_t n64, const int64_t* rowptr, const int
     ctx->hm.chunk_part = chunk_part;
     ctx->num_loss_slots = static_cast<int>(heavy_rows.size() + ctx->hm.wblk_k[WM_NARROW].size());
   }
+  {  // One launch for the scalar layer (a workgroup per subgraph) if every subgraph's vectors
+     // fit a compute unit's LDS and no subgraph is so large that its one workgroup would
+     // take longer than three launches spread over the whole chip (measured at c4: one
+     // subgraph with 147 k entries of the light stream, 3.8 times the mean, 0.40 ms against
+     // 0.09 ms).
+    int max_rows = 0;
+    int64_t max_light = 0;
+    for (int kk = 0; kk < P; ++kk) {
+      max_rows = std::max(max_rows, part_rows[kk + 1] - part_rows[kk]);
+      int64_t light = 0;
+      for (int r = part_rows[kk]; r < part_rows[kk + 1]; ++r) {
+        const int deg = lrowptr[r + 1] - lrowptr[r];
+        light += 1 + (deg >= kHeavyMin ? 0 : deg);
+      }
+      max_light = std::max(max_light, light);
+    }
+    const int NW = max_rows > 2048 ? 16 : 4;
+    const int cap = std::max(4, (max_rows + 3) / 4 * 4);
+    constexpr size_t kLdsPerComputeUnit = 160 * 1024;
+    constexpr int64_t kFusedMaxEntries = 40960;  // 40 steps per wavefront and pass
+    ctx->fused_scalar = scalar_fused_lds_bytes(NW, cap) <= kLdsPerComputeUnit && max_light <= kFusedMaxEntries;
+    ctx->fused_waves = NW;
+    ctx->fused_cap = cap;
+    if (ctx->fused_scalar) {
+      ctx->num_loss_slots = P;
+      // rows of every subgraph cut into NW contiguous runs of about equal cost (entries of
+      // the light stream plus one per row); a run is handed over as its range of the stream
+      std::vector<int2> cuts(static_cast<size_t>(P) * NW);
+      int64_t woff = 0;  // light-stream offset of the current row
+      for (int kk = 0; kk < P; ++kk) {
+        const int rb = part_rows[kk], re = part_rows[kk + 1];
+        std::vector<double> pre(static_cast<size_t>(re - rb) + 1, 0.0);
+        std::vector<int> off(static_cast<size_t>(re - rb) + 1, 0);
+        for (int r = rb; r < re; ++r) {
+          const int deg = lrowptr[r + 1] - lrowptr[r];
+          const int len = 1 + (deg >= kHeavyMin ? 0 : deg);
+          off[r - rb] = static_cast<int>(woff);
+          woff += len;
+          pre[r - rb + 1] = pre[r - rb] + 1 + len;
+        }
+        off[re - rb] = static_cast<int>(woff);
+        int r = rb;
+        for (int v = 0; v < NW; ++v) {
+          const int start = r;
+          const double want = pre[re - rb] * (v + 1) / NW;
+          while (r < re && (v == NW - 1 || pre[r - rb + 1] <= want)) ++r;
+          cuts[static_cast<size_t>(kk) * NW + v] = make_int2(off[start - rb], off[r - rb]);
+        }
+      }
+      std::vector<int> heavy_ptr(static_cast<size_t>(P) + 1, 0);
+      for (int kk : ctx->hm.heavy_part) heavy_ptr[kk + 1]++;
+      for (int kk = 0; kk < P; ++kk) heavy_ptr[kk + 1] += heavy_ptr[kk];
+      GALLOC(ctx->d_fused_cuts, cuts.size());
+      GALLOC(ctx->d_heavy_ptr, heavy_ptr.size());
+      HIPCHK(h2d(ctx, ctx->d_fused_cuts, cuts.data(), cuts.size()));
+      HIPCHK(h2d(ctx, ctx->d_heavy_ptr, heavy_ptr.data(), heavy_ptr.size()));
+    }
+  }
   ctx->full.allocated = false;
   ctx->sub.allocated = false;
   {
@@ -902,6 +976,7 @@ int gco_upload_graph(gco_ctx* ctx, int64_t n64, const int64_t* rowptr, const int
   g.went_t = ctx->d_went_t;
   g.wval = ctx->d_wval;
   g.wval_t = ctx->d_wval_t;
+  g.wrowid = ctx->d_wrowid;
   g.nblk_k = ctx->full.nblk_k;
   g.nblk_s = ctx->d_nblk_s;
   g.nblk_S = ctx->d_nblk_S;
@@ -1142,7 +1217,8 @@ int gco_set_linear_penalty(gco_ctx* ctx, const float* extra) {
 
 // ---- one epoch ------------------------------------------------------------------
 
-static void run_forward(gco_ctx* ctx, const GraphView& gv) {
+// Hidden layers of Eq. 3 and the transform of the scalar layer: leaves t.
+static void run_hidden_forward(gco_ctx* ctx, const GraphView& gv) {
   const Launch ln = ctx->launch();
   const gco_config& c = ctx->cfg;
   const int D = c.dim, L = c.num_layers;
@@ -1156,24 +1232,29 @@ static void run_forward(gco_ctx* ctx, const GraphView& gv) {
                         last ? ctx->W[L - 1] : nullptr, wos, ctx->t, ctx->d_heavy_partial);
     }
   }
-  launch_fwd_readout(ln, gv, ctx->t, ctx->z, ctx->p);
+}
+
+// The width-1 passes on t: passes = 1: z = A_hat t, p = sigmoid(z) (Eq. 4); 2: also the
+// loss partials of set `slot` (< kLossSets) and dL/dz (Eq. 5); 3: also g_t = A_hat^T dL/dz.
+// One launch when the subgraphs fit a compute unit's LDS, else one launch per pass.
+static void run_scalar_layer(gco_ctx* ctx, const GraphView& gv, int passes, int slot) {
+  const Launch ln = ctx->launch();
+  const float q = ctx->cfg.problem == GCO_PROBLEM_MAXCUT ? 2.f : ctx->cfg.alpha;
+  double* partial = ctx->loss_partial + static_cast<size_t>(slot) * gv.num_loss_slots;
+  if (ctx->fused_scalar) {
+    launch_scalar_fused(ln, gv, ctx->fused_waves, ctx->fused_cap, ctx->d_fused_cuts, ctx->d_heavy_ptr, ctx->t,
+                        ctx->p, ctx->d_c, q, ctx->g_t, partial, passes);
+  } else {
+    launch_fwd_readout(ln, gv, ctx->t, ctx->z, ctx->p);
+    if (passes >= 2) launch_loss(ln, gv, ctx->p, ctx->d_c, q, ctx->g_z, partial);
+    if (passes >= 3) launch_bwd_readout(ln, gv, ctx->g_z, ctx->g_t);
+  }
   ctx->probs_valid = true;
 }
 
-static void run_forward(gco_ctx* ctx) { run_forward(ctx, ctx->gv); }
-
-// Loss kernel; its workgroup partials go to set `slot` (< kLossSets) of loss_partial.
-static void run_loss_partials(gco_ctx* ctx, const GraphView& gv, int slot) {
-  const Launch ln = ctx->launch();
-  const float q = ctx->cfg.problem == GCO_PROBLEM_MAXCUT ? 2.f : ctx->cfg.alpha;
-  launch_loss(ln, gv, ctx->p, ctx->d_c, q, ctx->g_z,
-              ctx->loss_partial + static_cast<size_t>(slot) * gv.num_loss_slots);
-}
-
-// Loss at the current parameters: total to loss_out[0], per-subgraph values to ctx->loss_part.
-static void run_loss(gco_ctx* ctx, double* loss_out) {
-  run_loss_partials(ctx, ctx->gv, 0);
-  launch_loss_reduce(ctx->launch(), ctx->gv, ctx->loss_partial, 1, 0, ctx->loss_part, loss_out);
+static void run_forward(gco_ctx* ctx) {
+  run_hidden_forward(ctx, ctx->gv);
+  run_scalar_layer(ctx, ctx->gv, 1, 0);
 }
 
 // Adam constants for one more step when every subgraph and weight set has seen `step` steps.
@@ -1189,6 +1270,7 @@ static AdamStep adam_constants(const gco_config& c, int64_t step) {
   return ad;
 }
 
+// Backward pass from g_t on (run_scalar_layer with passes = 3 has run).
 // update = true: an Adam step with the constants adE (embedding rows) and adW (weights);
 // update = false: gradients are written to gE / gW.  gv and maps name the subgraphs that
 // take part.
@@ -1199,7 +1281,6 @@ static void run_backward(gco_ctx* ctx, const GraphView& gv, const gco_ctx::Activ
   const int D = c.dim, L = c.num_layers;
   const int ws = ctx->Pw == 1 ? 0 : D * D, wos = ctx->Pw == 1 ? 0 : D;
   const AdamStep& ad = adE;
-  launch_bwd_readout(ln, gv, ctx->g_z, ctx->g_t);
   BwdArgs a;
   a.g_t = ctx->g_t;
   a.w_out = ctx->W[L - 1];
@@ -1312,8 +1393,8 @@ static int train_impl(gco_ctx* ctx, int32_t epochs, const uint8_t* active, doubl
         adE.per_part = ctx->d_bc + static_cast<size_t>(e) * (P + Pw);
         adW.per_part = adE.per_part + P;
       }
-      run_forward(ctx, gv);
-      run_loss_partials(ctx, gv, e);
+      run_hidden_forward(ctx, gv);
+      run_scalar_layer(ctx, gv, 3, e);
       if (ctx->best_on) {
         // the parameters still are the ones this loss belongs to
         launch_best_update(ctx->launch(), gv, ctx->loss_partial + static_cast<size_t>(e) * gv.num_loss_slots,
@@ -1453,8 +1534,9 @@ int gco_get_probs(gco_ctx* ctx, float* p) {
 int gco_loss(gco_ctx* ctx, double* total, double* per_part) {
   if (!ctx) return GCO_EINVAL;
   NEED(ctx->has_params, GCO_ESTATE, "set_params must precede loss");
-  run_forward(ctx);
-  run_loss(ctx, ctx->loss_one);
+  run_hidden_forward(ctx, ctx->gv);
+  run_scalar_layer(ctx, ctx->gv, 2, 0);
+  launch_loss_reduce(ctx->launch(), ctx->gv, ctx->loss_partial, 1, 0, ctx->loss_part, ctx->loss_one);
   HIPCHK(hipGetLastError());
   if (total) HIPCHK(d2h(ctx, total, ctx->loss_one, 1));
   if (per_part) HIPCHK(d2h(ctx, per_part, ctx->loss_part, static_cast<size_t>(ctx->P)));
@@ -1474,8 +1556,8 @@ int gco_get_grads(gco_ctx* ctx, float* gE, float* const* gW) {
     d_gW[l - 1] = tmp.get<float>(static_cast<size_t>(ctx->Pw) * w_elems(ctx, l));
     NEED(d_gW[l - 1], GCO_ENOMEM, "device scratch allocation failed");
   }
-  run_forward(ctx);
-  run_loss(ctx, ctx->loss_one);
+  run_hidden_forward(ctx, ctx->gv);
+  run_scalar_layer(ctx, ctx->gv, 3, 0);
   run_backward(ctx, ctx->gv, ctx->full, false, AdamStep{}, AdamStep{}, d_gE, d_gW);
   HIPCHK(hipGetLastError());
   if (gE) {

@@ -49,6 +49,7 @@ enum KernelKind : int {
   KK_FORM_GZ,          // G_Z of the last hidden layer + gradient of the scalar layer's weights
   KK_BEST,             // best-by-loss snapshot: decision per model + copy of the improved ones
   KK_GRAD_W,           // weight gradient of a hidden layer from stored rows (bf16, width 128)
+  KK_SCALAR_FUSED,     // read-out, loss and the scalar layer's backward aggregation in one launch
   KK_COUNT
 };
 
@@ -102,9 +103,12 @@ struct GraphView {
   const int* wtile_hptr = nullptr;  // [tiles+1]
   const int2* went = nullptr;
   const int2* went_t = nullptr;
-  // the same entries' values in fp32 (width-1 kernels)
+  // the same entries' values in fp32 (width-1 kernels), and the row every entry of the
+  // stream belongs to (-2 for the lone entry of a pre-reduced row; the same for A_hat and
+  // its transpose)
   const float* wval = nullptr;
   const float* wval_t = nullptr;
+  const int* wrowid = nullptr;
   // narrow kernels: same scheme with kNarrowRows-row tiles
   const int* nblk_k = nullptr;
   const int* nblk_s = nullptr;
@@ -221,6 +225,18 @@ void launch_best_update(const Launch& ln, const GraphView& g, const double* loss
 void launch_param_copy(const Launch& ln, const GraphView& g, int models, int D, const int* flag,
                        const float* E_src, float* E_dst, const float* const* W_src, float* const* W_dst,
                        const int* w_elems, int num_w);
+
+// The three width-1 passes in one launch, one workgroup of `waves` (4 or 16) wavefronts per
+// subgraph; needs every subgraph's rows to fit the LDS (see scalar_fused_lds_bytes):
+// p = sigmoid(A_hat t) [passes >= 1]; loss partial of subgraph k to loss_partial[k] and
+// dL/dz kept in LDS [passes >= 2]; g_t = A_hat^T dL/dz [passes = 3].  cuts[k * waves + w] =
+// range [x, y) of the light stream (whole rows) of wavefront w of subgraph k; heavy_ptr[k .. k+1) = subgraph k's range in
+// g.heavy_rows; cap = row capacity of each of the two LDS vectors.  Subgraphs whose list in
+// g.loss_ptr is empty are skipped.
+size_t scalar_fused_lds_bytes(int waves, int cap);
+void launch_scalar_fused(const Launch& ln, const GraphView& g, int waves, int cap, const int2* cuts,
+                         const int* heavy_ptr, const float* t, float* p, const float* c, float q, float* g_t,
+                         double* loss_partial, int passes);
 
 // g_t = A_hat^T g_z.
 void launch_bwd_readout(const Launch& ln, const GraphView& g, const float* g_z, float* g_t);

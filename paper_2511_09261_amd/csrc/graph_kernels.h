@@ -35,7 +35,7 @@ void launch_pack_entries(hipStream_t st, int n, const int32_t* rowptr, const int
 // {column, value as a bf16 pair}, wval the value in fp32.
 void launch_light_count(hipStream_t st, int n, const int32_t* rowptr, int64_t* count);
 void launch_light_fill(hipStream_t st, int n, const int32_t* rowptr, const int2* ent, const float* diag,
-                       const int64_t* wptr64, int32_t* wrowptr, int2* went, float* wval);
+                       const int64_t* wptr64, int32_t* wrowptr, int2* went, float* wval, int32_t* wrowid);
 void launch_linear_coeff(hipStream_t st, int n, const float* c_base, const float* extra_orig,
                          const int32_t* perm, float* c);
 

@@ -241,30 +241,34 @@ __device__ __forceinline__ int split_bf16(float w) {
 }
 
 // One wavefront per row: {i, diag[i]}, then a light row's entries, to the light stream,
-// the values split into bf16 pairs.
+// the values split into bf16 pairs.  wrowid (may be null) receives the row of every entry of
+// the stream, -2 for the lone entry of a pre-reduced row.
 __global__ __launch_bounds__(kBlock) void light_fill_kernel(int n, const int32_t* __restrict__ rowptr,
                                                             const int2* __restrict__ ent,
                                                             const float* __restrict__ diag,
                                                             const int64_t* __restrict__ wptr64,
                                                             int32_t* __restrict__ wrowptr,
                                                             int2* __restrict__ went,
-                                                            float* __restrict__ wval) {
+                                                            float* __restrict__ wval,
+                                                            int32_t* __restrict__ wrowid) {
   const int i = blockIdx.x * (kBlock / 64) + threadIdx.x / 64;
   if (i > n) return;
   const int lane = threadIdx.x % 64;
   if (lane == 0) wrowptr[i] = static_cast<int32_t>(wptr64[i]);
   if (i == n) return;
   const int64_t out = wptr64[i];
+  const int deg = rowptr[i + 1] - rowptr[i];
   if (lane == 0) {
     went[out] = make_int2(i, split_bf16(diag[i]));
     wval[out] = diag[i];
+    if (wrowid != nullptr) wrowid[out] = deg >= kHeavyMin ? -2 : i;
   }
-  const int deg = rowptr[i + 1] - rowptr[i];
   if (deg >= kHeavyMin) return;
   for (int q = lane; q < deg; q += 64) {
     const int2 en = ent[rowptr[i] + q];
     went[out + 1 + q] = make_int2(en.x, split_bf16(__int_as_float(en.y)));
     wval[out + 1 + q] = __int_as_float(en.y);
+    if (wrowid != nullptr) wrowid[out + 1 + q] = i;
   }
 }
 
@@ -507,9 +511,9 @@ void launch_light_count(hipStream_t st, int n, const int32_t* rowptr, int64_t* c
 }
 
 void launch_light_fill(hipStream_t st, int n, const int32_t* rowptr, const int2* ent, const float* diag,
-                       const int64_t* wptr64, int32_t* wrowptr, int2* went, float* wval) {
+                       const int64_t* wptr64, int32_t* wrowptr, int2* went, float* wval, int32_t* wrowid) {
   light_fill_kernel<<<blocks_for(static_cast<int64_t>(n) + 1, kBlock / 64), kBlock, 0, st>>>(
-      n, rowptr, ent, diag, wptr64, wrowptr, went, wval);
+      n, rowptr, ent, diag, wptr64, wrowptr, went, wval, wrowid);
 }
 
 void launch_linear_coeff(hipStream_t st, int n, const float* c_base, const float* extra_orig,

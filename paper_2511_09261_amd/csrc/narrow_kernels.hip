@@ -3,20 +3,22 @@
 //
 // All three are sums over the entries of each row of one gathered scalar.  They run on
 // the light stream (per row its diagonal entry, then its neighbours; rows with very many
-// neighbours hold only the diagonal entry): a wavefront owns a contiguous run of rows of
-// one subgraph, cut on the host so that all wavefronts carry about the same number of
-// entries, and consumes the stream 64 entries at a time, one entry per lane, whatever
-// the row lengths:
-//   * the entries of the next step and the gathered values of this step are requested
-//     before the current step is reduced;
-//   * the rows that begin in the step mark their first entry (an LDS scatter of the row
-//     number), an inclusive max-scan over the lanes gives every entry its row, a segmented
-//     inclusive sum gives the last lane of every row the row's share of the step, which
-//     it adds to the row's accumulator in LDS -- one lane per row and step, steps in
-//     order: a fixed order;
-//   * at the end the lanes turn into rows and apply the row-wise epilogue.
-// Rows with very many neighbours are summed by one workgroup each (the first workgroups
-// of the grid), which also applies their epilogue; the stream part skips those rows.
+// neighbours hold only the diagonal entry), which also names the row of every entry: a
+// wavefront owns a contiguous run of rows of one subgraph, cut on the host so that all
+// wavefronts carry about the same number of entries, and consumes its range of the stream
+// 64 entries at a time, one entry per lane, whatever the row lengths:
+//   * the entries of the next K steps are requested while the current K are reduced, and
+//     the gathered value of the next step before the current step is reduced;
+//   * a segmented inclusive sum keyed by the row number (data-parallel-primitive moves,
+//     no LDS) gives the last lane of every row the row's share of the step; a row that runs
+//     on into the next step hands its partial sum over in a scalar register; the last lane
+//     of a row applies the row-wise epilogue.  One fixed order of additions.
+// Rows with very many neighbours are summed by a whole workgroup each, which also applies
+// their epilogue; the stream skips them (their row number reads -2).
+//
+// Two launch forms: three separate kernels over a common decomposition (any graph), or
+// ONE launch with a workgroup per subgraph that keeps the subgraph's vectors in LDS (when
+// they fit).
 #include "device_utils.h"
 #include "gco_internal.h"
 
@@ -24,7 +26,6 @@ namespace gco {
 namespace {
 
 constexpr int kWaves = kBlock / 64;
-constexpr int kBatchRows = 512;  // rows whose offsets and sums a wavefront keeps in LDS at a time
 
 // Sum of v over the workgroup in a fixed order; every thread gets the total.
 __device__ __forceinline__ float block_sum(float v, float* red) {
@@ -54,14 +55,6 @@ __device__ __forceinline__ float dpp_move(float fill, float v) {
 }
 #define GCO_SCAN_STEPS(STEP) \
   STEP(0x111, 0xf) STEP(0x112, 0xf) STEP(0x114, 0xf) STEP(0x118, 0xf) STEP(0x142, 0xa) STEP(0x143, 0xc)
-
-// Inclusive running maximum over the lanes (values >= -1).
-__device__ __forceinline__ int scan_max(int v) {
-#define GCO_STEP(C, M) v = max(v, dpp_move<C, M>(-1, v));
-  GCO_SCAN_STEPS(GCO_STEP)
-#undef GCO_STEP
-  return v;
-}
 
 // Inclusive sum over the lanes, restarted wherever key changes (equal keys are contiguous).
 __device__ __forceinline__ float scan_sum_by_key(float v, int key) {
@@ -114,6 +107,113 @@ struct LossOp {  // s = A_loc p; g_z = (c + q s) p (1 - p); loss term p (c + q/2
   }
 };
 
+// One wavefront sums the rows whose entries fill [E0, E1) of the light stream (went, wval,
+// wrowid): whole rows, in order.  K = steps of 64 entries requested at a time.
+template <class Op, int K>
+__device__ __forceinline__ void stream_rows(const int2* __restrict__ went, const float* __restrict__ wval,
+                                            const int* __restrict__ wrowid, const Op& op, int E0, int E1,
+                                            double& lsum) {
+  const int lane = threadIdx.x % 64;
+  int col_c[K], row_c[K];
+  float w_c[K];
+  auto request = [&](int base, int (&col)[K], int (&row)[K], float (&w)[K]) {
+#pragma unroll
+    for (int u = 0; u < K; ++u) {
+      const int idx = base + 64 * u + lane;
+      const bool ok = idx < E1;
+      col[u] = ok ? went[idx].x : 0;
+      row[u] = ok ? wrowid[idx] : -1;
+      w[u] = (ok && Op::kWeighted) ? wval[idx] : 0.f;
+    }
+  };
+  int carry_row = -1;     // the row that runs on from the previous step, and its sum so far
+  float carry_sum = 0.f;
+  float x_cur = 0.f;
+  // K steps from one set of registers; (ncol0, nrow0) = the first step of the other set
+  auto reduce_group = [&](int g0, const int (&col)[K], const int (&rowv)[K], const float (&w)[K], int ncol0,
+                          int nrow0) {
+#pragma unroll
+    for (int u = 0; u < K; ++u) {
+      const int e0 = g0 + 64 * u;
+      if (e0 < E1) {
+        const int ncol = u + 1 < K ? col[(u + 1) % K] : ncol0;
+        const int nrow = u + 1 < K ? rowv[(u + 1) % K] : nrow0;
+        float x_nxt = 0.f;
+        if (e0 + 64 + lane < E1) x_nxt = op.gather(ncol);
+        const int next_first = __builtin_amdgcn_readfirstlane(nrow);  // -1 past the range
+        const int row = rowv[u];
+        const bool valid = row >= 0;  // inside the range and not the entry of a pre-reduced row
+        float v = 0.f;
+        // the diagonal entry is the one whose column is the row itself (no self loops)
+        if (valid) v = Op::kWeighted ? w[u] * x_cur : (col[u] == row ? 0.f : x_cur);
+        v = scan_sum_by_key(v, row);
+        int next_row = __shfl_down(row, 1, 64);
+        if (lane == 63) next_row = next_first;
+        const float total = v + (row == carry_row ? carry_sum : 0.f);
+        if (valid && next_row != row) op.finish(row, total, lsum);
+        const int row63 = __builtin_amdgcn_readlane(row, 63);
+        const float tot63 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(total), 63));
+        const bool runs_on = row63 >= 0 && next_first == row63;
+        carry_row = runs_on ? row63 : -1;
+        carry_sum = runs_on ? tot63 : 0.f;
+        x_cur = x_nxt;
+      }
+    }
+  };
+  // two register sets take turns: one is reduced while the other's loads travel
+  int col_d[K], row_d[K];
+  float w_d[K];
+  request(E0, col_c, row_c, w_c);
+  if (E0 + lane < E1) x_cur = op.gather(col_c[0]);
+  for (int g0 = E0; g0 < E1; g0 += 128 * K) {
+    request(g0 + 64 * K, col_d, row_d, w_d);
+    reduce_group(g0, col_c, row_c, w_c, col_d[0], row_d[0]);
+    request(g0 + 128 * K, col_c, row_c, w_c);
+    reduce_group(g0 + 64 * K, col_d, row_d, w_d, col_c[0], row_c[0]);
+  }
+}
+
+// One row with very many neighbours, summed by the whole workgroup (NT threads): CSR
+// entries {column, A_hat value} of `ent`; kU entries per thread and pass: first all
+// entries, then all gathered values.  Thread 0 returns the row's sum (diagonal included
+// for the weighted operations); red holds NT / 64 floats.  Contains workgroup barriers.
+template <class Op, int NT>
+__device__ __forceinline__ float heavy_row_sum(const GraphView& g, const int2* __restrict__ ent, const Op& op,
+                                               int i, float* red) {
+  const int tid = threadIdx.x;
+  const int e0 = g.rowptr[i], e1 = g.rowptr[i + 1];
+  constexpr int kU = NT >= 1024 ? 8 : 32;
+  float acc = 0.f;
+  for (int e = e0 + tid; e < e1; e += kU * NT) {
+    int2 en[kU];
+    float v[kU];
+#pragma unroll
+    for (int u = 0; u < kU; ++u) {
+      const int ee = e + u * NT;
+      en[u] = ee < e1 ? ent[ee] : make_int2(i, 0);
+    }
+#pragma unroll
+    for (int u = 0; u < kU; ++u) {
+      const float x = op.gather(en[u].x);
+      v[u] = e + u * NT < e1 ? (Op::kWeighted ? __int_as_float(en[u].y) * x : x) : 0.f;
+    }
+#pragma unroll
+    for (int w = 1; w < kU; w *= 2)
+#pragma unroll
+      for (int u = 0; u < kU; u += 2 * w) v[u] += v[u + w];
+    acc += v[0];
+  }
+  acc = wave_sum(acc);
+  if (tid % 64 == 0) red[tid / 64] = acc;
+  __syncthreads();
+  float total = 0.f;
+#pragma unroll
+  for (int w = 0; w < NT / 64; ++w) total += red[w];
+  __syncthreads();
+  if (Op::kWeighted) total += g.diag[i] * op.gather(i);
+  return total;
+}
+
 // Grid: g.num_heavy workgroups for the rows with very many neighbours, then the stream
 // workgroups of decomposition WM_NARROW.  loss_partial (LossOp only) gets one value per
 // workgroup of the grid.
@@ -122,42 +222,14 @@ __global__ __launch_bounds__(kBlock) void narrow_stream_kernel(GraphView g, Op o
                                                                double* __restrict__ loss_partial) {
   __shared__ float red[kWaves];
   __shared__ double dred[kWaves];
-  __shared__ int mark_s[kWaves][64];
-  __shared__ int rp_s[kWaves][kBatchRows + 1];
-  __shared__ float rowacc_s[kWaves][kBatchRows];
   const int tid = threadIdx.x, lane = tid % 64, wave = tid / 64;
   double lsum = 0.0;
 
   if (static_cast<int>(blockIdx.x) < g.num_heavy) {
-    // one row with very many neighbours: CSR entries {column, A_hat value};
-    // 32 entries per thread and pass: first all entries, then all gathered values
     const int i = g.heavy_rows[blockIdx.x];
     if (i < 0) return;  // the row's subgraph sits out
-    const int e0 = g.rowptr[i], e1 = g.rowptr[i + 1];
-    constexpr int kU = 32;
-    float acc = 0.f;
-    for (int e = e0 + tid; e < e1; e += kU * kBlock) {
-      int2 en[kU];
-      float v[kU];
-#pragma unroll
-      for (int u = 0; u < kU; ++u) {
-        const int ee = e + u * kBlock;
-        en[u] = ee < e1 ? g.ent[ee] : make_int2(i, 0);
-      }
-#pragma unroll
-      for (int u = 0; u < kU; ++u) {
-        const float x = op.gather(en[u].x);
-        v[u] = e + u * kBlock < e1 ? (Op::kWeighted ? __int_as_float(en[u].y) * x : x) : 0.f;
-      }
-#pragma unroll
-      for (int w = 1; w < kU; w *= 2)
-#pragma unroll
-        for (int u = 0; u < kU; u += 2 * w) v[u] += v[u + w];
-      acc += v[0];
-    }
-    float total = block_sum(acc, red);
+    const float total = heavy_row_sum<Op, kBlock>(g, g.ent, op, i, red);
     if (tid == 0) {
-      if (Op::kWeighted) total += g.diag[i] * op.gather(i);
       op.finish(i, total, lsum);
       if (loss_partial != nullptr) loss_partial[blockIdx.x] = lsum;
     }
@@ -168,77 +240,123 @@ __global__ __launch_bounds__(kBlock) void narrow_stream_kernel(GraphView g, Op o
   const int k = g.wblk_k[WM_NARROW][b];
   if (k < 0) return;
   const WaveRun run = g.wave_runs[WM_NARROW][b * kWaves + wave];
-  const int r0 = run.rbeg + run.tile0 * kWaveRows, r1 = min(run.rend, run.rbeg + run.tile1 * kWaveRows);
-  int* mark = mark_s[wave];
-  int* rp = rp_s[wave];
-  float* rowacc = rowacc_s[wave];
-
-  for (int rb = r0; rb < r1; rb += kBatchRows) {
-    // a batch of rows: their stream offsets and accumulators live in LDS
-    const int nr = min(kBatchRows, r1 - rb);
-    for (int q = lane; q <= nr; q += 64) rp[q] = g.wrowptr[rb + q];
-    for (int q = lane; q < nr; q += 64) rowacc[q] = 0.f;
-    const int eb = g.wrowptr[rb], ee = g.wrowptr[rb + nr];
-    wave_lds_handoff();
-    int first = 0;   // first row of the batch whose entries have not begun yet
-    int carry = -1;  // the row that runs on from the previous step
-    // software pipeline: entries two steps ahead, gathered values one step ahead
-    int col_cur = 0, col_nxt = 0;
-    float w_cur = 0.f, w_nxt = 0.f, x_cur = 0.f;
-    if (eb + lane < ee) {
-      col_cur = g.went[eb + lane].x;
-      if (Op::kWeighted) w_cur = g.wval[eb + lane];
-      x_cur = op.gather(col_cur);
-    }
-    if (eb + 64 + lane < ee) {
-      col_nxt = g.went[eb + 64 + lane].x;
-      if (Op::kWeighted) w_nxt = g.wval[eb + 64 + lane];
-    }
-    for (int e0 = eb; e0 < ee; e0 += 64) {
-      int col_nn = 0;
-      float w_nn = 0.f, x_nxt = 0.f;
-      if (e0 + 128 + lane < ee) {
-        col_nn = g.went[e0 + 128 + lane].x;
-        if (Op::kWeighted) w_nn = g.wval[e0 + 128 + lane];
-      }
-      if (e0 + 64 + lane < ee) x_nxt = op.gather(col_nxt);
-      // Which row every entry of the step belongs to.  Every row has at least one entry,
-      // so at most 64 rows begin in the step: rows first, first + 1, ...
-      mark[lane] = -1;
-      const int myrow = first + lane;
-      const int myrp = myrow < nr ? rp[myrow] : ee;
-      const bool begins = myrow < nr && myrp < e0 + 64;
-      wave_lds_handoff();
-      if (begins) mark[myrp - e0] = myrow;
-      first += __builtin_popcountll(__ballot(begins));
-      wave_lds_handoff();
-      int row = mark[lane];
-      const bool is_start = row >= 0;
-      row = scan_max(row);
-      if (row < 0) row = carry;
-      // the row's share of the step, at the row's last lane
-      float v = 0.f;
-      if (e0 + lane < ee) v = Op::kWeighted ? w_cur * x_cur : (is_start ? 0.f : x_cur);
-      v = scan_sum_by_key(v, row);
-      const int next_row = __shfl_down(row, 1, 64);
-      if ((lane == 63 || next_row != row) && row >= 0) rowacc[row] += v;
-      wave_lds_handoff();
-      carry = __builtin_amdgcn_readlane(row, 63);
-      col_cur = col_nxt; w_cur = w_nxt; x_cur = x_nxt;
-      col_nxt = col_nn; w_nxt = w_nn;
-    }
-    for (int q = lane; q < nr; q += 64) {
-      const int i = rb + q;
-      const bool heavy = g.num_heavy > 0 && g.heavy_of_row[i] >= 0;
-      if (!heavy) op.finish(i, rowacc[q], lsum);
-    }
-    wave_lds_handoff();
-  }
+  stream_rows<Op, 4>(g.went, g.wval, g.wrowid, op, run.e0, run.e1, lsum);
   if (loss_partial != nullptr) {
     lsum = wave_sum(lsum);
     if (lane == 0) dred[wave] = lsum;
     __syncthreads();
     if (tid == 0) loss_partial[g.num_heavy + b] = ((dred[0] + dred[1]) + dred[2]) + dred[3];
+  }
+}
+
+// ---------------------------------------------------------------------------
+// The three width-1 passes of a subgraph in ONE launch: read-out (Eq. 4), loss with its
+// derivative (Eq. 5) and the backward aggregation of the scalar layer.  Subgraphs are
+// independent (Sec. 3.3), so the only dependencies are inside a subgraph: one workgroup
+// of NW wavefronts per subgraph keeps the subgraph's vectors in LDS (bufA: t, then dL/dz;
+// bufB: p) and separates the passes by workgroup barriers.  Each wavefront sums a
+// contiguous range of the subgraph's rows (cut on the host into equal shares of entries)
+// with the stream routine above (cuts[k * NW + w] = its range of the light stream); rows
+// with very many neighbours are summed by the whole workgroup after each pass.  `passes` = 1 stops after the probabilities, 2 after the loss.
+// ---------------------------------------------------------------------------
+struct FusedReadoutOp {
+  static constexpr bool kWeighted = true;
+  const float* bufA;   // t of the subgraph's rows
+  float* bufB;         // p
+  float* __restrict__ p;
+  int rbeg;
+  __device__ __forceinline__ float gather(int j) const { return bufA[j - rbeg]; }
+  __device__ __forceinline__ void finish(int i, float s, double&) const {
+    const float pi = 1.f / (1.f + expf(-s));
+    bufB[i - rbeg] = pi;
+    p[i] = pi;
+  }
+};
+struct FusedLossOp {
+  static constexpr bool kWeighted = false;
+  const float* bufB;   // p
+  float* bufA;         // in: the linear coefficient c of the row; out: dL/dz
+  float q;
+  int rbeg;
+  __device__ __forceinline__ float gather(int j) const { return bufB[j - rbeg]; }
+  __device__ __forceinline__ void finish(int i, float s, double& ls) const {
+    const float pi = bufB[i - rbeg], ci = bufA[i - rbeg];
+    bufA[i - rbeg] = (ci + q * s) * pi * (1.f - pi);
+    ls += static_cast<double>(pi) *
+          (static_cast<double>(ci) + 0.5 * static_cast<double>(q) * static_cast<double>(s));
+  }
+};
+struct FusedBackOp {
+  static constexpr bool kWeighted = true;
+  const float* bufA;   // dL/dz
+  float* __restrict__ g_t;
+  int rbeg;
+  __device__ __forceinline__ float gather(int j) const { return bufA[j - rbeg]; }
+  __device__ __forceinline__ void finish(int i, float s, double&) const { g_t[i] = s; }
+};
+
+template <int NW>
+__global__ __launch_bounds__(64 * NW) void scalar_layer_fused_kernel(
+    GraphView g, const int2* __restrict__ cuts, const int* __restrict__ heavy_ptr, int cap,
+    const float* __restrict__ t, float* __restrict__ p, const float* __restrict__ cl, float q,
+    float* __restrict__ g_t, double* __restrict__ loss_partial, int passes) {
+  extern __shared__ __align__(16) unsigned char smem[];
+  float* bufA = reinterpret_cast<float*>(smem);
+  float* bufB = bufA + cap;
+  float* red = bufB + cap;
+  double* dred = reinterpret_cast<double*>(red + NW + (NW % 2));
+  const int k = blockIdx.x;
+  if (g.loss_ptr[k + 1] == g.loss_ptr[k]) return;  // the subgraph sits out
+  const int tid = threadIdx.x, lane = tid % 64;
+  const int wave = __builtin_amdgcn_readfirstlane(tid / 64);
+  const int rbeg = g.part_rows[k], rend = g.part_rows[k + 1];
+  const int2 mine = cuts[k * NW + wave];  // this wavefront's range of the light stream
+  const int h0 = heavy_ptr[k], h1 = heavy_ptr[k + 1];
+  double lsum = 0.0;
+
+  for (int r = rbeg + tid; r < rend; r += 64 * NW) bufA[r - rbeg] = t[r];
+  __syncthreads();
+  {
+    const FusedReadoutOp op{bufA, bufB, p, rbeg};
+    stream_rows<FusedReadoutOp, 8>(g.went, g.wval, g.wrowid, op, mine.x, mine.y, lsum);
+    for (int hh = h0; hh < h1; ++hh) {
+      const int i = g.heavy_rows[hh];
+      const float total = heavy_row_sum<FusedReadoutOp, 64 * NW>(g, g.ent, op, i, red);
+      if (tid == 0) op.finish(i, total, lsum);
+    }
+  }
+  if (passes < 2) return;
+  __syncthreads();
+  // t has served; its place takes the linear coefficients, which the loss pass replaces row
+  // by row with dL/dz (no dependent global load inside the pass)
+  for (int r = rbeg + tid; r < rend; r += 64 * NW) bufA[r - rbeg] = cl[r];
+  __syncthreads();
+  {
+    const FusedLossOp op{bufB, bufA, q, rbeg};
+    stream_rows<FusedLossOp, 8>(g.went, g.wval, g.wrowid, op, mine.x, mine.y, lsum);
+    for (int hh = h0; hh < h1; ++hh) {
+      const int i = g.heavy_rows[hh];
+      const float total = heavy_row_sum<FusedLossOp, 64 * NW>(g, g.ent, op, i, red);
+      if (tid == 0) op.finish(i, total, lsum);
+    }
+  }
+  lsum = wave_sum(lsum);
+  if (lane == 0) dred[wave] = lsum;
+  __syncthreads();  // also: dL/dz of every row is in bufA
+  if (tid == 0) {
+    double total = 0.0;
+    for (int w = 0; w < NW; ++w) total += dred[w];
+    loss_partial[k] = total;
+  }
+  if (passes < 3) return;
+  {
+    const FusedBackOp op{bufA, g_t, rbeg};
+    stream_rows<FusedBackOp, 8>(g.went_t, g.wval_t, g.wrowid, op, mine.x, mine.y, lsum);
+    for (int hh = h0; hh < h1; ++hh) {
+      const int i = g.heavy_rows[hh];
+      const float total = heavy_row_sum<FusedBackOp, 64 * NW>(g, g.ent_t, op, i, red);
+      if (tid == 0) op.finish(i, total, lsum);
+    }
   }
 }
 
@@ -250,6 +368,30 @@ void launch_narrow(const Launch& ln, int kind, const GraphView& g, const Op& op,
 }
 
 }  // namespace
+
+size_t scalar_fused_lds_bytes(int waves, int cap) {
+  return 2 * static_cast<size_t>(cap) * sizeof(float) + static_cast<size_t>(waves + waves % 2) * sizeof(float) +
+         static_cast<size_t>(waves) * sizeof(double);
+}
+
+void launch_scalar_fused(const Launch& ln, const GraphView& g, int waves, int cap, const int2* cuts,
+                         const int* heavy_ptr, const float* t, float* p, const float* c, float q, float* g_t,
+                         double* loss_partial, int passes) {
+  const size_t lds = scalar_fused_lds_bytes(waves, cap);
+  ln.begin(KK_SCALAR_FUSED);
+  if (waves == 16) {
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(scalar_layer_fused_kernel<16>),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
+    scalar_layer_fused_kernel<16><<<g.P, 1024, lds, ln.st>>>(g, cuts, heavy_ptr, cap, t, p, c, q, g_t,
+                                                            loss_partial, passes);
+  } else {
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(scalar_layer_fused_kernel<4>),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
+    scalar_layer_fused_kernel<4><<<g.P, 256, lds, ln.st>>>(g, cuts, heavy_ptr, cap, t, p, c, q, g_t,
+                                                          loss_partial, passes);
+  }
+  ln.end(KK_SCALAR_FUSED);
+}
 
 void launch_fwd_readout(const Launch& ln, const GraphView& g, const float* t, float* z, float* p) {
   launch_narrow(ln, KK_FWD_READOUT, g, ReadoutOp{t, z, p}, nullptr);
