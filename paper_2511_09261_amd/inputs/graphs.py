@@ -212,6 +212,12 @@ def gumbel_uniforms(n: int, dim: int, seed: int) -> np.ndarray:
     return ((k.astype(np.float64) + 0.5) / float(1 << 23)).astype(np.float32).reshape(n, dim)
 
 
+def exploration_uniforms(rounds: int, seed: int) -> np.ndarray:
+    """float64 uniforms in [0, 1), two per round: the random draws of the cross-subgraph
+    coordination stage's epsilon-greedy agent (explore or not; which option)."""
+    return rng.uniform(rng.stream_key(seed, 13), 2 * rounds).reshape(rounds, 2)
+
+
 # --- the five workload configurations ---------------------------------------
 
 @dataclass
