@@ -25,25 +25,30 @@ HBM_PEAK_GBS = 8000.0  # MI355X HBM3E, published
 
 
 def cpu_baseline(wl, E, Ws, epochs):
-    """The fp64 checker, unmodified, on the host cores: epochs/s over `epochs`
-    epochs of the same workload."""
-    import numpy as np
+    """The fp64 checker, unmodified, on ONE host core (the numerical libraries under numpy
+    and scipy limited to one thread): epochs/s over `epochs` epochs of the same workload.
+    One more epoch with the libraries' own thread count is reported beside it."""
+    from threadpoolctl import threadpool_info, threadpool_limits
     from oracle import gcn
     g = wl.graph
     spec = gcn.Spec(problem=wl.problem, num_layers=wl.num_layers, lr=wl.lr)
     lg = gcn.local_graph(g.n, g.rowptr, g.col, wl.part, wl.num_parts, "sym")
     st = gcn.init_state(E, Ws)
+    with threadpool_limits(limits=1):
+        t0 = time.perf_counter()
+        losses, _ = gcn.train(lg, st, spec, epochs)
+        dt = time.perf_counter() - t0
+    threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
     t0 = time.perf_counter()
-    losses, _ = gcn.train(lg, st, spec, epochs)
-    dt = time.perf_counter() - t0
-    try:
-        from threadpoolctl import threadpool_info
-        cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
-    except Exception:
-        cores = os.cpu_count()
-    return {"value": epochs / dt, "unit": "epochs/s", "cores": int(cores), "kind": "oracle",
-            "sample": f"{epochs} full epochs of the same workload (all {wl.num_parts} subgraphs), fp64 numpy/scipy",
-            "first_loss": float(losses[0])}
+    gcn.train(lg, st, spec, 1)
+    dt_all = time.perf_counter() - t0
+    return {"value": epochs / dt, "unit": "epochs/s", "cores": 1, "kind": "oracle",
+            "sample": f"{epochs} full epochs of the same workload (all {wl.num_parts} subgraphs), fp64 numpy/scipy, "
+                      f"numerical libraries limited to one thread",
+            "first_loss": float(losses[0]),
+            "with_library_threads": {"value": 1.0 / dt_all, "unit": "epochs/s", "cores": int(threads),
+                                     "sample": "one more epoch, dense products on the libraries' own thread "
+                                               "count, sparse products single-threaded"}}
 
 
 def recorded_traffic(kernel):
@@ -85,7 +90,9 @@ def main():
                     help="leave out the subset fine-tune and best-snapshot timings (kernel traces "
                          "then hold full epochs only)")
     ap.add_argument("--pmc-probe", action="store_true",
-                    help="short run for hardware counters: three plain copies of 1 GiB, then 5 epochs")
+                    help="short run for hardware counters (rocprofv3 --pmc <counters> -- python3 bench.py "
+                         "--pmc-probe): three plain copies of 1 GiB, then 5 epochs; FETCH_SIZE / WRITE_SIZE "
+                         "give the traffic, MfmaUtil / VALUBusy / LdsUtil the compute-side picture")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: every subgraph of the graph is batched on a single "
@@ -204,8 +211,18 @@ def main():
     achieved = tim["bytes_per_launch"] / (avg_ms * 1e-3) / 1e9 if avg_ms > 0 else 0.0
     gb_epoch = sum(v["bytes_per_launch"] * v["launches"] / 5 for v in breakdown.values()) / 1e9
     launches_epoch = sum(v["launches"] for v in breakdown.values()) / 5
+    shape = {"c4": "Youtube-shaped 1.1M-node graph", "c5": "high-complexity 50-regular 2M-node graph",
+             "c3": "Facebook-shaped 4k-node graph", "c2": "3-regular 10k-node graph", "c1": "G(200, 0.05)",
+             "c4p1": "Youtube-shaped 1.1M-node graph as ONE subgraph (stress variant)",
+             "c5p1": "50-regular 2M-node graph as ONE subgraph (stress variant)"}.get(wl.name, wl.name)
+    kernel_gbs = {k: (breakdown[k]["bytes_per_launch"] * breakdown[k]["launches"] / 5) / (per_epoch[k] * 1e-3) / 1e9
+                  for k in per_epoch if per_epoch[k] > 0}
+    # the kernels the aggregation of Eq. 3 and the loss of Eq. 5 run in, beside the dominant one
+    named = [k for k in ("fwd_hidden", "bwd_hidden", "loss", "scalar_layer", "fwd_readout", "bwd_readout")
+             if k in kernel_gbs]
+    traffic = recorded_traffic(dominant) if args.workload == "c4" and args.partition == "bfs" else None
     out = {
-        "metric": "GNN train epochs/s (edge-aggregations/s in extra), Youtube-shaped 1.1M-node graph, 1 GPU",
+        "metric": f"GNN train epochs/s (edge-aggregations/s in extra), {shape}, 1 GPU",
         "value": eps, "unit": "epochs/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": dt / args.steps * 1e3, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "bf16" if wl.storage == "bf16" else "f32", "data": "synthetic",
@@ -218,8 +235,11 @@ def main():
                    **({} if partition_info is None else {"partition": partition_info})},
         "roofline": {"bound": "hbm", "kernel": dominant, "achieved": achieved, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": (recorded_traffic(dominant)
-                                 if args.workload == "c4" and args.partition == "bfs" else None),
+                     "traffic": traffic,
+                     "traffic_source": None if traffic is None else
+                     "recorded: profiles/c4_hbm_traffic.txt (rocprofv3 counters of the same sources), not measured in this run",
+                     "aggregation_and_loss_kernels": {k: {"achieved": kernel_gbs[k], "frac": kernel_gbs[k] / HBM_PEAK_GBS,
+                                                          "ms_per_epoch": per_epoch[k]} for k in named},
                      "copy_kernel_GBps": copy_gbs, "frac_of_copy": achieved / copy_gbs,
                      "avg_launch_ms": avg_ms, "algorithmic_bytes_per_launch": tim["bytes_per_launch"],
                      "launches_timed": tim["launches"]},
@@ -229,8 +249,8 @@ def main():
                   "epoch_frac_of_copy": gb_epoch * eps / copy_gbs,
                   "kernel_launches_per_epoch": launches_epoch,
                   "kernel_ms_per_epoch": per_epoch,
-                  "kernel_gbs": {k: (breakdown[k]["bytes_per_launch"] * breakdown[k]["launches"] / 5)
-                                 / (per_epoch[k] * 1e-3) / 1e9 for k in per_epoch if per_epoch[k] > 0},
+                  "kernel_gbs": kernel_gbs,
+                  "kernel_frac_of_peak": {k: v / HBM_PEAK_GBS for k, v in kernel_gbs.items()},
                   "generate_s": t_gen, "upload_preprocess_s": t_upload,
                   "forward_and_read_probs_s": t_fwd, "round_repair_s": t_rr, "cut_edges_s": t_cut,
                   "fine_tune_subset": {"subgraphs": len(listed), "of": wl.num_parts, "ms_per_epoch": None if t_sub is None else t_sub * 1e3},

@@ -85,6 +85,9 @@ int gco_default_config(gco_config* cfg);
 int gco_create(const gco_config* cfg, gco_ctx** out);
 int gco_destroy(gco_ctx* ctx);
 
+/* The configuration the context was created with. */
+int gco_get_config(gco_ctx* ctx, gco_config* out);
+
 /* Text of the last failure on ctx (valid until the next call on ctx). */
 const char* gco_last_error(gco_ctx* ctx);
 
@@ -234,6 +237,48 @@ int gco_cross_mask(gco_ctx* ctx, uint8_t* c);
 /* Conflict edges (Alg. 1 stage 3, first line): the cross edges with x[u] = x[v] = 1,
  * same order and two-call pattern as gco_cut_edges.  x is uint8[n]. */
 int gco_conflict_edges(gco_ctx* ctx, const uint8_t* x, int64_t* count, int32_t* u, int32_t* v);
+
+/* Cross-subgraph coordination (Sec. 3.3; Alg. 1 stage 3), for GCO_PROBLEM_MIS: a thin
+ * host-side loop over the calls above.  After the subgraphs have been trained, cross edges
+ * whose ends are both selected are conflicts; for a conflict (i, j) either i's or j's
+ * subgraph is fine-tuned with the penalty lambda on that node (gco_set_linear_penalty +
+ * gco_train_subset) so that its probability falls below 0.5.  A tabular Q-learning agent
+ * picks the options over `rounds` rounds; the best assignment is returned.
+ *
+ * The paper leaves the following open; this is the reading implemented (the same, step by
+ * step, as the checker's):
+ *   score   of an assignment x = [p >= 0.5]: beta |S| - alpha #{edges of the whole graph
+ *           inside S} (the negated objective of Eq. 5 at p = x);
+ *   base action ("linear cover"): one pass over the current conflict edges in (u, v) order;
+ *           an edge with an end already chosen is covered, otherwise the end with the
+ *           smaller probability (ties: smaller id) is chosen;
+ *   diff    nothing, or the other end at ONE edge where the pass chose (the pass is redone
+ *           with that choice forced);
+ *   state   x on the ends of the first round's conflict edges; action = the node a diff
+ *           brings in (-1: none); unseen Q entries are 0; greedy ties go to the earlier
+ *           candidate; round t explores iff uniforms[2t] < epsilon, then takes candidate
+ *           floor(uniforms[2t+1] * count);  Q(s,a) += q_lr (r + q_gamma max Q(s',.) - Q(s,a))
+ *           with r = the change of the score;
+ *   fine-tune: chosen nodes keep the penalty (penalties accumulate); the subgraphs that own
+ *           this round's chosen nodes train epochs_per_round epochs;
+ *   stop    after `rounds` rounds or when no conflict is left.
+ * part_id: int32[n] as given to gco_upload_graph (NULL = one subgraph: nothing to do).
+ * uniforms: double[2 * rounds] in [0, 1), supplied by the caller.
+ * Outputs (host; each may be NULL except x_best): x_best uint8[n] and *score_best, the
+ * assignment of the highest score (the first on ties); actions int32[rounds]; scores
+ * double[rounds + 1] and conflicts int64[rounds + 1] (cross conflicts) of every evaluated
+ * assignment, entry 0 before the first round; *rounds_run.  The context is left with the
+ * penalties and parameters of the last round.  alpha and beta are the context's.  EINVAL
+ * for a context that is not GCO_PROBLEM_MIS. */
+typedef struct {
+  int32_t rounds;
+  int32_t epochs_per_round;
+  float lambda;            /* penalty coefficient of Sec. 3.3 */
+  float q_lr, q_gamma, epsilon;
+} gco_rl_config;
+int gco_coordinate(gco_ctx* ctx, const int32_t* part_id, const gco_rl_config* rl, const double* uniforms,
+                   uint8_t* x_best, double* score_best, int32_t* actions, double* scores,
+                   int64_t* conflicts, int32_t* rounds_run);
 
 /* Graph partitioning by modularity (Sec. 3.1): the Louvain heuristic, on the host (no
  * context, no device).  Same graph format as gco_upload_graph (symmetric CSR, no self

@@ -37,6 +37,11 @@ class Config(C.Structure):
     ]
 
 
+class RLConfig(C.Structure):
+    _fields_ = [("rounds", C.c_int32), ("epochs_per_round", C.c_int32), ("lam", C.c_float),
+                ("q_lr", C.c_float), ("q_gamma", C.c_float), ("epsilon", C.c_float)]
+
+
 class GcoError(RuntimeError):
     def __init__(self, code, message):
         super().__init__(f"gco error {code}: {message}")
@@ -50,6 +55,7 @@ _PROTOTYPES = {
     "gco_default_config": (C.c_int, [C.POINTER(Config)]),
     "gco_create": (C.c_int, [C.POINTER(Config), C.POINTER(C.c_void_p)]),
     "gco_destroy": (C.c_int, [C.c_void_p]),
+    "gco_get_config": (C.c_int, [C.c_void_p, C.POINTER(Config)]),
     "gco_last_error": (C.c_char_p, [C.c_void_p]),
     "gco_upload_graph": (C.c_int, [C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32]),
     "gco_graph_info": (C.c_int, [C.c_void_p] + [C.POINTER(C.c_int64)] * 4),
@@ -78,6 +84,9 @@ _PROTOTYPES = {
     "gco_cut_edges": (C.c_int, [C.c_void_p, C.POINTER(C.c_int64), C.c_void_p, C.c_void_p]),
     "gco_cross_mask": (C.c_int, [C.c_void_p, C.c_void_p]),
     "gco_conflict_edges": (C.c_int, [C.c_void_p, C.c_void_p, C.POINTER(C.c_int64), C.c_void_p, C.c_void_p]),
+    "gco_coordinate": (C.c_int, [C.c_void_p, C.c_void_p, C.POINTER(RLConfig), C.c_void_p, C.c_void_p,
+                                 C.POINTER(C.c_double), C.c_void_p, C.c_void_p, C.c_void_p,
+                                 C.POINTER(C.c_int32)]),
     "gco_louvain": (C.c_int, [C.c_int64, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p,
                               C.POINTER(C.c_int32), C.POINTER(C.c_double)]),
     "gco_pack_parts": (C.c_int, [C.c_int64, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.POINTER(C.c_int32)]),
@@ -373,6 +382,27 @@ class Context:
         self._check(self.lib.gco_round_repair_static(self.h, thr, REPAIR[repair_scope], _ptr(x),
                                                      C.byref(obj), C.byref(cb), C.byref(ca)))
         return x, obj.value, cb.value, ca.value
+
+    def coordinate(self, part, uniforms, rounds, epochs_per_round, lam=1.0, q_lr=0.5, q_gamma=0.9,
+                   epsilon=0.2):
+        """gco_coordinate: dict with x_best, score_best, actions, scores, conflicts (of the
+        rounds that ran)."""
+        part = None if part is None else np.ascontiguousarray(part, dtype=np.int32)
+        uniforms = np.ascontiguousarray(uniforms, dtype=np.float64).reshape(-1)
+        if uniforms.shape[0] < 2 * rounds:
+            raise ValueError("two uniforms per round are needed")
+        cfg = RLConfig(rounds, epochs_per_round, lam, q_lr, q_gamma, epsilon)
+        x = np.empty(self.n, dtype=np.uint8)
+        best, ran = C.c_double(), C.c_int32()
+        actions = np.empty(max(rounds, 1), dtype=np.int32)
+        scores = np.empty(rounds + 1, dtype=np.float64)
+        conflicts = np.empty(rounds + 1, dtype=np.int64)
+        self._check(self.lib.gco_coordinate(self.h, _ptr(part), C.byref(cfg), _ptr(uniforms), _ptr(x),
+                                            C.byref(best), _ptr(actions), _ptr(scores), _ptr(conflicts),
+                                            C.byref(ran)))
+        r = ran.value
+        return {"x_best": x, "score_best": best.value, "actions": actions[:r].tolist(),
+                "scores": scores[:r + 1].tolist(), "conflicts": conflicts[:r + 1].tolist()}
 
     def cut_edges(self):
         cnt = C.c_int64()

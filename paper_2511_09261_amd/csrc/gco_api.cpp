@@ -513,9 +513,13 @@ GraphView view_with(const gco_ctx* ctx, const gco_ctx::ActiveMaps& m) {
   return g;
 }
 
+// Algorithmic bytes per launch of every kernel kind: each array of the METHOD that the
+// kernel reads or writes, once (gathers taken as cache-served).  Buffers that exist only
+// because of how the work is cut up (per-workgroup partial sums of the weight gradients and
+// of the loss, chunk partials of pre-reduced rows) are not counted.
 void traffic_model(gco_ctx* ctx) {
   const double n = ctx->n, nnz = static_cast<double>(ctx->nnz_loc), D = ctx->cfg.dim;
-  const double s = ctx->elem_bytes(), Pw = ctx->Pw, NB = ctx->gv.num_blocks;
+  const double s = ctx->elem_bytes(), Pw = ctx->Pw;
   const int L = ctx->cfg.num_layers;
   const double idx = nnz * 4 + (n + 1) * 4, scales = 2 * n * 4;
   double* kb = ctx->kind_bytes;
@@ -531,22 +535,18 @@ void traffic_model(gco_ctx* ctx) {
   kb[KK_BWD_READOUT] = idx + scales + 2 * n * 4;
   // the three passes in one launch: t and c in, p and g_t out; z and dL/dz never travel
   kb[KK_SCALAR_FUSED] = 3 * idx + 2 * scales + 4 * n * 4;
-  // On the wave-per-tile path the weight-gradient partials come from that path's own
-  // workgroups, the scalar layer's from the narrow ones, and G_Z of the last hidden layer
-  // is formed by a kernel of its own (KK_FORM_GZ) instead of inside the layer's backward.
+  // On the wave-per-tile path G_Z of the last hidden layer is formed by a kernel of its own
+  // (KK_FORM_GZ) instead of inside the layer's backward.
   const bool wave = ctx->wave_path() && L >= 2;
   const bool split = ctx->split_grad_w() && L >= 2;
-  const double NBh = wave ? ctx->gv.num_wblocks[WM_BWD] : NB;
-  const double NBe = wave ? ctx->gv.num_wblocks[ctx->grad_map(1)] : NB;
-  const double NBo = wave ? ctx->gv.num_nblocks : NB;
-  const double last_extra = wave ? 0 : n * 4 + NBo * D * 4;  // g_t read + gw_out partials
-  if (wave) kb[KK_FORM_GZ] = 2 * n * D * s + n * 4 + Pw * D * 4 + NBo * D * 4;
-  // gathered gradient source + Hprev read + GZ write
-  kb[KK_BWD_HIDDEN] = idx + scales + 3 * n * D * s + Pw * D * D * 4 + NBh * D * D * 4 + (L == 3 ? last_extra : 0);
+  const double last_extra = wave ? 0 : n * 4;  // g_t read
+  if (wave) kb[KK_FORM_GZ] = 2 * n * D * s + n * 4 + Pw * D * 4;
+  // gathered gradient source + Hprev read + GZ write + W (the weight gradient itself: Pw D^2)
+  kb[KK_BWD_HIDDEN] = idx + scales + 3 * n * D * s + 2 * Pw * D * D * 4 + (L == 3 ? last_extra : 0);
   if (split) {
-    // the partials move to grad_w, which reads Hprev and the stored rows of G_T
-    kb[KK_BWD_HIDDEN] += n * D * s - NBh * D * D * 4;
-    kb[KK_GRAD_W] = 2 * n * D * s + NBh * D * D * 4;
+    // the weight gradient moves to grad_w, which reads Hprev and the stored rows of G_T
+    kb[KK_BWD_HIDDEN] += n * D * s - Pw * D * D * 4;
+    kb[KK_GRAD_W] = 2 * n * D * s + Pw * D * D * 4;
   }
   // first layer: gathered source + embedding (working copy) read + Adam state in/out
   const double adam_e = ctx->cfg.train_embed ? (6 * n * D * 4 + (s == 2 ? n * D * 2 : 0)) : 0;
@@ -554,20 +554,18 @@ void traffic_model(gco_ctx* ctx) {
   if (L >= 2 && split)  // gathered source + G_T rows out + Adam; the working copy is read by grad_w
     kb[KK_BWD_EMBED] = idx + scales + 2 * n * D * s + Pw * D * D * 4 + adam_e;
   else if (L >= 2)
-    kb[KK_BWD_EMBED] = idx + scales + n * D * s + hprev_read + Pw * D * D * 4 + NBe * D * D * 4 + adam_e +
+    kb[KK_BWD_EMBED] = idx + scales + n * D * s + hprev_read + 2 * Pw * D * D * 4 + adam_e +
                        (L == 2 ? last_extra : 0);
   else
-    kb[KK_BWD_EMBED] = n * 4 + hprev_read + adam_e + NB * D * 4;
-  // one launch serves all weight tensors: W, m, v in and out, and the partials
+    kb[KK_BWD_EMBED] = n * 4 + hprev_read + adam_e + Pw * D * 4;
+  // one launch serves all weight tensors: the gradient in, W, m, v in and out
   double wtot = 0;
   for (int l = 1; l <= L; ++l) {
     const double e = l < L ? D * D : D;
-    const double nb = l == L ? NBo : (l == 1 ? NBe : NBh);
-    wtot += Pw * e * 24 + nb * e * 4;
+    wtot += Pw * e * 28;
   }
   kb[KK_ADAM_W] = wtot;
-  // one set of partials; the training loop reduces many sets per launch
-  kb[KK_LOSS_REDUCE] = ctx->gv.num_loss_slots * 8.0 + ctx->P * 8.0;
+  kb[KK_LOSS_REDUCE] = ctx->P * 8.0;
   kb[KK_HEAVY] = 0;  // reported by time only
   kb[KK_BEST] = 0;   // depends on how many models improved
   if (!split) kb[KK_GRAD_W] = 0;
@@ -630,6 +628,12 @@ int gco_destroy(gco_ctx* ctx) {
   if (!ctx) return GCO_EINVAL;
   ctx->free_graph();
   delete ctx;
+  return GCO_OK;
+}
+
+int gco_get_config(gco_ctx* ctx, gco_config* out) {
+  if (!ctx || !out) return GCO_EINVAL;
+  *out = ctx->cfg;
   return GCO_OK;
 }
 
