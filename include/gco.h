@@ -63,7 +63,7 @@ typedef struct {
                              GCO_STORAGE_BF16: node features and their gradients are
                              stored in bf16 and multiplied on the matrix cores with fp32
                              accumulation; parameters, Adam state, probabilities and the
-                             loss stay fp32 (bf16 needs dim >= 32)                            */
+                             loss stay fp32 (dim 64 or 128 only)                            */
   int32_t weight_sharing; /* 0: one weight set per subgraph (Alg. 1 stage 1: one net per
                              subgraph); 1: one set shared by all subgraphs                    */
   int32_t train_embed;    /* 1: node embeddings are trained; 0: only W (Sec. 3.2 names W only) */
@@ -129,8 +129,11 @@ int gco_get_params(gco_ctx* ctx, float* E, float* const* W);
 int gco_set_params_gumbel(gco_ctx* ctx, const float* E, const float* U, float tau,
                           const float* const* W);
 
-/* Adam state ("store net/optimizer states", Alg. 1 stage 1): first and second
- * moments shaped like the parameters, and the step counter t. */
+/* Adam state, for checkpoints (Alg. 1 stage 1 keeps every subgraph's network and optimizer
+ * state): first and second moments shaped like the parameters, and the step counter t.
+ * When subgraphs have been trained different numbers of times (gco_train_subset), `step`
+ * alone does not describe the state: save gco_get_steps too and restore with
+ * gco_set_opt_state followed by gco_set_steps. */
 int gco_get_opt_state(gco_ctx* ctx, float* mE, float* vE, float* const* mW, float* const* vW,
                       int64_t* step);
 int gco_set_opt_state(gco_ctx* ctx, const float* mE, const float* vE, const float* const* mW,
@@ -176,7 +179,9 @@ int gco_set_steps(gco_ctx* ctx, const int64_t* steps_embed, const int64_t* steps
  * snapshot before the update.  enable != 0 starts tracking and forgets earlier snapshots
  * (allocates one more copy of the parameters, fp32); enable == 0 stops tracking and keeps
  * the snapshots.  gco_set_params and a new graph forget them too.  Optimizer state is not
- * part of the snapshot. */
+ * part of the snapshot.  With shared weights the one model is judged by the sum over the
+ * subgraphs an epoch trains: totals of gco_train and of a gco_train_subset over fewer
+ * subgraphs are not comparable, so enable tracking anew before changing the set. */
 int gco_keep_best(gco_ctx* ctx, int32_t enable);
 /* Lowest loss per model: double[Pw] (host), +infinity for a model never offered. */
 int gco_get_best_loss(gco_ctx* ctx, double* best_loss);
@@ -184,7 +189,7 @@ int gco_get_best_loss(gco_ctx* ctx, double* best_loss);
  * Adam moments and step counts are left as they are.  ESTATE if tracking was never on. */
 int gco_restore_best(gco_ctx* ctx);
 
-/* Forward pass at the current parameters (Alg. 1 stage 2: "run forward to get p"). */
+/* Forward pass at the current parameters: the probabilities of Alg. 1 stage 2. */
 int gco_forward(gco_ctx* ctx);
 /* Probabilities of the last forward / the forward of the last epoch: float[n]. */
 int gco_get_probs(gco_ctx* ctx, float* p);

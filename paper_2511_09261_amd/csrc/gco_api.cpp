@@ -219,8 +219,8 @@ struct gco_ctx {
     loss_hist = nullptr;
   }
   int elem_bytes() const { return cfg.storage == GCO_STORAGE_BF16 ? 2 : 4; }
-  // the hidden layers run on the wave-per-tile kernels (bf16 storage, width 64 or 128)
-  bool wave_path() const { return cfg.storage == GCO_STORAGE_BF16 && (cfg.dim == 64 || cfg.dim == 128); }
+  // the hidden layers run on the wave-per-tile kernels (bf16 storage: width 64 or 128)
+  bool wave_path() const { return cfg.storage == GCO_STORAGE_BF16; }
   // width 128: the weight gradients come from a kernel of their own, fed with stored G_T rows
   bool split_grad_w() const { return wave_path() && cfg.dim == 128; }
   // decomposition whose workgroups wrote the weight-gradient partials of hidden layer l
@@ -606,7 +606,7 @@ int gco_create(const gco_config* cfg, gco_ctx** out) {
   if (cfg->problem != GCO_PROBLEM_MIS && cfg->problem != GCO_PROBLEM_MAXCUT) return GCO_EINVAL;
   if (cfg->norm != GCO_NORM_SYM && cfg->norm != GCO_NORM_MEAN) return GCO_EINVAL;
   if (cfg->storage != GCO_STORAGE_FP32 && cfg->storage != GCO_STORAGE_BF16) return GCO_EINVAL;
-  if (cfg->storage == GCO_STORAGE_BF16 && D < 32) return GCO_EINVAL;
+  if (cfg->storage == GCO_STORAGE_BF16 && D != 64 && D != 128) return GCO_EINVAL;
   if ((cfg->dev_alloc == nullptr) != (cfg->dev_free == nullptr)) return GCO_EINVAL;
   if (!(cfg->lr > 0.f) || !(cfg->adam_b1 >= 0.f && cfg->adam_b1 < 1.f) ||
       !(cfg->adam_b2 >= 0.f && cfg->adam_b2 < 1.f) || !(cfg->adam_eps > 0.f))
@@ -1359,10 +1359,18 @@ static int train_impl(gco_ctx* ctx, int32_t epochs, const uint8_t* active, doubl
   const GraphView& gv = active ? ctx->gv_sub : ctx->gv;
   const gco_ctx::ActiveMaps& maps = active ? ctx->sub : ctx->full;
   if (ctx->loss_hist_cap < epochs) {
-    // the old array (if any) stays owned by the graph allocation list
-    ctx->loss_hist = nullptr;
-    GALLOC(ctx->loss_hist, static_cast<size_t>(epochs));
-    ctx->loss_hist_cap = epochs;
+    // grow geometrically; the old array is released once the stream has drained
+    if (ctx->loss_hist != nullptr) {
+      HIPCHK(hipStreamSynchronize(ctx->st));
+      auto it = std::find(ctx->graph_allocs.begin(), ctx->graph_allocs.end(), static_cast<void*>(ctx->loss_hist));
+      if (it != ctx->graph_allocs.end()) ctx->graph_allocs.erase(it);
+      ctx->raw_free(ctx->loss_hist);
+      ctx->loss_hist = nullptr;
+      ctx->loss_hist_cap = 0;
+    }
+    const int64_t cap = std::max<int64_t>(epochs, 2 * ctx->loss_hist_cap);
+    GALLOC(ctx->loss_hist, static_cast<size_t>(cap));
+    ctx->loss_hist_cap = cap;
   }
   // which weight sets take part: a subgraph's own, or the shared one if any subgraph does
   std::vector<uint8_t> actE(P, 1), actW(Pw, 0);

@@ -275,8 +275,8 @@ struct BwdArgs {
 void launch_bwd_hidden(const Launch& ln, int storage, int D, bool last, bool to_embed,
                        const GraphView& g, const BwdArgs& a);
 
-// bf16-storage, matrix-core versions (layer_kernels_bf16.hip); `gt` already has
-// the scale vectors of A_hat^T.
+// bf16-storage, matrix-core versions (layer_launch_bf16.hip, widths 64 and 128); `gt`
+// already has the scale vectors of A_hat^T.
 void launch_fwd_hidden_bf16(const Launch& ln, int D, const GraphView& g, const void* X, const float* W,
                             int w_stride, void* Y, const float* w_out, int wout_stride, float* t,
                             float* heavy_partial);

@@ -107,7 +107,6 @@ FWD_BWD_CASES = [
     ("bfs12", "mis", 3, 32, "sym", "fp32", False),
     ("bfs12", "maxcut", 1, 16, "mean", "fp32", True),
     ("random", "mis", 3, 64, "sym", "bf16", False),
-    ("random", "maxcut", 2, 32, "mean", "bf16", False),
     ("hubs", "mis", 3, 64, "sym", "bf16", False),
     ("hubs_parts", "mis", 2, 128, "sym", "bf16", False),
     ("bfs12", "maxcut", 3, 128, "sym", "bf16", True),
@@ -164,7 +163,6 @@ def test_forward_and_gradients_at_fixed_weights(gco, kind, problem, L, D, norm, 
     ("maxcut", 3, 64, "mean", 2),
     ("mis", 3, 128, "sym", 3),
     ("maxcut", 2, 128, "mean", 5),
-    ("mis", 3, 32, "sym", 4),
     ("mis", 2, 64, "sym", 6),
 ])
 def test_bf16_on_exactly_reproducible_inputs(gco, problem, L, D, norm, seed):
@@ -566,6 +564,8 @@ def test_malformed_inputs_are_rejected_with_codes(gco):
         gco.Context(dim=24)
     with pytest.raises(gco.GcoError):
         gco.Context(dim=16, storage="bf16")
+    with pytest.raises(gco.GcoError):
+        gco.Context(dim=32, storage="bf16")             # bf16 storage: widths 64 and 128
 
 
 # ------------------------------------------------------------------ paper-literal model
@@ -624,4 +624,46 @@ def test_repeated_subset_calls_same_list_then_another(gco):
     E2, _ = ctx.get_params()
     untouched = ~np.isin(np.asarray(part), [0, 2, 5])
     np.testing.assert_array_equal(E2[untouched], E[untouched])
+    ctx.destroy()
+
+
+def test_checkpoint_after_a_subset_fine_tune_needs_the_step_counts(gco):
+    """After gco_train_subset the subgraphs have different Adam step counts: parameters,
+    moments AND gco_get_steps make the checkpoint; restored into a fresh context the run
+    continues bit for bit.  Without the step counts it does not."""
+    g, part, P = make_case("bfs12", seed=31)
+    ctx, spec, lg, E, Ws = run_pair(gco, g, part, P, L=3, D=64, storage="bf16", lr=5e-3)
+    ctx.train(3, return_loss=False)
+    ctx.train_subset(4, [1, 5, 6], return_loss=False)
+    Em, Wm = ctx.get_params()
+    state = ctx.get_opt_state()
+    steps = ctx.get_steps()
+    assert len(set(steps[0].tolist())) == 2 and state[4] == 7      # the largest count is reported
+    cont = ctx.train(3)
+    E_end, _ = ctx.get_params()
+    ctx.destroy()
+    for with_steps in (True, False):
+        ctx2 = gco.Context(problem="mis", num_layers=3, dim=64, storage="bf16", lr=5e-3)
+        ctx2.upload_graph(g.n, g.rowptr, g.col, part, P)
+        ctx2.set_params(Em, Wm)
+        ctx2.set_opt_state(*state)
+        if with_steps:
+            ctx2.set_steps(*steps)
+        again = ctx2.train(3)
+        if with_steps:
+            np.testing.assert_array_equal(again, cont)
+            np.testing.assert_array_equal(ctx2.get_params()[0], E_end)
+        else:
+            assert not np.array_equal(ctx2.get_params()[0], E_end)
+        ctx2.destroy()
+
+
+def test_growing_epoch_counts_reuse_the_loss_history(gco):
+    g, part, P = make_case("random", seed=2)
+    ctx, spec, lg, E, Ws = run_pair(gco, g, part, P)
+    a = ctx.train(3)
+    b = ctx.train(40)
+    c = ctx.train(200)
+    ctx.set_params(E, Ws)
+    np.testing.assert_array_equal(ctx.train(243), np.concatenate([a, b, c]))
     ctx.destroy()
