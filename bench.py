@@ -190,18 +190,10 @@ def main():
         t_best = (time.perf_counter() - t0) / 20
         ctx.keep_best(False)
 
-    # what a plain device-to-device copy reaches on this GPU (read + write bytes per second)
-    src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
-    dst = torch.empty_like(src)
-    dst.copy_(src)
-    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    ev0.record()
-    for _ in range(5):
-        dst.copy_(src)
-    ev1.record()
-    torch.cuda.synchronize()
-    copy_gbs = 5 * 2 * src.numel() * 4 / (ev0.elapsed_time(ev1) * 1e-3) / 1e9
-    del src, dst
+    # what plain streaming kernels of the library reach on this GPU (bytes moved per second):
+    # read-only, copy, and three arrays updated in place (the pattern of Adam on the embeddings)
+    probes = {kind: binding.stream_probe(kind, 1 << 30, 5) for kind in ("read", "copy", "update")}
+    copy_gbs = probes["copy"]
 
     L = wl.num_layers
     nnz = 2 * info["m_local"]
@@ -241,6 +233,7 @@ def main():
                      "aggregation_and_loss_kernels": {k: {"achieved": kernel_gbs[k], "frac": kernel_gbs[k] / HBM_PEAK_GBS,
                                                           "ms_per_epoch": per_epoch[k]} for k in named},
                      "copy_kernel_GBps": copy_gbs, "frac_of_copy": achieved / copy_gbs,
+                     "stream_probes_GBps": probes,
                      "avg_launch_ms": avg_ms, "algorithmic_bytes_per_launch": tim["bytes_per_launch"],
                      "launches_timed": tim["launches"]},
         "extra": {"edge_aggregations_per_s": ea_per_epoch * eps, "edge_aggregations_per_epoch": ea_per_epoch,

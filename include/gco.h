@@ -306,6 +306,14 @@ int gco_louvain(int64_t n, const int64_t* rowptr, const int32_t* col, int32_t ma
 int gco_pack_parts(int64_t n, const int32_t* part_id, int32_t num_parts, int32_t max_parts,
                    int32_t* part_out, int32_t* num_out);
 
+/* Measurement aid (no context): what a plain streaming kernel reaches on the current
+ * device, in GB/s of bytes moved, over `repeats` launches on arrays of bytes_per_array
+ * bytes (allocated and freed inside; at least 1 MiB).  kind 0: one array read; 1: one array
+ * copied to another; 2: three arrays read and written in place (the access pattern of the
+ * Adam update of the embeddings).  The benchmark reports the training kernels against
+ * these figures beside the published HBM bandwidth. */
+int gco_stream_probe(int32_t kind, size_t bytes_per_array, int32_t repeats, double* gbytes_per_s);
+
 /* Wait for the context's stream. */
 int gco_sync(gco_ctx* ctx);
 

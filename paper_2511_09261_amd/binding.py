@@ -87,6 +87,7 @@ _PROTOTYPES = {
     "gco_coordinate": (C.c_int, [C.c_void_p, C.c_void_p, C.POINTER(RLConfig), C.c_void_p, C.c_void_p,
                                  C.POINTER(C.c_double), C.c_void_p, C.c_void_p, C.c_void_p,
                                  C.POINTER(C.c_int32)]),
+    "gco_stream_probe": (C.c_int, [C.c_int32, C.c_size_t, C.c_int32, C.POINTER(C.c_double)]),
     "gco_louvain": (C.c_int, [C.c_int64, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p,
                               C.POINTER(C.c_int32), C.POINTER(C.c_double)]),
     "gco_pack_parts": (C.c_int, [C.c_int64, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.POINTER(C.c_int32)]),
@@ -121,6 +122,16 @@ def exported_symbols():
 
 def _ptr(a):
     return None if a is None else a.ctypes.data
+
+
+def stream_probe(kind, bytes_per_array=1 << 30, repeats=10):
+    """gco_stream_probe: GB/s of a plain streaming kernel ("read", "copy" or "update")."""
+    lib = load()
+    out = C.c_double()
+    rc = lib.gco_stream_probe({"read": 0, "copy": 1, "update": 2}[kind], bytes_per_array, repeats, C.byref(out))
+    if rc != 0:
+        raise GcoError(rc, "gco_stream_probe failed")
+    return out.value
 
 
 def louvain(n, rowptr, col, max_levels=32):

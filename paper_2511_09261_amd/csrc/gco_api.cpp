@@ -145,6 +145,11 @@ struct gco_ctx {
   int2 *d_ent = nullptr, *d_ent_t = nullptr;
   float* d_diag = nullptr;
   float* d_heavy_partial = nullptr;
+  // chunk partials of the pre-reduced rows for the FIRST layer (from the bf16 working copy of
+  // the embeddings), written by the last launch of an epoch for the next one; valid while
+  // they belong to the current embeddings of every subgraph
+  float* d_heavy_partial_E = nullptr;
+  bool heavy_E_valid = false;
   GraphView gv;
   std::vector<void*> graph_allocs;
 
@@ -214,6 +219,7 @@ struct gco_ctx {
     for (void* q : graph_allocs) raw_free(q);
     graph_allocs.clear();
     has_graph = has_params = probs_valid = false;
+    heavy_E_valid = false;
     best_on = best_alloc = false;
     loss_hist_cap = 0;
     loss_hist = nullptr;
@@ -950,6 +956,7 @@ int gco_upload_graph(gco_ctx* ctx, int64_t n64, const int64_t* rowptr, const int
     GALLOC(ctx->d_chunk_begin, chunk_begin.size());
     GALLOC(ctx->d_chunk_end, chunk_end.size());
     GALLOC(ctx->d_heavy_partial, static_cast<size_t>(num_chunks) * D);
+    GALLOC(ctx->d_heavy_partial_E, static_cast<size_t>(num_chunks) * D);
     HIPCHK(h2d(ctx, ctx->d_heavy_of_row, heavy_of_row.data(), heavy_of_row.size()));
     HIPCHK(h2d(ctx, ctx->d_heavy_chunk_ptr, heavy_chunk_ptr.data(), heavy_chunk_ptr.size()));
     HIPCHK(h2d(ctx, ctx->d_chunk_begin, chunk_begin.data(), chunk_begin.size()));
@@ -1126,6 +1133,7 @@ static int set_params_impl(gco_ctx* ctx, const float* E, const float* U, float t
     HIPCHK(hipMemsetAsync(ctx->vW[l - 1], 0, cnt * sizeof(float), ctx->st));
   }
   if (ctx->Eb) launch_to_bf16(ctx->launch(), ctx->E, ctx->Eb, static_cast<int64_t>(nd));
+  ctx->heavy_E_valid = false;
   if (ctx->best_alloc) {
     rc = reset_best(ctx);
     if (rc != GCO_OK) return rc;
@@ -1232,8 +1240,10 @@ static void run_hidden_forward(gco_ctx* ctx, const GraphView& gv) {
   } else {
     for (int l = 1; l <= L - 1; ++l) {
       const bool last = l == L - 1;
+      const bool ready = l == 1 && ctx->heavy_E_valid && ctx->d_heavy_partial_E != nullptr;
       launch_fwd_hidden(ln, c.storage, D, gv, ctx->H[l - 1], ctx->W[l - 1], ws, ctx->H[l],
-                        last ? ctx->W[L - 1] : nullptr, wos, ctx->t, ctx->d_heavy_partial);
+                        last ? ctx->W[L - 1] : nullptr, wos, ctx->t,
+                        ready ? ctx->d_heavy_partial_E : ctx->d_heavy_partial, ready);
     }
   }
 }
@@ -1334,7 +1344,20 @@ static void run_backward(gco_ctx* ctx, const GraphView& gv, const gco_ctx::Activ
   const int writers = (ctx->wave_path() && L >= 2)
                           ? std::max({gv.num_wblocks[WM_BWD], gv.num_wblocks[WM_EMBED], gv.num_nblocks})
                           : gv.num_blocks;
-  launch_adam_w(ln, ctx->Pw, wt, L, adW, update, /*many_partials=*/writers / ctx->Pw >= 512);
+  const bool many_partials = writers / ctx->Pw >= 512;
+  // the last launch of an epoch also pre-reduces the long rows of the new embeddings
+  ChunkTail tail;
+  const bool fold = update && c.train_embed && ctx->wave_path() && L >= 2 && gv.num_chunks > 0 && !many_partials;
+  if (fold) {
+    tail.g = gv;
+    tail.X = ctx->Eb;
+    tail.partial = ctx->d_heavy_partial_E;
+    tail.D = D;
+  }
+  if (update && c.train_embed && !fold) ctx->heavy_E_valid = false;  // the embeddings change, the partials do not follow
+  launch_adam_w(ln, ctx->Pw, wt, L, adW, update, many_partials, fold ? &tail : nullptr);
+  // a run over a subset refreshes only its own subgraphs' chunks: valid only on top of valid
+  if (fold) ctx->heavy_E_valid = ctx->heavy_E_valid || &maps == &ctx->full;
   if (update) ctx->probs_valid = true;  // p is that of the parameters before the step
 }
 
@@ -1499,6 +1522,7 @@ int gco_restore_best(gco_ctx* ctx) {
   copy_params(ctx, ctx->gv, ctx->d_has_best, /*to_best=*/false);
   if (ctx->Eb)
     launch_to_bf16(ctx->launch(), ctx->E, ctx->Eb, static_cast<int64_t>(ctx->n) * ctx->cfg.dim);
+  ctx->heavy_E_valid = false;
   HIPCHK(hipGetLastError());
   ctx->probs_valid = false;
   return GCO_OK;

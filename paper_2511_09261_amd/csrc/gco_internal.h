@@ -190,9 +190,11 @@ enum EmbedMode : int { EMBED_ADAM = 0, EMBED_WRITE_GRAD = 1, EMBED_SKIP = 2 };
 
 // Hidden layer forward: Y = relu((A_hat X) W^k); with w_out != nullptr also
 // t = Y w_out^k (the scalar layer's transform fused into the last hidden layer).
+// partial_ready: the chunk partials of the pre-reduced rows for X are in heavy_partial
+// already (bf16 storage only; otherwise a launch of its own computes them first).
 void launch_fwd_hidden(const Launch& ln, int storage, int D, const GraphView& g, const void* X,
                        const float* W, int w_stride, void* Y, const float* w_out,
-                       int wout_stride, float* t, float* heavy_partial);
+                       int wout_stride, float* t, float* heavy_partial, bool partial_ready = false);
 
 // t = X w^k (used only when L = 1).
 void launch_fwd_gemv(const Launch& ln, int storage, int D, const GraphView& g, const void* X,
@@ -279,7 +281,7 @@ void launch_bwd_hidden(const Launch& ln, int storage, int D, bool last, bool to_
 // already has the scale vectors of A_hat^T.
 void launch_fwd_hidden_bf16(const Launch& ln, int D, const GraphView& g, const void* X, const float* W,
                             int w_stride, void* Y, const float* w_out, int wout_stride, float* t,
-                            float* heavy_partial);
+                            float* heavy_partial, bool partial_ready);
 void launch_bwd_hidden_bf16(const Launch& ln, int D, bool last, bool to_embed, const GraphView& gt,
                             const BwdArgs& a);
 
@@ -313,8 +315,17 @@ struct WeightTensor {
 };
 // many_partials: few weight sets with hundreds of partials each; the sum over a set's
 // partials is then shared by 16 wavefronts per 64 weights.
+// tail (bf16 storage, not with many_partials): the same launch also pre-reduces the chunks
+// of the rows with very many neighbours of view g from the bf16 rows X into `partial`,
+// ready for the next forward pass.
+struct ChunkTail {
+  GraphView g;
+  const void* X = nullptr;
+  float* partial = nullptr;
+  int D = 0;
+};
 void launch_adam_w(const Launch& ln, int Pw, const WeightTensor* tensors, int count, const AdamStep& adam,
-                   bool update, bool many_partials);  // adam.per_part, if set, is indexed by weight set; sets without partials are left alone
+                   bool update, bool many_partials, const ChunkTail* tail = nullptr);  // adam.per_part, if set, is indexed by weight set; sets without partials are left alone
 
 // fp32 -> bf16 copy (round to nearest even).
 // X[i, :] <- softmax((X[i, :] - log(-log(U[i, :]))) / tau), rows of width D (Sec. 3.2).

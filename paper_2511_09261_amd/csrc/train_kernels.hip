@@ -14,6 +14,7 @@
 #include "device_utils.h"
 #include "gather.h"
 #include "gco_internal.h"
+#include "heavy_chunk.h"
 
 namespace gco {
 namespace {
@@ -503,7 +504,23 @@ __device__ inline void adam_on_weight(const WeightTensor& wt, int64_t gid, float
 
 // One thread per weight of every tensor.  The partials are added in groups of 16
 // (pairwise inside a group, groups in list order) so that 16 loads are in flight.
-__global__ __launch_bounds__(kBlock) void adam_w_kernel(int Pw, WeightTensors wts, AdamStep ad, int update) {
+// DC > 0 (the feature width): the workgroups from weight_blocks on pre-reduce, for the next
+// forward pass, the chunks of the rows with very many neighbours from the bf16 working copy
+// of the embeddings, which the launch before this one has finished writing.
+template <int DC>
+__global__ __launch_bounds__(kBlock) void adam_w_kernel(int Pw, WeightTensors wts, AdamStep ad, int update,
+                                                        int weight_blocks, GraphView g,
+                                                        const bf16_t* __restrict__ Eb,
+                                                        float* __restrict__ chunk_partial) {
+  if constexpr (DC > 0) {
+    __shared__ float red[kBlock * 8];
+    if (static_cast<int>(blockIdx.x) >= weight_blocks) {
+      const int ch = blockIdx.x - weight_blocks;
+      if (g.chunk_part[ch] < 0) return;  // the row's subgraph sits out
+      reduce_chunk<DC>(g, ChunkPlainRows<DC>{Eb}, chunk_partial, ch, red);
+      return;
+    }
+  }
   const WeightElem e = locate_weight(Pw, wts, static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x);
   if (e.which >= wts.count) return;
   const WeightTensor& wt = wts.t[e.which];
@@ -632,9 +649,9 @@ static void fwd_hidden_t(const Launch& ln, const GraphView& g, const void* X, co
 
 void launch_fwd_hidden(const Launch& ln, int storage, int D, const GraphView& g, const void* X,
                        const float* W, int w_stride, void* Y, const float* w_out, int wout_stride,
-                       float* t, float* heavy_partial) {
+                       float* t, float* heavy_partial, bool partial_ready) {
   if (storage == GCO_STORAGE_BF16) {
-    launch_fwd_hidden_bf16(ln, D, g, X, W, w_stride, Y, w_out, wout_stride, t, heavy_partial);
+    launch_fwd_hidden_bf16(ln, D, g, X, W, w_stride, Y, w_out, wout_stride, t, heavy_partial, partial_ready);
   } else {
     GCO_DISPATCH_D(float, D, (fwd_hidden_t<float, DD>(ln, g, X, W, w_stride, Y, w_out, wout_stride, t, heavy_partial)))
   }
@@ -739,7 +756,7 @@ void launch_bwd_single(const Launch& ln, int storage, int D, const GraphView& g,
 }
 
 void launch_adam_w(const Launch& ln, int Pw, const WeightTensor* tensors, int count, const AdamStep& adam,
-                   bool update, bool many_partials) {
+                   bool update, bool many_partials, const ChunkTail* tail) {
   WeightTensors wts;
   wts.count = count;
   int64_t total = 0;
@@ -753,7 +770,16 @@ void launch_adam_w(const Launch& ln, int Pw, const WeightTensor* tensors, int co
     adam_w_split_kernel<<<blocks, 64 * kAdamSplit, 0, ln.st>>>(Pw, wts, adam, update ? 1 : 0);
   } else {
     const int blocks = static_cast<int>((total + kBlock - 1) / kBlock);
-    adam_w_kernel<<<blocks, kBlock, 0, ln.st>>>(Pw, wts, adam, update ? 1 : 0);
+    const bf16_t* Eb = tail ? static_cast<const bf16_t*>(tail->X) : nullptr;
+    if (tail != nullptr && tail->D == 64)
+      adam_w_kernel<64><<<blocks + tail->g.num_chunks, kBlock, 0, ln.st>>>(Pw, wts, adam, update ? 1 : 0, blocks,
+                                                                          tail->g, Eb, tail->partial);
+    else if (tail != nullptr && tail->D == 128)
+      adam_w_kernel<128><<<blocks + tail->g.num_chunks, kBlock, 0, ln.st>>>(Pw, wts, adam, update ? 1 : 0, blocks,
+                                                                           tail->g, Eb, tail->partial);
+    else
+      adam_w_kernel<0><<<blocks, kBlock, 0, ln.st>>>(Pw, wts, adam, update ? 1 : 0, blocks, GraphView{}, nullptr,
+                                                     nullptr);
   }
   ln.end(KK_ADAM_W);
 }

@@ -40,6 +40,7 @@
 #include "bf16_common.h"
 #include "device_utils.h"
 #include "gco_internal.h"
+#include "heavy_chunk.h"
 
 namespace gco {
 namespace {
@@ -473,15 +474,30 @@ __global__ __launch_bounds__(kBlock, D == 64 ? 3 : 2) void fwd_wave_kernel(
 //   GZ[i, :] = g_t[i] * w_out^k * [Hcur[i, :] > 0]      (rounded to bf16)
 // and the scalar layer's weight gradient, one partial per workgroup:
 //   gwout_partial[workgroup, :] = sum_i Hcur[i, :] g_t[i].
-// One workgroup per 256-row tile of the narrow decomposition.
+// One workgroup per 256-row tile of the narrow decomposition.  The g.num_chunks workgroups
+// after those pre-reduce the chunks of the rows with very many neighbours for the
+// aggregation A_hat^T G_Z that follows (g is the view of the transposed matrix): they form
+// the rows of G_Z they gather on the fly, to the same bits as the rows stored here.
 // ---------------------------------------------------------------------------
 template <int D>
 __global__ __launch_bounds__(kBlock) void form_gz_last_kernel(
     GraphView g, const bf16_t* __restrict__ Hcur, const float* __restrict__ g_t,
     const float* __restrict__ w_out, int wout_stride, bf16_t* __restrict__ GZ,
-    float* __restrict__ gwout_partial) {
+    float* __restrict__ gwout_partial, float* __restrict__ heavy_partial) {
   constexpr int LPR = D / 8, RP = kBlock / LPR;  // lanes per row, rows per pass
   __shared__ float red[RP][D + 1];
+  static_assert(sizeof(red) >= kBlock * 8 * sizeof(float), "the chunk reduction shares this buffer");
+  if (static_cast<int>(blockIdx.x) >= g.num_nblocks) {
+    const int ch = blockIdx.x - g.num_nblocks;
+    const int kc = g.chunk_part[ch];
+    if (kc < 0) return;  // the row's subgraph sits out
+    ChunkLastLayerRows<D> rows{Hcur, g_t, {}};
+#pragma unroll
+    for (int x = 0; x < 8; ++x)
+      rows.w[x] = w_out[static_cast<size_t>(kc) * wout_stride + (threadIdx.x % LPR) * 8 + x];
+    reduce_chunk<D>(g, rows, heavy_partial, ch, &red[0][0]);
+    return;
+  }
   const int k = g.nblk_k[blockIdx.x];
   if (k < 0) return;
   const int s = g.nblk_s[blockIdx.x];
@@ -963,13 +979,13 @@ void allow_lds(K kernel, size_t bytes) {
 void launch_form_gz_last(const Launch& ln, int D, const GraphView& g, const BwdArgs& a) {
   ln.begin(KK_FORM_GZ);
   if (D == 64)
-    form_gz_last_kernel<64><<<g.num_nblocks, kBlock, 0, ln.st>>>(
+    form_gz_last_kernel<64><<<g.num_nblocks + g.num_chunks, kBlock, 0, ln.st>>>(
         g, static_cast<const bf16_t*>(a.Hcur), a.g_t, a.w_out, a.wout_stride, static_cast<bf16_t*>(a.GZ_last),
-        a.gwout_partial);
+        a.gwout_partial, a.heavy_partial);
   else if (D == 128)
-    form_gz_last_kernel<128><<<g.num_nblocks, kBlock, 0, ln.st>>>(
+    form_gz_last_kernel<128><<<g.num_nblocks + g.num_chunks, kBlock, 0, ln.st>>>(
         g, static_cast<const bf16_t*>(a.Hcur), a.g_t, a.w_out, a.wout_stride, static_cast<bf16_t*>(a.GZ_last),
-        a.gwout_partial);
+        a.gwout_partial, a.heavy_partial);
   ln.end(KK_FORM_GZ);
 }
 
