@@ -202,6 +202,15 @@ __device__ __forceinline__ void stream_tiles(const GraphView& g, const int2* __r
   int2 cur[8];
 #pragma unroll
   for (int j = 0; j < 8; ++j) cur[j] = went[E0 + grp * 8 + j];
+  // The first entries are taken here, before the loop.  Inside the loop the entries of a
+  // step arrive together with the rows of the step before; if the compiler had to allow
+  // for these first loads still being on their way at the top of the loop, it would put a
+  // wait there that, vector memory operations completing in order, also waits for the
+  // stores of the tile epilogue just before -- ahead of the row requests instead of
+  // beside them.
+  asm volatile("" ::"v"(cur[0].x), "v"(cur[1].x), "v"(cur[2].x), "v"(cur[3].x), "v"(cur[4].x), "v"(cur[5].x),
+               "v"(cur[6].x), "v"(cur[7].x), "v"(cur[0].y), "v"(cur[1].y), "v"(cur[2].y), "v"(cur[3].y),
+               "v"(cur[4].y), "v"(cur[5].y), "v"(cur[6].y), "v"(cur[7].y));
 
   for (int b0 = E0; b0 < E1; b0 += G_::SE) {
     // the next step's entries and this step's source rows: one round trip
