@@ -53,7 +53,8 @@ def cpu_baseline(wl, E, Ws, epochs):
 
 def recorded_traffic(kernel):
     """HBM bytes per launch of `kernel` from the committed counter summary, or None when the
-    kernel sources have changed since (the summary records their digest)."""
+    sources the kernel is compiled from have changed since: the summary names those files
+    (the kernel's translation unit and the headers it includes) and records their digest."""
     import hashlib
     root = os.path.dirname(os.path.abspath(__file__))
     path = os.path.join(root, "profiles", "c4_hbm_traffic.txt")
@@ -67,9 +68,11 @@ def recorded_traffic(kernel):
         rec[k.strip()] = v.strip()
     h = hashlib.sha256()
     csrc = os.path.join(root, "paper_2511_09261_amd", "csrc")
-    for name in sorted(os.listdir(csrc)):
-        if name.endswith((".hip", ".h", ".cpp")) and name != "louvain.cpp":  # host-only file
+    try:
+        for name in rec.get("sources", "").split():
             h.update(open(os.path.join(csrc, name), "rb").read())
+    except OSError:
+        return None
     if rec.get("sources_sha256") != h.hexdigest() or rec.get("kernel") != kernel:
         return None
     return float(rec["traffic_bytes_per_launch"])
