@@ -88,6 +88,23 @@ int gco_destroy(gco_ctx* ctx);
 /* The configuration the context was created with. */
 int gco_get_config(gco_ctx* ctx, gco_config* out);
 
+/* How the three width-1 passes of the scalar layer (the aggregation before the sigmoid of
+ * Eq. 4, the loss of Eq. 5 with its derivative, the first aggregation of back-propagation)
+ * are launched.  GCO_SCALAR_AUTO (the default) chooses at gco_upload_graph from the sizes of
+ * the subgraphs; the other values force one form (tests, tuning):
+ *   STREAMS     three launches, the gathered scalars come from memory (any graph);
+ *   STAGED      three launches, each workgroup first copies its subgraph's vector into LDS
+ *               (the largest subgraph's float vector must fit a compute unit's LDS twice);
+ *   ONE_LAUNCH  one launch with a workgroup per subgraph (two such vectors must fit once).
+ * All forms compute the same sums; where a row's entries fall into the 64-entry steps of
+ * the kernels differs, so results agree to fp32 rounding, not bit for bit.  Call before
+ * gco_upload_graph, which returns GCO_ERANGE if the subgraphs do not fit a forced form.
+ * EINVAL for an unknown value. */
+enum { GCO_SCALAR_AUTO = 0, GCO_SCALAR_STREAMS = 1, GCO_SCALAR_STAGED = 2, GCO_SCALAR_ONE_LAUNCH = 3 };
+int gco_set_scalar_layer_form(gco_ctx* ctx, int form);
+/* The form in use for the uploaded graph (one of the three; ESTATE before upload). */
+int gco_get_scalar_layer_form(gco_ctx* ctx, int* form);
+
 /* Text of the last failure on ctx (valid until the next call on ctx). */
 const char* gco_last_error(gco_ctx* ctx);
 

@@ -21,6 +21,7 @@ PROBLEM = {"mis": 0, "maxcut": 1}
 NORM = {"sym": 0, "mean": 1}
 STORAGE = {"fp32": 0, "bf16": 1}
 REPAIR = {"none": 0, "local": 1, "all": 2}
+SCALAR_FORM = {"auto": 0, "streams": 1, "staged": 2, "one_launch": 3}
 
 ALLOC_FN = C.CFUNCTYPE(C.c_void_p, C.c_size_t, C.c_void_p)
 FREE_FN = C.CFUNCTYPE(None, C.c_void_p, C.c_void_p)
@@ -56,6 +57,8 @@ _PROTOTYPES = {
     "gco_create": (C.c_int, [C.POINTER(Config), C.POINTER(C.c_void_p)]),
     "gco_destroy": (C.c_int, [C.c_void_p]),
     "gco_get_config": (C.c_int, [C.c_void_p, C.POINTER(Config)]),
+    "gco_set_scalar_layer_form": (C.c_int, [C.c_void_p, C.c_int]),
+    "gco_get_scalar_layer_form": (C.c_int, [C.c_void_p, C.POINTER(C.c_int)]),
     "gco_last_error": (C.c_char_p, [C.c_void_p]),
     "gco_upload_graph": (C.c_int, [C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32]),
     "gco_graph_info": (C.c_int, [C.c_void_p] + [C.POINTER(C.c_int64)] * 4),
@@ -242,6 +245,15 @@ class Context:
         return arr
 
     # -- the ABI --
+    def set_scalar_layer_form(self, form):
+        """form: "auto", "streams", "staged" or "one_launch"; before upload_graph."""
+        self._check(self.lib.gco_set_scalar_layer_form(self.h, SCALAR_FORM[form]))
+
+    def get_scalar_layer_form(self):
+        out = C.c_int(0)
+        self._check(self.lib.gco_get_scalar_layer_form(self.h, C.byref(out)))
+        return {v: k for k, v in SCALAR_FORM.items()}[out.value]
+
     def destroy(self):
         if self.h:
             self.lib.gco_destroy(self.h)

@@ -109,12 +109,16 @@ struct gco_ctx {
   int32_t *d_blk_S = nullptr, *d_nblk_S = nullptr;
   int32_t *d_heavy_of_row = nullptr, *d_heavy_chunk_ptr = nullptr, *d_chunk_begin = nullptr,
           *d_chunk_end = nullptr;
+  int2* d_hpart = nullptr;
+  int32_t *d_hpart_ptr = nullptr, *d_hpart_count = nullptr;
+  float* d_hpart_partial = nullptr;
+  int num_hparts = 0;
   int32_t* d_wrowptr = nullptr;
   // Everything that names which subgraph a unit of work belongs to, on the host (as built
   // at upload) and on the device twice: for all subgraphs (`full`) and for the subset of
   // the current gco_train_subset call (`sub`, units of the other subgraphs marked -1).
   struct HostMaps {
-    std::vector<int> blk_k, nblk_k, wblk_k[kWaveMaps], chunk_part, heavy_rows, heavy_part;
+    std::vector<int> blk_k, nblk_k, wblk_k[kWaveMaps], chunk_part, heavy_rows, heavy_part, staged_k;
   } hm;
   struct ActiveMaps {
     int32_t *blk_k = nullptr, *nblk_k = nullptr, *wblk_k[kWaveMaps] = {}, *chunk_part = nullptr,
@@ -135,6 +139,11 @@ struct gco_ctx {
   // two float vectors of the largest subgraph fit the LDS of a compute unit
   bool fused_scalar = false;
   int fused_waves = 0, fused_cap = 0;
+  // the three width-1 passes as three launches that copy the gathered vector into LDS first
+  bool staged_scalar = false;
+  int staged_wgs = 0, staged_cap = 0;
+  int32_t *d_staged_k = nullptr, *d_staged_ptr = nullptr, *d_staged_launch = nullptr;
+  int scalar_form_wanted = GCO_SCALAR_AUTO;
   int2* d_fused_cuts = nullptr;
   int32_t* d_heavy_ptr = nullptr;
   WaveRun* d_wave_runs[kWaveMaps] = {};
@@ -220,6 +229,7 @@ struct gco_ctx {
     graph_allocs.clear();
     has_graph = has_params = probs_valid = false;
     heavy_E_valid = false;
+    num_hparts = 0;
     best_on = best_alloc = false;
     loss_hist_cap = 0;
     loss_hist = nullptr;
@@ -493,12 +503,14 @@ int upload_active_maps(gco_ctx* ctx, gco_ctx::ActiveMaps& m, const uint8_t* acti
     if (heavy_part[q] < 0) heavy_rows[q] = -1;
   PUT(put(m.heavy_rows, heavy_rows, heavy_rows.size()));
   // loss partial slots: one per pre-reduced row, then one per workgroup of the width-1
-  // kernels; with the one-launch scalar layer, one per subgraph
+  // kernels; with the one-launch scalar layer, one per subgraph; with the staged form, one
+  // per workgroup of those launches
   std::vector<int> slot_k(heavy_part);
   slot_k.insert(slot_k.end(), narrow.begin(), narrow.end());
-  if (ctx->fused_scalar) {
-    slot_k.resize(static_cast<size_t>(P));
-    for (int k = 0; k < P; ++k) slot_k[k] = (active == nullptr || active[k]) ? k : -1;
+  if (ctx->fused_scalar || ctx->staged_scalar) {
+    slot_k = h.staged_k;  // subgraph of every workgroup of that launch
+    for (int& k : slot_k)
+      if (active != nullptr && !active[k]) k = -1;
   }
   PUT(put_lists(m.loss_ptr, m.loss_list, slot_k, P));
 #undef PUT
@@ -640,6 +652,20 @@ int gco_destroy(gco_ctx* ctx) {
 int gco_get_config(gco_ctx* ctx, gco_config* out) {
   if (!ctx || !out) return GCO_EINVAL;
   *out = ctx->cfg;
+  return GCO_OK;
+}
+
+int gco_set_scalar_layer_form(gco_ctx* ctx, int form) {
+  if (!ctx) return GCO_EINVAL;
+  NEED(form >= GCO_SCALAR_AUTO && form <= GCO_SCALAR_ONE_LAUNCH, GCO_EINVAL, "unknown scalar-layer form %d", form);
+  ctx->scalar_form_wanted = form;
+  return GCO_OK;
+}
+
+int gco_get_scalar_layer_form(gco_ctx* ctx, int* form) {
+  if (!ctx || !form) return GCO_EINVAL;
+  NEED(ctx->has_graph, GCO_ESTATE, "no graph uploaded");
+  *form = ctx->fused_scalar ? GCO_SCALAR_ONE_LAUNCH : ctx->staged_scalar ? GCO_SCALAR_STAGED : GCO_SCALAR_STREAMS;
   return GCO_OK;
 }
 
@@ -872,13 +898,17 @@ int gco_upload_graph(gco_ctx* ctx, int64_t n64, const int64_t* rowptr, const int
     ctx->hm.chunk_part = chunk_part;
     ctx->num_loss_slots = static_cast<int>(heavy_rows.size() + ctx->hm.wblk_k[WM_NARROW].size());
   }
-  {  // One launch for the scalar layer (a workgroup per subgraph) if every subgraph's vectors
-     // fit a compute unit's LDS and no subgraph is so large that its one workgroup would
-     // take longer than three launches spread over the whole chip (measured at c4: one
+  {  // Form of the scalar layer's three passes.
+     // ONE launch (a workgroup per subgraph, vectors in LDS): if two vectors of the largest
+     // subgraph fit a compute unit's LDS and no subgraph is so large that its one workgroup
+     // would take longer than three launches spread over the whole chip (measured at c4: one
      // subgraph with 147 k entries of the light stream, 3.8 times the mean, 0.40 ms against
-     // 0.09 ms).
+     // 0.09 ms).  Else three launches that STAGE the gathered vector of a subgraph in LDS
+     // (several workgroups per subgraph), if that vector fits twice per compute unit.  Else
+     // three launches that gather from memory.
     int max_rows = 0;
-    int64_t max_light = 0;
+    int64_t max_light = 0, total_light = 0;
+    std::vector<int64_t> light_of(P, 0);
     for (int kk = 0; kk < P; ++kk) {
       max_rows = std::max(max_rows, part_rows[kk + 1] - part_rows[kk]);
       int64_t light = 0;
@@ -886,23 +916,75 @@ int gco_upload_graph(gco_ctx* ctx, int64_t n64, const int64_t* rowptr, const int
         const int deg = lrowptr[r + 1] - lrowptr[r];
         light += 1 + (deg >= kHeavyMin ? 0 : deg);
       }
+      light_of[kk] = light;
+      total_light += light;
       max_light = std::max(max_light, light);
     }
-    const int NW = max_rows > 2048 ? 16 : 4;
     const int cap = std::max(4, (max_rows + 3) / 4 * 4);
     constexpr size_t kLdsPerComputeUnit = 160 * 1024;
     constexpr int64_t kFusedMaxEntries = 40960;  // 40 steps per wavefront and pass
-    ctx->fused_scalar = scalar_fused_lds_bytes(NW, cap) <= kLdsPerComputeUnit && max_light <= kFusedMaxEntries;
-    ctx->fused_waves = NW;
+    const int fused_nw = max_rows > 2048 ? 16 : 4;
+    const bool fused_fits = scalar_fused_lds_bytes(fused_nw, cap) <= kLdsPerComputeUnit;
+    const int staged_cap = (max_rows + 3 + 3) / 4 * 4;
+    const bool staged_fits =
+        2 * scalar_staged_lds_bytes(staged_cap) <= kLdsPerComputeUnit && staged_cap <= scalar_staged_max_cap();
+    const int form = ctx->scalar_form_wanted;
+    NEED(form != GCO_SCALAR_ONE_LAUNCH || fused_fits, GCO_ERANGE,
+         "the one-launch scalar layer needs two vectors of the largest subgraph (%d rows) in %zu bytes of LDS",
+         max_rows, kLdsPerComputeUnit);
+    NEED(form != GCO_SCALAR_STAGED || staged_fits, GCO_ERANGE,
+         "the staged scalar layer needs the largest subgraph's vector (%d rows) twice in %zu bytes of LDS and at "
+         "most %d rows", max_rows, kLdsPerComputeUnit, scalar_staged_max_cap() - 3);
+    ctx->fused_scalar =
+        form == GCO_SCALAR_ONE_LAUNCH || (form == GCO_SCALAR_AUTO && fused_fits && max_light <= kFusedMaxEntries);
+    ctx->staged_scalar = form == GCO_SCALAR_STAGED || (form == GCO_SCALAR_AUTO && !ctx->fused_scalar && staged_fits);
+    ctx->fused_waves = fused_nw;
     ctx->fused_cap = cap;
-    if (ctx->fused_scalar) {
-      ctx->num_loss_slots = P;
-      // rows of every subgraph cut into NW contiguous runs of about equal cost (entries of
-      // the light stream plus one per row); a run is handed over as its range of the stream
-      std::vector<int2> cuts(static_cast<size_t>(P) * NW);
+    ctx->staged_cap = staged_cap;
+    ctx->hm.staged_k.clear();
+    if (ctx->fused_scalar || ctx->staged_scalar) {
+      // workgroups per subgraph: one, or (staged) a share of about two per compute unit in
+      // proportion to the subgraph's entries, such that a wavefront keeps a few steps of work
+      const int NW = ctx->fused_scalar ? fused_nw : scalar_staged_waves();
+      std::vector<int> wg_ptr(static_cast<size_t>(P) + 1, 0);
+      const int64_t target = std::max<int64_t>(P, std::min<int64_t>(512, total_light / (static_cast<int64_t>(NW) * 256)));
+      for (int kk = 0; kk < P; ++kk) {
+        int per = 1;
+        if (ctx->staged_scalar && total_light > 0)
+          per = static_cast<int>(std::max<int64_t>(1, (light_of[kk] * target + total_light / 2) / total_light));
+        wg_ptr[kk + 1] = wg_ptr[kk] + per;
+        for (int q = 0; q < per; ++q) ctx->hm.staged_k.push_back(kk);
+      }
+      const int num_wgs = wg_ptr[P];
+      ctx->num_loss_slots = num_wgs;
+      // Launch order of the staged form: workgroup ids go round the 8 XCDs, so the
+      // workgroups of a subgraph get ids that are equal mod 8: they share one L2, and the
+      // vector they all copy is fetched into it once.  Subgraphs are dealt to the XCD with
+      // the least work so far; launch_of[b] = workgroup that launch id b stands for (-1: none).
+      std::vector<int> launch_of;
+      if (ctx->staged_scalar) {
+        std::vector<std::vector<int>> on_xcd(8);
+        for (int kk = 0; kk < P; ++kk) {
+          size_t best = 0;
+          for (size_t x = 1; x < 8; ++x)
+            if (on_xcd[x].size() < on_xcd[best].size()) best = x;
+          for (int w = wg_ptr[kk]; w < wg_ptr[kk + 1]; ++w) on_xcd[best].push_back(w);
+        }
+        size_t depth = 0;
+        for (const auto& v : on_xcd) depth = std::max(depth, v.size());
+        launch_of.assign(depth * 8, -1);
+        for (size_t x = 0; x < 8; ++x)
+          for (size_t q = 0; q < on_xcd[x].size(); ++q) launch_of[q * 8 + x] = on_xcd[x][q];
+      }
+      ctx->staged_wgs = static_cast<int>(launch_of.size());
+      // rows of every subgraph cut into contiguous runs of about equal cost (entries of the
+      // light stream plus one per row), one per wavefront of its workgroups; a run is handed
+      // over as its range of the stream
+      std::vector<int2> cuts(static_cast<size_t>(num_wgs) * NW);
       int64_t woff = 0;  // light-stream offset of the current row
       for (int kk = 0; kk < P; ++kk) {
         const int rb = part_rows[kk], re = part_rows[kk + 1];
+        const int V = (wg_ptr[kk + 1] - wg_ptr[kk]) * NW;
         std::vector<double> pre(static_cast<size_t>(re - rb) + 1, 0.0);
         std::vector<int> off(static_cast<size_t>(re - rb) + 1, 0);
         for (int r = rb; r < re; ++r) {
@@ -914,11 +996,11 @@ int gco_upload_graph(gco_ctx* ctx, int64_t n64, const int64_t* rowptr, const int
         }
         off[re - rb] = static_cast<int>(woff);
         int r = rb;
-        for (int v = 0; v < NW; ++v) {
+        for (int v = 0; v < V; ++v) {
           const int start = r;
-          const double want = pre[re - rb] * (v + 1) / NW;
-          while (r < re && (v == NW - 1 || pre[r - rb + 1] <= want)) ++r;
-          cuts[static_cast<size_t>(kk) * NW + v] = make_int2(off[start - rb], off[r - rb]);
+          const double want = pre[re - rb] * (v + 1) / V;
+          while (r < re && (v == V - 1 || pre[r - rb + 1] <= want)) ++r;
+          cuts[static_cast<size_t>(wg_ptr[kk]) * NW + v] = make_int2(off[start - rb], off[r - rb]);
         }
       }
       std::vector<int> heavy_ptr(static_cast<size_t>(P) + 1, 0);
@@ -926,8 +1008,16 @@ int gco_upload_graph(gco_ctx* ctx, int64_t n64, const int64_t* rowptr, const int
       for (int kk = 0; kk < P; ++kk) heavy_ptr[kk + 1] += heavy_ptr[kk];
       GALLOC(ctx->d_fused_cuts, cuts.size());
       GALLOC(ctx->d_heavy_ptr, heavy_ptr.size());
+      GALLOC(ctx->d_staged_k, ctx->hm.staged_k.size());
+      GALLOC(ctx->d_staged_ptr, wg_ptr.size());
+      if (!launch_of.empty()) {
+        GALLOC(ctx->d_staged_launch, launch_of.size());
+        HIPCHK(h2d(ctx, ctx->d_staged_launch, launch_of.data(), launch_of.size()));
+      }
       HIPCHK(h2d(ctx, ctx->d_fused_cuts, cuts.data(), cuts.size()));
       HIPCHK(h2d(ctx, ctx->d_heavy_ptr, heavy_ptr.data(), heavy_ptr.size()));
+      HIPCHK(h2d(ctx, ctx->d_staged_k, ctx->hm.staged_k.data(), ctx->hm.staged_k.size()));
+      HIPCHK(h2d(ctx, ctx->d_staged_ptr, wg_ptr.data(), wg_ptr.size()));
     }
   }
   ctx->full.allocated = false;
@@ -961,6 +1051,24 @@ int gco_upload_graph(gco_ctx* ctx, int64_t n64, const int64_t* rowptr, const int
     HIPCHK(h2d(ctx, ctx->d_heavy_chunk_ptr, heavy_chunk_ptr.data(), heavy_chunk_ptr.size()));
     HIPCHK(h2d(ctx, ctx->d_chunk_begin, chunk_begin.data(), chunk_begin.size()));
     HIPCHK(h2d(ctx, ctx->d_chunk_end, chunk_end.data(), chunk_end.size()));
+    // parts of the pre-reduced rows for the width-1 launches
+    std::vector<int2> hpart;
+    std::vector<int> hpart_ptr(1, 0);
+    for (int hh = 0; hh < num_heavy; ++hh) {
+      const int chunks = heavy_chunk_ptr[hh + 1] - heavy_chunk_ptr[hh];
+      const int parts = (chunks + kNarrowPartChunks - 1) / kNarrowPartChunks;
+      for (int j = 0; j < parts; ++j) hpart.push_back(make_int2(hh, j));
+      hpart_ptr.push_back(static_cast<int>(hpart.size()));
+    }
+    ctx->num_hparts = static_cast<int>(hpart.size());
+    const std::vector<int> zeros(static_cast<size_t>(num_heavy), 0);
+    GALLOC(ctx->d_hpart, hpart.size());
+    GALLOC(ctx->d_hpart_ptr, hpart_ptr.size());
+    GALLOC(ctx->d_hpart_partial, hpart.size());
+    GALLOC(ctx->d_hpart_count, zeros.size());
+    HIPCHK(h2d(ctx, ctx->d_hpart, hpart.data(), hpart.size()));
+    HIPCHK(h2d(ctx, ctx->d_hpart_ptr, hpart_ptr.data(), hpart_ptr.size()));
+    HIPCHK(h2d(ctx, ctx->d_hpart_count, zeros.data(), zeros.size()));
   }
 
   GraphView& g = ctx->gv;
@@ -1006,6 +1114,11 @@ int gco_upload_graph(gco_ctx* ctx, int64_t n64, const int64_t* rowptr, const int
   g.chunk_begin = ctx->d_chunk_begin;
   g.chunk_end = ctx->d_chunk_end;
   g.chunk_part = ctx->full.chunk_part;
+  g.num_hparts = ctx->num_hparts;
+  g.hpart = ctx->d_hpart;
+  g.hpart_ptr = ctx->d_hpart_ptr;
+  g.hpart_partial = ctx->d_hpart_partial;
+  g.hpart_count = ctx->d_hpart_count;
 
   // parameters, optimizer state, activations
   const size_t nd = static_cast<size_t>(n) * D;
@@ -1259,9 +1372,18 @@ static void run_scalar_layer(gco_ctx* ctx, const GraphView& gv, int passes, int 
     launch_scalar_fused(ln, gv, ctx->fused_waves, ctx->fused_cap, ctx->d_fused_cuts, ctx->d_heavy_ptr, ctx->t,
                         ctx->p, ctx->d_c, q, ctx->g_t, partial, passes);
   } else {
-    launch_fwd_readout(ln, gv, ctx->t, ctx->z, ctx->p);
-    if (passes >= 2) launch_loss(ln, gv, ctx->p, ctx->d_c, q, ctx->g_z, partial);
-    if (passes >= 3) launch_bwd_readout(ln, gv, ctx->g_z, ctx->g_t);
+    ScalarStaging staging;
+    staging.num_launch = ctx->staged_wgs;
+    staging.cap = ctx->staged_cap;
+    staging.cuts = ctx->d_fused_cuts;
+    staging.heavy_ptr = ctx->d_heavy_ptr;
+    staging.wg_k = ctx->d_staged_k;
+    staging.wg_ptr = ctx->d_staged_ptr;
+    staging.launch_of = ctx->d_staged_launch;
+    const ScalarStaging* sg = ctx->staged_scalar ? &staging : nullptr;
+    launch_fwd_readout(ln, gv, ctx->t, ctx->z, ctx->p, sg);
+    if (passes >= 2) launch_loss(ln, gv, ctx->p, ctx->d_c, q, ctx->g_z, partial, sg);
+    if (passes >= 3) launch_bwd_readout(ln, gv, ctx->g_z, ctx->g_t, sg);
   }
   ctx->probs_valid = true;
 }

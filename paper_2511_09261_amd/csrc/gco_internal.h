@@ -18,6 +18,7 @@ constexpr int kNarrowRows = 256; // rows of one tile in the width-1 kernels
 constexpr int kLightMax = 64;    // rows with more local neighbours are reduced by the whole block
 constexpr int kHeavyMin = 256;   // rows with at least this many neighbours are pre-reduced in chunks
 constexpr int kChunk = 256;      // neighbours per chunk of a pre-reduced row
+constexpr int kNarrowPartChunks = 8;  // width-1 passes: chunks of a pre-reduced row summed by one workgroup
 constexpr int kWideBlocks = 2048;        // workgroups aimed at by the wide kernels
 constexpr int kMaxTilesPerBlock = 16;     // tiles one wide workgroup may own
 constexpr int kWaveRows = 32;            // rows of a tile in the wave-per-tile kernels
@@ -114,9 +115,8 @@ struct GraphView {
   const int* nblk_s = nullptr;
   const int* nblk_S = nullptr;
   int num_nblocks = 0;
-  // loss partials: the width-1 kernels' grid is num_heavy workgroups (one per pre-reduced
-  // row) followed by the workgroups of decomposition WM_NARROW, one partial each; those of
-  // subgraph k are loss_list[loss_ptr[k] .. loss_ptr[k+1])
+  // loss partials: one per pre-reduced row (num_heavy), then one per workgroup of
+  // decomposition WM_NARROW; those of subgraph k are loss_list[loss_ptr[k] .. loss_ptr[k+1])
   int num_loss_slots = 0;
   const int* loss_ptr = nullptr;
   const int* loss_list = nullptr;
@@ -131,6 +131,16 @@ struct GraphView {
   const int* chunk_begin = nullptr;
   const int* chunk_end = nullptr;
   const int* chunk_part = nullptr;    // subgraph of the row that owns the chunk (< 0: skip the chunk)
+  // Width-1 passes as three launches: a pre-reduced row is summed by one workgroup per
+  // kNarrowPartChunks of its chunks ("part").  hpart[q] = {h, index of the part in row h};
+  // row h owns partial sums hpart_partial[hpart_ptr[h] .. hpart_ptr[h+1]); the workgroup that
+  // finds hpart_count[h] at (parts - 1) adds them in order, applies the row's epilogue and
+  // puts the count back to zero.
+  int num_hparts = 0;
+  const int2* hpart = nullptr;
+  const int* hpart_ptr = nullptr;
+  float* hpart_partial = nullptr;
+  int* hpart_count = nullptr;
 };
 
 // The view of the transposed matrix: scale vectors and entry arrays exchanged.
@@ -201,12 +211,36 @@ void launch_fwd_gemv(const Launch& ln, int storage, int D, const GraphView& g, c
                      const float* w, int w_stride, float* t);
 
 // ---- width-1 kernels (narrow_kernels.hip) ----
+// How the three passes run when each is a launch of its own and the gathered vector of a
+// subgraph is first copied into LDS.  Workgroups of scalar_staged_waves() wavefronts;
+// workgroup w works for subgraph wg_k[w] and is number w - wg_ptr[wg_k[w]] of the
+// wg_ptr[k+1] - wg_ptr[k] that share subgraph k; cuts[w * waves + v] = range [x, y) of the
+// light stream (whole rows) of its wavefront v; heavy_ptr[k .. k+1) = subgraph k's range in
+// g.heavy_rows; cap = capacity of the LDS vector in floats, a multiple of 4, at least the
+// largest subgraph's rows + 3 (the copy starts at a 16-byte boundary).  The grid has
+// num_launch ids; id b stands for workgroup launch_of[b] (-1: none).  Loss partials: one per
+// workgroup w.  Passing nullptr instead selects the form that gathers from memory
+// (workgroups of decomposition WM_NARROW).
+struct ScalarStaging {
+  int num_launch = 0;
+  int cap = 0;
+  const int2* cuts = nullptr;
+  const int* heavy_ptr = nullptr;
+  const int* wg_k = nullptr;
+  const int* wg_ptr = nullptr;
+  const int* launch_of = nullptr;
+};
+int scalar_staged_waves();
+int scalar_staged_max_cap();  // largest cap the kernel's one-round copy covers
+size_t scalar_staged_lds_bytes(int cap);
+
 // z = A_hat t, p = sigmoid(z).
-void launch_fwd_readout(const Launch& ln, const GraphView& g, const float* t, float* z, float* p);
+void launch_fwd_readout(const Launch& ln, const GraphView& g, const float* t, float* z, float* p,
+                        const ScalarStaging* sg);
 
 // s = A_loc p; g_z = (c + q s) p (1 - p); loss partial per workgroup (g.num_loss_slots of them).
 void launch_loss(const Launch& ln, const GraphView& g, const float* p, const float* c, float q,
-                 float* g_z, double* loss_partial);
+                 float* g_z, double* loss_partial, const ScalarStaging* sg);
 
 // For each of `sets` sets of workgroup partials (set s starts at loss_partial + s * set_stride):
 // loss_part[s, k] = sum of the partials of subgraph k (if loss_part != nullptr);
@@ -241,7 +275,8 @@ void launch_scalar_fused(const Launch& ln, const GraphView& g, int waves, int ca
                          double* loss_partial, int passes);
 
 // g_t = A_hat^T g_z.
-void launch_bwd_readout(const Launch& ln, const GraphView& g, const float* g_z, float* g_t);
+void launch_bwd_readout(const Launch& ln, const GraphView& g, const float* g_z, float* g_t,
+                        const ScalarStaging* sg);
 
 // Backward of hidden layer l (and of the scalar layer when `last`):
 //   last:  G_Z[j,:] = g_t[j] * w_out^k * [Hcur[j,:] > 0] is formed while gathering,

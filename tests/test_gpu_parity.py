@@ -75,7 +75,7 @@ def make_case(kind, seed):
 
 
 def run_pair(gco, g, part, P, *, problem="mis", L=2, D=16, norm="sym", storage="fp32",
-             share=False, train_embed=True, seed=0, lr=1e-2, extra=None):
+             share=False, train_embed=True, seed=0, lr=1e-2, extra=None, form="auto"):
     Pw = 1 if share else P
     E, Ws = inputs.init_params(g.n, part, Pw, L, D, seed)
     # larger weights than the training initialisation, so that every term matters
@@ -83,7 +83,10 @@ def run_pair(gco, g, part, P, *, problem="mis", L=2, D=16, norm="sym", storage="
     E = (E * 5).astype(np.float32)
     ctx = gco.Context(problem=problem, num_layers=L, dim=D, norm=norm, storage=storage,
                       weight_sharing=share, train_embed=train_embed, lr=lr)
+    ctx.set_scalar_layer_form(form)
     ctx.upload_graph(g.n, g.rowptr, g.col, part, P)
+    if form != "auto":
+        assert ctx.get_scalar_layer_form() == form
     ctx.set_params(E, Ws)
     if extra is not None:
         ctx.set_linear_penalty(extra)
@@ -155,6 +158,57 @@ def test_forward_and_gradients_at_fixed_weights(gco, kind, problem, L, D, norm, 
     assert rel(dE, gE) <= tol
     for l in range(L):
         assert rel(dWs[l], gWs[l]) <= tol, f"layer {l + 1}"
+    ctx.destroy()
+
+
+@pytest.mark.parametrize("form", ["streams", "staged", "one_launch"])
+@pytest.mark.parametrize("kind,problem,L,D,norm,storage,share", [
+    ("hubs", "mis", 3, 16, "sym", "fp32", False),
+    ("hubs_parts", "maxcut", 3, 32, "mean", "fp32", False),
+    ("bfs12", "mis", 2, 16, "sym", "fp32", True),
+    ("tiny_parts", "mis", 2, 16, "sym", "fp32", False),
+    ("hubs_parts", "mis", 3, 64, "sym", "bf16", False),
+    ("random", "mis", 1, 8, "mean", "fp32", False),
+])
+def test_every_form_of_the_scalar_layer(gco, form, kind, problem, L, D, norm, storage, share):
+    """The three ways the width-1 passes are launched (gathers from memory, gathered vector
+    staged in LDS by several workgroups per subgraph, one workgroup per subgraph), each
+    forced on graphs with long rows, several subgraphs and subgraphs smaller than a tile:
+    probabilities, loss per subgraph, gradients at fixed weights, a five-epoch trajectory and
+    a fine-tune on a subset with a linear penalty."""
+    g, part, P = make_case(kind, seed=7 + L)
+    rs = np.random.RandomState(3)
+    extra = (rs.random(g.n) < 0.1).astype(np.float32) * 0.7 if problem == "mis" else None
+    ctx, spec, lg, E, Ws = run_pair(gco, g, part, P, problem=problem, L=L, D=D, norm=norm, storage=storage,
+                                    share=share, extra=extra, form=form)
+    label = f"{form}/{kind}/{problem}/L{L}/D{D}/{storage}"
+    if storage == "bf16":
+        parity.compare_bf16_run(ctx, lg, E, Ws, spec, extra, label=label)
+        tol_traj = 2e-2
+    else:
+        cache = gcn.forward(lg, E, Ws, spec)
+        want_loss, want_per = gcn.loss(lg, cache["p"], spec, extra)
+        gE, gWs = gcn.backward(lg, cache, Ws, spec, extra)
+        ctx.forward()
+        assert rel(ctx.get_probs(), cache["p"]) <= 1e-5
+        tot, per = ctx.loss()
+        assert abs(tot - want_loss) <= 1e-5 * max(1.0, np.abs(want_per).sum())
+        assert rel(per, want_per) <= 1e-4
+        dE, dWs = ctx.get_grads()
+        assert rel(dE, gE) <= 1e-5
+        for l in range(L):
+            assert rel(dWs[l], gWs[l]) <= 1e-5, f"layer {l + 1}"
+        tol_traj = 1e-4
+    st = gcn.init_state(E, Ws)
+    got = ctx.train(5)
+    want, _ = gcn.train(lg, st, spec, 5, extra_linear=extra)
+    assert np.abs(got - want).max() <= tol_traj * np.abs(want).max(), label
+    if P >= 2 and not share:
+        active = np.zeros(P, dtype=bool)
+        active[::2] = True
+        got = ctx.train_subset(3, np.flatnonzero(active))
+        want, _ = gcn.train(lg, st, spec, 3, extra_linear=extra, active=active)
+        assert np.abs(got - want).max() <= tol_traj * max(np.abs(want).max(), 1e-3), label
     ctx.destroy()
 
 
