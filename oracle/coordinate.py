@@ -12,17 +12,17 @@ Q-learning agent picks which options to apply over T rounds; the best assignment
 kept.
 
 The paper leaves most of the stage open.  PARITY UNPINNED: no printed value, closed form or
-invariant fixes the choices below; they are this build's reading, written down once here
+invariant fixes the choices below; they are one reading of the paper, written down once here
 and followed step by step by the library's gco_coordinate, so the two can be compared
 decision by decision.
 
   score        the negated objective of the whole graph on the binarised assignment:
                score(x) = beta |S| - alpha #{edges of the WHOLE graph inside S}  (Eq. 5 at p = x)
-  base action  ("initialize agent base action via linear cover"): one pass over the
+  base action  (Alg. 1 stage 3 starts the agent from a linear-time cover): one pass over the
                current conflict edges in (u, v) order; an edge with an end already chosen
                is covered; otherwise the end with the smaller probability (compared in
                fp32; ties: smaller id) is chosen.  The chosen nodes cover every conflict.
-  diff         ("select diff"): either nothing, or the other end at ONE of the edges where
+  diff         (the difference to the base action that the agent selects): either nothing, or the other end at ONE of the edges where
                the pass made a choice; the pass is then redone with that choice forced.
   state        the assignment restricted to the ends of the FIRST round's conflict edges
                (Sec. 3.3: binarised cross-node probabilities).
@@ -32,7 +32,7 @@ decision by decision.
                Q(s, a) += eta (r + gamma max_a' Q(s', a') - Q(s, a)), r = score' - score.
   fine-tune    the chosen nodes get the penalty lambda for good (penalties accumulate);
                the subgraphs that own this round's chosen nodes train `epochs` epochs.
-  best         the assignment of the highest score, the first one on ties ("keep best").
+  best         the assignment of the highest score, the first one on ties.
 The stage stops early when no conflict is left.
 """
 from __future__ import annotations

@@ -1,6 +1,6 @@
 """The checker's cross-subgraph coordination stage (oracle/coordinate.py, CPU only).
 
-The stage is this build's reading of Sec. 3.3 / Alg. 1 stage 3 (parity unpinned: the paper
+The stage follows one reading of Sec. 3.3 / Alg. 1 stage 3 (parity unpinned: the paper
 fixes neither state, reward nor schedule).  What can be fixed is fixed here: the score is
 the pinned loss evaluated on 0/1 vectors of the whole graph; the base action is a cover of
 the conflict edges built by the stated rule (hand example); the run keeps the best
