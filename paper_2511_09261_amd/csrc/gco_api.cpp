@@ -240,7 +240,7 @@ struct gco_ctx {
   // width 128: the weight gradients come from a kernel of their own, fed with stored G_T rows
   bool split_grad_w() const { return wave_path() && cfg.dim == 128; }
   // decomposition whose workgroups wrote the weight-gradient partials of hidden layer l
-  int grad_map(int l) const { return (l == 1 && !split_grad_w()) ? WM_EMBED : WM_BWD; }
+  int grad_map(int l) const { return split_grad_w() ? WM_GRADW : (l == 1 ? WM_EMBED : WM_BWD); }
   Launch launch() { return Launch{st, prof.mode ? &prof : nullptr}; }
 };
 
@@ -1146,7 +1146,7 @@ int gco_upload_graph(gco_ctx* ctx, int64_t n64, const int64_t* rowptr, const int
     GALLOC(q, nd * eb);
     ctx->H[l] = q;
     GALLOC(ctx->gW_partial[l - 1],
-           static_cast<size_t>(std::max({g.num_blocks, g.num_wblocks[WM_BWD], g.num_wblocks[WM_EMBED]})) * D * D);
+           static_cast<size_t>(std::max({g.num_blocks, g.num_wblocks[WM_BWD], g.num_wblocks[WM_EMBED], g.num_wblocks[WM_GRADW]})) * D * D);
   }
   // G_Z between two hidden layers; the wave-per-tile kernels also store that of the last one
   for (int l = 1; l <= (ctx->wave_path() ? L - 1 : L - 2); ++l) {

@@ -24,9 +24,10 @@ constexpr int kMaxTilesPerBlock = 16;     // tiles one wide workgroup may own
 constexpr int kWaveRows = 32;            // rows of a tile in the wave-per-tile kernels
 // cuts of the tiles among the wavefronts, one per kernel kind: cost of a row relative to
 // one light-stream entry (measured per-tile against per-entry time of each kernel)
-enum WaveMap : int { WM_FWD = 0, WM_BWD = 1, WM_EMBED = 2, WM_NARROW = 3, kWaveMaps = 4 };
-constexpr double kWaveRowCost[kWaveMaps] = {0.7, 1.5, 100.0, 1.0};
-constexpr int kWaveBlocksFor[kWaveMaps] = {3072, 960, 3072, 2048};  // workgroups aimed at (measured best)
+enum WaveMap : int { WM_FWD = 0, WM_BWD = 1, WM_EMBED = 2, WM_NARROW = 3, WM_GRADW = 4, kWaveMaps = 5 };
+constexpr double kWaveRowCost[kWaveMaps] = {0.7, 1.5, 100.0, 1.0, 100.0};
+// workgroups aimed at (measured best); WM_GRADW: one per compute unit, which is all that fit at its size
+constexpr int kWaveBlocksFor[kWaveMaps] = {3072, 960, 3072, 2048, 256};
 constexpr int kEntPad = 512;             // zero entries appended to the packed entry arrays
 // gco_round_repair_static works inside a block of device memory that is part of the
 // library's code object: up to this many nodes, 7 bytes per node plus counters.

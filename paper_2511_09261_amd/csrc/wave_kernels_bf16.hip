@@ -869,9 +869,51 @@ __global__ __launch_bounds__(kBlock, 2) void bwd_wave_kernel(GraphView g, BwdArg
 // leave room for one wavefront per SIMD; the next tile's rows are requested before the
 // products of the current one.  The four wavefronts' sums are added in order at the end.
 // ---------------------------------------------------------------------------
+// ---- rows copied straight into LDS (no register receives them), transposing LDS reads ----
+__device__ __forceinline__ uint32_t lds_offset(const void* p) {
+  return static_cast<uint32_t>(reinterpret_cast<uintptr_t>((__attribute__((address_space(3))) const void*)p));
+}
+// Each lane copies 16 bytes from its own global address to lds_base + 16 * lane.  The copy is
+// one of the wavefront's vector memory operations (they complete in the order issued), but
+// the compiler does not know what it writes: whoever reads the LDS bytes waits by hand.
+__device__ __forceinline__ void load_to_lds_16(const void* gp, uint32_t lds_base) {
+  uint32_t keep;
+  asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %1, off\n\ts_mov_b32 m0, %0"
+               : "=&s"(keep)
+               : "v"(gp), "s"(__builtin_amdgcn_readfirstlane(lds_base))
+               : "memory");
+}
+// Transposing 8-byte LDS read (ds_read_b64_tr_b16): in every group of 16 lanes, lane 4 r + c
+// receives element c (16 bits) of the four 8-byte chunks addressed by lanes r, r + 4, r + 8,
+// r + 12 of the group, in that order.
+typedef short i16x4_t __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ i16x4_t lds_read_transposed(uint32_t addr) {
+  return __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) i16x4_t*)(uintptr_t)addr);
+}
+__device__ __forceinline__ bf16x8 frag_of(const i16x4_t& lo, const i16x4_t& hi) {
+  uint4 u;
+  u.x = (static_cast<uint32_t>(static_cast<uint16_t>(lo[1])) << 16) | static_cast<uint16_t>(lo[0]);
+  u.y = (static_cast<uint32_t>(static_cast<uint16_t>(lo[3])) << 16) | static_cast<uint16_t>(lo[2]);
+  u.z = (static_cast<uint32_t>(static_cast<uint16_t>(hi[1])) << 16) | static_cast<uint16_t>(hi[0]);
+  u.w = (static_cast<uint32_t>(static_cast<uint16_t>(hi[3])) << 16) | static_cast<uint16_t>(hi[2]);
+  return as_frag(u);
+}
+
+// ---------------------------------------------------------------------------
+// Width 128: gW = Hprev^T G_T from stored rows, one wavefront per SIMD (the 128 x 128
+// accumulator is 256 registers per lane).  With a single wavefront per SIMD nothing hides a
+// memory round trip but the wavefront's own requests, so the rows travel straight into a
+// wave-private LDS ring of two tiles (32 rows of both matrices each) and up to two tiles are
+// on their way while one is multiplied.  A tile sits in LDS row by row: the 16-byte pieces of
+// rows 4 i .. 4 i + 3 fill 1 KB, piece p of row r at position p ^ 2 (r % 4), which spreads the
+// four rows of a transposing read over all banks.  Fragments: lane (n, h) of an operand needs
+// 8 consecutive rows of feature 32 t + n -- two transposing reads whose source lane
+// s = 4 j + r' (of the 16-lane group g) points at row (8 (g / 2) + j [+ 4]) of the contraction
+// step, features 32 t + 16 (g % 2) + 4 r' .. + 3.
+// ---------------------------------------------------------------------------
 template <int D>
 constexpr size_t grad_w_lds() {
-  return 4 * 2 * static_cast<size_t>(D) * WG<D>::GP;
+  return 4 * 2 * 2 * static_cast<size_t>(RW) * D * 2;  // 4 wavefronts x 2 tiles x 2 matrices
 }
 
 template <int D>
@@ -879,18 +921,18 @@ __global__ __launch_bounds__(kBlock, 1) void grad_w_wave_kernel(GraphView g, con
                                                                 const bf16_t* __restrict__ GT,
                                                                 float* __restrict__ gW_partial) {
   using G_ = WG<D>;
-  static_assert(RW / G_::NG == 8 && G_::NG == 4, "8 rows per lane, four 16-byte row groups per feature");
-  static_assert(grad_w_lds<D>() >= static_cast<size_t>(D) * D * sizeof(float), "room for the reduction");
+  static_assert(D == 128, "16 lanes per row of 16-byte pieces");
+  static_assert(grad_w_lds<D>() >= 2 * static_cast<size_t>(D) * D * sizeof(float), "room for the reduction");
+  constexpr uint32_t kTile = RW * D * 2;  // bytes of one matrix's tile
   extern __shared__ __align__(16) unsigned char smem[];
-  const int k = g.wblk_k[WM_BWD][blockIdx.x];
+  const int k = g.wblk_k[WM_GRADW][blockIdx.x];
   if (k < 0) return;
   const int tid = threadIdx.x, lane = tid % 64;
   const int wave = __builtin_amdgcn_readfirstlane(tid / 64);
   const int n = lane % 32, h = lane / 32;
-  const int grp = lane / G_::LPR, sub = lane % G_::LPR;
-  const WaveRun run = g.wave_runs[WM_BWD][blockIdx.x * (kBlock / 64) + wave];
-  unsigned char* hl = smem + wave * (2 * D * G_::GP);
-  unsigned char* gl = hl + D * G_::GP;
+  const WaveRun run = g.wave_runs[WM_GRADW][blockIdx.x * (kBlock / 64) + wave];
+  unsigned char* ring = smem + wave * (4 * kTile);
+  const uint32_t ring_lds = lds_offset(ring);
   floatx16 acc[G_::NT][G_::NT];
 #pragma unroll
   for (int ta = 0; ta < G_::NT; ++ta)
@@ -901,77 +943,102 @@ __global__ __launch_bounds__(kBlock, 1) void grad_w_wave_kernel(GraphView g, con
 
   if (run.tile0 < run.tile1) {
     const int rbeg = run.rbeg;
-    const int row_end = min(run.rend, rbeg + run.tile1 * RW);
-    uint4 hr[8], gr[8];
-    auto request = [&](int row0) {
+    const int row_end = min(run.rend, rbeg + run.tile1 * RW);  // > rbeg + run.tile0 * RW
+    // what this lane copies in every request: row (lane / 16) of a group of four, piece
+    // (lane % 16) ^ 2 (lane / 16) of it
+    const int copy_row = lane / 16;
+    const int copy_off = ((lane % 16) ^ (2 * copy_row)) * 8;  // in bf16 elements
+    // rows past the end are read from the last valid row and zeroed in LDS afterwards
+    auto request = [&](int tau, int slot) {
+      const int row0 = rbeg + tau * RW;
+      const uint32_t base = ring_lds + slot * (2 * kTile);
 #pragma unroll
-      for (int u = 0; u < 8; ++u) {
-        const int r = row0 + 8 * grp + u;
-        hr[u] = make_uint4(0u, 0u, 0u, 0u);
-        gr[u] = make_uint4(0u, 0u, 0u, 0u);
-        if (r < row_end) {
-          hr[u] = load_streamed(Hprev + static_cast<size_t>(r) * D + sub * 8);
-          gr[u] = load_streamed(GT + static_cast<size_t>(r) * D + sub * 8);
-        }
+      for (int i = 0; i < RW / 4; ++i) {
+        const size_t r = static_cast<size_t>(min(row0 + 4 * i + copy_row, row_end - 1));
+        load_to_lds_16(Hprev + r * D + copy_off, base + i * 1024);
+        load_to_lds_16(GT + r * D + copy_off, base + kTile + i * 1024);
       }
     };
-    // rows 8 grp .. + 7 x features 8 sub .. + 7 of a tile -> [feature][row], the 16-byte row
-    // groups of a feature rotated by feature / 8 (LDS banks)
-    auto park = [&](const uint4 (&raw)[8], unsigned char* dst) {
-#pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        uint32_t d[4];
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          const uint32_t x = (&raw[2 * q].x)[i / 2], y = (&raw[2 * q + 1].x)[i / 2];
-          d[q] = (i % 2 == 0) ? lower_halves(x, y) : upper_halves(x, y);
-        }
-        *reinterpret_cast<uint4*>(dst + (sub * 8 + i) * G_::GP + ((grp + sub) % 4) * 16) =
-            make_uint4(d[0], d[1], d[2], d[3]);
-      }
+    // byte offset inside a tile of this lane's chunk in a transposing read of feature tile t,
+    // contraction step ks, row half q
+    const int g16 = lane / 16, s16 = lane % 16, jj = s16 / 4, rr = s16 % 4;
+    auto chunk = [&](int t, int ks, int q) -> uint32_t {
+      const int piece = (4 * t + 2 * (g16 % 2) + rr / 2) ^ (2 * jj);
+      return static_cast<uint32_t>((4 * ks + 2 * (g16 / 2) + q) * 1024 + jj * 256 + piece * 16 + (rr % 2) * 8);
     };
-    request(rbeg + run.tile0 * RW);
+    request(run.tile0, 0);
+    if (run.tile0 + 1 < run.tile1) request(run.tile0 + 1, 1);
     for (int tau = run.tile0; tau < run.tile1; ++tau) {
-      park(hr, hl);
-      park(gr, gl);
-      request(rbeg + (tau + 1) * RW);  // rows past the wavefront's run read as zero
+      const int slot = (tau - run.tile0) & 1;
+      const uint32_t base = ring_lds + slot * (2 * kTile);
+      // tile tau has landed once at most the next tile's 2 * RW / 4 copies are outstanding
+      if (tau + 1 < run.tile1) asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
+      else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+      static_assert(2 * (RW / 4) == 16, "the wait above counts the copies of one tile");
+      const int nrows = min(RW, row_end - (rbeg + tau * RW));
+      if (nrows < RW) {  // the subgraph's last tile: rows past its end count as zero
+        for (int r = nrows + lane / 16; r < RW; r += 4)
+          *reinterpret_cast<uint4*>(ring + slot * (2 * kTile) + (r / 4) * 1024 + (r % 4) * 256 + (lane % 16) * 16) =
+              make_uint4(0u, 0u, 0u, 0u);
+      }
       wave_lds_handoff();
+      bf16x8 af[G_::NT][RW / 16], bf[G_::NT][RW / 16];
 #pragma unroll
-      for (int ks = 0; ks < RW / 16; ++ks) {
-        bf16x8 af[G_::NT], bf[G_::NT];
+      for (int ks = 0; ks < RW / 16; ++ks)
 #pragma unroll
         for (int t = 0; t < G_::NT; ++t) {
-          const int off = (32 * t + n) * G_::GP + ((2 * ks + h + (32 * t + n) / 8) % 4) * 16;
-          af[t] = as_frag(*reinterpret_cast<const uint4*>(hl + off));
-          bf[t] = as_frag(*reinterpret_cast<const uint4*>(gl + off));
+          af[t][ks] = frag_of(lds_read_transposed(base + chunk(t, ks, 0)), lds_read_transposed(base + chunk(t, ks, 1)));
+          bf[t][ks] = frag_of(lds_read_transposed(base + kTile + chunk(t, ks, 0)),
+                              lds_read_transposed(base + kTile + chunk(t, ks, 1)));
         }
+      // every fragment is in registers: the slot may receive the tile after the next
+      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+      if (tau + 2 < run.tile1) request(tau + 2, slot);
+#pragma unroll
+      for (int ks = 0; ks < RW / 16; ++ks)
 #pragma unroll
         for (int ta = 0; ta < G_::NT; ++ta)
 #pragma unroll
           for (int tb = 0; tb < G_::NT; ++tb)
-            acc[ta][tb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[ta], bf[tb], acc[ta][tb], 0, 0, 0);
-      }
-      wave_lds_handoff();
+            acc[ta][tb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[ta][ks], bf[tb][ks], acc[ta][tb], 0, 0, 0);
     }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   }
 
-  // ((wave 0 + wave 1) + wave 2) + wave 3
+  // ((wave 0 + wave 1) + wave 2) + wave 3: the running sum travels through two halves of the
+  // LDS in turn, so a wavefront first reads all of what the one before wrote (nothing it
+  // writes lies between its reads) and then writes all of its own
   float* buf = reinterpret_cast<float*>(smem);
+  __syncthreads();  // every ring is done with
+#pragma unroll 1
   for (int w = 0; w < kBlock / 64; ++w) {
-    __syncthreads();
     if (wave == w) {
+      const float* src = buf + ((w - 1) & 1) * (D * D) + n;
+      float* dst = buf + (w & 1) * (D * D) + n;
+      if (w == 0) {
 #pragma unroll
-      for (int ta = 0; ta < G_::NT; ++ta)
+        for (int ta = 0; ta < G_::NT; ++ta)
 #pragma unroll
-        for (int tb = 0; tb < G_::NT; ++tb)
+          for (int tb = 0; tb < G_::NT; ++tb)
 #pragma unroll
-          for (int r = 0; r < 16; ++r) {
-            float* p = buf + acc_feature(ta, h, r) * D + 32 * tb + n;
-            *p = w == 0 ? acc[ta][tb][r] : *p + acc[ta][tb][r];
+            for (int r = 0; r < 16; ++r) dst[acc_feature(ta, h, r) * D + 32 * tb] = acc[ta][tb][r];
+      } else {
+#pragma unroll
+        for (int ta = 0; ta < G_::NT; ++ta)
+#pragma unroll
+          for (int tb = 0; tb < G_::NT; ++tb) {
+            float sum[16];
+#pragma unroll
+            for (int r = 0; r < 16; ++r) sum[r] = src[acc_feature(ta, h, r) * D + 32 * tb];
+#pragma unroll
+            for (int r = 0; r < 16; ++r) dst[acc_feature(ta, h, r) * D + 32 * tb] = sum[r] + acc[ta][tb][r];
+            __builtin_amdgcn_sched_barrier(0);  // 16 reads at a time: all 256 at once do not fit the registers
           }
+      }
     }
+    __syncthreads();
   }
-  __syncthreads();
+  buf += ((kBlock / 64 - 1) & 1) * (D * D);  // where the last wavefront wrote
   float* out = gW_partial + static_cast<size_t>(blockIdx.x) * D * D;
   for (int idx = tid; idx < D * D; idx += kBlock) out[idx] = buf[idx];
 }
@@ -1020,7 +1087,7 @@ void launch_bwd_hidden_wave(const Launch& ln, int D, bool to_embed, const GraphV
     // the weight gradient from the stored rows of G_T
     allow_lds(grad_w_wave_kernel<128>, grad_w_lds<128>());
     ln.begin(KK_GRAD_W);
-    grad_w_wave_kernel<128><<<gt.num_wblocks[WM_BWD], kBlock, grad_w_lds<128>(), ln.st>>>(
+    grad_w_wave_kernel<128><<<gt.num_wblocks[WM_GRADW], kBlock, grad_w_lds<128>(), ln.st>>>(
         gt, static_cast<const bf16_t*>(a.Hprev), static_cast<const bf16_t*>(a.GT), a.gW_partial);
     ln.end(KK_GRAD_W);
   }
