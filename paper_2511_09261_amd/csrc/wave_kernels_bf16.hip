@@ -859,16 +859,6 @@ __global__ __launch_bounds__(kBlock, 2) void bwd_wave_kernel(GraphView g, BwdArg
   }
 }
 
-// ---------------------------------------------------------------------------
-// Weight gradient of a hidden layer of width 128, from stored rows:
-//   gW partial[workgroup] = sum over the workgroup's rows of Hprev[row, :]^T GT[row, :].
-// Same decomposition as the hidden backward kernel (a wavefront owns a run of 32-row
-// tiles).  Per tile both operands are loaded as full rows (16 bytes per lane, 8 rows per
-// lane), transposed in the lane and parked in LDS as [feature][row]; the contraction over
-// the 32 rows runs on the matrix cores.  The D*D/64 = 256 accumulator registers per lane
-// leave room for one wavefront per SIMD; the next tile's rows are requested before the
-// products of the current one.  The four wavefronts' sums are added in order at the end.
-// ---------------------------------------------------------------------------
 // ---- rows copied straight into LDS (no register receives them), transposing LDS reads ----
 __device__ __forceinline__ uint32_t lds_offset(const void* p) {
   return static_cast<uint32_t>(reinterpret_cast<uintptr_t>((__attribute__((address_space(3))) const void*)p));
@@ -900,7 +890,10 @@ __device__ __forceinline__ bf16x8 frag_of(const i16x4_t& lo, const i16x4_t& hi) 
 }
 
 // ---------------------------------------------------------------------------
-// Width 128: gW = Hprev^T G_T from stored rows, one wavefront per SIMD (the 128 x 128
+// Weight gradient of a hidden layer of width 128 (the weight part of Eq. 3's backward), from
+// stored rows:  gW partial[workgroup] = sum over the workgroup's rows of Hprev[row, :]^T GT[row, :].
+// A decomposition of its own (WM_GRADW: a wavefront owns a run of 32-row tiles, one
+// workgroup per compute unit).  One wavefront per SIMD (the 128 x 128
 // accumulator is 256 registers per lane).  With a single wavefront per SIMD nothing hides a
 // memory round trip but the wavefront's own requests, so the rows travel straight into a
 // wave-private LDS ring of two tiles (32 rows of both matrices each) and up to two tiles are
