@@ -160,12 +160,23 @@ __device__ __forceinline__ uint32_t upper_halves(uint32_t x, uint32_t y) {
   return __builtin_amdgcn_perm(y, x, 0x07060302u);
 }
 
+template <bool FIRST, typename A, typename B>
+__device__ __forceinline__ auto& select_array(A& a, B& b) {
+  if constexpr (FIRST) return a;
+  else return b;
+}
+
 // Calls on_tile(row0, nrows, agg) for every tile of the wavefront's run, in order.  agg[tn][r] at lane (n, h) is element (row0 + n, acc_feature(tn, h, r)) of
 // A_hat X in fp32 (zero for rows past nrows).  `went` is the light stream of the matrix
 // that is applied (A_hat or its transpose); xf (xf_bytes) and wts (wts_bytes) are this
 // wavefront's LDS; pair_mask is the workgroup's table from fill_pair_masks.  on_tile may
 // overwrite xf.
-template <int D, typename OnTile>
+// EARLY_ROWS: the source rows of a step are requested during the step before it, as soon as
+// that step's rows are parked in LDS (their registers are free again), together with the
+// entries of the step after; the products and tile epilogues of a step then run beside the
+// next step's round trip.  The rows in flight occupy 32 registers through the epilogue and
+// the entries another 16: for the kernel that has them to spare (forward, width 128).
+template <int D, bool EARLY_ROWS, typename OnTile>
 __device__ __forceinline__ void stream_tiles(const GraphView& g, const int2* __restrict__ went,
                                              const bf16_t* __restrict__ X, const WaveRun& run,
                                              unsigned char* xf, uint32_t* wts, const uint4* pair_mask,
@@ -212,18 +223,35 @@ __device__ __forceinline__ void stream_tiles(const GraphView& g, const int2* __r
                "v"(cur[6].x), "v"(cur[7].x), "v"(cur[0].y), "v"(cur[1].y), "v"(cur[2].y), "v"(cur[3].y),
                "v"(cur[4].y), "v"(cur[5].y), "v"(cur[6].y), "v"(cur[7].y));
 
-  for (int b0 = E0; b0 < E1; b0 += G_::SE) {
-    // the next step's entries and this step's source rows: one round trip
-    int2 nxt[8];
-#pragma unroll
-    for (int j = 0; j < 8; ++j) nxt[j] = went[b0 + G_::SE + grp * 8 + j];
-    uint4 raw[8];
+  // rows of the step that starts at entry b: 8 slots per lane group, 16 bytes per lane
+  auto request_rows = [&](uint4 (&rows)[8], const int2 (&ent)[8], int b) {
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
-      raw[j] = make_uint4(0u, 0u, 0u, 0u);
-      if (b0 + grp * 8 + j < E1)
-        raw[j] = *reinterpret_cast<const uint4*>(X + static_cast<size_t>(cur[j].x) * D + sub * 8);
+      rows[j] = make_uint4(0u, 0u, 0u, 0u);
+      if (b + grp * 8 + j < E1)
+        rows[j] = *reinterpret_cast<const uint4*>(X + static_cast<size_t>(ent[j].x) * D + sub * 8);
     }
+  };
+  static_assert(kEntPad >= 3 * G_::SE, "entries are read up to two steps past the end of the stream");
+  // what EARLY_ROWS carries from one step to the next (unused otherwise)
+  int2 nxt_carried[EARLY_ROWS ? 8 : 1];
+  uint4 raw_carried[EARLY_ROWS ? 8 : 1];
+  if constexpr (EARLY_ROWS) {
+#pragma unroll
+    for (int j = 0; j < 8; ++j) nxt_carried[j] = went[E0 + G_::SE + grp * 8 + j];
+    request_rows(raw_carried, cur, E0);
+  }
+  for (int b0 = E0; b0 < E1; b0 += G_::SE) {
+    int2 nxt_here[EARLY_ROWS ? 1 : 8];
+    uint4 raw_here[EARLY_ROWS ? 1 : 8];
+    if constexpr (!EARLY_ROWS) {
+      // the next step's entries and this step's source rows: one round trip
+#pragma unroll
+      for (int j = 0; j < 8; ++j) nxt_here[j] = went[b0 + G_::SE + grp * 8 + j];
+      request_rows(raw_here, cur, b0);
+    }
+    auto& nxt = select_array<EARLY_ROWS>(nxt_carried, nxt_here);
+    auto& raw = select_array<EARLY_ROWS>(raw_carried, raw_here);
     // transpose in the lane (8 slots x 8 features) and park as [feature][slot]
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
@@ -248,6 +276,12 @@ __device__ __forceinline__ void stream_tiles(const GraphView& g, const int2* __r
       *reinterpret_cast<uint4*>(wts + G_::SE / 2 + grp * 4) =
           make_uint4(lower_halves(y[0], y[1]), lower_halves(y[2], y[3]), lower_halves(y[4], y[5]),
                      lower_halves(y[6], y[7]));
+    }
+    int2 nx2[8];
+    if constexpr (EARLY_ROWS) {
+      request_rows(raw, nxt, b0 + G_::SE);
+#pragma unroll
+      for (int j = 0; j < 8; ++j) nx2[j] = went[b0 + 2 * G_::SE + grp * 8 + j];
     }
     wave_lds_handoff();
     // fragments of the step: slots 16 ks + 8h .. + 7 of feature 32 tn + n, and their values
@@ -350,6 +384,10 @@ __device__ __forceinline__ void stream_tiles(const GraphView& g, const int2* __r
     }
 #pragma unroll
     for (int j = 0; j < 8; ++j) cur[j] = nxt[j];
+    if constexpr (EARLY_ROWS) {
+#pragma unroll
+      for (int j = 0; j < 8; ++j) nxt[j] = nx2[j];
+    }
     wave_lds_handoff();
   }
 }
@@ -413,7 +451,7 @@ __global__ __launch_bounds__(kBlock, D == 64 ? 3 : 2) void fwd_wave_kernel(
   if (run.tile0 >= run.tile1) return;
   unsigned char* my_lds = wave_mem + wave * G_::wave_bytes;
   bf16_t* ot = reinterpret_cast<bf16_t*>(my_lds);  // overlays the row buffer
-  stream_tiles<D>(g, g.went, X, run, my_lds,
+  stream_tiles<D, D == 128>(g, g.went, X, run, my_lds,
                   reinterpret_cast<uint32_t*>(my_lds + G_::xf_bytes), pair_mask, heavy_partial,
                   [&](int row0, int nrows, const floatx16 (&agg)[G_::NT]) {
     // Z^T = W^T AGG^T: the rounded aggregate is the B operand as it stands
@@ -633,7 +671,7 @@ __global__ __launch_bounds__(kBlock, 2) void bwd_wave_kernel(GraphView g, BwdArg
     };
     request_hprev(rbeg + run.tile0 * RW);
 
-    stream_tiles<D>(g, g.went, GZ, run, R, reinterpret_cast<uint32_t*>(R + G_::region_bytes),
+    stream_tiles<D, false>(g, g.went, GZ, run, R, reinterpret_cast<uint32_t*>(R + G_::region_bytes),
                     pair_mask, a.heavy_partial,
                     [&](int row0, int nrows, const floatx16 (&agg)[G_::NT]) {
       // G_T^T rounded to bf16: B operands of the second product
