@@ -68,6 +68,16 @@ def make_case(kind, seed):
         u = rs.randint(0, n, 6000)
         v = np.clip(u + rs.randint(-4, 5, 6000), 0, n - 1)     # mostly inside or next to a subgraph
         return inputs.from_edges(n, u, v), part, 700
+    if kind == "mid3":          # three unequal subgraphs, large enough that at width 128 the
+        # wavefronts of the weight-gradient kernel (at most 1024 of them) own 2 to 3 tiles each
+        rs = np.random.RandomState(seed)
+        n = 83000 + 19
+        u = rs.randint(0, n, 3 * n)
+        v = np.clip(u + rs.randint(-3000, 3001, 3 * n), 0, n - 1)
+        part = np.zeros(n, dtype=np.int32)
+        part[50000:75000] = 1
+        part[75000:] = 2
+        return inputs.from_edges(n, u, v), part, 3
     if kind == "bfs12":         # more than 8 subgraphs: the XCD-grouped block map
         g = inputs.random_regular(3000, 6, seed)
         return g, inputs.bfs_partition(g, 12, seed), 12
@@ -127,6 +137,7 @@ FWD_BWD_CASES = [
     # width 128: the weight gradient comes from stored rows of A_hat^T G_Z
     ("hubs", "mis", 3, 128, "mean", "bf16", False),
     ("random", "maxcut", 3, 128, "sym", "bf16", False),
+    ("mid3", "mis", 2, 128, "sym", "bf16", False),
 ]
 
 
