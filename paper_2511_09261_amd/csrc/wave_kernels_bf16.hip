@@ -286,12 +286,18 @@ __device__ __forceinline__ void stream_tiles(const GraphView& g, const int2* __r
     wave_lds_handoff();
     // fragments of the step: slots 16 ks + 8h .. + 7 of feature 32 tn + n, and their values
     bf16x8 xa[G_::NT][G_::KS1];
+    {
+      // the fragment addresses are worked out again in every step (a few integer operations):
+      // held in registers across the whole step they are the first to be spilled
+      int nf = n;
+      asm volatile("" : "+v"(nf));
 #pragma unroll
-    for (int tn = 0; tn < G_::NT; ++tn)
+      for (int tn = 0; tn < G_::NT; ++tn)
 #pragma unroll
-      for (int ks = 0; ks < G_::KS1; ++ks)
-        xa[tn][ks] = as_frag(*reinterpret_cast<const uint4*>(
-            xf + (tn * 32 + n) * G_::XP + ((2 * ks + h + (tn * 32 + n) / 8) % G_::NG) * 16));
+        for (int ks = 0; ks < G_::KS1; ++ks)
+          xa[tn][ks] = as_frag(*reinterpret_cast<const uint4*>(
+              xf + (tn * 32 + nf) * G_::XP + ((2 * ks + h + (tn * 32 + nf) / 8) % G_::NG) * 16));
+    }
     const int b1 = min(b0 + G_::SE, E1);
     while (true) {
       // slots of the step that belong to row n of the current tile, as a bit mask
