@@ -80,7 +80,10 @@ struct WG {
   static constexpr size_t ot_bytes = static_cast<size_t>(RW) * PA * 2;
   // the output tile reuses the row buffer: the step's fragments are in registers by then
   static constexpr size_t wave_bytes = xf_bytes + wts_bytes;
-  static constexpr size_t bwd_wave_bytes = region_bytes + wts_bytes;
+  // width 128: the backward kernels keep the next step's entries in LDS
+  static constexpr bool BWD_LDS_ENTRIES = D == 128;
+  static constexpr size_t ent_bytes = static_cast<size_t>(SE) * 8;
+  static constexpr size_t bwd_wave_bytes = region_bytes + wts_bytes + (BWD_LDS_ENTRIES ? ent_bytes : 0);
   static_assert(ot_bytes <= xf_bytes && ot_bytes <= region_bytes, "the output tile overlays the row buffer");
   static constexpr size_t w_bytes = static_cast<size_t>(D) * D * 2;
   static_assert(SE <= 64, "slot masks are 64 bits wide");
@@ -160,6 +163,29 @@ __device__ __forceinline__ uint32_t upper_halves(uint32_t x, uint32_t y) {
   return __builtin_amdgcn_perm(y, x, 0x07060302u);
 }
 
+// ---- copies from global memory straight into LDS (no register receives the data) ----
+__device__ __forceinline__ uint32_t lds_offset(const void* p) {
+  return static_cast<uint32_t>(reinterpret_cast<uintptr_t>((__attribute__((address_space(3))) const void*)p));
+}
+// Each lane copies 16 bytes from its own global address to lds_base + 16 * lane.  The copy is
+// one of the wavefront's vector memory operations (they complete in the order issued), but
+// the compiler does not know what it writes: whoever reads the LDS bytes waits by hand.
+__device__ __forceinline__ void load_to_lds_16(const void* gp, uint32_t lds_base) {
+  uint32_t keep;
+  asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %1, off\n\ts_mov_b32 m0, %0"
+               : "=&s"(keep)
+               : "v"(gp), "s"(__builtin_amdgcn_readfirstlane(lds_base))
+               : "memory");
+}
+// The same with 4 bytes per lane, to lds_base + 4 * lane.
+__device__ __forceinline__ void load_to_lds_4(const void* gp, uint32_t lds_base) {
+  uint32_t keep;
+  asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %2\n\tglobal_load_lds_dword %1, off\n\ts_mov_b32 m0, %0"
+               : "=&s"(keep)
+               : "v"(gp), "s"(__builtin_amdgcn_readfirstlane(lds_base))
+               : "memory");
+}
+
 template <bool FIRST, typename A, typename B>
 __device__ __forceinline__ auto& select_array(A& a, B& b) {
   if constexpr (FIRST) return a;
@@ -176,12 +202,19 @@ __device__ __forceinline__ auto& select_array(A& a, B& b) {
 // entries of the step after; the products and tile epilogues of a step then run beside the
 // next step's round trip.  The rows in flight occupy 32 registers through the epilogue and
 // the entries another 16: for the kernel that has them to spare (forward, width 128).
-template <int D, bool EARLY_ROWS, typename OnTile>
+// LDS_ENTRIES (not with EARLY_ROWS): the entries of the next step are copied straight into
+// ent_lds (8 * SE bytes of this wavefront's LDS) instead of into 16 registers that stay live
+// through the whole step, and are read from there when the step ends.  The copy is issued
+// before the step's row requests, so it has landed when the rows have (vector memory
+// operations complete in order); the kernels at the register limit use it.
+template <int D, bool EARLY_ROWS, bool LDS_ENTRIES, typename OnTile>
 __device__ __forceinline__ void stream_tiles(const GraphView& g, const int2* __restrict__ went,
                                              const bf16_t* __restrict__ X, const WaveRun& run,
                                              unsigned char* xf, uint32_t* wts, const uint4* pair_mask,
-                                             const float* __restrict__ heavy_partial, OnTile&& on_tile) {
+                                             const float* __restrict__ heavy_partial, unsigned char* ent_lds,
+                                             OnTile&& on_tile) {
   using G_ = WG<D>;
+  static_assert(!(EARLY_ROWS && LDS_ENTRIES), "one way of prefetching entries at a time");
   const int lane = threadIdx.x % 64;
   const int n = lane % 32, h = lane / 32;
   const int grp = lane / G_::LPR, sub = lane % G_::LPR;
@@ -242,9 +275,17 @@ __device__ __forceinline__ void stream_tiles(const GraphView& g, const int2* __r
     request_rows(raw_carried, cur, E0);
   }
   for (int b0 = E0; b0 < E1; b0 += G_::SE) {
-    int2 nxt_here[EARLY_ROWS ? 1 : 8];
+    int2 nxt_here[EARLY_ROWS || LDS_ENTRIES ? 1 : 8];
     uint4 raw_here[EARLY_ROWS ? 1 : 8];
-    if constexpr (!EARLY_ROWS) {
+    if constexpr (LDS_ENTRIES) {
+      // the previous contents of ent_lds have been read (the reads were issued a step ago)
+      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+      const uint32_t ent_base = lds_offset(ent_lds);
+#pragma unroll
+      for (int i = 0; i < G_::SE * 2 / 64; ++i)
+        load_to_lds_4(reinterpret_cast<const uint32_t*>(went + b0 + G_::SE) + i * 64 + lane, ent_base + i * 256);
+      request_rows(raw_here, cur, b0);
+    } else if constexpr (!EARLY_ROWS) {
       // the next step's entries and this step's source rows: one round trip
 #pragma unroll
       for (int j = 0; j < 8; ++j) nxt_here[j] = went[b0 + G_::SE + grp * 8 + j];
@@ -388,8 +429,15 @@ __device__ __forceinline__ void stream_tiles(const GraphView& g, const int2* __r
       ra = __shfl(factsA, n, 64);
       rb = __shfl(factsA, n + 1, 64);
     }
+    if constexpr (LDS_ENTRIES) {
+      // after this step's rows, which were requested after the copy, have been used
+      asm volatile("" ::: "memory");
 #pragma unroll
-    for (int j = 0; j < 8; ++j) cur[j] = nxt[j];
+      for (int j = 0; j < 8; ++j) cur[j] = reinterpret_cast<const int2*>(ent_lds)[grp * 8 + j];
+    } else {
+#pragma unroll
+      for (int j = 0; j < 8; ++j) cur[j] = nxt[j];
+    }
     if constexpr (EARLY_ROWS) {
 #pragma unroll
       for (int j = 0; j < 8; ++j) nxt[j] = nx2[j];
@@ -457,8 +505,8 @@ __global__ __launch_bounds__(kBlock, D == 64 ? 3 : 2) void fwd_wave_kernel(
   if (run.tile0 >= run.tile1) return;
   unsigned char* my_lds = wave_mem + wave * G_::wave_bytes;
   bf16_t* ot = reinterpret_cast<bf16_t*>(my_lds);  // overlays the row buffer
-  stream_tiles<D, D == 128>(g, g.went, X, run, my_lds,
-                  reinterpret_cast<uint32_t*>(my_lds + G_::xf_bytes), pair_mask, heavy_partial,
+  stream_tiles<D, D == 128, false>(g, g.went, X, run, my_lds,
+                  reinterpret_cast<uint32_t*>(my_lds + G_::xf_bytes), pair_mask, heavy_partial, nullptr,
                   [&](int row0, int nrows, const floatx16 (&agg)[G_::NT]) {
     // Z^T = W^T AGG^T: the rounded aggregate is the B operand as it stands
     floatx16 z[G_::NT];
@@ -677,8 +725,8 @@ __global__ __launch_bounds__(kBlock, 2) void bwd_wave_kernel(GraphView g, BwdArg
     };
     request_hprev(rbeg + run.tile0 * RW);
 
-    stream_tiles<D, false>(g, g.went, GZ, run, R, reinterpret_cast<uint32_t*>(R + G_::region_bytes),
-                    pair_mask, a.heavy_partial,
+    stream_tiles<D, false, G_::BWD_LDS_ENTRIES>(g, g.went, GZ, run, R, reinterpret_cast<uint32_t*>(R + G_::region_bytes),
+                    pair_mask, a.heavy_partial, R + G_::region_bytes + G_::wts_bytes,
                     [&](int row0, int nrows, const floatx16 (&agg)[G_::NT]) {
       // G_T^T rounded to bf16: B operands of the second product
       uint4 bq[G_::KS2];
@@ -903,20 +951,6 @@ __global__ __launch_bounds__(kBlock, 2) void bwd_wave_kernel(GraphView g, BwdArg
   }
 }
 
-// ---- rows copied straight into LDS (no register receives them), transposing LDS reads ----
-__device__ __forceinline__ uint32_t lds_offset(const void* p) {
-  return static_cast<uint32_t>(reinterpret_cast<uintptr_t>((__attribute__((address_space(3))) const void*)p));
-}
-// Each lane copies 16 bytes from its own global address to lds_base + 16 * lane.  The copy is
-// one of the wavefront's vector memory operations (they complete in the order issued), but
-// the compiler does not know what it writes: whoever reads the LDS bytes waits by hand.
-__device__ __forceinline__ void load_to_lds_16(const void* gp, uint32_t lds_base) {
-  uint32_t keep;
-  asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %1, off\n\ts_mov_b32 m0, %0"
-               : "=&s"(keep)
-               : "v"(gp), "s"(__builtin_amdgcn_readfirstlane(lds_base))
-               : "memory");
-}
 // Transposing 8-byte LDS read (ds_read_b64_tr_b16): in every group of 16 lanes, lane 4 r + c
 // receives element c (16 bits) of the four 8-byte chunks addressed by lanes r, r + 4, r + 8,
 // r + 12 of the group, in that order.
