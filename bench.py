@@ -156,10 +156,11 @@ def main():
     per_epoch = {k: v["total_ms"] / 5 for k, v in breakdown.items() if v["launches"]}
     dominant = max(per_epoch, key=per_epoch.get)
 
-    # timed region: only the dominant kernel carries events
+    # timed region: only the dominant kernel carries events, and only every eighth launch of
+    # it (an event pair leaves the stream idle for about 11 us, 1.2 % of an epoch at c4)
     ctx.set_params(E, Ws)
     ctx.train(args.warmup, return_loss=False)
-    ctx.set_profiling(2, [dominant])
+    ctx.set_profiling(3, [dominant])
     ctx.reset_timing()
     ctx.sync()
     torch.cuda.synchronize()

@@ -336,8 +336,10 @@ int gco_sync(gco_ctx* ctx);
 
 /* Per-kernel timing.  With profiling on, every kernel launch of gco_train /
  * gco_forward is bracketed by events on the context's stream (this slows the
- * epoch slightly).  gco_set_profiling(ctx, 2) brackets only the kernel kinds
- * whose bit is set in kind_mask (bit i = kind i).
+ * epoch slightly: an event costs a few microseconds of idle stream).
+ * gco_set_profiling(ctx, 2) brackets only the kernel kinds whose bit is set in
+ * kind_mask (bit i = kind i); mode 3 brackets every eighth launch of those kinds,
+ * counted from this call (the first one included).
  * gco_get_timing: for kernel kind i in [0, gco_num_kernel_kinds()) returns the
  * launches counted and their summed duration in ms since the last reset, and
  * the algorithmic bytes of one launch.  gco_kernel_kind_name gives its name. */

@@ -37,9 +37,13 @@ struct ProfilerImpl : Profiler {
   std::vector<EventPair> spare;
   int64_t launches[KK_COUNT] = {};
   double total_ms[KK_COUNT] = {};
-  bool on(int kind) const { return mode == 1 || (mode == 2 && ((mask >> kind) & 1ull)); }
+  int64_t seen[KK_COUNT] = {};  // launches since the mode was set (mode 3 times one in kSampleEvery)
+  bool open[KK_COUNT] = {};     // begin() recorded an event that end() has to close
+  static constexpr int kSampleEvery = 8;
+  bool on(int kind) const { return mode == 1 || (mode >= 2 && ((mask >> kind) & 1ull)); }
   void begin(int kind, hipStream_t st) override {
     if (!on(kind)) return;
+    if (mode == 3 && (seen[kind]++ % kSampleEvery) != 0) return;
     EventPair ev;
     if (!spare.empty()) {
       ev = spare.back();
@@ -49,10 +53,12 @@ struct ProfilerImpl : Profiler {
     }
     (void)hipEventRecord(ev.a, st);
     pending[kind].push_back(ev);
+    open[kind] = true;
   }
   void end(int kind, hipStream_t st) override {
-    if (!on(kind) || pending[kind].empty()) return;
+    if (!open[kind]) return;
     (void)hipEventRecord(pending[kind].back().b, st);
+    open[kind] = false;
   }
   void harvest() {  // the stream must be idle
     for (int k = 0; k < KK_COUNT; ++k) {
@@ -1932,11 +1938,12 @@ int gco_conflict_edges(gco_ctx* ctx, const uint8_t* x, int64_t* count, int32_t* 
 
 int gco_set_profiling(gco_ctx* ctx, int32_t mode, uint64_t kind_mask) {
   if (!ctx) return GCO_EINVAL;
-  NEED(mode >= 0 && mode <= 2, GCO_EINVAL, "bad profiling mode %d", mode);
+  NEED(mode >= 0 && mode <= 3, GCO_EINVAL, "bad profiling mode %d", mode);
   HIPCHK(hipStreamSynchronize(ctx->st));
   ctx->prof.harvest();
   ctx->prof.mode = mode;
   ctx->prof.mask = kind_mask;
+  for (int k = 0; k < KK_COUNT; ++k) ctx->prof.seen[k] = 0;
   return GCO_OK;
 }
 
