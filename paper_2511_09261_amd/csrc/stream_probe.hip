@@ -91,7 +91,7 @@ extern "C" int gco_stream_probe(int32_t kind, size_t bytes_per_array, int32_t re
     auto launch = [&]() {
       if (kind == 0) probe_read_kernel<4><<<grid, kBlock>>>(buf[0], sink, n4);
       else if (kind == 1) probe_copy_kernel<4><<<grid, kBlock>>>(buf[0], buf[1], n4);
-      else probe_update_kernel<2><<<grid, kBlock>>>(buf[0], buf[1], buf[2], n4);
+      else probe_update_kernel<4><<<grid, kBlock>>>(buf[0], buf[1], buf[2], n4);
     };
     launch();  // warm-up
     (void)hipEventRecord(t0, nullptr);
