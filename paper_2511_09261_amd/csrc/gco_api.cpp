@@ -852,7 +852,8 @@ int gco_upload_graph(gco_ctx* ctx, int64_t n64, const int64_t* rowptr, const int
   // one decomposition per kernel kind (different cost per row)
   for (int v = 0; v < kWaveMaps; ++v) {
     std::vector<WaveRun> wave_runs;
-    build_wave_map(P, part_rows, lrowptr, kWaveBlocksFor[v], kWaveRowCost[v], group_by_xcd, ctx->hm.wblk_k[v],
+    build_wave_map(P, part_rows, lrowptr, (ctx->cfg.dim == 128 ? kWaveBlocksFor128 : kWaveBlocksFor)[v],
+                   kWaveRowCost[v], group_by_xcd, ctx->hm.wblk_k[v],
                    wave_runs);
     ctx->num_wblocks[v] = static_cast<int>(ctx->hm.wblk_k[v].size());
     GALLOC(ctx->d_wave_runs[v], wave_runs.size());
