@@ -213,6 +213,17 @@ int gco_get_probs(gco_ctx* ctx, float* p);
 /* Forward + loss at the current parameters: total and, if per_part is not NULL,
  * double[num_parts] per-subgraph values. */
 int gco_loss(gco_ctx* ctx, double* total, double* per_part);
+/* Test hook for the host side of the work decomposition (no device call): the shares of
+ * `target` workgroups that n subgraphs of weight work[k] >= 0 get, share[k] within
+ * [lo[k], hi[k]] (0 <= lo[k] <= hi[k]).  The shares add up to exactly `target` whenever
+ * sum(lo) <= target <= sum(hi), and to the nearest bound otherwise; units go where the
+ * work per unit is largest.  A launch is sized to whole rounds of the workgroups that are
+ * resident at once; a handful more would run as a round of their own.
+ * All pointers are host memory of n elements.  GCO_EINVAL on null pointers, n < 0,
+ * target < 0 or lo[k] > hi[k]. */
+int gco_apportion(const double* work, int32_t n, int64_t target, const int32_t* lo, const int32_t* hi,
+                  int32_t* share);
+
 /* Forward + backward at the current parameters without an update (test hook):
  * gradients shaped like the parameters. */
 int gco_get_grads(gco_ctx* ctx, float* gE, float* const* gW);

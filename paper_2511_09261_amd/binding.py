@@ -57,6 +57,8 @@ _PROTOTYPES = {
     "gco_create": (C.c_int, [C.POINTER(Config), C.POINTER(C.c_void_p)]),
     "gco_destroy": (C.c_int, [C.c_void_p]),
     "gco_get_config": (C.c_int, [C.c_void_p, C.POINTER(Config)]),
+    "gco_apportion": (C.c_int, [C.POINTER(C.c_double), C.c_int32, C.c_int64, C.POINTER(C.c_int32),
+                                C.POINTER(C.c_int32), C.POINTER(C.c_int32)]),
     "gco_set_scalar_layer_form": (C.c_int, [C.c_void_p, C.c_int]),
     "gco_get_scalar_layer_form": (C.c_int, [C.c_void_p, C.POINTER(C.c_int)]),
     "gco_last_error": (C.c_char_p, [C.c_void_p]),
@@ -135,6 +137,21 @@ def stream_probe(kind, bytes_per_array=1 << 30, repeats=10):
     if rc != 0:
         raise GcoError(rc, "gco_stream_probe failed")
     return out.value
+
+
+def apportion(work, target, lo, hi):
+    """gco_apportion: shares of `target` workgroups in proportion to work, within [lo, hi].  Host only."""
+    lib = load()
+    work = np.ascontiguousarray(work, dtype=np.float64)
+    lo = np.ascontiguousarray(lo, dtype=np.int32)
+    hi = np.ascontiguousarray(hi, dtype=np.int32)
+    share = np.empty(work.shape[0], dtype=np.int32)
+    as_p = lambda a, t: a.ctypes.data_as(C.POINTER(t))
+    rc = lib.gco_apportion(as_p(work, C.c_double), work.shape[0], int(target), as_p(lo, C.c_int32),
+                           as_p(hi, C.c_int32), as_p(share, C.c_int32))
+    if rc != 0:
+        raise GcoError(rc, "gco_apportion failed (bad bounds or sizes)")
+    return share
 
 
 def louvain(n, rowptr, col, max_levels=32):

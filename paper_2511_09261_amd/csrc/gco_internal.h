@@ -27,10 +27,10 @@ constexpr int kWaveRows = 32;            // rows of a tile in the wave-per-tile 
 enum WaveMap : int { WM_FWD = 0, WM_BWD = 1, WM_EMBED = 2, WM_NARROW = 3, WM_GRADW = 4, kWaveMaps = 5 };
 constexpr double kWaveRowCost[kWaveMaps] = {0.7, 1.5, 100.0, 1.0, 100.0};
 // workgroups aimed at (measured best); WM_GRADW: one per compute unit, which is all that fit at its size
-constexpr int kWaveBlocksFor[kWaveMaps] = {3072, 960, 3072, 2048, 256};
+constexpr int kWaveBlocksFor[kWaveMaps] = {1536, 512, 3072, 2048, 256};
 // width 128 (two workgroups of the layer kernels per compute unit): forward two rounds of 512,
 // embedding backward twelve
-constexpr int kWaveBlocksFor128[kWaveMaps] = {1024, 960, 6144, 2048, 256};
+constexpr int kWaveBlocksFor128[kWaveMaps] = {1024, 1024, 6144, 2048, 256};
 constexpr int kEntPad = 512;             // zero entries appended to the packed entry arrays
 // gco_round_repair_static works inside a block of device memory that is part of the
 // library's code object: up to this many nodes, 7 bytes per node plus counters.
