@@ -367,15 +367,16 @@ std::vector<int> apportion(const std::vector<double>& work, int64_t target, cons
 void build_block_map(int P, const std::vector<int>& part_rows, const std::vector<int32_t>& lrowptr,
                      int tile_rows, int target_blocks, int max_tiles_per_block,
                      std::vector<int>& blk_k, std::vector<int>& blk_s, std::vector<int>& blk_S,
-                     bool group_by_xcd, double row_cost = 2.0) {
+                     bool group_by_xcd, double row_cost = 2.0, const std::vector<double>* entries_of = nullptr) {
+  // entries_of: the entries a subgraph's workgroups walk, where that is not every local
+  // neighbour (the wave kernels leave the rows with very many neighbours to other workgroups)
   std::vector<int> tiles(P), Sk(P);
   std::vector<double> work(P);
-  double total = 0;
   for (int k = 0; k < P; ++k) {
     const int rows = part_rows[k + 1] - part_rows[k];
     tiles[k] = (rows + tile_rows - 1) / tile_rows;
-    work[k] = row_cost * rows + (lrowptr[part_rows[k + 1]] - lrowptr[part_rows[k]]);
-    total += work[k];
+    work[k] = row_cost * rows +
+              (entries_of ? (*entries_of)[k] : static_cast<double>(lrowptr[part_rows[k + 1]] - lrowptr[part_rows[k]]));
   }
   {
     std::vector<int> lo(P), hi(P);
@@ -441,8 +442,16 @@ void build_wave_map(int P, const std::vector<int>& part_rows, const std::vector<
                     std::vector<WaveRun>& wave_runs) {
   constexpr int kWaves = kBlock / 64;
   std::vector<int> blk_s, blk_S;
+  // the subgraphs' shares follow the same cost as the cuts below: the light stream's entries
+  // (the neighbours of pre-reduced rows are summed elsewhere) plus row_cost per row
+  std::vector<double> light(static_cast<size_t>(P), 0.0);
+  for (int k = 0; k < P; ++k)
+    for (int r = part_rows[k]; r < part_rows[k + 1]; ++r) {
+      const int deg = lrowptr[r + 1] - lrowptr[r];
+      light[k] += 1 + (deg >= kHeavyMin ? 0 : deg);
+    }
   build_block_map(P, part_rows, lrowptr, kWaveRows * kWaves, target_blocks, 0, wblk_k, blk_s, blk_S,
-                  group_by_xcd, 1.0 + row_cost);
+                  group_by_xcd, row_cost, &light);
   wave_runs.assign(wblk_k.size() * kWaves, WaveRun{});
   // light-stream offset of every row (one entry per row plus the neighbours of rows that
   // are not pre-reduced) and global number of every subgraph's first tile

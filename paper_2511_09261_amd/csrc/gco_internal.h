@@ -25,9 +25,9 @@ constexpr int kWaveRows = 32;            // rows of a tile in the wave-per-tile 
 // cuts of the tiles among the wavefronts, one per kernel kind: cost of a row relative to
 // one light-stream entry (measured per-tile against per-entry time of each kernel)
 enum WaveMap : int { WM_FWD = 0, WM_BWD = 1, WM_EMBED = 2, WM_NARROW = 3, WM_GRADW = 4, kWaveMaps = 5 };
-constexpr double kWaveRowCost[kWaveMaps] = {0.7, 1.5, 100.0, 1.0, 100.0};
+constexpr double kWaveRowCost[kWaveMaps] = {1.25, 1.5, 100.0, 1.0, 100.0};
 // workgroups aimed at (measured best); WM_GRADW: one per compute unit, which is all that fit at its size
-constexpr int kWaveBlocksFor[kWaveMaps] = {1536, 512, 3072, 2048, 256};
+constexpr int kWaveBlocksFor[kWaveMaps] = {768, 512, 3072, 2048, 256};
 // width 128 (two workgroups of the layer kernels per compute unit): forward two rounds of 512,
 // embedding backward twelve
 constexpr int kWaveBlocksFor128[kWaveMaps] = {1024, 1024, 6144, 2048, 256};
